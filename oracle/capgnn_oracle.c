@@ -1,0 +1,230 @@
+/*
+ * CPU oracle for the partition-local layer step of cache-assisted full-batch GNN training.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, fp64 definition of what the
+ * HIP library must compute.  It shares no code, header, table or helper with the HIP
+ * path and is never called by it.  Only the tests, the smoke check and the benchmark's
+ * cpu_baseline leg may load it.
+ *
+ * Every floating-point routine works in double precision and sums each output element
+ * sequentially in the order stated; OpenMP is used only across independent output
+ * elements (rows, or feature columns), so results do not depend on the thread count.
+ *
+ * What each routine follows in the paper (arxiv 2508.13716):
+ *   orc_placement     JACA, "Vertex Importance": cache the highest-priority halo vertices
+ *                     first (Eq. 2 gives the priority; Alg. 1 "sort R(v_k) and select top k").
+ *   orc_gather        JACA workflow: the receiving worker looks the halo rows up in the
+ *                     local / global cache and places them in the layer input.
+ *   orc_gcn_scales    notation table: A-hat is the symmetrically normalised adjacency.
+ *   orc_spmm_fwd      aggregation step of Eq. 1; A-hat * H in the GCN rule of Lemma 2's proof.
+ *   orc_spmm_bwd      the transposed product the chain rule of that rule needs
+ *                     (Lemma 3's recursion, operands put in conformable order).
+ *   orc_matmul        combination step: the dense transform by W, and its gradients.
+ *   orc_softmax_ce    evaluation setup: cross-entropy loss for single-label tasks.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int orc_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void orc_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* ---------------------------------------------------------------- placement (O1) */
+typedef struct { int64_t prio, gid, idx; } orc_rank_t;
+
+static int orc_rank_cmp(const void *a, const void *b)
+{
+    const orc_rank_t *x = (const orc_rank_t *)a, *y = (const orc_rank_t *)b;
+    if (x->prio != y->prio) return (x->prio > y->prio) ? -1 : 1;   /* higher priority first */
+    if (x->gid != y->gid) return (x->gid < y->gid) ? -1 : 1;       /* ties: smaller global id first */
+    return 0;
+}
+
+/* order[k] = halo-local index of the k-th ranked vertex; tier[h] = 0 (GPU) for the first
+ * min(cap_gpu, n_halo) ranked vertices, 1 (host) for the rest. */
+void orc_placement(int64_t n_halo, const int64_t *gid, const int64_t *prio, int64_t cap_gpu,
+                   int64_t *order, int8_t *tier)
+{
+    orc_rank_t *r = (orc_rank_t *)malloc(sizeof(orc_rank_t) * (size_t)(n_halo > 0 ? n_halo : 1));
+    for (int64_t h = 0; h < n_halo; ++h) { r[h].prio = prio[h]; r[h].gid = gid[h]; r[h].idx = h; }
+    qsort(r, (size_t)n_halo, sizeof(orc_rank_t), orc_rank_cmp);
+    for (int64_t k = 0; k < n_halo; ++k) {
+        order[k] = r[k].idx;
+        tier[r[k].idx] = (k < cap_gpu) ? 0 : 1;
+    }
+    free(r);
+}
+
+/* ---------------------------------------------------------------- gather (O2) */
+/* out[r, :] = table[ids[r], :] as raw bytes; an id outside [0, n_rows) gives a zero row.
+ * Returns the number of such absent ids. */
+int64_t orc_gather(const uint8_t *table, int64_t n_rows, int64_t row_bytes,
+                   const int64_t *ids, int64_t n, uint8_t *out)
+{
+    int64_t absent = 0;
+    for (int64_t r = 0; r < n; ++r) {
+        int64_t id = ids[r];
+        if (id < 0 || id >= n_rows) {
+            memset(out + r * row_bytes, 0, (size_t)row_bytes);
+            ++absent;
+        } else {
+            memcpy(out + r * row_bytes, table + id * row_bytes, (size_t)row_bytes);
+        }
+    }
+    return absent;
+}
+
+/* ---------------------------------------------------------------- normalisation scales */
+/* Symmetric normalisation A-hat[i,j] = r_i A_ij c_j with r_i = d_i^(-1/2), d_i = number of
+ * stored entries of row i (the self loop is among them).  A local column j uses c_j = r_j; a
+ * halo column uses its degree in the whole graph, clamped to at least 1. */
+void orc_gcn_scales(int64_t n_loc, int64_t n_halo, const int64_t *rowptr,
+                    const int64_t *halo_degree, double *r, double *c)
+{
+    for (int64_t i = 0; i < n_loc; ++i) {
+        int64_t d = rowptr[i + 1] - rowptr[i];
+        if (d < 1) d = 1;
+        r[i] = 1.0 / sqrt((double)d);
+        c[i] = r[i];
+    }
+    for (int64_t h = 0; h < n_halo; ++h) {
+        int64_t d = halo_degree[h];
+        if (d < 1) d = 1;
+        c[n_loc + h] = 1.0 / sqrt((double)d);
+    }
+}
+
+/* Mean aggregator: r_i = 1/deg_i (0 for an empty row), c_j = 1. */
+void orc_mean_scales(int64_t n_loc, int64_t n_cols, const int64_t *rowptr, double *r, double *c)
+{
+    for (int64_t i = 0; i < n_loc; ++i) {
+        int64_t d = rowptr[i + 1] - rowptr[i];
+        r[i] = d > 0 ? 1.0 / (double)d : 0.0;
+    }
+    for (int64_t j = 0; j < n_cols; ++j) c[j] = 1.0;
+}
+
+/* ---------------------------------------------------------------- SpMM (O3, O4) */
+/* Y[i,f] = r[i] * sum_{e in row i, in order} v[e] * c[col[e]] * X[col[e], f];  v == NULL means 1. */
+void orc_spmm_fwd(int64_t n_loc, const int64_t *rowptr, const int32_t *col,
+                  const double *r, const double *c, const double *v,
+                  const double *X, int64_t F, double *Y)
+{
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t i = 0; i < n_loc; ++i) {
+        double *y = Y + i * F;
+        for (int64_t f = 0; f < F; ++f) y[f] = 0.0;
+        for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+            int64_t j = col[e];
+            double w = (v ? v[e] : 1.0) * c[j];
+            const double *x = X + j * F;
+            for (int64_t f = 0; f < F; ++f) y[f] += w * x[f];
+        }
+        for (int64_t f = 0; f < F; ++f) y[f] *= r[i];
+    }
+}
+
+/* dX[j,f] = c[j] * sum_{e: col[e]=j, increasing e} v[e] * r[row(e)] * dY[row(e), f], for every j < n_cols.
+ * Edges are visited in increasing e; threads split the feature columns, never the edges. */
+void orc_spmm_bwd(int64_t n_loc, int64_t n_cols, const int64_t *rowptr, const int32_t *col,
+                  const double *r, const double *c, const double *v,
+                  const double *dY, int64_t F, double *dX)
+{
+    int nt = orc_max_threads();
+    if (nt > F) nt = (int)(F > 0 ? F : 1);
+#pragma omp parallel for schedule(static) num_threads(nt)
+    for (int t = 0; t < nt; ++t) {
+        int64_t f0 = F * t / nt, f1 = F * (t + 1) / nt;
+        for (int64_t j = 0; j < n_cols; ++j)
+            for (int64_t f = f0; f < f1; ++f) dX[j * F + f] = 0.0;
+        for (int64_t i = 0; i < n_loc; ++i) {
+            const double *g = dY + i * F;
+            for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+                double w = (v ? v[e] : 1.0) * r[i];
+                double *d = dX + (int64_t)col[e] * F;
+                for (int64_t f = f0; f < f1; ++f) d[f] += w * g[f];
+            }
+        }
+        for (int64_t j = 0; j < n_cols; ++j)
+            for (int64_t f = f0; f < f1; ++f) dX[j * F + f] *= c[j];
+    }
+}
+
+/* ---------------------------------------------------------------- dense products */
+/* C[M,N] (+)= op(A) op(B), reduction length K, every C[i,j] summed over k = 0..K-1 in order.
+ * ta: A is stored [K,M] (use A^T);  tb: B is stored [N,K] (use B^T).  All row-major, dense. */
+void orc_matmul(int ta, int tb, int64_t M, int64_t N, int64_t K,
+                const double *A, const double *B, double *C, int accumulate)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        double *c = C + i * N;
+        if (!accumulate) for (int64_t j = 0; j < N; ++j) c[j] = 0.0;
+        if (!tb) {
+            for (int64_t k = 0; k < K; ++k) {
+                double a = ta ? A[k * M + i] : A[i * K + k];
+                const double *b = B + k * N;
+                for (int64_t j = 0; j < N; ++j) c[j] += a * b[j];
+            }
+        } else {
+            for (int64_t j = 0; j < N; ++j) {
+                const double *b = B + j * K;
+                double s = 0.0;
+                for (int64_t k = 0; k < K; ++k) s += (ta ? A[k * M + i] : A[i * K + k]) * b[k];
+                c[j] += s;
+            }
+        }
+    }
+}
+
+/* ---------------------------------------------------------------- loss (O7) */
+/* L = (1/norm) * sum_{i masked} (logsumexp(Z_i) - Z_i[y_i]);  dZ_i = (softmax(Z_i) - e_{y_i}) / norm
+ * on masked rows, 0 elsewhere.  norm <= 0 means "number of masked rows".  mask == NULL: all rows. */
+double orc_softmax_ce(int64_t n, int64_t C, const double *Z, const int32_t *y, const uint8_t *mask,
+                      double norm, double *dZ)
+{
+    if (norm <= 0.0) {
+        int64_t cnt = 0;
+        for (int64_t i = 0; i < n; ++i) cnt += (!mask || mask[i]) ? 1 : 0;
+        norm = cnt > 0 ? (double)cnt : 1.0;
+    }
+    double loss = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        const double *z = Z + i * C;
+        double *g = dZ ? dZ + i * C : NULL;
+        if (mask && !mask[i]) {
+            if (g) for (int64_t k = 0; k < C; ++k) g[k] = 0.0;
+            continue;
+        }
+        double m = z[0];
+        for (int64_t k = 1; k < C; ++k) if (z[k] > m) m = z[k];
+        double s = 0.0;
+        for (int64_t k = 0; k < C; ++k) s += exp(z[k] - m);
+        double lse = m + log(s);
+        loss += lse - z[y[i]];
+        if (g) {
+            for (int64_t k = 0; k < C; ++k) g[k] = exp(z[k] - lse) / norm;
+            g[y[i]] -= 1.0 / norm;
+        }
+    }
+    return loss / norm;
+}

@@ -1,0 +1,279 @@
+"""CPU oracle: the plain fp64 definition of the partition-local layer step.
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product path may import this module; only
+``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` do.
+It imports nothing from the HIP package and shares no code with it.
+
+The numeric steps live in ``capgnn_oracle.c`` (plain loops, double precision, each output
+summed sequentially); this file marshals numpy arrays into it and writes the layer and
+epoch out in the paper's order:
+
+* GCN layer (forward rule in the proof of Lemma 2):   Z = A_hat H W (+ bias),  H' = sigma(Z)
+* GraphSAGE-mean layer (Eq. 1 with AGGREGATE = mean, COMBINE = two linear maps + sigma)
+* backward: the chain rule of those two rules (Lemma 3's recursion, made conformable)
+* loss: cross-entropy (evaluation setup), averaged over the masked local rows
+* epoch: for each layer, halo rows are first taken from the cache tables (JACA workflow),
+  then the layer runs on [local rows; halo rows]; backward visits the layers in reverse;
+  the optional parameter step is W <- W - tau * grad (update rule in the theorem's proof).
+
+Readings where the paper is silent (self loops, halo degrees, sigma = ReLU with
+sigma'(0) = 0, mean aggregator, ties by global id, ...) are listed in the design notes
+at the repository root.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from fractions import Fraction
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "capgnn_oracle.c")
+_SO = os.path.join(_HERE, "libcapgnn_oracle.so")
+_lib_handle = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C part with gcc (-O2, OpenMP).  Returns the path of the shared object."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99",
+                               "-o", _SO, _SRC, "-lm"])
+    return _SO
+
+
+def _lib():
+    global _lib_handle
+    if _lib_handle is None:
+        build()
+        L = C.CDLL(_SO)
+        i64, p = C.c_int64, C.c_void_p
+        L.orc_max_threads.restype = C.c_int
+        L.orc_set_threads.argtypes = [C.c_int]
+        L.orc_placement.argtypes = [i64, p, p, i64, p, p]
+        L.orc_gather.argtypes = [p, i64, i64, p, i64, p]
+        L.orc_gather.restype = i64
+        L.orc_gcn_scales.argtypes = [i64, i64, p, p, p, p]
+        L.orc_mean_scales.argtypes = [i64, i64, p, p, p]
+        L.orc_spmm_fwd.argtypes = [i64, p, p, p, p, p, p, i64, p]
+        L.orc_spmm_bwd.argtypes = [i64, i64, p, p, p, p, p, p, i64, p]
+        L.orc_matmul.argtypes = [C.c_int, C.c_int, i64, i64, i64, p, p, p, C.c_int]
+        L.orc_softmax_ce.argtypes = [i64, i64, p, p, p, C.c_double, p]
+        L.orc_softmax_ce.restype = C.c_double
+        _lib_handle = L
+    return _lib_handle
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def max_threads() -> int:
+    return int(_lib().orc_max_threads())
+
+
+def set_threads(n: int) -> None:
+    _lib().orc_set_threads(int(n))
+
+
+# ------------------------------------------------------------------ cache side
+def placement(gid: np.ndarray, prio: np.ndarray, cap_gpu: int):
+    """Rank halo vertices by (priority descending, global id ascending); the first
+    min(cap_gpu, n_halo) go to the GPU tier (0), the rest to the host tier (1)."""
+    gid = np.ascontiguousarray(gid, np.int64)
+    prio = np.ascontiguousarray(prio, np.int64)
+    n = len(gid)
+    order = np.zeros(n, np.int64)
+    tier = np.zeros(n, np.int8)
+    _lib().orc_placement(n, _ptr(gid), _ptr(prio), int(cap_gpu), _ptr(order), _ptr(tier))
+    return order, tier
+
+
+def cal_capacity(mem_gb, reserved_mb, dims: Sequence[int], n_candidates: int, elem_bytes: int = 4) -> int:
+    """Adaptive cache capacity (Alg. 1): rows = min(floor(((mem_gb*1024 - reserved_mb) * 1024^2)
+    / sum_k(dims[k] * elem_bytes)), n_candidates), exact rational arithmetic, never negative."""
+    num = (Fraction(mem_gb) * 1024 - Fraction(reserved_mb)) * 1024 * 1024
+    den = sum(int(d) for d in dims) * int(elem_bytes)
+    rows = int(num // den) if num > 0 else 0
+    return min(rows, int(n_candidates))
+
+
+def gather(table: np.ndarray, ids: np.ndarray):
+    """out[r,:] = table[ids[r],:] as a bit copy; ids outside the table give zero rows.  Returns (out, absent)."""
+    table = np.ascontiguousarray(table)
+    ids = np.ascontiguousarray(ids, np.int64)
+    row_bytes = table.strides[0] if table.shape[0] > 0 else table.shape[1] * table.itemsize
+    out = np.zeros((len(ids), table.shape[1]), dtype=table.dtype)
+    absent = _lib().orc_gather(_ptr(table), table.shape[0], row_bytes, _ptr(ids), len(ids), _ptr(out))
+    return out, int(absent)
+
+
+def overlap_ratio(halo_sets: Sequence[np.ndarray]):
+    """Vertex overlap ratio (Eq. 2): for every vertex in the union of the partitions' halo sets, the
+    number of partitions whose halo set contains it.  Returns (vertex ids ascending, counts)."""
+    allv = np.concatenate([np.unique(np.asarray(h, np.int64)) for h in halo_sets]) if len(halo_sets) else np.zeros(0, np.int64)
+    ids, cnt = np.unique(allv, return_counts=True)
+    return ids, cnt.astype(np.int64)
+
+
+# ------------------------------------------------------------------ graph
+@dataclass
+class Graph:
+    n_loc: int
+    n_cols: int
+    rowptr: np.ndarray            # int64
+    col: np.ndarray               # int32
+    r: np.ndarray                 # float64 [n_loc]   row scale
+    c: np.ndarray                 # float64 [n_cols]  column scale
+    v: Optional[np.ndarray] = None  # float64 [nnz] edge values or None (= 1)
+
+
+def gcn_graph(n_loc: int, n_halo: int, rowptr, col, halo_degree) -> Graph:
+    rowptr = np.ascontiguousarray(rowptr, np.int64)
+    col = np.ascontiguousarray(col, np.int32)
+    hd = np.ascontiguousarray(halo_degree, np.int64)
+    r = np.zeros(n_loc, np.float64)
+    c = np.zeros(n_loc + n_halo, np.float64)
+    _lib().orc_gcn_scales(n_loc, n_halo, _ptr(rowptr), _ptr(hd), _ptr(r), _ptr(c))
+    return Graph(n_loc, n_loc + n_halo, rowptr, col, r, c)
+
+
+def mean_graph(n_loc: int, n_halo: int, rowptr, col) -> Graph:
+    rowptr = np.ascontiguousarray(rowptr, np.int64)
+    col = np.ascontiguousarray(col, np.int32)
+    r = np.zeros(n_loc, np.float64)
+    c = np.zeros(n_loc + n_halo, np.float64)
+    _lib().orc_mean_scales(n_loc, n_loc + n_halo, _ptr(rowptr), _ptr(r), _ptr(c))
+    return Graph(n_loc, n_loc + n_halo, rowptr, col, r, c)
+
+
+def spmm_fwd(g: Graph, X) -> np.ndarray:
+    X = _f64(X)
+    assert X.shape[0] == g.n_cols
+    F = X.shape[1]
+    Y = np.zeros((g.n_loc, F), np.float64)
+    _lib().orc_spmm_fwd(g.n_loc, _ptr(g.rowptr), _ptr(g.col), _ptr(g.r), _ptr(g.c), _ptr(g.v), _ptr(X), F, _ptr(Y))
+    return Y
+
+
+def spmm_bwd(g: Graph, dY) -> np.ndarray:
+    dY = _f64(dY)
+    assert dY.shape[0] == g.n_loc
+    F = dY.shape[1]
+    dX = np.zeros((g.n_cols, F), np.float64)
+    _lib().orc_spmm_bwd(g.n_loc, g.n_cols, _ptr(g.rowptr), _ptr(g.col), _ptr(g.r), _ptr(g.c), _ptr(g.v),
+                        _ptr(dY), F, _ptr(dX))
+    return dX
+
+
+def matmul(A, B, ta: bool = False, tb: bool = False) -> np.ndarray:
+    A, B = _f64(A), _f64(B)
+    M = A.shape[1] if ta else A.shape[0]
+    K = A.shape[0] if ta else A.shape[1]
+    N = B.shape[0] if tb else B.shape[1]
+    assert (B.shape[1] if tb else B.shape[0]) == K
+    out = np.zeros((M, N), np.float64)
+    _lib().orc_matmul(int(ta), int(tb), M, N, K, _ptr(A), _ptr(B), _ptr(out), 0)
+    return out
+
+
+def softmax_ce(Z, y, mask=None, norm: float = 0.0):
+    Z = _f64(Z)
+    y = np.ascontiguousarray(y, np.int32)
+    m = None if mask is None else np.ascontiguousarray(mask, np.uint8)
+    dZ = np.zeros_like(Z)
+    loss = _lib().orc_softmax_ce(Z.shape[0], Z.shape[1], _ptr(Z), _ptr(y), _ptr(m), float(norm), _ptr(dZ))
+    return float(loss), dZ
+
+
+# ------------------------------------------------------------------ layers
+@dataclass
+class Layer:
+    kind: str                     # 'gcn' | 'sage'
+    W: np.ndarray                 # [f_in, f_out]
+    bias: Optional[np.ndarray]    # [f_out] or None
+    act: str = "relu"             # 'relu' | 'none'
+    W_self: Optional[np.ndarray] = None
+
+    @staticmethod
+    def of(p) -> "Layer":
+        """From a synthetic LayerParams record (float32 arrays widened exactly)."""
+        return Layer(p.kind, _f64(p.W), None if p.bias is None else _f64(p.bias), p.act,
+                     None if p.W_self is None else _f64(p.W_self))
+
+
+def layer_fwd(g: Graph, l: Layer, X):
+    """X is [n_cols, f_in] = [local rows; halo rows].  Returns (H [n_loc, f_out], saved)."""
+    X = _f64(X)
+    M = spmm_fwd(g, X)                                   # aggregate
+    Z = matmul(M, l.W)                                   # combine
+    if l.kind == "sage":
+        Z = Z + matmul(X[: g.n_loc], l.W_self)
+    if l.bias is not None:
+        Z = Z + l.bias[None, :]
+    H = np.maximum(Z, 0.0) if l.act == "relu" else Z
+    return H, {"M": M, "Z": Z}
+
+
+def layer_bwd(g: Graph, l: Layer, X, saved, dH, need_dx: bool = True):
+    """Chain rule of layer_fwd.  Returns dict(dW, dW_self, db, dX) with dX over all n_cols rows."""
+    X = _f64(X)
+    dH = _f64(dH)
+    dZ = dH * (saved["Z"] > 0.0) if l.act == "relu" else dH      # sigma'(0) = 0
+    out = {"db": dZ.sum(axis=0), "dW": matmul(saved["M"], dZ, ta=True), "dW_self": None, "dX": None}
+    if l.kind == "sage":
+        out["dW_self"] = matmul(X[: g.n_loc], dZ, ta=True)
+    if need_dx:
+        dM = matmul(dZ, l.W, tb=True)                    # [n_loc, f_in]
+        dX = spmm_bwd(g, dM)                             # [n_cols, f_in]
+        if l.kind == "sage":
+            dX[: g.n_loc] += matmul(dZ, l.W_self, tb=True)
+        out["dX"] = dX
+    return out
+
+
+def epoch(g: Graph, layers: List[Layer], X0_local, halo_tables: Sequence[Optional[np.ndarray]],
+          labels, mask=None, loss_norm: float = 0.0, lr: float = 0.0, halo_grad: bool = False):
+    """One full-batch forward + backward over the partition.
+
+    halo_tables[l] is the logical [n_halo, f_in(l)] cache table feeding layer l (None when the
+    partition has no halo).  Returns dict(loss, logits, dW, dW_self, db, dX_halo, new_W ...).
+    """
+    n_halo = g.n_cols - g.n_loc
+    ids = np.arange(n_halo, dtype=np.int64)
+    H = _f64(X0_local)
+    Xs, saves = [], []
+    for li, l in enumerate(layers):
+        if n_halo > 0:
+            rows, absent = gather(_f64(halo_tables[li]), ids)    # pick the halo rows from the cache
+            assert absent == 0
+            X = np.concatenate([H, rows], axis=0)
+        else:
+            X = H
+        H, sv = layer_fwd(g, l, X)
+        Xs.append(X)
+        saves.append(sv)
+    logits = H
+    loss, dH = softmax_ce(logits, labels, mask, loss_norm)
+    res = {"loss": loss, "logits": logits, "dW": [None] * len(layers), "dW_self": [None] * len(layers),
+           "db": [None] * len(layers), "dX_halo": [None] * len(layers), "hidden": [s["Z"] for s in saves]}
+    for li in range(len(layers) - 1, -1, -1):
+        need_dx = li > 0 or halo_grad
+        b = layer_bwd(g, layers[li], Xs[li], saves[li], dH, need_dx=need_dx)
+        res["dW"][li], res["dW_self"][li], res["db"][li] = b["dW"], b["dW_self"], b["db"]
+        if b["dX"] is not None:
+            res["dX_halo"][li] = b["dX"][g.n_loc:]
+            dH = b["dX"][: g.n_loc]
+    if lr:
+        res["new_W"] = [l.W - lr * res["dW"][i] for i, l in enumerate(layers)]
+        res["new_W_self"] = [None if l.W_self is None else l.W_self - lr * res["dW_self"][i]
+                             for i, l in enumerate(layers)]
+        res["new_bias"] = [None if l.bias is None else l.bias - lr * res["db"][i] for i, l in enumerate(layers)]
+    return res
