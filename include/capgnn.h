@@ -1,0 +1,295 @@
+/*
+ * capgnn.h - C ABI of the MI355X-native partition-local layer step of cache-assisted
+ * full-batch GNN training (CaPGNN, arxiv 2508.13716).
+ *
+ * One GPU's share of the method: the halo rows of each layer input are taken from a
+ * two-tier cache (GPU memory = local cache, pinned host memory = global cache; section
+ * "Joint Adaptive Caching Algorithm"), then a GCN or GraphSAGE-mean layer runs on the
+ * partition's local+halo graph (aggregate, combine; Eq. 1 and the forward rule in the proof
+ * of Lemma 2), followed by the backward pass (the chain rule behind Lemma 3).
+ *
+ * Conventions
+ *   - Every call returns an int: 0 = CAPGNN_OK, < 0 = error.  Nothing is printed, nothing
+ *     aborts.  capgnn_last_error() gives a text for the most recent failure on this thread.
+ *   - "device" pointers are HIP device memory, "host" pointers are ordinary host memory,
+ *     "pinned" pointers are page-locked host memory that the GPU can read (hipHostMalloc).
+ *   - The caller owns every feature / activation / gradient / weight / cache-tier buffer.
+ *     The library owns only its opaque handles and the index structures inside them
+ *     (CSR/CSC copies, slot maps), which it allocates at create/build time and frees at destroy.
+ *   - Device work is enqueued on the caller's stream (void* = hipStream_t, NULL = default
+ *     stream) and the call returns without synchronising unless the call says otherwise.
+ *   - Matrices are row-major with an explicit leading dimension `ld` counted in ELEMENTS;
+ *     a buffer with n rows must hold n*ld elements.  dtype selects the storage type of
+ *     features/activations: CAPGNN_F32 (float) or CAPGNN_BF16 (bfloat16 bits, fp32 accumulate,
+ *     round-to-nearest-even on store).  Scales, biases and weight gradients are always float.
+ *   - Scratch memory is caller-provided: ask *_workspace_bytes(), pass (ws, ws_bytes).
+ *     ws must be 256-byte aligned device memory.
+ *   - Handles are not thread-safe; distinct handles are independent.
+ */
+#ifndef CAPGNN_H
+#define CAPGNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CAPGNN_OK            0
+#define CAPGNN_EINVAL       (-1)  /* bad argument (shape, alignment, NULL, range)         */
+#define CAPGNN_ENOMEM       (-2)  /* host or device allocation failed / workspace too small */
+#define CAPGNN_EHIP         (-3)  /* a HIP runtime call failed (text in capgnn_last_error) */
+#define CAPGNN_ENOTFOUND    (-4)  /* a requested id is in neither cache tier              */
+#define CAPGNN_EUNSUPPORTED (-5)  /* valid request this build does not implement          */
+
+#define CAPGNN_F32   0
+#define CAPGNN_BF16  1
+
+#define CAPGNN_GCN        0
+#define CAPGNN_SAGE_MEAN  1
+
+#define CAPGNN_ACT_NONE 0
+#define CAPGNN_ACT_RELU 1
+
+#define CAPGNN_ORDER_AUTO   0   /* library picks the cheaper association of A_hat X W          */
+#define CAPGNN_AGG_FIRST    1   /* (A_hat X) W : SpMM at f_in, GEMM over local rows            */
+#define CAPGNN_XFORM_FIRST  2   /* A_hat (X W) : GEMM over all columns, SpMM at f_out          */
+
+#define CAPGNN_MAP_DIRECT 0     /* ids are halo-local indices 0..n_halo-1                     */
+#define CAPGNN_MAP_HASH   1     /* additionally build a hash table over the 64-bit global ids */
+
+#define CAPGNN_NORM_SYM   0     /* r_i = d_i^-1/2, c_j = d_j^-1/2 (symmetric normalisation)    */
+#define CAPGNN_NORM_MEAN  1     /* r_i = 1/d_i (0 for empty rows), c_j = 1 (mean aggregator)   */
+
+#define CAPGNN_GRAPH_SYMMETRIC 1u  /* n_halo == 0 and A_hat^T == A_hat: backward reuses the CSR */
+
+#define CAPGNN_MISS_ZEROCOPY 0  /* host-tier rows are read by a kernel straight from pinned memory */
+#define CAPGNN_MISS_STAGED   1  /* host tier is DMA-copied into a device staging area, then scattered */
+
+typedef struct capgnn_graph capgnn_graph;
+typedef struct capgnn_cache capgnn_cache;
+
+const char *capgnn_last_error(void);
+int capgnn_version(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Graph: the partition's local+halo graph.  Rows = local (inner) vertices, columns = local
+ * vertices [0,n_loc) followed by halo vertices [n_loc, n_loc+n_halo) (section "Graph
+ * Partition": halo vertices are the remote endpoints of cut edges; they have no rows).
+ * A_hat[i,j] = row_scale[i] * A[i,j] * col_scale[j], A[i,j] = sum of edge_val over stored
+ * entries (i,j) (1 each when edge_val is NULL).
+ * ---------------------------------------------------------------------------------------- */
+
+/* Host helper: the default scales.  CAPGNN_NORM_SYM follows the notation table's "adjacency
+ * matrix after symmetric normalization": d_i = stored entries of row i (a self loop, if the
+ * caller wants one, must be among them), clamped to >= 1; local column j uses row j's d;
+ * halo column h uses halo_degree[h] (its degree in the whole graph, host, may be NULL = 1).
+ * CAPGNN_NORM_MEAN is the mean aggregator of GraphSAGE (Eq. 1 with AGGREGATE = mean).
+ * rowptr: host int64[n_loc+1]; outputs: host float[n_loc], float[n_loc+n_halo].  No GPU work. */
+int capgnn_norm_scales(int kind, int64_t n_loc, int64_t n_halo, const int64_t *rowptr,
+                       const int64_t *halo_degree, float *row_scale, float *col_scale);
+
+/* Uploads the CSR, builds the CSC (= CSR of A_hat^T) and the degree-ordered work lists.
+ * rowptr: host int64[n_loc+1], rowptr[0]==0, non-decreasing; col: host int32[nnz], each in
+ * [0, n_loc+n_halo); nnz < 2^31.  row_scale/col_scale: host float arrays or NULL (= 1).
+ * edge_val: host float[nnz] or NULL.  Synchronises `stream` before returning (setup call).
+ * Errors: EINVAL on malformed CSR, ENOMEM, EHIP. */
+int capgnn_graph_create(capgnn_graph **g, int64_t n_loc, int64_t n_halo,
+                        const int64_t *rowptr, const int32_t *col,
+                        const float *row_scale, const float *col_scale, const float *edge_val,
+                        uint32_t flags, void *stream);
+int capgnn_graph_destroy(capgnn_graph *g);
+
+/* ------------------------------------------------------------------------------------------
+ * Aggregation ("SpMM is related to the number of edges", section on RAPA's cost model; the
+ * `aggregation` stage of the evaluation's stage breakdown).
+ * ---------------------------------------------------------------------------------------- */
+
+/* Y[i,0:F] = row_scale[i] * sum_{e in row i} edge_val[e]*col_scale[col e] * X[col e, 0:F], i < n_loc.
+ * X: device [n_cols x ldx], Y: device [n_loc x ldy], both of `dtype`; accumulation in fp32.
+ * Fast path needs 16-byte aligned bases and row pitches; other layouts run a scalar path. */
+size_t capgnn_spmm_workspace_bytes(const capgnn_graph *g, int F, int dtype);
+int capgnn_spmm_fwd(const capgnn_graph *g, const void *X, int64_t ldx, void *Y, int64_t ldy,
+                    int F, int dtype, void *ws, size_t ws_bytes, void *stream);
+
+/* dX[j,0:F] = col_scale[j] * sum_{e: col e = j} edge_val[e]*row_scale[row e] * dY[row e, 0:F], j < n_cols
+ * (= A_hat^T dY; the product the backward recursion of Lemma 3 needs).  Atomic-free: runs over the
+ * CSC built at create time.  dY: device [n_loc x lddy]; dX: device [n_cols x lddx]. */
+int capgnn_spmm_bwd(const capgnn_graph *g, const void *dY, int64_t lddy, void *dX, int64_t lddx,
+                    int F, int dtype, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Joint cache (section "Joint Adaptive Caching Algorithm"): which halo vertices live in GPU
+ * memory, which in pinned host memory, and the lookup / gather that fills a layer input.
+ * ---------------------------------------------------------------------------------------- */
+
+/* Adaptive cache capacity, Alg. 1 (cal_capacity): rows = min(floor(((mem_gb*1024 - reserved_mb)
+ * * 1024^2) / sum_k(dims[k]*elem_bytes)), n_candidates), never negative.  The paper fixes
+ * elem_bytes = 4 (fp32 rows); 2 is this library's extension for bf16 tables.  Host only. */
+int capgnn_cal_capacity(double mem_gb, double reserved_mb, const int32_t *dims, int n_layers,
+                        int elem_bytes, int64_t n_candidates, int64_t *capacity_rows);
+
+/* Bytes the caller must provide for the two tiers (all layers) and, for CAPGNN_MISS_STAGED,
+ * for the device staging area.  Row pitch of layer l's table = dims[l] rounded up to 16 bytes. */
+int capgnn_cache_sizes(int64_t n_halo, int64_t cap_gpu, const int32_t *dims, int n_layers, int dtype,
+                       size_t *gpu_bytes, size_t *host_bytes, size_t *staging_bytes);
+
+/* Placement: halo vertices ranked by (prio descending, gid ascending); the first min(cap_gpu,n_halo)
+ * go to the GPU tier, the rest to the host tier (priority = vertex overlap ratio, Eq. 2, or any
+ * other importance the caller supplies).  gid, prio: host int64[n_halo], gid unique.
+ * dims[l] = width of the rows cached for layer l's input (Alg. 1's f_dim).  gpu_tier: device,
+ * host_tier: pinned, both caller-owned and at least capgnn_cache_sizes() bytes, 256-byte aligned.
+ * Builds the id -> (tier, slot) map (direct array; plus a hash table over gid for MAP_HASH).
+ * Synchronises `stream`.  Errors: EINVAL (duplicate gid, bad sizes), ENOMEM, EHIP. */
+int capgnn_cache_build(capgnn_cache **c, int64_t n_halo, const int64_t *gid, const int64_t *prio,
+                       int64_t cap_gpu, const int32_t *dims, int n_layers, int dtype,
+                       void *gpu_tier, void *host_tier, int map_kind, void *stream);
+int capgnn_cache_destroy(capgnn_cache *c);
+
+/* How capgnn_epoch moves host-tier rows: CAPGNN_MISS_ZEROCOPY (default) or CAPGNN_MISS_STAGED (then
+ * capgnn_epoch_workspace_bytes() includes the staging area). */
+int capgnn_cache_set_miss_mode(capgnn_cache *c, int mode);
+
+/* Loads layer `layer`'s logical table (host, [n_halo x ld], halo-local row order) into both tiers.
+ * Synchronous (setup call). */
+int capgnn_cache_fill(capgnn_cache *c, int layer, const void *rows, int64_t ld, void *stream);
+
+/* check_cache on the host (for tests and planning): ids are halo-local indices, or global ids when
+ * by_gid != 0 (needs MAP_HASH).  tier[k] = 0 GPU, 1 host, -1 absent; slot[k] = row inside that tier
+ * (-1 if absent).  All arrays host.  Returns ENOTFOUND if any id is absent (outputs still complete). */
+int capgnn_cache_query(const capgnn_cache *c, const int64_t *ids, int64_t n, int by_gid,
+                       int8_t *tier, int64_t *slot);
+
+/* check_cache on the GPU: same result, ids / tier / slot are device arrays; asynchronous. */
+int capgnn_cache_lookup(const capgnn_cache *c, const int64_t *ids, int64_t n, int by_gid,
+                        int8_t *tier, int64_t *slot, void *stream);
+
+typedef struct {
+    int64_t hits;     /* rows served from the GPU tier  */
+    int64_t misses;   /* rows served from the host tier */
+    int64_t absent;   /* ids found in neither tier (rows zero-filled) */
+} capgnn_gather_stats;
+
+/* pick_cache: out[k, 0:dims[layer]] = table_layer[ids[k], :] as a bit copy.
+ * ids: device int64[n] (halo-local indices, or global ids when by_gid), duplicates and any order
+ * allowed; ids == NULL means "every halo vertex in halo-local order" (n must equal n_halo), the
+ * case of full-batch training.  out: device [n x ld] of the cache's dtype.
+ * GPU-tier rows are copied on `stream`.  Host-tier rows are moved on `side_stream` when it is
+ * non-NULL (it first waits for everything enqueued on `stream` so far; `stream` then waits for the
+ * transfer before the call returns control of `out` to later work on `stream`), else on `stream`.
+ * staging: device scratch of capgnn_cache_sizes().staging_bytes for CAPGNN_MISS_STAGED, or NULL to
+ * read pinned memory directly from the kernel (CAPGNN_MISS_ZEROCOPY).
+ * stats != NULL forces a stream synchronisation and fills the counters.
+ * Absent ids give zero rows and CAPGNN_ENOTFOUND (only detectable when stats != NULL). */
+int capgnn_halo_gather(capgnn_cache *c, int layer, const int64_t *ids, int64_t n, int by_gid,
+                       void *out, int64_t ld, void *stream, void *side_stream, void *staging,
+                       capgnn_gather_stats *stats);
+
+/* ------------------------------------------------------------------------------------------
+ * Dense products on the matrix cores ("MM is related to the number of vertices").
+ * C[M x N] (+)= op(A) op(B) with fp32 accumulation; optional fused bias / ReLU epilogue.
+ * trans_a: A is stored [K x M];  trans_b: B is stored [N x K].  bias: device float[N] or NULL.
+ * relu_mask: device [M x ldm] of `dtype` or NULL; when given, C[i,j] is zeroed where
+ * relu_mask[i,j] <= 0 (the sigma' factor of the backward recursion).
+ * ws is needed only when trans_a (reduction over the vertex dimension is split over workgroups and
+ * reduced in a fixed order): capgnn_gemm_workspace_bytes().
+ * out_f32 != 0 stores C as float even when dtype is BF16 (weight gradients, logits).
+ * ---------------------------------------------------------------------------------------- */
+size_t capgnn_gemm_workspace_bytes(int trans_a, int64_t M, int64_t N, int64_t K);
+int capgnn_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K,
+                const void *A, int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc,
+                int dtype, int out_f32, int accumulate, const float *bias, int relu,
+                const void *relu_mask, int64_t ldm, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Layer and epoch.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct {
+    int kind;            /* CAPGNN_GCN | CAPGNN_SAGE_MEAN                                   */
+    int f_in, f_out;
+    int act;             /* CAPGNN_ACT_NONE | CAPGNN_ACT_RELU                               */
+    int dtype;           /* storage type of X, H and of W / W_self                          */
+    int order;           /* CAPGNN_ORDER_AUTO | CAPGNN_AGG_FIRST | CAPGNN_XFORM_FIRST       */
+    int out_f32;         /* store H as float even when dtype is BF16 (the layer that feeds the loss) */
+    void *W;             /* device [f_in x f_out], dense (ld = f_out); neighbour weight for SAGE */
+    void *W_self;        /* device [f_in x f_out], SAGE only, else NULL                     */
+    float *bias;         /* device float[f_out] or NULL                                     */
+} capgnn_layer;
+
+/* The association the library would use for this layer (resolves ORDER_AUTO with a byte/FLOP
+ * cost model that includes the backward pass). */
+int capgnn_layer_order(const capgnn_graph *g, const capgnn_layer *l, int need_dx);
+
+/* Forward: H = act(A_hat X W + bias)            (GCN, proof of Lemma 2)
+ *          H = act(X_loc W_self + mean_agg(X) W + bias)   (GraphSAGE-mean)
+ * X: device [n_cols x ldx] = [local rows; halo rows]; H: device [n_loc x ldh].
+ * saved: device buffer of capgnn_layer_saved_bytes() that layer_bwd needs (the aggregated input
+ * for AGG_FIRST; nothing for XFORM_FIRST). */
+size_t capgnn_layer_saved_bytes(const capgnn_graph *g, const capgnn_layer *l);
+size_t capgnn_layer_workspace_bytes(const capgnn_graph *g, const capgnn_layer *l);
+int capgnn_layer_fwd(const capgnn_graph *g, const capgnn_layer *l, const void *X, int64_t ldx,
+                     void *H, int64_t ldh, void *saved, void *ws, size_t ws_bytes, void *stream);
+
+/* Backward of the same layer.  H is the forward output (its sign pattern is sigma').  dH: device
+ * [n_loc x lddh], gradient w.r.t. H; it is overwritten with dZ = dH * 1[H > 0] for ReLU layers.
+ * dW, dW_self: device float [f_in x f_out] (dense); dbias: device float[f_out]; any may be NULL.
+ * dX: device [n_rows_dx x lddx] or NULL; n_rows_dx = n_cols when need_halo_grad, else n_loc
+ * (gradient w.r.t. the halo rows is computed only on request; it is never sent anywhere). */
+int capgnn_layer_bwd(const capgnn_graph *g, const capgnn_layer *l, const void *X, int64_t ldx,
+                     const void *H, int64_t ldh, const void *saved, void *dH, int64_t lddh,
+                     float *dW, float *dW_self, float *dbias, void *dX, int64_t lddx,
+                     int need_halo_grad, void *ws, size_t ws_bytes, void *stream);
+
+/* Masked softmax cross-entropy (evaluation setup: cross-entropy for single-label tasks) and its
+ * gradient: loss = (1/norm) sum_{mask} (logsumexp(Z_i) - Z_i[y_i]); dZ_i = (softmax(Z_i)-e_y)/norm.
+ * Z: device float [n x ldz] (C classes); labels: device int32[n]; mask: device uint8[n] or NULL;
+ * loss_norm <= 0 means "number of masked rows".  loss_dev: device float[1].  dZ: device [n x lddz] of dz_dtype
+ * (float, or bf16 so that a bf16 backward pass can consume it directly), or NULL.
+ * Labels outside [0,C) are clamped into range.  ws: capgnn_loss_workspace_bytes(n). */
+size_t capgnn_loss_workspace_bytes(int64_t n);
+int capgnn_softmax_ce(int64_t n, int C, const float *Z, int64_t ldz, const int32_t *labels,
+                      const uint8_t *mask, double loss_norm, float *loss_dev, void *dZ, int64_t lddz,
+                      int dz_dtype, void *ws, size_t ws_bytes, void *stream);
+
+#define CAPGNN_MAX_RECORDS 96
+#define CAPGNN_K_GATHER_HIT   1
+#define CAPGNN_K_GATHER_MISS  2
+#define CAPGNN_K_SPMM_FWD     3
+#define CAPGNN_K_SPMM_BWD     4
+#define CAPGNN_K_GEMM         5
+#define CAPGNN_K_LOSS         6
+#define CAPGNN_K_ELEMENTWISE  7
+
+typedef struct {
+    /* stage names follow the evaluation's breakdown: check_cache, pick_cache, communication,
+     * aggregation; `communication` here is the host-tier transfer on the side stream. */
+    float total_ms, check_cache_ms, pick_cache_ms, communication_ms, aggregation_ms,
+          combine_ms, loss_ms, other_ms;
+    int n_records;
+    struct { int kind, layer, backward; float ms; } records[CAPGNN_MAX_RECORDS];
+} capgnn_epoch_times;
+
+/* One full-batch epoch over the partition: for l = 0..L-1 { halo rows of layer l's input <- cache;
+ * layer forward }, loss, for l = L-1..0 { layer backward }, optional W <- W - lr*dW (update rule in
+ * the proof of the convergence theorem).
+ *   X0: device [n_cols x ld0]; rows [0,n_loc) hold the local input features, rows [n_loc,n_cols)
+ *       are filled by this call from the cache's layer-0 table.
+ *   c: NULL iff n_halo == 0.  labels/mask: device.  logits: device float [n_loc x f_out(L-1)] dense, or NULL.
+ *   dW[l], dW_self[l], dbias[l]: device float buffers per layer (dW_self[l] NULL for GCN).
+ *   loss_out: host float*, written after a stream synchronisation (the only forced sync);
+ *   times: NULL, or filled from HIP events recorded on the streams the kernels run on (adds a sync).
+ *   ws: capgnn_epoch_workspace_bytes(); side_stream may be NULL (then everything runs on `stream`).
+ * Errors: EINVAL, ENOMEM (workspace too small), EUNSUPPORTED, EHIP. */
+size_t capgnn_epoch_workspace_bytes(const capgnn_graph *g, const capgnn_cache *c,
+                                    const capgnn_layer *layers, int L);
+int capgnn_epoch(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer *layers, int L,
+                 void *X0, int64_t ld0, const int32_t *labels, const uint8_t *mask, double loss_norm,
+                 float *logits, float **dW, float **dW_self, float **dbias, float lr,
+                 float *loss_out, capgnn_epoch_times *times,
+                 void *ws, size_t ws_bytes, void *stream, void *side_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CAPGNN_H */

@@ -1,0 +1,495 @@
+// Two-tier halo cache: placement, id -> (tier, slot) maps, lookup and the row gather.
+//
+// GPU tier = rows in device memory, host tier = rows in pinned host memory.  Placement ranks the
+// halo vertices by (priority descending, global id ascending).  Within a tier, slots are numbered
+// in ascending halo-local order so that the full-batch gather walks both the table and the
+// destination buffer monotonically.  The gather itself is a plain row copy: 16-byte lanes, several
+// rows per wave when rows are short, no arithmetic on the data (results are bit copies).
+#include "common.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <numeric>
+
+namespace capgnn {
+
+__host__ __device__ inline uint64_t mix64(uint64_t x) {
+    x += 0x9e3779b97f4a7c15ull;
+    x = (x ^ (x >> 30)) * 0xbf58476d1ce4e5b9ull;
+    x = (x ^ (x >> 27)) * 0x94d049bb133111ebull;
+    return x ^ (x >> 31);
+}
+
+uint64_t hash_gid(uint64_t x) { return mix64(x); }
+
+struct MapView {
+    int64_t n_halo;
+    const int32_t *slot;      // [n_halo]
+    const int64_t *hkeys;     // hash keys or null
+    const int32_t *hvals;
+    uint64_t hmask;
+};
+
+// halo-local index of a request id, or -1
+__host__ __device__ inline int64_t resolve(const MapView &m, int64_t id, int by_gid) {
+    if (!by_gid) return (id >= 0 && id < m.n_halo) ? id : -1;
+    if (!m.hkeys) return -1;
+    uint64_t p = mix64(static_cast<uint64_t>(id)) & m.hmask;
+    for (uint64_t probes = 0; probes <= m.hmask; ++probes) {
+        const int32_t v = m.hvals[p];
+        if (v < 0) return -1;
+        if (m.hkeys[p] == id) return v;
+        p = (p + 1) & m.hmask;
+    }
+    return -1;
+}
+
+__global__ __launch_bounds__(256) void lookup_kernel(MapView m, const int64_t *ids, int64_t n, int by_gid,
+                                                     int8_t *tier, int64_t *slot) {
+    const int64_t k = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (k >= n) return;
+    const int64_t h = resolve(m, ids[k], by_gid);
+    if (h < 0) {
+        tier[k] = -1;
+        slot[k] = -1;
+    } else {
+        const int32_t s = m.slot[h];
+        tier[k] = s >= 0 ? 0 : 1;
+        slot[k] = s >= 0 ? s : -1 - static_cast<int64_t>(s);
+    }
+}
+
+// copies row_bytes bytes from s to d with the lanes l, l+lpr, ... of one lane group
+__device__ __forceinline__ void copy_row(const char *s, char *d, int row_bytes, int l, int lpr, int vec16, int es) {
+    int done = 0;
+    if (vec16) {
+        const int nfull = row_bytes >> 4;
+        const uint4 *sv = reinterpret_cast<const uint4 *>(s);
+        uint4 *dv = reinterpret_cast<uint4 *>(d);
+        int c = l;
+        for (; c + 3 * lpr < nfull; c += 4 * lpr) {
+            const uint4 a0 = sv[c], a1 = sv[c + lpr], a2 = sv[c + 2 * lpr], a3 = sv[c + 3 * lpr];
+            dv[c] = a0; dv[c + lpr] = a1; dv[c + 2 * lpr] = a2; dv[c + 3 * lpr] = a3;
+        }
+        for (; c < nfull; c += lpr) dv[c] = sv[c];
+        done = nfull << 4;
+    }
+    if (es == 4) {
+        for (int b = done + l * 4; b < row_bytes; b += lpr * 4)
+            *reinterpret_cast<uint32_t *>(d + b) = *reinterpret_cast<const uint32_t *>(s + b);
+    } else {
+        for (int b = done + l * 2; b < row_bytes; b += lpr * 2)
+            *reinterpret_cast<uint16_t *>(d + b) = *reinterpret_cast<const uint16_t *>(s + b);
+    }
+}
+
+__device__ __forceinline__ void zero_row(char *d, int row_bytes, int l, int lpr, int es) {
+    if (es == 4) for (int b = l * 4; b < row_bytes; b += lpr * 4) *reinterpret_cast<uint32_t *>(d + b) = 0u;
+    else for (int b = l * 2; b < row_bytes; b += lpr * 2) *reinterpret_cast<uint16_t *>(d + b) = 0;
+}
+
+// out[dst_list[k]] = table[k]  (full-batch gather of one tier; dst_list = halo-local index of slot k)
+__global__ __launch_bounds__(256) void scatter_tier_kernel(const char *table, int64_t pitch, const int32_t *dst_list,
+                                                           int64_t n, char *out, int64_t out_pitch, int row_bytes,
+                                                           int lpr, int vec16, int es) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int64_t k = wave * (64 / lpr) + lane / lpr;
+    if (k >= n) return;
+    copy_row(table + k * pitch, out + static_cast<int64_t>(dst_list[k]) * out_pitch, row_bytes, lane % lpr, lpr, vec16, es);
+}
+
+// request-list gather with lookup; which: bit0 = serve GPU-tier rows (and absent ids), bit1 = serve host-tier rows
+__global__ __launch_bounds__(256) void gather_ids_kernel(MapView m, const int64_t *ids, int64_t n, int by_gid,
+                                                         const char *gpu_table, const char *host_table, int64_t pitch,
+                                                         int which, char *out, int64_t out_pitch, int row_bytes,
+                                                         int lpr, int vec16, int es, unsigned long long *counters) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int64_t k = wave * (64 / lpr) + lane / lpr;
+    if (k >= n) return;
+    const int l = lane % lpr;
+    const int64_t h = resolve(m, ids[k], by_gid);
+    char *d = out + k * out_pitch;
+    if (h < 0) {
+        if (which & 1) {
+            zero_row(d, row_bytes, l, lpr, es);
+            if (counters && l == 0) atomicAdd(&counters[2], 1ull);
+        }
+        return;
+    }
+    const int32_t s = m.slot[h];
+    if (s >= 0) {
+        if (which & 1) {
+            copy_row(gpu_table + static_cast<int64_t>(s) * pitch, d, row_bytes, l, lpr, vec16, es);
+            if (counters && l == 0) atomicAdd(&counters[0], 1ull);
+        }
+    } else if (which & 2) {
+        copy_row(host_table + (-1 - static_cast<int64_t>(s)) * pitch, d, row_bytes, l, lpr, vec16, es);
+        if (counters && l == 0) atomicAdd(&counters[1], 1ull);
+    }
+}
+
+__global__ void zero_counters_kernel(unsigned long long *c) {
+    if (threadIdx.x < 4) c[threadIdx.x] = 0ull;
+}
+
+static int lanes_per_row(int row_bytes, int vec16, int es) {
+    const int units = vec16 ? (row_bytes + 15) / 16 : (row_bytes + es - 1) / es;
+    int lpr = 4;
+    while (lpr < 64 && lpr < units) lpr <<= 1;
+    return lpr;
+}
+
+struct CopyGeom {
+    int row_bytes, lpr, vec16, es;
+    int64_t out_pitch;
+};
+
+static int copy_geom(const capgnn_cache *c, int layer, const void *out, int64_t ld, const void *src_base, CopyGeom *g) {
+    g->es = elem_bytes(c->dtype);
+    g->row_bytes = c->dims[layer] * g->es;
+    g->out_pitch = ld * g->es;
+    if (ld < c->dims[layer]) CG_FAIL(CAPGNN_EINVAL, "halo_gather: ld=%lld smaller than the row width %d", (long long)ld, c->dims[layer]);
+    g->vec16 = aligned16(out) && g->out_pitch % 16 == 0 && aligned16(src_base) && c->pitch[layer] % 16 == 0;
+    g->lpr = lanes_per_row(g->row_bytes, g->vec16, g->es);
+    return CAPGNN_OK;
+}
+
+static MapView view_dev(const capgnn_cache *c) {
+    MapView m;
+    m.n_halo = c->n_halo; m.slot = c->slot_d; m.hkeys = c->hkeys_d; m.hvals = c->hvals_d; m.hmask = c->hmask;
+    return m;
+}
+
+static MapView view_host(const capgnn_cache *c) {
+    MapView m;
+    m.n_halo = c->n_halo; m.slot = c->slot_h.data();
+    m.hkeys = c->hkeys_h.empty() ? nullptr : c->hkeys_h.data();
+    m.hvals = c->hvals_h.empty() ? nullptr : c->hvals_h.data();
+    m.hmask = c->hmask;
+    return m;
+}
+
+static unsigned blocks_for(int64_t n, int lpr) {
+    const int64_t rows_per_block = 4 * (64 / lpr);
+    return static_cast<unsigned>((n + rows_per_block - 1) / rows_per_block);
+}
+
+// GPU-tier part of the full-batch gather of one layer, on `st`.
+int gather_all_hits(const capgnn_cache *c, int layer, void *out, int64_t ld, hipStream_t st) {
+    if (c->cap_gpu == 0) return CAPGNN_OK;
+    CopyGeom g;
+    const char *tab = c->gpu_tier + c->gpu_off[layer];
+    CG_TRY(copy_geom(c, layer, out, ld, tab, &g));
+    hipLaunchKernelGGL(scatter_tier_kernel, dim3(blocks_for(c->cap_gpu, g.lpr)), dim3(256), 0, st, tab, c->pitch[layer],
+                       c->gpu_list_d, c->cap_gpu, static_cast<char *>(out), g.out_pitch, g.row_bytes, g.lpr, g.vec16, g.es);
+    CG_HIP(hipGetLastError());
+    return CAPGNN_OK;
+}
+
+// Host-tier part of the full-batch gather of one layer, on `st`: either a kernel that reads pinned
+// memory directly, or a DMA copy into `staging` followed by the same scatter from device memory.
+int gather_all_misses(const capgnn_cache *c, int layer, void *out, int64_t ld, void *staging, hipStream_t st) {
+    if (c->n_host == 0) return CAPGNN_OK;
+    const char *tab = c->host_tier + c->host_off[layer];
+    if (staging) {
+        char *stg = static_cast<char *>(staging) + c->host_off[layer];
+        CG_HIP(hipMemcpyAsync(stg, tab, static_cast<size_t>(c->n_host) * c->pitch[layer], hipMemcpyHostToDevice, st));
+        tab = stg;
+    }
+    CopyGeom g;
+    CG_TRY(copy_geom(c, layer, out, ld, tab, &g));
+    hipLaunchKernelGGL(scatter_tier_kernel, dim3(blocks_for(c->n_host, g.lpr)), dim3(256), 0, st, tab, c->pitch[layer],
+                       c->host_list_d, c->n_host, static_cast<char *>(out), g.out_pitch, g.row_bytes, g.lpr, g.vec16, g.es);
+    CG_HIP(hipGetLastError());
+    return CAPGNN_OK;
+}
+
+template <typename T>
+static int dev_copy(capgnn_cache *c, const std::vector<T> &h, T **d) {
+    void *p = nullptr;
+    const size_t bytes = std::max<size_t>(h.size(), 1) * sizeof(T);
+    if (hipMalloc(&p, bytes) != hipSuccess) CG_FAIL(CAPGNN_ENOMEM, "cache_build: hipMalloc of %zu bytes failed", bytes);
+    c->dev_allocs.push_back(p);
+    if (!h.empty()) CG_HIP(hipMemcpy(p, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice));
+    *d = static_cast<T *>(p);
+    return CAPGNN_OK;
+}
+
+}  // namespace capgnn
+
+using namespace capgnn;
+
+extern "C" int capgnn_cal_capacity(double mem_gb, double reserved_mb, const int32_t *dims, int n_layers,
+                                   int elem_bytes_, int64_t n_candidates, int64_t *capacity_rows) {
+    if (!dims || n_layers <= 0 || !capacity_rows || n_candidates < 0 || (elem_bytes_ != 4 && elem_bytes_ != 2))
+        CG_FAIL(CAPGNN_EINVAL, "cal_capacity: bad argument");
+    long double den = 0;
+    for (int k = 0; k < n_layers; ++k) {
+        if (dims[k] <= 0) CG_FAIL(CAPGNN_EINVAL, "cal_capacity: dims[%d] must be positive", k);
+        den += static_cast<long double>(dims[k]) * elem_bytes_;
+    }
+    const long double num = (static_cast<long double>(mem_gb) * 1024.0L - static_cast<long double>(reserved_mb)) * 1048576.0L;
+    int64_t rows = 0;
+    if (num > 0) {
+        long double q = floorl(num / den);
+        while ((q + 1) * den <= num) q += 1;
+        while (q * den > num) q -= 1;
+        rows = q > 9.0e18L ? INT64_MAX : static_cast<int64_t>(q);
+    }
+    *capacity_rows = std::min<int64_t>(rows, n_candidates);
+    return CAPGNN_OK;
+}
+
+static int64_t pitch_of(int dim, int dtype) { return static_cast<int64_t>(align_up(static_cast<size_t>(dim) * elem_bytes(dtype), 16)); }
+
+extern "C" int capgnn_cache_sizes(int64_t n_halo, int64_t cap_gpu, const int32_t *dims, int n_layers, int dtype,
+                                  size_t *gpu_bytes, size_t *host_bytes, size_t *staging_bytes) {
+    if (n_halo < 0 || cap_gpu < 0 || !dims || n_layers <= 0 || (dtype != CAPGNN_F32 && dtype != CAPGNN_BF16))
+        CG_FAIL(CAPGNN_EINVAL, "cache_sizes: bad argument");
+    const int64_t k = std::min(cap_gpu, n_halo);
+    size_t gb = 0, hb = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        if (dims[l] <= 0) CG_FAIL(CAPGNN_EINVAL, "cache_sizes: dims[%d] must be positive", l);
+        gb += align_up(static_cast<size_t>(k) * pitch_of(dims[l], dtype), 256);
+        hb += align_up(static_cast<size_t>(n_halo - k) * pitch_of(dims[l], dtype), 256);
+    }
+    if (gpu_bytes) *gpu_bytes = gb;
+    if (host_bytes) *host_bytes = hb;
+    if (staging_bytes) *staging_bytes = hb;
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_cache_build(capgnn_cache **out, int64_t n_halo, const int64_t *gid, const int64_t *prio,
+                                  int64_t cap_gpu, const int32_t *dims, int n_layers, int dtype, void *gpu_tier,
+                                  void *host_tier, int map_kind, void *stream) {
+    if (!out) CG_FAIL(CAPGNN_EINVAL, "cache_build: c is NULL");
+    *out = nullptr;
+    if (n_halo < 0 || n_halo >= (int64_t(1) << 31) - 1 || cap_gpu < 0 || !dims || n_layers <= 0 ||
+        (dtype != CAPGNN_F32 && dtype != CAPGNN_BF16) || (map_kind != CAPGNN_MAP_DIRECT && map_kind != CAPGNN_MAP_HASH))
+        CG_FAIL(CAPGNN_EINVAL, "cache_build: bad argument");
+    if (n_halo > 0 && (!gid || !prio)) CG_FAIL(CAPGNN_EINVAL, "cache_build: gid/prio is NULL");
+    const int64_t k = std::min(cap_gpu, n_halo);
+    if (k > 0 && !gpu_tier) CG_FAIL(CAPGNN_EINVAL, "cache_build: gpu_tier is NULL");
+    if (n_halo - k > 0 && !host_tier) CG_FAIL(CAPGNN_EINVAL, "cache_build: host_tier is NULL");
+    if ((reinterpret_cast<uintptr_t>(gpu_tier) | reinterpret_cast<uintptr_t>(host_tier)) & 255u)
+        CG_FAIL(CAPGNN_EINVAL, "cache_build: tiers must be 256-byte aligned");
+    for (int l = 0; l < n_layers; ++l)
+        if (dims[l] <= 0) CG_FAIL(CAPGNN_EINVAL, "cache_build: dims[%d] must be positive", l);
+    {
+        std::vector<int64_t> s(gid, gid + n_halo);
+        std::sort(s.begin(), s.end());
+        if (std::adjacent_find(s.begin(), s.end()) != s.end()) CG_FAIL(CAPGNN_EINVAL, "cache_build: duplicate global id");
+    }
+    capgnn_cache *c = new (std::nothrow) capgnn_cache();
+    if (!c) CG_FAIL(CAPGNN_ENOMEM, "cache_build: out of host memory");
+    auto fail = [&](int rc) { capgnn_cache_destroy(c); return rc; };
+    c->n_halo = n_halo; c->cap_gpu = k; c->n_host = n_halo - k; c->n_layers = n_layers; c->dtype = dtype;
+    c->map_kind = map_kind;
+    c->dims.assign(dims, dims + n_layers);
+    c->gpu_tier = static_cast<char *>(gpu_tier);
+    c->host_tier = static_cast<char *>(host_tier);
+    size_t go = 0, ho = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        c->pitch.push_back(pitch_of(dims[l], dtype));
+        c->gpu_off.push_back(go);
+        c->host_off.push_back(ho);
+        go += align_up(static_cast<size_t>(k) * c->pitch[l], 256);
+        ho += align_up(static_cast<size_t>(c->n_host) * c->pitch[l], 256);
+    }
+    // placement: rank by (priority descending, global id ascending)
+    std::vector<int32_t> rank(n_halo);
+    std::iota(rank.begin(), rank.end(), 0);
+    std::sort(rank.begin(), rank.end(), [&](int32_t a, int32_t b) {
+        if (prio[a] != prio[b]) return prio[a] > prio[b];
+        return gid[a] < gid[b];
+    });
+    std::vector<uint8_t> on_gpu(n_halo, 0);
+    for (int64_t r = 0; r < k; ++r) on_gpu[rank[r]] = 1;
+    c->slot_h.resize(n_halo);
+    c->gid_h.assign(gid, gid + n_halo);
+    std::vector<int32_t> gpu_list, host_list;
+    gpu_list.reserve(k);
+    host_list.reserve(n_halo - k);
+    for (int64_t h = 0; h < n_halo; ++h) {
+        if (on_gpu[h]) { c->slot_h[h] = static_cast<int32_t>(gpu_list.size()); gpu_list.push_back(static_cast<int32_t>(h)); }
+        else { c->slot_h[h] = -1 - static_cast<int32_t>(host_list.size()); host_list.push_back(static_cast<int32_t>(h)); }
+    }
+    if (map_kind == CAPGNN_MAP_HASH) {
+        uint64_t cap = 16;
+        while (cap < static_cast<uint64_t>(n_halo) * 2) cap <<= 1;
+        c->hmask = cap - 1;
+        c->hkeys_h.assign(cap, 0);
+        c->hvals_h.assign(cap, -1);
+        for (int64_t h = 0; h < n_halo; ++h) {
+            uint64_t p = mix64(static_cast<uint64_t>(gid[h])) & c->hmask;
+            while (c->hvals_h[p] >= 0) p = (p + 1) & c->hmask;
+            c->hkeys_h[p] = gid[h];
+            c->hvals_h[p] = static_cast<int32_t>(h);
+        }
+    }
+    int rc;
+    if ((rc = dev_copy(c, c->slot_h, &c->slot_d))) return fail(rc);
+    if ((rc = dev_copy(c, gpu_list, &c->gpu_list_d))) return fail(rc);
+    if ((rc = dev_copy(c, host_list, &c->host_list_d))) return fail(rc);
+    if (map_kind == CAPGNN_MAP_HASH) {
+        if ((rc = dev_copy(c, c->hkeys_h, &c->hkeys_d))) return fail(rc);
+        if ((rc = dev_copy(c, c->hvals_h, &c->hvals_d))) return fail(rc);
+    }
+    std::vector<int64_t> zeros(4, 0);
+    if ((rc = dev_copy(c, zeros, &c->counters_d))) return fail(rc);
+    if (hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
+        set_error("cache_build: hipEventCreate failed");
+        return fail(CAPGNN_EHIP);
+    }
+    c->ev_layer.assign(n_layers, nullptr);
+    for (int l = 0; l < n_layers; ++l)
+        if (hipEventCreateWithFlags(&c->ev_layer[l], hipEventDisableTiming) != hipSuccess) {
+            set_error("cache_build: hipEventCreate failed");
+            return fail(CAPGNN_EHIP);
+        }
+    if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) {
+        set_error("cache_build: stream synchronisation failed");
+        return fail(CAPGNN_EHIP);
+    }
+    *out = c;
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_cache_destroy(capgnn_cache *c) {
+    if (!c) return CAPGNN_OK;
+    for (void *p : c->dev_allocs) (void)hipFree(p);
+    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    for (hipEvent_t e : c->ev_layer) if (e) (void)hipEventDestroy(e);
+    delete c;
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_cache_set_miss_mode(capgnn_cache *c, int mode) {
+    if (!c || (mode != CAPGNN_MISS_ZEROCOPY && mode != CAPGNN_MISS_STAGED)) CG_FAIL(CAPGNN_EINVAL, "cache_set_miss_mode: bad argument");
+    c->miss_mode = mode;
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_cache_fill(capgnn_cache *c, int layer, const void *rows, int64_t ld, void *stream) {
+    if (!c || layer < 0 || layer >= c->n_layers) CG_FAIL(CAPGNN_EINVAL, "cache_fill: bad cache or layer");
+    if (c->n_halo == 0) return CAPGNN_OK;
+    if (!rows || ld < c->dims[layer]) CG_FAIL(CAPGNN_EINVAL, "cache_fill: rows is NULL or ld too small");
+    const int es = elem_bytes(c->dtype);
+    const size_t rb = static_cast<size_t>(c->dims[layer]) * es;
+    const int64_t pitch = c->pitch[layer];
+    const char *src = static_cast<const char *>(rows);
+    std::vector<char> pack(static_cast<size_t>(c->cap_gpu) * pitch, 0);
+    char *host_tab = c->host_tier + c->host_off[layer];
+    for (int64_t h = 0; h < c->n_halo; ++h) {
+        const int32_t s = c->slot_h[h];
+        char *dst = s >= 0 ? pack.data() + static_cast<size_t>(s) * pitch : host_tab + static_cast<size_t>(-1 - s) * pitch;
+        std::memcpy(dst, src + static_cast<size_t>(h) * ld * es, rb);
+        if (static_cast<size_t>(pitch) > rb) std::memset(dst + rb, 0, pitch - rb);
+    }
+    CG_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+    if (c->cap_gpu > 0)
+        CG_HIP(hipMemcpy(c->gpu_tier + c->gpu_off[layer], pack.data(), pack.size(), hipMemcpyHostToDevice));
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_cache_query(const capgnn_cache *c, const int64_t *ids, int64_t n, int by_gid, int8_t *tier,
+                                  int64_t *slot) {
+    if (!c || n < 0 || (n > 0 && (!ids || !tier || !slot))) CG_FAIL(CAPGNN_EINVAL, "cache_query: bad argument");
+    if (by_gid && c->map_kind != CAPGNN_MAP_HASH) CG_FAIL(CAPGNN_EINVAL, "cache_query: by_gid needs a cache built with MAP_HASH");
+    const MapView m = view_host(c);
+    int64_t absent = 0;
+    for (int64_t k = 0; k < n; ++k) {
+        const int64_t h = resolve(m, ids[k], by_gid);
+        if (h < 0) { tier[k] = -1; slot[k] = -1; ++absent; continue; }
+        const int32_t s = c->slot_h[h];
+        tier[k] = s >= 0 ? 0 : 1;
+        slot[k] = s >= 0 ? s : -1 - static_cast<int64_t>(s);
+    }
+    if (absent) CG_FAIL(CAPGNN_ENOTFOUND, "cache_query: %lld ids are in neither tier", (long long)absent);
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_cache_lookup(const capgnn_cache *c, const int64_t *ids, int64_t n, int by_gid, int8_t *tier,
+                                   int64_t *slot, void *stream) {
+    if (!c || n < 0 || (n > 0 && (!ids || !tier || !slot))) CG_FAIL(CAPGNN_EINVAL, "cache_lookup: bad argument");
+    if (by_gid && c->map_kind != CAPGNN_MAP_HASH) CG_FAIL(CAPGNN_EINVAL, "cache_lookup: by_gid needs a cache built with MAP_HASH");
+    if (n == 0) return CAPGNN_OK;
+    hipLaunchKernelGGL(lookup_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), view_dev(c), ids, n, by_gid, tier, slot);
+    CG_HIP(hipGetLastError());
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_halo_gather(capgnn_cache *c, int layer, const int64_t *ids, int64_t n, int by_gid, void *out,
+                                  int64_t ld, void *stream, void *side_stream, void *staging,
+                                  capgnn_gather_stats *stats) {
+    if (!c || layer < 0 || layer >= c->n_layers) CG_FAIL(CAPGNN_EINVAL, "halo_gather: bad cache or layer");
+    if (n < 0) CG_FAIL(CAPGNN_EINVAL, "halo_gather: n < 0");
+    if (by_gid && c->map_kind != CAPGNN_MAP_HASH) CG_FAIL(CAPGNN_EINVAL, "halo_gather: by_gid needs a cache built with MAP_HASH");
+    if (!ids && n != c->n_halo) CG_FAIL(CAPGNN_EINVAL, "halo_gather: ids == NULL needs n == n_halo");
+    if (stats) stats->hits = stats->misses = stats->absent = 0;
+    if (n == 0) return CAPGNN_OK;
+    if (!out) CG_FAIL(CAPGNN_EINVAL, "halo_gather: out is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipStream_t side = side_stream ? static_cast<hipStream_t>(side_stream) : st;
+    const bool forked = side != st;
+
+    if (!ids) {
+        const bool has_miss = c->n_host > 0;
+        if (forked && has_miss) {
+            CG_HIP(hipEventRecord(c->ev_fork, st));
+            CG_HIP(hipStreamWaitEvent(side, c->ev_fork, 0));
+        }
+        if (has_miss) CG_TRY(gather_all_misses(c, layer, out, ld, staging, side));
+        CG_TRY(gather_all_hits(c, layer, out, ld, st));
+        if (forked && has_miss) {
+            CG_HIP(hipEventRecord(c->ev_join, side));
+            CG_HIP(hipStreamWaitEvent(st, c->ev_join, 0));
+        }
+        if (stats) {
+            CG_HIP(hipStreamSynchronize(st));
+            stats->hits = c->cap_gpu;
+            stats->misses = c->n_host;
+        }
+        return CAPGNN_OK;
+    }
+
+    CopyGeom g;
+    const char *gtab = c->gpu_tier + c->gpu_off[layer];
+    const char *htab = c->host_tier + c->host_off[layer];
+    CG_TRY(copy_geom(c, layer, out, ld, gtab, &g));
+    if (!(aligned16(htab))) g.vec16 = 0;
+    unsigned long long *ctr = stats ? reinterpret_cast<unsigned long long *>(c->counters_d) : nullptr;
+    if (ctr) hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, st, ctr);
+    const unsigned blocks = blocks_for(n, g.lpr);
+    const MapView m = view_dev(c);
+    if (forked && c->n_host > 0) {
+        CG_HIP(hipEventRecord(c->ev_fork, st));
+        CG_HIP(hipStreamWaitEvent(side, c->ev_fork, 0));
+        hipLaunchKernelGGL(gather_ids_kernel, dim3(blocks), dim3(256), 0, side, m, ids, n, by_gid, gtab, htab,
+                           c->pitch[layer], 2, static_cast<char *>(out), g.out_pitch, g.row_bytes, g.lpr, g.vec16, g.es, ctr);
+        hipLaunchKernelGGL(gather_ids_kernel, dim3(blocks), dim3(256), 0, st, m, ids, n, by_gid, gtab, htab,
+                           c->pitch[layer], 1, static_cast<char *>(out), g.out_pitch, g.row_bytes, g.lpr, g.vec16, g.es, ctr);
+        CG_HIP(hipEventRecord(c->ev_join, side));
+        CG_HIP(hipStreamWaitEvent(st, c->ev_join, 0));
+    } else {
+        hipLaunchKernelGGL(gather_ids_kernel, dim3(blocks), dim3(256), 0, st, m, ids, n, by_gid, gtab, htab,
+                           c->pitch[layer], 3, static_cast<char *>(out), g.out_pitch, g.row_bytes, g.lpr, g.vec16, g.es, ctr);
+    }
+    CG_HIP(hipGetLastError());
+    if (stats) {
+        unsigned long long h[4] = {0, 0, 0, 0};
+        CG_HIP(hipMemcpyAsync(h, ctr, sizeof(h), hipMemcpyDeviceToHost, st));
+        CG_HIP(hipStreamSynchronize(st));
+        stats->hits = static_cast<int64_t>(h[0]);
+        stats->misses = static_cast<int64_t>(h[1]);
+        stats->absent = static_cast<int64_t>(h[2]);
+        if (h[2]) CG_FAIL(CAPGNN_ENOTFOUND, "halo_gather: %llu ids are in neither tier", h[2]);
+    }
+    return CAPGNN_OK;
+}

@@ -1,0 +1,130 @@
+// Internal declarations shared by the translation units of libcapgnn (HIP, gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdarg.h>
+#include <vector>
+
+#include "../../include/capgnn.h"
+
+namespace capgnn {
+
+void set_error(const char *fmt, ...);
+
+#define CG_FAIL(code, ...)                       \
+    do {                                         \
+        ::capgnn::set_error(__VA_ARGS__);        \
+        return (code);                           \
+    } while (0)
+
+#define CG_HIP(expr)                                                                     \
+    do {                                                                                 \
+        hipError_t e__ = (expr);                                                         \
+        if (e__ != hipSuccess) {                                                         \
+            ::capgnn::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__),  \
+                                __FILE__, __LINE__);                                     \
+            return CAPGNN_EHIP;                                                          \
+        }                                                                                \
+    } while (0)
+
+#define CG_TRY(expr)                 \
+    do {                             \
+        int rc__ = (expr);           \
+        if (rc__ != CAPGNN_OK) return rc__; \
+    } while (0)
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline int elem_bytes(int dtype) { return dtype == CAPGNN_BF16 ? 2 : 4; }
+static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// One direction of the sparse operator: output row k sums over entries [ptr[k], ptr[k+1]).
+struct SpOp {
+    int64_t n_out = 0;          // rows of the output
+    int64_t n_in = 0;           // rows of the gathered operand
+    int64_t nnz = 0;
+    const int64_t *ptr = nullptr;     // device [n_out+1]
+    const int32_t *idx = nullptr;     // device [nnz]   source row of each entry
+    const float *val = nullptr;       // device [nnz] or null
+    const float *out_scale = nullptr; // device [n_out] or null
+    const float *in_scale = nullptr;  // device [n_in]  or null
+    // work lists: output rows ordered by entry count, descending
+    const int32_t *order = nullptr;   // device [n_out]
+    int64_t n_long = 0;               // first n_long entries of `order` have >= LONG_ROW entries
+    int64_t n_sub = 0;                // rows [0, n_sub) of the output restricted list (bwd: local columns only)
+    const int32_t *order_sub = nullptr;
+    int64_t n_long_sub = 0;
+    int64_t max_deg = 0;
+};
+
+constexpr int LONG_ROW = 2048;  // rows at least this long are reduced by a whole workgroup
+
+}  // namespace capgnn
+
+struct capgnn_graph {
+    int64_t n_loc = 0, n_halo = 0, n_cols = 0, nnz = 0;
+    uint32_t flags = 0;
+    capgnn::SpOp fwd, bwd;
+    std::vector<void *> dev_allocs;
+};
+
+struct capgnn_cache {
+    int64_t n_halo = 0, cap_gpu = 0, n_host = 0;
+    int n_layers = 0, dtype = 0, map_kind = 0;
+    std::vector<int32_t> dims;
+    std::vector<int64_t> pitch;         // row pitch in bytes per layer
+    std::vector<size_t> gpu_off, host_off;  // byte offset of each layer's table inside the tiers
+    char *gpu_tier = nullptr;
+    char *host_tier = nullptr;
+    // host copies
+    std::vector<int32_t> slot_h;        // [n_halo]  >=0: GPU slot, <0: host slot = -1-value
+    std::vector<int64_t> gid_h;
+    std::vector<int64_t> hkeys_h;       // hash table keys (gid) ...
+    std::vector<int32_t> hvals_h;       // ... and halo-local index, -1 = empty
+    uint64_t hmask = 0;
+    // device copies
+    int32_t *slot_d = nullptr;
+    int32_t *gpu_list_d = nullptr;      // [cap_gpu]  halo-local index of GPU slot k
+    int32_t *host_list_d = nullptr;     // [n_host]
+    int64_t *hkeys_d = nullptr;
+    int32_t *hvals_d = nullptr;
+    int64_t *counters_d = nullptr;      // [4] hits, misses, absent
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    std::vector<hipEvent_t> ev_layer;   // one per layer: host-tier rows of that layer have landed
+    int miss_mode = CAPGNN_MISS_ZEROCOPY;
+    std::vector<void *> dev_allocs;
+};
+
+namespace capgnn {
+
+// ---- kernels' host-side launchers (each validates what its kernel assumes) ----
+struct SpmmEpilogue {
+    const float *bias = nullptr;   // [F] added after scaling
+    int relu = 0;
+    int accumulate = 0;            // add the previous contents of Y
+    int out_f32 = 0;               // store Y as float although X is bf16
+};
+
+int launch_spmm(const SpOp &op, bool restrict_sub, const void *X, int64_t ldx, void *Y, int64_t ldy, int F,
+                int dtype, const SpmmEpilogue &ep, hipStream_t stream);
+
+int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
+                const void *B, int64_t ldb, void *C, int64_t ldc, int dtype, int out_f32, int accumulate,
+                const float *bias, int relu, const void *relu_mask, int64_t ldm, void *ws, size_t ws_bytes,
+                hipStream_t stream);
+size_t gemm_ws_bytes(int trans_a, int64_t M, int64_t N, int64_t K);
+
+// dZ = dH * 1[H > 0] in place (when relu) and dbias[f] = sum_i dZ[i,f] (when dbias), fixed summation order.
+size_t relu_bias_ws_bytes(int64_t n, int F);
+int launch_relu_mask_dbias(int64_t n, int F, void *dH, int64_t lddh, const void *H, int64_t ldh, int dtype,
+                           int h_dtype, int relu, float *dbias, void *ws, size_t ws_bytes, hipStream_t stream);
+int launch_sgd(float *W, const float *dW, int64_t n, float lr, hipStream_t stream);
+
+uint64_t hash_gid(uint64_t x);
+
+// full-batch gather of one layer's halo rows, one tier at a time (used by the epoch's two-stream schedule)
+int gather_all_hits(const capgnn_cache *c, int layer, void *out, int64_t ld, hipStream_t st);
+int gather_all_misses(const capgnn_cache *c, int layer, void *out, int64_t ld, void *staging, hipStream_t st);
+
+}  // namespace capgnn

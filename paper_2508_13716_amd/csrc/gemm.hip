@@ -1,0 +1,336 @@
+// Dense products on the gfx950 matrix cores: C[M x N] (+)= op(A) op(B), fp32 accumulation.
+//
+// A workgroup of four 64-wide waves (2 x 2) owns a BM x BN tile of C.  Operand tiles of depth
+// BK = 16 are staged through LDS in k-major order (As[k][i], Bs[k][j]) so that the operands of
+// v_mfma_f32_32x32x2_f32 (lane l supplies A[i = l%32][k = l/32] and B[k = l/32][j = l%32]) are read
+// from consecutive LDS words.  Global loads of the next tile are issued before the MFMAs of the
+// current one (register prefetch + two LDS buffers, one barrier per k-step).  bf16 operands are
+// widened to fp32 while they are staged.  The vertex-dimension reduction of the weight gradient
+// (trans_a) is split over workgroups; partial tiles go to the workspace and are summed in a fixed
+// order by a second kernel, which also applies the epilogue.
+#include "common.h"
+
+#include <algorithm>
+
+namespace capgnn {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+struct GemmArgs {
+    int64_t M, N, K;
+    const char *A; int64_t lda;
+    const char *B; int64_t ldb;
+    char *C; int64_t ldc;           // final destination
+    float *part;                    // split partials [S][M][N] or null
+    int64_t k_chunk;                // reduction range per grid.z
+    int a_vec, b_vec;               // operand rows allow 4-element vector loads
+    int out_bf16, accumulate, relu;
+    const float *bias;
+    const char *mask; int64_t ldm; int mask_bf16;
+};
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// four consecutive elements starting at element index `off` of a row; only the first nvalid are read
+template <bool BF16>
+__device__ __forceinline__ float4 load4(const char *base, int64_t off, int nvalid, int vec) {
+    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (nvalid <= 0) return r;
+    if constexpr (BF16) {
+        const uint16_t *p = reinterpret_cast<const uint16_t *>(base) + off;
+        if (vec && nvalid >= 4) {
+            uint2 v = *reinterpret_cast<const uint2 *>(p);
+            r.x = __uint_as_float(v.x << 16); r.y = __uint_as_float(v.x & 0xffff0000u);
+            r.z = __uint_as_float(v.y << 16); r.w = __uint_as_float(v.y & 0xffff0000u);
+        } else {
+            r.x = __uint_as_float(static_cast<uint32_t>(p[0]) << 16);
+            if (nvalid > 1) r.y = __uint_as_float(static_cast<uint32_t>(p[1]) << 16);
+            if (nvalid > 2) r.z = __uint_as_float(static_cast<uint32_t>(p[2]) << 16);
+            if (nvalid > 3) r.w = __uint_as_float(static_cast<uint32_t>(p[3]) << 16);
+        }
+    } else {
+        const float *p = reinterpret_cast<const float *>(base) + off;
+        if (vec && nvalid >= 4) {
+            r = *reinterpret_cast<const float4 *>(p);
+        } else {
+            r.x = p[0];
+            if (nvalid > 1) r.y = p[1];
+            if (nvalid > 2) r.z = p[2];
+            if (nvalid > 3) r.w = p[3];
+        }
+    }
+    return r;
+}
+
+constexpr int BK = 16;
+constexpr int PAD = 4;
+
+// Stages one operand tile.  KC: the operand is stored with the reduction index contiguous
+// (rows = output index); otherwise the output index is contiguous (rows = reduction index).
+template <bool BF16, bool KC, int BT>
+struct TileLoader {
+    static constexpr int NLD = BT * BK / 4 / 256;   // float4 per thread
+    float4 r[NLD];
+
+    __device__ __forceinline__ void fetch(const char *base, int64_t ld, int64_t t0, int64_t T, int64_t k0,
+                                          int64_t k_end, int vec, int tid) {
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const int idx = tid + 256 * q;
+            if constexpr (KC) {
+                const int row = idx >> 2, kq = idx & 3;
+                const int64_t t = t0 + row, k = k0 + 4 * kq;
+                const int nv = (t < T) ? static_cast<int>(k_end - k < 4 ? k_end - k : 4) : 0;
+                r[q] = load4<BF16>(base, t * ld + k, nv, vec);
+            } else {
+                constexpr int QPR = BT / 4;
+                const int kk = idx / QPR, tq = idx % QPR;
+                const int64_t k = k0 + kk, t = t0 + 4 * tq;
+                const int nv = (k < k_end) ? static_cast<int>(T - t < 4 ? T - t : 4) : 0;
+                r[q] = load4<BF16>(base, k * ld + t, nv, vec);
+            }
+        }
+    }
+
+    __device__ __forceinline__ void stash(float (*s)[BT + PAD], int tid) const {
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const int idx = tid + 256 * q;
+            if constexpr (KC) {
+                const int row = idx >> 2, kq = idx & 3;
+                s[4 * kq + 0][row] = r[q].x;
+                s[4 * kq + 1][row] = r[q].y;
+                s[4 * kq + 2][row] = r[q].z;
+                s[4 * kq + 3][row] = r[q].w;
+            } else {
+                constexpr int QPR = BT / 4;
+                const int kk = idx / QPR, tq = idx % QPR;
+                *reinterpret_cast<float4 *>(&s[kk][4 * tq]) = r[q];
+            }
+        }
+    }
+};
+
+template <bool BF16, bool A_KC, bool B_KC, int BM, int BN>
+__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
+    constexpr int WM = BM / 2, WN = BN / 2;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    __shared__ __attribute__((aligned(16))) float As[2][BK][BM + PAD];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BK][BN + PAD];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int64_t m0 = static_cast<int64_t>(blockIdx.y) * BM;
+    const int64_t n0 = static_cast<int64_t>(blockIdx.x) * BN;
+    const int64_t k_begin = static_cast<int64_t>(blockIdx.z) * g.k_chunk;
+    const int64_t k_end = (k_begin + g.k_chunk < g.K) ? k_begin + g.k_chunk : g.K;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    TileLoader<BF16, A_KC, BM> la;
+    TileLoader<BF16, B_KC, BN> lb;
+    const int64_t nk = (k_end > k_begin) ? (k_end - k_begin + BK - 1) / BK : 0;
+    if (nk > 0) {
+        la.fetch(g.A, g.lda, m0, g.M, k_begin, k_end, g.a_vec, tid);
+        lb.fetch(g.B, g.ldb, n0, g.N, k_begin, k_end, g.b_vec, tid);
+        la.stash(As[0], tid);
+        lb.stash(Bs[0], tid);
+    }
+    __syncthreads();
+    for (int64_t kt = 0; kt < nk; ++kt) {
+        const int buf = static_cast<int>(kt & 1);
+        const bool more = kt + 1 < nk;
+        if (more) {
+            la.fetch(g.A, g.lda, m0, g.M, k_begin + (kt + 1) * BK, k_end, g.a_vec, tid);
+            lb.fetch(g.B, g.ldb, n0, g.N, k_begin + (kt + 1) * BK, k_end, g.b_vec, tid);
+        }
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            float a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = As[buf][kk + half][wm * WM + i * 32 + l32];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = Bs[buf][kk + half][wn * WN + j * 32 + l32];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) {
+            la.stash(As[buf ^ 1], tid);
+            lb.stash(Bs[buf ^ 1], tid);
+        }
+        __syncthreads();
+    }
+
+    // D layout of the 32x32 MFMA: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int64_t col = n0 + wn * WN + j * 32 + l32;
+            if (col >= g.N) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (row >= g.M) continue;
+                float v = acc[i][j][r];
+                if (g.part) {
+                    g.part[(static_cast<int64_t>(blockIdx.z) * g.M + row) * g.N + col] = v;
+                    continue;
+                }
+                if (g.accumulate) {
+                    v += g.out_bf16 ? __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t *>(g.C)[row * g.ldc + col]) << 16)
+                                    : reinterpret_cast<const float *>(g.C)[row * g.ldc + col];
+                }
+                if (g.bias) v += g.bias[col];
+                if (g.relu) v = v > 0.f ? v : 0.f;
+                if (g.mask) {
+                    const float mv = g.mask_bf16 ? __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t *>(g.mask)[row * g.ldm + col]) << 16)
+                                                 : reinterpret_cast<const float *>(g.mask)[row * g.ldm + col];
+                    if (!(mv > 0.f)) v = 0.f;
+                }
+                if (g.out_bf16) reinterpret_cast<uint16_t *>(g.C)[row * g.ldc + col] = static_cast<uint16_t>(f32_to_bf16_rne(v));
+                else reinterpret_cast<float *>(g.C)[row * g.ldc + col] = v;
+            }
+        }
+}
+
+// Sums the split partials in order z = 0..S-1 and applies the epilogue.
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmArgs g, int S) {
+    const int64_t total = g.M * g.N;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; t < total;
+         t += static_cast<int64_t>(gridDim.x) * 256) {
+        const int64_t row = t / g.N, col = t % g.N;
+        float v = 0.f;
+        for (int z = 0; z < S; ++z) v += g.part[static_cast<int64_t>(z) * total + t];
+        if (g.accumulate) {
+            v += g.out_bf16 ? __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t *>(g.C)[row * g.ldc + col]) << 16)
+                            : reinterpret_cast<const float *>(g.C)[row * g.ldc + col];
+        }
+        if (g.bias) v += g.bias[col];
+        if (g.relu) v = v > 0.f ? v : 0.f;
+        if (g.mask) {
+            const float mv = g.mask_bf16 ? __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t *>(g.mask)[row * g.ldm + col]) << 16)
+                                         : reinterpret_cast<const float *>(g.mask)[row * g.ldm + col];
+            if (!(mv > 0.f)) v = 0.f;
+        }
+        if (g.out_bf16) reinterpret_cast<uint16_t *>(g.C)[row * g.ldc + col] = static_cast<uint16_t>(f32_to_bf16_rne(v));
+        else reinterpret_cast<float *>(g.C)[row * g.ldc + col] = v;
+    }
+}
+
+static int choose_split(int trans_a, int64_t M, int64_t N, int64_t K, int bm, int bn) {
+    if (!trans_a) return 1;
+    const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+    int64_t s = 1536 / (tiles > 0 ? tiles : 1);
+    const int64_t max_by_k = K / (BK * 16) > 0 ? K / (BK * 16) : 1;   // at least 16 k-steps per split
+    if (s > max_by_k) s = max_by_k;
+    if (s > 512) s = 512;
+    if (s < 1) s = 1;
+    return static_cast<int>(s);
+}
+
+static void tile_for(int64_t N, int *bm, int *bn) {
+    *bm = 128;
+    *bn = (N <= 64) ? 64 : 128;
+}
+
+size_t gemm_ws_bytes(int trans_a, int64_t M, int64_t N, int64_t K) {
+    int bm, bn;
+    tile_for(N, &bm, &bn);
+    const int s = choose_split(trans_a, M, N, K, bm, bn);
+    return s > 1 ? align_up(static_cast<size_t>(s) * M * N * sizeof(float), 256) : 0;
+}
+
+template <bool BF16, bool A_KC, bool B_KC>
+static void launch_tiles(const GemmArgs &g, int bn, dim3 grid, hipStream_t st) {
+    if (bn == 64) hipLaunchKernelGGL((gemm_kernel<BF16, A_KC, B_KC, 128, 64>), grid, dim3(256), 0, st, g);
+    else hipLaunchKernelGGL((gemm_kernel<BF16, A_KC, B_KC, 128, 128>), grid, dim3(256), 0, st, g);
+}
+
+int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
+                const void *B, int64_t ldb, void *C, int64_t ldc, int dtype, int out_f32, int accumulate,
+                const float *bias, int relu, const void *relu_mask, int64_t ldm, void *ws, size_t ws_bytes,
+                hipStream_t stream) {
+    if (dtype != CAPGNN_F32 && dtype != CAPGNN_BF16) CG_FAIL(CAPGNN_EINVAL, "gemm: unknown dtype %d", dtype);
+    if (M < 0 || N < 0 || K < 0) CG_FAIL(CAPGNN_EINVAL, "gemm: negative size");
+    if (M == 0 || N == 0) return CAPGNN_OK;
+    if (!A || !B || !C) CG_FAIL(CAPGNN_EINVAL, "gemm: NULL operand");
+    if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N || (relu_mask && ldm < N))
+        CG_FAIL(CAPGNN_EINVAL, "gemm: leading dimension too small");
+    if (M >= (int64_t(1) << 31) * 64 || N > (1 << 22)) CG_FAIL(CAPGNN_EINVAL, "gemm: size out of range");
+    const int es = elem_bytes(dtype);
+    int bm, bn;
+    tile_for(N, &bm, &bn);
+    const int S = choose_split(trans_a, M, N, K, bm, bn);
+    GemmArgs g;
+    g.M = M; g.N = N; g.K = K;
+    g.A = static_cast<const char *>(A); g.lda = lda;
+    g.B = static_cast<const char *>(B); g.ldb = ldb;
+    g.C = static_cast<char *>(C); g.ldc = ldc;
+    g.part = nullptr;
+    g.k_chunk = K > 0 ? K : 1;
+    const size_t va = 4 * es;   // bytes of one 4-element vector
+    g.a_vec = (reinterpret_cast<uintptr_t>(A) % va == 0) && ((lda * es) % va == 0);
+    g.b_vec = (reinterpret_cast<uintptr_t>(B) % va == 0) && ((ldb * es) % va == 0);
+    g.out_bf16 = (dtype == CAPGNN_BF16 && !out_f32);
+    g.accumulate = accumulate; g.relu = relu; g.bias = bias;
+    g.mask = static_cast<const char *>(relu_mask); g.ldm = ldm; g.mask_bf16 = (dtype == CAPGNN_BF16);
+    if (S > 1) {
+        const size_t need = static_cast<size_t>(S) * M * N * sizeof(float);
+        if (!ws || ws_bytes < need) CG_FAIL(CAPGNN_ENOMEM, "gemm: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+        g.part = static_cast<float *>(ws);
+        const int64_t steps = (K + BK - 1) / BK;
+        g.k_chunk = (steps + S - 1) / S * BK;
+    }
+    const int64_t gy = (M + bm - 1) / bm, gx = (N + bn - 1) / bn;
+    if (gy > 65535) CG_FAIL(CAPGNN_EINVAL, "gemm: M=%lld needs more than 65535 row tiles", (long long)M);
+    dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(S));
+    const bool bf = dtype == CAPGNN_BF16;
+    const bool akc = !trans_a, bkc = trans_b != 0;
+#define CG_GEMM_CASE(BF, AK, BKC_) if (bf == BF && akc == AK && bkc == BKC_) launch_tiles<BF, AK, BKC_>(g, bn, grid, stream);
+    CG_GEMM_CASE(false, true, false) CG_GEMM_CASE(false, true, true)
+    CG_GEMM_CASE(false, false, false) CG_GEMM_CASE(false, false, true)
+    CG_GEMM_CASE(true, true, false) CG_GEMM_CASE(true, true, true)
+    CG_GEMM_CASE(true, false, false) CG_GEMM_CASE(true, false, true)
+#undef CG_GEMM_CASE
+    CG_HIP(hipGetLastError());
+    if (S > 1) {
+        const int64_t total = M * N;
+        const unsigned blocks = static_cast<unsigned>(std::min<int64_t>((total + 255) / 256, 4096));
+        hipLaunchKernelGGL(gemm_reduce_kernel, dim3(blocks), dim3(256), 0, stream, g, S);
+        CG_HIP(hipGetLastError());
+    }
+    return CAPGNN_OK;
+}
+
+}  // namespace capgnn
+
+using namespace capgnn;
+
+extern "C" size_t capgnn_gemm_workspace_bytes(int trans_a, int64_t M, int64_t N, int64_t K) {
+    return gemm_ws_bytes(trans_a, M, N, K);
+}
+
+extern "C" int capgnn_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
+                           const void *B, int64_t ldb, void *C, int64_t ldc, int dtype, int out_f32, int accumulate,
+                           const float *bias, int relu, const void *relu_mask, int64_t ldm, void *ws,
+                           size_t ws_bytes, void *stream) {
+    return launch_gemm(trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, dtype, out_f32, accumulate, bias, relu,
+                       relu_mask, ldm, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}

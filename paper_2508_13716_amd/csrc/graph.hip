@@ -1,0 +1,170 @@
+// Graph handle: validation, CSC construction, degree-ordered work lists, upload.
+#include "common.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <numeric>
+
+namespace capgnn {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+template <typename T>
+static int upload(capgnn_graph *g, const T *host, size_t n, const T **dev_out) {
+    void *d = nullptr;
+    size_t bytes = std::max<size_t>(n, 1) * sizeof(T);
+    if (hipMalloc(&d, bytes) != hipSuccess) CG_FAIL(CAPGNN_ENOMEM, "hipMalloc of %zu bytes failed", bytes);
+    g->dev_allocs.push_back(d);
+    if (n) CG_HIP(hipMemcpy(d, host, n * sizeof(T), hipMemcpyHostToDevice));
+    *dev_out = static_cast<const T *>(d);
+    return CAPGNN_OK;
+}
+
+// Output rows ordered by entry count (descending, ties by index); returns how many are "long".
+static int64_t degree_order(const std::vector<int64_t> &ptr, int64_t lo, int64_t hi, std::vector<int32_t> &order) {
+    order.resize(hi - lo);
+    std::iota(order.begin(), order.end(), static_cast<int32_t>(lo));
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        return (ptr[a + 1] - ptr[a]) > (ptr[b + 1] - ptr[b]);
+    });
+    int64_t n_long = 0;
+    while (n_long < static_cast<int64_t>(order.size()) &&
+           ptr[order[n_long] + 1] - ptr[order[n_long]] >= LONG_ROW)
+        ++n_long;
+    return n_long;
+}
+
+}  // namespace capgnn
+
+using namespace capgnn;
+
+extern "C" const char *capgnn_last_error(void) { return capgnn::g_err; }
+extern "C" int capgnn_version(void) { return 100; }
+
+extern "C" int capgnn_norm_scales(int kind, int64_t n_loc, int64_t n_halo, const int64_t *rowptr,
+                                  const int64_t *halo_degree, float *row_scale, float *col_scale) {
+    if (n_loc < 0 || n_halo < 0 || !rowptr || !row_scale || !col_scale) CG_FAIL(CAPGNN_EINVAL, "norm_scales: bad argument");
+    if (kind == CAPGNN_NORM_SYM) {
+        for (int64_t i = 0; i < n_loc; ++i) {
+            int64_t d = std::max<int64_t>(rowptr[i + 1] - rowptr[i], 1);
+            row_scale[i] = static_cast<float>(1.0 / std::sqrt(static_cast<double>(d)));
+            col_scale[i] = row_scale[i];
+        }
+        for (int64_t h = 0; h < n_halo; ++h) {
+            int64_t d = halo_degree ? std::max<int64_t>(halo_degree[h], 1) : 1;
+            col_scale[n_loc + h] = static_cast<float>(1.0 / std::sqrt(static_cast<double>(d)));
+        }
+    } else if (kind == CAPGNN_NORM_MEAN) {
+        for (int64_t i = 0; i < n_loc; ++i) {
+            int64_t d = rowptr[i + 1] - rowptr[i];
+            row_scale[i] = d > 0 ? static_cast<float>(1.0 / static_cast<double>(d)) : 0.0f;
+        }
+        for (int64_t j = 0; j < n_loc + n_halo; ++j) col_scale[j] = 1.0f;
+    } else {
+        CG_FAIL(CAPGNN_EINVAL, "norm_scales: unknown kind %d", kind);
+    }
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_graph_create(capgnn_graph **out, int64_t n_loc, int64_t n_halo, const int64_t *rowptr,
+                                   const int32_t *col, const float *row_scale, const float *col_scale,
+                                   const float *edge_val, uint32_t flags, void *stream) {
+    if (!out) CG_FAIL(CAPGNN_EINVAL, "graph_create: g is NULL");
+    *out = nullptr;
+    if (n_loc < 0 || n_halo < 0 || !rowptr) CG_FAIL(CAPGNN_EINVAL, "graph_create: bad sizes or NULL rowptr");
+    const int64_t n_cols = n_loc + n_halo;
+    if (n_cols >= (int64_t(1) << 31) - 1) CG_FAIL(CAPGNN_EINVAL, "graph_create: n_loc+n_halo must be < 2^31-1");
+    if (rowptr[0] != 0) CG_FAIL(CAPGNN_EINVAL, "graph_create: rowptr[0] must be 0");
+    for (int64_t i = 0; i < n_loc; ++i)
+        if (rowptr[i + 1] < rowptr[i]) CG_FAIL(CAPGNN_EINVAL, "graph_create: rowptr decreases at row %lld", (long long)i);
+    const int64_t nnz = rowptr[n_loc];
+    if (nnz >= (int64_t(1) << 31) - 1) CG_FAIL(CAPGNN_EINVAL, "graph_create: nnz must be < 2^31-1");
+    if (nnz > 0 && !col) CG_FAIL(CAPGNN_EINVAL, "graph_create: col is NULL");
+    for (int64_t e = 0; e < nnz; ++e)
+        if (col[e] < 0 || col[e] >= n_cols)
+            CG_FAIL(CAPGNN_EINVAL, "graph_create: col[%lld]=%d outside [0,%lld)", (long long)e, col[e], (long long)n_cols);
+    if ((flags & CAPGNN_GRAPH_SYMMETRIC) && n_halo != 0)
+        CG_FAIL(CAPGNN_EINVAL, "graph_create: SYMMETRIC needs n_halo == 0");
+
+    // CSC = CSR of the transpose; entries of one column keep increasing edge order
+    std::vector<int64_t> colptr(n_cols + 1, 0);
+    for (int64_t e = 0; e < nnz; ++e) ++colptr[col[e] + 1];
+    for (int64_t j = 0; j < n_cols; ++j) colptr[j + 1] += colptr[j];
+    std::vector<int32_t> rowidx(std::max<int64_t>(nnz, 1));
+    std::vector<float> cscval(edge_val ? std::max<int64_t>(nnz, 1) : 0);
+    {
+        std::vector<int64_t> cur(colptr.begin(), colptr.end() - 1);
+        for (int64_t i = 0; i < n_loc; ++i)
+            for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+                int64_t p = cur[col[e]]++;
+                rowidx[p] = static_cast<int32_t>(i);
+                if (edge_val) cscval[p] = edge_val[e];
+            }
+    }
+    bool share = false;
+    if (flags & CAPGNN_GRAPH_SYMMETRIC) {
+        bool same = std::equal(colptr.begin(), colptr.end(), rowptr) &&
+                    (nnz == 0 || std::memcmp(rowidx.data(), col, nnz * sizeof(int32_t)) == 0) &&
+                    (!edge_val || std::memcmp(cscval.data(), edge_val, nnz * sizeof(float)) == 0);
+        if (!same) CG_FAIL(CAPGNN_EINVAL, "graph_create: SYMMETRIC flag set but the CSR differs from its transpose");
+        share = true;
+    }
+
+    capgnn_graph *g = new (std::nothrow) capgnn_graph();
+    if (!g) CG_FAIL(CAPGNN_ENOMEM, "graph_create: out of host memory");
+    g->n_loc = n_loc; g->n_halo = n_halo; g->n_cols = n_cols; g->nnz = nnz; g->flags = flags;
+    auto fail = [&](int rc) { capgnn_graph_destroy(g); return rc; };
+
+    std::vector<int64_t> rp(rowptr, rowptr + n_loc + 1);
+    std::vector<int32_t> order_f, order_b, order_bs;
+    int64_t nl_f = degree_order(rp, 0, n_loc, order_f);
+    int rc;
+    SpOp &f = g->fwd;
+    f.n_out = n_loc; f.n_in = n_cols; f.nnz = nnz; f.n_long = nl_f; f.n_sub = n_loc; f.n_long_sub = nl_f;
+    if ((rc = upload(g, rowptr, n_loc + 1, &f.ptr))) return fail(rc);
+    if ((rc = upload(g, col, nnz, &f.idx))) return fail(rc);
+    if (edge_val && (rc = upload(g, edge_val, nnz, &f.val))) return fail(rc);
+    if (row_scale && (rc = upload(g, row_scale, n_loc, &f.out_scale))) return fail(rc);
+    if (col_scale && (rc = upload(g, col_scale, n_cols, &f.in_scale))) return fail(rc);
+    if ((rc = upload(g, order_f.data(), order_f.size(), &f.order))) return fail(rc);
+    f.order_sub = f.order;
+    for (int64_t i = 0; i < n_loc; ++i) f.max_deg = std::max(f.max_deg, rowptr[i + 1] - rowptr[i]);
+
+    SpOp &b = g->bwd;
+    b.n_out = n_cols; b.n_in = n_loc; b.nnz = nnz; b.out_scale = f.in_scale; b.in_scale = f.out_scale;
+    if (share) {
+        b.ptr = f.ptr; b.idx = f.idx; b.val = f.val; b.order = f.order; b.n_long = f.n_long;
+        b.order_sub = f.order; b.n_sub = n_loc; b.n_long_sub = f.n_long; b.max_deg = f.max_deg;
+    } else {
+        b.n_long = degree_order(colptr, 0, n_cols, order_b);
+        b.n_long_sub = degree_order(colptr, 0, n_loc, order_bs);
+        b.n_sub = n_loc;
+        if ((rc = upload(g, colptr.data(), n_cols + 1, &b.ptr))) return fail(rc);
+        if ((rc = upload(g, rowidx.data(), nnz, &b.idx))) return fail(rc);
+        if (edge_val && (rc = upload(g, cscval.data(), nnz, &b.val))) return fail(rc);
+        if ((rc = upload(g, order_b.data(), order_b.size(), &b.order))) return fail(rc);
+        if ((rc = upload(g, order_bs.data(), order_bs.size(), &b.order_sub))) return fail(rc);
+        for (int64_t j = 0; j < n_cols; ++j) b.max_deg = std::max(b.max_deg, colptr[j + 1] - colptr[j]);
+    }
+    if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) {
+        set_error("graph_create: stream synchronisation failed");
+        return fail(CAPGNN_EHIP);
+    }
+    *out = g;
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_graph_destroy(capgnn_graph *g) {
+    if (!g) return CAPGNN_OK;
+    for (void *p : g->dev_allocs) (void)hipFree(p);
+    delete g;
+    return CAPGNN_OK;
+}

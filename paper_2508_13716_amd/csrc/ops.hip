@@ -1,0 +1,225 @@
+// Small VALU kernels around the layer: sigma' masking + bias gradient, softmax cross-entropy, SGD step.
+#include "common.h"
+
+#include <algorithm>
+
+namespace capgnn {
+
+__device__ __forceinline__ float ld_elem(const char *p, int64_t i, int bf16) {
+    return bf16 ? __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t *>(p)[i]) << 16)
+                : reinterpret_cast<const float *>(p)[i];
+}
+
+__device__ __forceinline__ void st_elem(char *p, int64_t i, float v, int bf16) {
+    if (bf16) {
+        uint32_t u = __float_as_uint(v);
+        if ((u & 0x7fffffffu) > 0x7f800000u) u = (u >> 16) | 0x40u;
+        else u = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+        reinterpret_cast<uint16_t *>(p)[i] = static_cast<uint16_t>(u);
+    } else {
+        reinterpret_cast<float *>(p)[i] = v;
+    }
+}
+
+// ------------------------------------------------------------------ dZ = dH * 1[H>0], dbias partials
+constexpr int RB_ROWS = 128;   // rows per workgroup
+
+// blockDim = (TX, 256/TX): threadIdx.x walks the feature columns, threadIdx.y the rows of the chunk.
+__global__ __launch_bounds__(256) void relu_mask_dbias_kernel(int64_t n, int F, char *dH, int64_t lddh, const char *H,
+                                                              int64_t ldh, int bf16, int h_bf16, int relu, float *partial) {
+    __shared__ float red[256];
+    const int tx = threadIdx.x, ty = threadIdx.y, TX = blockDim.x, TY = blockDim.y;
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * RB_ROWS;
+    const int64_t r1 = r0 + RB_ROWS < n ? r0 + RB_ROWS : n;
+    for (int f0 = 0; f0 < F; f0 += TX) {
+        const int f = f0 + tx;
+        float s = 0.f;
+        if (f < F) {
+            for (int64_t r = r0 + ty; r < r1; r += TY) {
+                float g = ld_elem(dH, r * lddh + f, bf16);
+                if (relu) {
+                    const float h = ld_elem(H, r * ldh + f, h_bf16);
+                    if (!(h > 0.f)) {
+                        g = 0.f;
+                        if (bf16) reinterpret_cast<uint16_t *>(dH)[r * lddh + f] = 0;
+                        else reinterpret_cast<float *>(dH)[r * lddh + f] = 0.f;
+                    }
+                }
+                s += g;
+            }
+        }
+        if (partial) {
+            red[ty * TX + tx] = s;
+            __syncthreads();
+            if (ty == 0 && f < F) {
+                float t = 0.f;
+                for (int y = 0; y < TY; ++y) t += red[y * TX + tx];
+                partial[static_cast<int64_t>(blockIdx.x) * F + f] = t;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void dbias_final_kernel(int64_t nblocks, int F, const float *partial, float *dbias) {
+    const int f = blockIdx.x * 256 + threadIdx.x;
+    if (f >= F) return;
+    double s = 0.0;
+    for (int64_t b = 0; b < nblocks; ++b) s += static_cast<double>(partial[b * F + f]);
+    dbias[f] = static_cast<float>(s);
+}
+
+size_t relu_bias_ws_bytes(int64_t n, int F) {
+    const int64_t nb = (n + RB_ROWS - 1) / RB_ROWS;
+    return align_up(static_cast<size_t>(std::max<int64_t>(nb, 1)) * F * sizeof(float), 256);
+}
+
+int launch_relu_mask_dbias(int64_t n, int F, void *dH, int64_t lddh, const void *H, int64_t ldh, int dtype,
+                           int h_dtype, int relu, float *dbias, void *ws, size_t ws_bytes, hipStream_t stream) {
+    if (F <= 0) return CAPGNN_OK;
+    if (n <= 0) {   // no rows: the bias gradient is zero (summing zero partial blocks)
+        if (dbias) {
+            hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 255) / 256), dim3(256), 0, stream, int64_t(0), F,
+                               static_cast<const float *>(nullptr), dbias);
+            CG_HIP(hipGetLastError());
+        }
+        return CAPGNN_OK;
+    }
+    if (!relu && !dbias) return CAPGNN_OK;
+    if (!dH || (relu && !H)) CG_FAIL(CAPGNN_EINVAL, "relu_mask_dbias: NULL operand");
+    if (lddh < F || (relu && ldh < F)) CG_FAIL(CAPGNN_EINVAL, "relu_mask_dbias: leading dimension smaller than F");
+    const int64_t nb = (n + RB_ROWS - 1) / RB_ROWS;
+    if (dbias && (!ws || ws_bytes < static_cast<size_t>(nb) * F * sizeof(float)))
+        CG_FAIL(CAPGNN_ENOMEM, "relu_mask_dbias: workspace too small");
+    int TX = 1;
+    while (TX < F && TX < 256) TX <<= 1;
+    dim3 block(TX, 256 / TX);
+    hipLaunchKernelGGL(relu_mask_dbias_kernel, dim3(static_cast<unsigned>(nb)), block, 0, stream, n, F,
+                       static_cast<char *>(dH), lddh, static_cast<const char *>(H), ldh, dtype == CAPGNN_BF16 ? 1 : 0,
+                       h_dtype == CAPGNN_BF16 ? 1 : 0, relu, dbias ? static_cast<float *>(ws) : nullptr);
+    CG_HIP(hipGetLastError());
+    if (dbias) {
+        hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 255) / 256), dim3(256), 0, stream, nb, F,
+                           static_cast<const float *>(ws), dbias);
+        CG_HIP(hipGetLastError());
+    }
+    return CAPGNN_OK;
+}
+
+// ------------------------------------------------------------------ SGD
+__global__ __launch_bounds__(256) void sgd_kernel(float *W, const float *dW, int64_t n, float lr) {
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < n;
+         i += static_cast<int64_t>(gridDim.x) * 256)
+        W[i] = W[i] - lr * dW[i];
+}
+
+int launch_sgd(float *W, const float *dW, int64_t n, float lr, hipStream_t stream) {
+    if (n <= 0) return CAPGNN_OK;
+    if (!W || !dW) CG_FAIL(CAPGNN_EINVAL, "sgd: NULL operand");
+    const unsigned blocks = static_cast<unsigned>(std::min<int64_t>((n + 255) / 256, 2048));
+    hipLaunchKernelGGL(sgd_kernel, dim3(blocks), dim3(256), 0, stream, W, dW, n, lr);
+    CG_HIP(hipGetLastError());
+    return CAPGNN_OK;
+}
+
+// ------------------------------------------------------------------ masked softmax cross-entropy
+// scratch layout: [0] = normaliser (float), [64 ..] = per-row loss terms
+__global__ __launch_bounds__(1024) void count_mask_kernel(int64_t n, const uint8_t *mask, float *norm_out) {
+    __shared__ unsigned long long red[1024];
+    unsigned long long c = 0;
+    for (int64_t i = threadIdx.x; i < n; i += 1024) c += mask[i] ? 1 : 0;
+    red[threadIdx.x] = c;
+    __syncthreads();
+    for (int s = 512; s > 0; s >>= 1) {
+        if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) norm_out[0] = red[0] > 0 ? static_cast<float>(red[0]) : 1.f;
+}
+
+// one wave per row; lanes stride over the classes
+__global__ __launch_bounds__(256) void softmax_ce_kernel(int64_t n, int C, const float *Z, int64_t ldz,
+                                                         const int32_t *labels, const uint8_t *mask, float norm_val,
+                                                         const float *norm_dev, float *row_loss, char *dZ,
+                                                         int64_t lddz, int dz_bf16) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (row >= n) return;
+    const float norm = norm_dev ? norm_dev[0] : norm_val;
+    const bool on = !mask || mask[row];
+    if (!on) {
+        if (lane == 0) row_loss[row] = 0.f;
+        if (dZ) for (int k = lane; k < C; k += 64) st_elem(dZ, row * lddz + k, 0.f, dz_bf16);
+        return;
+    }
+    const float *z = Z + row * ldz;
+    float m = -INFINITY;
+    for (int k = lane; k < C; k += 64) m = fmaxf(m, z[k]);
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    float s = 0.f;
+    for (int k = lane; k < C; k += 64) s += expf(z[k] - m);
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    const float lse = m + logf(s);
+    int y = labels[row];
+    y = y < 0 ? 0 : (y >= C ? C - 1 : y);
+    if (lane == 0) row_loss[row] = lse - z[y];
+    if (dZ) {
+        const float inv = 1.f / norm;
+        for (int k = lane; k < C; k += 64) {
+            float p = expf(z[k] - lse);
+            st_elem(dZ, row * lddz + k, (p - (k == y ? 1.f : 0.f)) * inv, dz_bf16);
+        }
+    }
+}
+
+__global__ __launch_bounds__(1024) void loss_reduce_kernel(int64_t n, const float *row_loss, float norm_val,
+                                                           const float *norm_dev, float *loss_out) {
+    __shared__ double red[1024];
+    double c = 0.0;
+    for (int64_t i = threadIdx.x; i < n; i += 1024) c += static_cast<double>(row_loss[i]);
+    red[threadIdx.x] = c;
+    __syncthreads();
+    for (int s = 512; s > 0; s >>= 1) {
+        if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const double norm = norm_dev ? static_cast<double>(norm_dev[0]) : static_cast<double>(norm_val);
+        loss_out[0] = static_cast<float>(red[0] / norm);
+    }
+}
+
+}  // namespace capgnn
+
+using namespace capgnn;
+
+extern "C" size_t capgnn_loss_workspace_bytes(int64_t n) {
+    return align_up(256 + static_cast<size_t>(n > 0 ? n : 1) * sizeof(float), 256);
+}
+
+extern "C" int capgnn_softmax_ce(int64_t n, int C, const float *Z, int64_t ldz, const int32_t *labels,
+                                 const uint8_t *mask, double loss_norm, float *loss_dev, void *dZ, int64_t lddz,
+                                 int dz_dtype, void *ws, size_t ws_bytes, void *stream) {
+    if (dz_dtype != CAPGNN_F32 && dz_dtype != CAPGNN_BF16) CG_FAIL(CAPGNN_EINVAL, "softmax_ce: unknown dz_dtype");
+    if (n < 0 || C <= 0) CG_FAIL(CAPGNN_EINVAL, "softmax_ce: bad sizes");
+    if (n == 0) return CAPGNN_OK;
+    if (!Z || !labels || !loss_dev) CG_FAIL(CAPGNN_EINVAL, "softmax_ce: NULL operand");
+    if (ldz < C || (dZ && lddz < C)) CG_FAIL(CAPGNN_EINVAL, "softmax_ce: leading dimension smaller than C");
+    if (!ws || ws_bytes < capgnn_loss_workspace_bytes(n)) CG_FAIL(CAPGNN_ENOMEM, "softmax_ce: workspace too small");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *norm_dev = nullptr;
+    float norm_val = 1.f;
+    float *scratch = static_cast<float *>(ws);
+    if (loss_norm > 0.0) norm_val = static_cast<float>(loss_norm);
+    else if (!mask) norm_val = static_cast<float>(n);
+    else {
+        norm_dev = scratch;
+        hipLaunchKernelGGL(count_mask_kernel, dim3(1), dim3(1024), 0, st, n, mask, norm_dev);
+    }
+    float *row_loss = scratch + 64;
+    hipLaunchKernelGGL(softmax_ce_kernel, dim3(static_cast<unsigned>((n + 3) / 4)), dim3(256), 0, st, n, C, Z, ldz,
+                       labels, mask, norm_val, norm_dev, row_loss, static_cast<char *>(dZ), lddz, dz_dtype == CAPGNN_BF16 ? 1 : 0);
+    hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, st, n, row_loss, norm_val, norm_dev, loss_dev);
+    CG_HIP(hipGetLastError());
+    return CAPGNN_OK;
+}

@@ -1,0 +1,157 @@
+"""Layer and epoch parity of the HIP library against the CPU oracle (needs an MI355X)."""
+import numpy as np
+import pytest
+
+from paper_2508_13716_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def env(orc):
+    import torch
+    from paper_2508_13716_amd import binding as B, harness as H
+    from tests import oracle_side as O
+    assert torch.cuda.is_available()
+    B.lib()
+    return dict(torch=torch, B=B, H=H, O=O, orc=orc)
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def compare_epoch(env, prob, dp, ref, loss, tol, tag):
+    O = env["O"]
+    got = dp.results()
+    errs = {"logits": O.normwise(got["logits"], ref["logits"])}
+    for l in range(dp.L):
+        errs[f"dW{l}"] = O.normwise(got["dW"][l], ref["dW"][l])
+        errs[f"db{l}"] = O.normwise(got["db"][l], ref["db"][l])
+        if ref["dW_self"][l] is not None:
+            errs[f"dWs{l}"] = O.normwise(got["dW_self"][l], ref["dW_self"][l])
+    errs["loss"] = abs(loss - ref["loss"]) / max(1.0, abs(ref["loss"]))
+    say(f"{tag}: " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()))
+    bad = {k: v for k, v in errs.items() if not (v <= tol)}
+    assert not bad, (tag, bad)
+
+
+@pytest.mark.parametrize("orders", ["auto", "agg", "xform"])
+@pytest.mark.parametrize("miss_mode", [0, 1])
+def test_epoch_config1_matches_oracle(env, orders, miss_mode):
+    B, H, O = env["B"], env["H"], env["O"]
+    import copy
+    cfg = copy.deepcopy(synth.CONFIGS["C1"])
+    cfg.cache_frac = 0.4 if miss_mode else 1.0        # config 1 proper caches every halo row on the GPU
+    prob = H.make_problem(cfg, mask_frac=0.5)
+    ords = None if orders == "auto" else [B.AGG_FIRST if orders == "agg" else B.XFORM_FIRST] * 2
+    dp = H.DeviceProblem(prob, orders=ords, miss_mode=miss_mode)
+    ref = O.oracle_epoch(prob)
+    for rep in range(2):                                # second run: buffers are reused, result unchanged
+        loss, _ = dp.run_epoch()
+        compare_epoch(env, prob, dp, ref, loss, TOL["f32"], f"C1 {orders} miss_mode={miss_mode} rep={rep}")
+    dp.close()
+
+
+@pytest.mark.parametrize("name,scale", [("C2", 0.02), ("C3", 0.01), ("C4", 0.002), ("C5", 0.004)])
+def test_epoch_scaled_configs_match_oracle(env, name, scale):
+    B, H, O = env["B"], env["H"], env["O"]
+    cfg = synth.CONFIGS[name].scaled(scale)
+    prob = H.make_problem(cfg, mask_frac=0.5)
+    say(f"{cfg.name}: n_loc={prob.part.n_loc} n_halo={prob.part.n_halo} nnz={prob.part.nnz} dims={cfg.dims} {cfg.dtype}")
+    dp = H.DeviceProblem(prob)
+    say(f"orders={dp.resolved_orders()}")
+    ref = O.oracle_epoch(prob)
+    loss, times = dp.run_epoch(want_times=True)
+    compare_epoch(env, prob, dp, ref, loss, TOL[cfg.dtype], cfg.name)
+    assert times["total_ms"] > 0 and times["aggregation_ms"] > 0 and len(times["records"]) >= 2 * dp.L
+    # without a side stream the result is the same
+    dp2 = H.DeviceProblem(prob, use_side_stream=False, orders=[B.XFORM_FIRST if l % 2 else B.AGG_FIRST for l in range(dp.L)])
+    loss2, _ = dp2.run_epoch()
+    compare_epoch(env, prob, dp2, ref, loss2, TOL[cfg.dtype], cfg.name + " single-stream, mixed orders")
+    dp.close()
+    dp2.close()
+
+
+@pytest.mark.parametrize("kind", ["gcn", "sage"])
+@pytest.mark.parametrize("order", ["agg", "xform"])
+def test_layer_fwd_bwd_with_halo_gradient(env, kind, order):
+    torch, B, H, O, orc = env["torch"], env["B"], env["H"], env["O"], env["orc"]
+    part = synth.make_partition("layer", 900, 700, 12000, seed=41, max_deg=2500, self_loops=(kind == "gcn"))
+    fi, fo = 50, 36
+    rng = np.random.default_rng(7)
+    X = rng.standard_normal((part.n_cols, fi)).astype(np.float32)
+    W = (rng.standard_normal((fi, fo)) * 0.2).astype(np.float32)
+    Ws = (rng.standard_normal((fi, fo)) * 0.2).astype(np.float32) if kind == "sage" else None
+    b = rng.standard_normal(fo).astype(np.float32)
+    dH = rng.standard_normal((part.n_loc, fo)).astype(np.float32)
+    og = O.oracle_graph(part, kind)
+    ol = orc.Layer(kind, W.astype(np.float64), b.astype(np.float64), "relu", None if Ws is None else Ws.astype(np.float64))
+    Href, saved = orc.layer_fwd(og, ol, X.astype(np.float64))
+    bref = orc.layer_bwd(og, ol, X.astype(np.float64), saved, dH.astype(np.float64), need_dx=True)
+
+    r, c = B.norm_scales(B.NORM_SYM if kind == "gcn" else B.NORM_MEAN, part.n_loc, part.n_halo, part.rowptr, part.halo_degree)
+    g = B.Graph(part.n_loc, part.n_halo, part.rowptr, part.col, r, c)
+    Wd, Wsd, bd = H.np_to_dev(W), (None if Ws is None else H.np_to_dev(Ws)), H.np_to_dev(b)
+    ly = B.make_layer(B.GCN if kind == "gcn" else B.SAGE_MEAN, fi, fo, B.ACT_RELU, B.F32, Wd, Wsd, bd,
+                      B.AGG_FIRST if order == "agg" else B.XFORM_FIRST)
+    ldx, ldh = 52, 36
+    Xd = H.padded_matrix(X, ldx)
+    Hd = torch.zeros((part.n_loc, ldh), device="cuda")
+    saved_d = torch.empty(max(B.layer_saved_bytes(g, ly), 256), dtype=torch.uint8, device="cuda")
+    wsb = B.layer_workspace_bytes(g, ly)
+    ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+    B.layer_fwd(g, ly, Xd, ldx, Hd, ldh, saved_d, ws, wsb)
+    torch.cuda.synchronize()
+    assert O.normwise(Hd.cpu().numpy(), Href) <= TOL["f32"]
+    for need_halo in (True, False):
+        dHd = H.np_to_dev(dH)
+        dW, dWs, db = torch.zeros_like(Wd), (None if Ws is None else torch.zeros_like(Wd)), torch.zeros_like(bd)
+        rows = part.n_cols if need_halo else part.n_loc
+        dX = torch.full((rows, ldx), 5.0, device="cuda")
+        B.layer_bwd(g, ly, Xd, ldx, Hd, ldh, saved_d, dHd, fo, dW, dWs, db, dX, ldx, need_halo, ws, wsb)
+        torch.cuda.synchronize()
+        say(f"layer {kind} {order} need_halo={need_halo}")
+        assert O.normwise(dW.cpu().numpy(), bref["dW"]) <= TOL["f32"]
+        assert O.normwise(db.cpu().numpy(), bref["db"]) <= TOL["f32"]
+        if Ws is not None:
+            assert O.normwise(dWs.cpu().numpy(), bref["dW_self"]) <= TOL["f32"]
+        got = dX.cpu().numpy()
+        assert O.normwise(got[:, :fi], bref["dX"][:rows]) <= TOL["f32"]
+        assert (got[:, fi:] == 5.0).all()
+    g.close()
+
+
+def test_epoch_sgd_step_and_no_halo(env):
+    """Partition without halo vertices (cache is NULL) and the in-place W <- W - lr dW update."""
+    torch, B, H, O = env["torch"], env["B"], env["H"], env["O"]
+    cfg = synth.Config("nohalo", "gcn", 3000, 0, 30000, [40, 32, 5], "f32", 0.0, max_deg=400, symmetric=True, seed=77)
+    prob = H.make_problem(cfg, mask_frac=0.7)
+    dp = H.DeviceProblem(prob)
+    ref = O.oracle_epoch(prob, lr=0.05)
+    loss, _ = dp.run_epoch(lr=0.05)
+    compare_epoch(env, prob, dp, ref, loss, TOL["f32"], "no-halo symmetric")
+    torch.cuda.synchronize()
+    for l in range(dp.L):
+        assert O.normwise(H.dev_to_np(dp.W[l]), ref["new_W"][l]) <= TOL["f32"]
+        assert O.normwise(H.dev_to_np(dp.bias[l]), ref["new_bias"][l]) <= TOL["f32"]
+    dp.close()
+
+
+def test_epoch_rejects_bad_arguments(env):
+    torch, B, H = env["torch"], env["B"], env["H"]
+    import copy
+    cfg = copy.deepcopy(synth.CONFIGS["C1"]).scaled(0.1)
+    prob = H.make_problem(cfg)
+    dp = H.DeviceProblem(prob)
+    with pytest.raises(B.CapgnnError) as e:       # workspace too small
+        B.epoch(dp.graph, dp.cache, dp.layers, dp.X0, dp.ld0, dp.labels, dp.mask, 0.0, dp.logits, dp.dW, None,
+                dp.dbias, 0.0, dp.ws, 1024, dp.stream, dp.side)
+    assert e.value.code == B.ENOMEM
+    with pytest.raises(B.CapgnnError) as e:       # halo vertices but no cache
+        B.epoch(dp.graph, None, dp.layers, dp.X0, dp.ld0, dp.labels, dp.mask, 0.0, dp.logits, dp.dW, None,
+                dp.dbias, 0.0, dp.ws, dp.ws_bytes, dp.stream, dp.side)
+    assert e.value.code == B.EINVAL
+    dp.close()
