@@ -289,6 +289,12 @@ int capgnn_epoch(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer *lay
                  float *loss_out, capgnn_epoch_times *times,
                  void *ws, size_t ws_bytes, void *stream, void *side_stream);
 
+/* Where capgnn_epoch leaves the output of hidden layer l (0 <= l < L-1) inside ws: *ptr = device
+ * address of H_l ([n_loc x *ld] of the layers' dtype), valid until ws is reused.  Same arguments as
+ * capgnn_epoch_workspace_bytes; no GPU work.  For callers that want the embeddings, and for tests. */
+int capgnn_epoch_activation(const capgnn_graph *g, const capgnn_cache *c, const capgnn_layer *layers, int L,
+                            int l, void *ws, void **ptr, int64_t *ld);
+
 #ifdef __cplusplus
 }
 #endif

@@ -222,11 +222,20 @@ def layer_fwd(g: Graph, l: Layer, X):
     return H, {"M": M, "Z": Z}
 
 
-def layer_bwd(g: Graph, l: Layer, X, saved, dH, need_dx: bool = True):
-    """Chain rule of layer_fwd.  Returns dict(dW, dW_self, db, dX) with dX over all n_cols rows."""
+def layer_bwd(g: Graph, l: Layer, X, saved, dH, need_dx: bool = True, relu_on=None):
+    """Chain rule of layer_fwd.  Returns dict(dW, dW_self, db, dX) with dX over all n_cols rows.
+
+    relu_on: optional boolean [n_loc, f_out] that replaces the decision 1[Z > 0].  The decision is an
+    integer taken from a floating-point value; a caller comparing against an fp32 implementation passes
+    that implementation's decisions for the elements whose Z is zero within fp32 rounding, so that both
+    sides differentiate the same piecewise-linear function."""
     X = _f64(X)
     dH = _f64(dH)
-    dZ = dH * (saved["Z"] > 0.0) if l.act == "relu" else dH      # sigma'(0) = 0
+    if l.act == "relu":
+        on = (saved["Z"] > 0.0) if relu_on is None else np.asarray(relu_on, bool)   # sigma'(0) = 0
+        dZ = dH * on
+    else:
+        dZ = dH
     out = {"db": dZ.sum(axis=0), "dW": matmul(saved["M"], dZ, ta=True), "dW_self": None, "dX": None}
     if l.kind == "sage":
         out["dW_self"] = matmul(X[: g.n_loc], dZ, ta=True)
@@ -240,11 +249,13 @@ def layer_bwd(g: Graph, l: Layer, X, saved, dH, need_dx: bool = True):
 
 
 def epoch(g: Graph, layers: List[Layer], X0_local, halo_tables: Sequence[Optional[np.ndarray]],
-          labels, mask=None, loss_norm: float = 0.0, lr: float = 0.0, halo_grad: bool = False):
+          labels, mask=None, loss_norm: float = 0.0, lr: float = 0.0, halo_grad: bool = False,
+          relu_on: Optional[Sequence] = None):
     """One full-batch forward + backward over the partition.
 
     halo_tables[l] is the logical [n_halo, f_in(l)] cache table feeding layer l (None when the
-    partition has no halo).  Returns dict(loss, logits, dW, dW_self, db, dX_halo, new_W ...).
+    partition has no halo).  relu_on[l], when given, overrides layer l's backward decision 1[Z > 0]
+    (see layer_bwd).  Returns dict(loss, logits, dW, dW_self, db, dX_halo, hidden, new_W ...).
     """
     n_halo = g.n_cols - g.n_loc
     ids = np.arange(n_halo, dtype=np.int64)
@@ -266,7 +277,8 @@ def epoch(g: Graph, layers: List[Layer], X0_local, halo_tables: Sequence[Optiona
            "db": [None] * len(layers), "dX_halo": [None] * len(layers), "hidden": [s["Z"] for s in saves]}
     for li in range(len(layers) - 1, -1, -1):
         need_dx = li > 0 or halo_grad
-        b = layer_bwd(g, layers[li], Xs[li], saves[li], dH, need_dx=need_dx)
+        b = layer_bwd(g, layers[li], Xs[li], saves[li], dH, need_dx=need_dx,
+                      relu_on=None if relu_on is None else relu_on[li])
         res["dW"][li], res["dW_self"][li], res["db"][li] = b["dW"], b["dW_self"], b["db"]
         if b["dX"] is not None:
             res["dX_halo"][li] = b["dX"][g.n_loc:]

@@ -93,6 +93,7 @@ SIGNATURES = {
     "capgnn_loss_workspace_bytes": (_sz, [_i64]),
     "capgnn_softmax_ce": (_i32, [_i64, _i32, _vp, _i64, _vp, _vp, C.c_double, _vp, _vp, _i64, _i32, _vp, _sz, _vp]),
     "capgnn_epoch_workspace_bytes": (_sz, [_vp, _vp, C.POINTER(Layer), _i32]),
+    "capgnn_epoch_activation": (_i32, [_vp, _vp, C.POINTER(Layer), _i32, _i32, _vp, C.POINTER(_vp), C.POINTER(_i64)]),
     "capgnn_epoch": (_i32, [_vp, _vp, C.POINTER(Layer), _i32, _vp, _i64, _vp, _vp, C.c_double, _vp, C.POINTER(_vp),
                             C.POINTER(_vp), C.POINTER(_vp), C.c_float, C.POINTER(C.c_float), C.POINTER(EpochTimes),
                             _vp, _sz, _vp, _vp]),
@@ -332,6 +333,15 @@ def softmax_ce(n: int, n_classes: int, Z, ldz: int, labels, mask, loss_norm: flo
 def epoch_workspace_bytes(g: Graph, c: Optional[Cache], layers: List[Layer]) -> int:
     arr = (Layer * len(layers))(*layers)
     return int(lib().capgnn_epoch_workspace_bytes(g.h, c.h if c is not None else None, arr, len(layers)))
+
+
+def epoch_activation(g: Graph, c: Optional[Cache], layers: List[Layer], l: int, ws):
+    """(device address, leading dimension) of hidden layer l's output inside the epoch workspace."""
+    arr = (Layer * len(layers))(*layers)
+    ptr, ld = C.c_void_p(), C.c_int64()
+    _check(lib().capgnn_epoch_activation(g.h, c.h if c is not None else None, arr, len(layers), l, _p(ws),
+                                         C.byref(ptr), C.byref(ld)))
+    return int(ptr.value), int(ld.value)
 
 
 def epoch(g: Graph, c: Optional[Cache], layers: List[Layer], X0, ld0: int, labels, mask, loss_norm: float, logits,

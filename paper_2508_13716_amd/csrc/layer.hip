@@ -146,7 +146,7 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
                           const void *H, int64_t ldh, const void *saved, void *dH, int64_t lddh, float *dW,
                           float *dW_self, float *dbias, void *dX, int64_t lddx, int need_halo_grad, void *ws,
                           size_t ws_bytes, hipStream_t st) {
-    const int dt = l->dtype, es = elem_bytes(dt);
+    const int dt = l->dtype;
     const bool sage = l->kind == CAPGNN_SAGE_MEAN;
     const int relu = l->act == CAPGNN_ACT_RELU;
     if (!X || !dH || (relu && !H)) CG_FAIL(CAPGNN_EINVAL, "layer_bwd: NULL operand");
@@ -332,6 +332,17 @@ extern "C" size_t capgnn_epoch_workspace_bytes(const capgnn_graph *g, const capg
     // ld0 does not enter the plan's sizes (layer 0 reads the caller's buffer)
     plan_epoch(g, c, layers, L, layers[0].f_in, &p);
     return p.total;
+}
+
+extern "C" int capgnn_epoch_activation(const capgnn_graph *g, const capgnn_cache *c, const capgnn_layer *layers, int L,
+                                       int l, void *ws, void **ptr, int64_t *ld) {
+    CG_TRY(check_epoch_args(g, c, layers, L));
+    if (l < 0 || l >= L - 1 || !ws || !ptr || !ld) CG_FAIL(CAPGNN_EINVAL, "epoch_activation: bad argument (hidden layers are 0..L-2)");
+    EpochPlan p;
+    plan_epoch(g, c, layers, L, layers[0].f_in, &p);
+    *ptr = static_cast<char *>(ws) + p.x_off[l + 1];
+    *ld = p.ldx[l + 1];
+    return CAPGNN_OK;
 }
 
 extern "C" int capgnn_epoch(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer *layers, int L, void *X0,

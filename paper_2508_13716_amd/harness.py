@@ -143,6 +143,16 @@ class DeviceProblem:
                        self.dW_self if any(t is not None for t in self.dW_self) else None, self.dbias, lr,
                        self.ws, self.ws_bytes, self.stream, self.side, want_loss=want_loss, want_times=want_times)
 
+    def hidden(self, l: int) -> np.ndarray:
+        """Output of hidden layer l after the last epoch, [n_loc, f_out(l)] (bf16 as uint16 bits)."""
+        torch = _torch()
+        torch.cuda.synchronize()
+        ptr, ld = B.epoch_activation(self.graph, self.cache, self.layers, l, self.ws)
+        off = ptr - self.ws.data_ptr()
+        n_loc, f = self.prob.part.n_loc, self.prob.model[l].f_out
+        raw = self.ws[off: off + n_loc * ld * self.es].view(self.tdtype).view(n_loc, ld)
+        return dev_to_np(raw[:, :f].contiguous())
+
     def results(self) -> Dict:
         _torch().cuda.synchronize()
         return {"logits": dev_to_np(self.logits),
