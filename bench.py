@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the partition-local epoch (halo gather from the two-tier cache + GCN/SAGE forward and
+backward) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2]
+
+A step is one full epoch over one synthetic partition: for every layer the halo rows are gathered from
+the GPU tier (device copy) and the pinned-host tier (side stream), then the layer runs; loss; backward.
+All inputs that the method keeps on the device are resident in HBM before the timed region; the host
+tier is in pinned host memory because that is where the method keeps it.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+FP32_MATRIX_PEAK_TFLOPS = 157.3
+
+
+def spmm_launches(cfg, part, orders):
+    """(layer, backward) -> (F, n_out, n_in_touched) of every SpMM launch of one epoch."""
+    import numpy as np
+    L = len(cfg.dims) - 1
+    touched_fwd = int(np.unique(part.col).size)                 # source rows that any edge reads
+    touched_bwd = int((np.diff(part.rowptr) > 0).sum())
+    out = {}
+    for l in range(L):
+        fi, fo = cfg.dims[l], cfg.dims[l + 1]
+        agg = orders[l] == 1
+        out[(l, 0)] = (fi if agg else fo, part.n_loc, touched_fwd)
+        if agg:
+            if l > 0:                                            # dX = A_hat^T dM over the local columns
+                out[(l, 1)] = (fi, part.n_loc, touched_bwd)
+        else:                                                    # dT = A_hat^T dZ over all columns
+            out[(l, 1)] = (fo, part.n_cols, touched_bwd)
+    return out
+
+
+def spmm_min_bytes(part, F, n_out, n_in_touched, es):
+    """Compulsory traffic of one SpMM launch: every index once, every needed source row once, every
+    output row once (nnz*4 + (n_out+1)*8 + touched*F*s + n_out*F*s)."""
+    return part.nnz * 4 + (n_out + 1) * 8 + n_in_touched * F * es + n_out * F * es
+
+
+def cpu_baseline(cfg, scale, full_prob):
+    """The oracle as it stands, timed on the host cores: on the same partition when scale >= 1, else on a
+    scaled-down partition of the same shape (same average degree, widths and cache fraction)."""
+    from oracle import oracle as orc
+    from paper_2508_13716_amd import harness as H
+    from tests import oracle_side as O
+    prob = full_prob if scale >= 1.0 else H.make_problem(cfg.scaled(scale))
+    t0 = time.perf_counter()
+    ref = O.oracle_epoch(prob)
+    dt = time.perf_counter() - t0
+    return prob, ref, dt, orc.max_threads()
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="C2")
+    ap.add_argument("--miss-mode", type=int, default=None, help="0 zero-copy kernel, 1 staged DMA (default: library default)")
+    ap.add_argument("--orders", default=None, help="comma list of 1 (aggregate first) / 2 (transform first) per layer")
+    ap.add_argument("--cpu-scale", type=float, default=None,
+                    help="share of the workload the oracle is timed on (0 = skip; default: sized for 10-30 s of CPU work)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs the partition-local step on ONE GPU; --gpus > 1 is not part of it "
+              "(no collectives, no sharding across GPUs).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2508_13716_amd import binding as B, harness as H, synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    B.lib()
+
+    cfg = synth.CONFIGS[args.config]
+    t_gen = time.perf_counter()
+    prob = H.make_problem(cfg)
+    part = prob.part
+    t_gen = time.perf_counter() - t_gen
+    orders = [int(x) for x in args.orders.split(",")] if args.orders else None
+    dp = H.DeviceProblem(prob, orders=orders, miss_mode=B.MISS_ZEROCOPY if args.miss_mode is None else args.miss_mode)
+    res_orders = dp.resolved_orders()
+    es = dp.es
+
+    for _ in range(args.warmup):
+        dp.run_epoch()
+    torch.cuda.synchronize()
+    acc = {}
+    stage = {}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        loss, times = dp.run_epoch(want_times=True)
+        for r in times["records"]:
+            acc.setdefault((r["kind"], r["layer"], r["backward"]), []).append(r["ms"])
+        for k in ("pick_cache_ms", "communication_ms", "aggregation_ms", "combine_ms", "loss_ms", "other_ms", "total_ms"):
+            stage[k] = stage.get(k, 0.0) + times[k] / args.steps
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    launches = spmm_launches(cfg, part, res_orders)
+    # the method's own count: one aggregation per layer forward, one transposed aggregation per layer
+    # backward except the first layer (whose input needs no gradient) - whatever association is run
+    n_agg = 2 * dp.L - 1
+    edges_per_epoch = part.nnz * n_agg
+    kernels = []
+    for (kind, layer, bwd), v in sorted(acc.items(), key=lambda kv: -sum(kv[1])):
+        # a record may cover more than one launch of the same kind (e.g. the GEMMs of one layer)
+        kernels.append({"kind": kind, "layer": layer, "backward": bwd, "ms": float(np.mean(v))})
+    spmm_recs = [k for k in kernels if k["kind"] in ("spmm_fwd", "spmm_bwd")]
+    dom = spmm_recs[0] if spmm_recs else kernels[0]
+    F, n_out, touched = launches[(dom["layer"], dom["backward"])]
+    bmin = spmm_min_bytes(part, F, n_out, touched, es)
+    bgather = part.nnz * (4 + F * es) + n_out * F * es
+    achieved = bmin / (dom["ms"] * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            tj = json.load(open(tpath))
+            traffic = tj.get(f"{cfg.name}:{dom['kind']}:L{dom['layer']}:F{F}")
+        except Exception:
+            traffic = None
+    spmm_ms = sum(k["ms"] for k in spmm_recs)
+    hit_bytes = sum(2 * dp.cache.cap_gpu * cfg.dims[l] * es for l in range(dp.L)) if dp.cache else 0
+    miss_bytes = sum((part.n_halo - dp.cache.cap_gpu) * cfg.dims[l] * es for l in range(dp.L)) if dp.cache else 0
+    hit_ms = sum(k["ms"] for k in kernels if k["kind"] == "gather_hit")
+    miss_ms = sum(k["ms"] for k in kernels if k["kind"] == "gather_miss")
+
+    out = {
+        "metric": "aggregation GEdges/s + achieved HBM GB/s; partition epoch ms (fwd+bwd)",
+        "value": edges_per_epoch / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GEdges/s (edges aggregated per epoch / epoch wall time)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if cfg.dtype == "f32" else "bf16 storage, f32 accumulate", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {part.n_loc} local + {part.n_halo} halo vertices, {part.nnz} edges, "
+                               f"{cfg.kind} dims {cfg.dims}, GPU tier {dp.cache.cap_gpu if dp.cache else 0} halo rows",
+                   "orders": ["agg_first" if o == 1 else "xform_first" for o in res_orders],
+                   "spmm_launches_per_epoch": len(launches), "loss": loss},
+        "epoch_ms_device": stage.get("total_ms"),
+        "stages_ms": {k: round(v, 4) for k, v in stage.items()},
+        "aggregation_gedges_s_kernel_only": part.nnz * len(launches) / (spmm_ms * 1e-3) / 1e9 if spmm_ms else None,
+        "gather": {"hit_GBps": hit_bytes / (hit_ms * 1e-3) / 1e9 if hit_ms else None, "hit_bytes": hit_bytes,
+                   "miss_host_link_GBps": miss_bytes / (miss_ms * 1e-3) / 1e9 if miss_ms else None,
+                   "miss_bytes": miss_bytes},
+        "kernels": kernels[:12],
+        "roofline": {"kernel": f"{dom['kind']} layer {dom['layer']} F={F}", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "algorithmic_bytes": bmin, "gathered_bytes_no_reuse": bgather,
+                     "gather_rate_GBps": bgather / (dom["ms"] * 1e-3) / 1e9, "ms": dom["ms"],
+                     "gedges_s": part.nnz / (dom["ms"] * 1e-3) / 1e9},
+    }
+    if args.cpu_scale is None:
+        # the oracle moves about 3 GFLOP-equivalents per second per 16 cores on this kind of epoch
+        est_full_s = part.nnz * sum(cfg.dims[:-1]) * 2 * 2 / 3.0e9 / 8
+        args.cpu_scale = 1.0 if est_full_s <= 30 else max(0.02, 20.0 / est_full_s)
+    if args.cpu_scale > 0:
+        sprob, _, dt, cores = cpu_baseline(cfg, args.cpu_scale, prob)
+        s_edges = sprob.part.nnz * n_agg
+        out["cpu_baseline"] = {"value": s_edges / dt / 1e9, "unit": "GEdges/s (edges aggregated per epoch / epoch wall time)",
+                               "cores": cores, "kind": "oracle",
+                               "sample": f"{cfg.name} at {min(args.cpu_scale, 1.0):g} of its vertices and edges "
+                                         f"({sprob.part.n_loc} local, {sprob.part.n_halo} halo, {sprob.part.nnz} edges; same "
+                                         f"average degree and widths), one full fp64 oracle epoch, {dt:.2f} s",
+                               "epoch_s_on_sample": dt}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

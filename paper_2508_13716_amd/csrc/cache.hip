@@ -94,10 +94,12 @@ __global__ __launch_bounds__(256) void scatter_tier_kernel(const char *table, in
                                                            int64_t n, char *out, int64_t out_pitch, int row_bytes,
                                                            int lpr, int vec16, int es) {
     const int lane = threadIdx.x & 63;
-    const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    const int64_t k = wave * (64 / lpr) + lane / lpr;
-    if (k >= n) return;
-    copy_row(table + k * pitch, out + static_cast<int64_t>(dst_list[k]) * out_pitch, row_bytes, lane % lpr, lpr, vec16, es);
+    const int rows_per_wave = 64 / lpr;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * 4 * rows_per_wave;
+    int64_t k = (static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6)) * rows_per_wave + lane / lpr;
+    for (; k < n; k += stride)
+        copy_row(table + k * pitch, out + static_cast<int64_t>(dst_list[k]) * out_pitch, row_bytes, lane % lpr, lpr,
+                 vec16, es);
 }
 
 // request-list gather with lookup; which: bit0 = serve GPU-tier rows (and absent ids), bit1 = serve host-tier rows
@@ -172,6 +174,8 @@ static MapView view_host(const capgnn_cache *c) {
     return m;
 }
 
+constexpr unsigned HOST_READ_BLOCKS = 128;
+
 static unsigned blocks_for(int64_t n, int lpr) {
     const int64_t rows_per_block = 4 * (64 / lpr);
     return static_cast<unsigned>((n + rows_per_block - 1) / rows_per_block);
@@ -201,7 +205,11 @@ int gather_all_misses(const capgnn_cache *c, int layer, void *out, int64_t ld, v
     }
     CopyGeom g;
     CG_TRY(copy_geom(c, layer, out, ld, tab, &g));
-    hipLaunchKernelGGL(scatter_tier_kernel, dim3(blocks_for(c->n_host, g.lpr)), dim3(256), 0, st, tab, c->pitch[layer],
+    // A kernel that reads pinned memory is bound by the host link, not by the CUs: a small grid keeps enough
+    // requests in flight and leaves the compute units to the kernels of the main stream.
+    unsigned blocks = blocks_for(c->n_host, g.lpr);
+    if (!staging && blocks > HOST_READ_BLOCKS) blocks = HOST_READ_BLOCKS;
+    hipLaunchKernelGGL(scatter_tier_kernel, dim3(blocks), dim3(256), 0, st, tab, c->pitch[layer],
                        c->host_list_d, c->n_host, static_cast<char *>(out), g.out_pitch, g.row_bytes, g.lpr, g.vec16, g.es);
     CG_HIP(hipGetLastError());
     return CAPGNN_OK;
