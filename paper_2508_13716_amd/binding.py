@@ -188,12 +188,16 @@ def graph_create(*a, **k) -> Graph:
     return Graph(*a, **k)
 
 
-def spmm_fwd(g: Graph, X, ldx: int, Y, ldy: int, F: int, dtype: int, stream=None):
-    _check(lib().capgnn_spmm_fwd(g.h, _p(X), ldx, _p(Y), ldy, F, dtype, None, 0, _stream(stream)))
+def spmm_workspace_bytes(g: Graph, F: int, dtype: int) -> int:
+    return int(lib().capgnn_spmm_workspace_bytes(g.h, F, dtype))
 
 
-def spmm_bwd(g: Graph, dY, lddy: int, dX, lddx: int, F: int, dtype: int, stream=None):
-    _check(lib().capgnn_spmm_bwd(g.h, _p(dY), lddy, _p(dX), lddx, F, dtype, None, 0, _stream(stream)))
+def spmm_fwd(g: Graph, X, ldx: int, Y, ldy: int, F: int, dtype: int, stream=None, ws=None, ws_bytes: int = 0):
+    _check(lib().capgnn_spmm_fwd(g.h, _p(X), ldx, _p(Y), ldy, F, dtype, _p(ws), ws_bytes, _stream(stream)))
+
+
+def spmm_bwd(g: Graph, dY, lddy: int, dX, lddx: int, F: int, dtype: int, stream=None, ws=None, ws_bytes: int = 0):
+    _check(lib().capgnn_spmm_bwd(g.h, _p(dY), lddy, _p(dX), lddx, F, dtype, _p(ws), ws_bytes, _stream(stream)))
 
 
 # --------------------------------------------------------------------------- cache

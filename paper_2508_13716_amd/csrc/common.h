@@ -56,9 +56,23 @@ struct SpOp {
     const int32_t *order_sub = nullptr;
     int64_t n_long_sub = 0;
     int64_t max_deg = 0;
+    // Column-blocked copy of the entries (built for dense-degree operators whose gathered operand does not
+    // fit an L2): entries regrouped by (source block cb = idx / CB_ROWS, position p in `order`), original
+    // entry order kept inside a group.  Group (cb, p) = entries [b_off[cb*n_out+p], b_off[cb*n_out+p+1]).
+    int ncb = 0;                      // 0: no blocked copy
+    const uint32_t *b_off = nullptr;  // device [ncb*n_out + 1]
+    const int2 *b_ew = nullptr;       // device [nnz]  {source row, bits of the float weight val * in_scale[source]}
+    // positions [0, b_long) hold rows whose groups are long enough for a whole workgroup, [b_long, b_mid) for
+    // one wave per group, the rest are walked eight rows per wave (`order` is descending in entry count)
+    int64_t b_long = 0, b_mid = 0;
 };
 
 constexpr int LONG_ROW = 2048;  // rows at least this long are reduced by a whole workgroup
+constexpr int CB_ROWS = 16384;  // source rows per column block: 16384 x 128-byte slices = 2 MB, half an XCD's L2
+constexpr int B_LONG_GROUP = 512; // rows with at least this many entries per source block on average: workgroup per group
+constexpr int B_MID_GROUP = 128;  // ... at least this many: wave per group
+constexpr int SLICE_BYTES = 128;  // feature bytes of one source row that one task of the blocked kernel gathers
+constexpr int NUM_XCD = 8;        // L2 domains of the chip; workgroup b is dispatched to domain b % NUM_XCD
 
 }  // namespace capgnn
 
@@ -104,7 +118,11 @@ struct SpmmEpilogue {
     int relu = 0;
     int accumulate = 0;            // add the previous contents of Y
     int out_f32 = 0;               // store Y as float although X is bf16
+    void *ws = nullptr;            // scratch for the column-blocked kernel (spmm_ws_bytes), may be null
+    size_t ws_bytes = 0;
 };
+
+size_t spmm_ws_bytes(const SpOp &op, int F, int dtype);
 
 int launch_spmm(const SpOp &op, bool restrict_sub, const void *X, int64_t ldx, void *Y, int64_t ldy, int F,
                 int dtype, const SpmmEpilogue &ep, hipStream_t stream);

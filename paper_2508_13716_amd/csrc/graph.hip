@@ -42,6 +42,60 @@ static int64_t degree_order(const std::vector<int64_t> &ptr, int64_t lo, int64_t
     return n_long;
 }
 
+// Column-blocked copy of one direction of the operator (see SpOp).  Worth building only when the gathered
+// operand spans several blocks and a (block, row) group holds enough entries to amortise its overhead.
+struct BlockedHost {
+    int ncb = 0;
+    int64_t n_long = 0, n_mid = 0;
+    std::vector<uint32_t> off;
+    std::vector<int2> ew;
+};
+
+static int32_t float_bits(float f) {
+    int32_t b;
+    std::memcpy(&b, &f, sizeof(b));
+    return b;
+}
+
+static bool build_blocked(const int64_t *ptr, const int32_t *idx, const float *val, const float *in_scale,
+                          const std::vector<int32_t> &order, int64_t n_out, int64_t n_in, BlockedHost *out) {
+    const int64_t ncb = (n_in + CB_ROWS - 1) / CB_ROWS;
+    const int64_t nnz = ptr[n_out];
+    if (ncb < 2 || n_out == 0 || nnz / (n_out * ncb) < 16 || n_out * ncb >= (int64_t(1) << 28)) return false;
+    const size_t groups = static_cast<size_t>(ncb) * n_out;
+    out->ncb = static_cast<int>(ncb);
+    out->off.assign(groups + 1, 0u);
+    for (int64_t p = 0; p < n_out; ++p) {
+        const int64_t r = order[p];
+        for (int64_t e = ptr[r]; e < ptr[r + 1]; ++e) ++out->off[static_cast<size_t>(idx[e] / CB_ROWS) * n_out + p + 1];
+    }
+    for (size_t t = 0; t < groups; ++t) out->off[t + 1] += out->off[t];
+    out->ew.resize(nnz);
+    while (out->n_long < n_out && ptr[order[out->n_long] + 1] - ptr[order[out->n_long]] >= B_LONG_GROUP * ncb) ++out->n_long;
+    out->n_mid = out->n_long;
+    while (out->n_mid < n_out && ptr[order[out->n_mid] + 1] - ptr[order[out->n_mid]] >= B_MID_GROUP * ncb) ++out->n_mid;
+    std::vector<uint32_t> cur(out->off.begin(), out->off.end() - 1);
+    for (int64_t p = 0; p < n_out; ++p) {
+        const int64_t r = order[p];
+        for (int64_t e = ptr[r]; e < ptr[r + 1]; ++e) {
+            const uint32_t q = cur[static_cast<size_t>(idx[e] / CB_ROWS) * n_out + p]++;
+            float wt = in_scale ? in_scale[idx[e]] : 1.f;     // same fp32 product the unblocked kernel forms
+            if (val) wt *= val[e];
+            out->ew[q] = make_int2(idx[e], float_bits(wt));
+        }
+    }
+    return true;
+}
+
+static int upload_blocked(capgnn_graph *g, const BlockedHost &bh, SpOp *op) {
+    CG_TRY(upload(g, bh.off.data(), bh.off.size(), &op->b_off));
+    CG_TRY(upload(g, bh.ew.data(), bh.ew.size(), &op->b_ew));
+    op->ncb = bh.ncb;
+    op->b_long = bh.n_long;
+    op->b_mid = bh.n_mid;
+    return CAPGNN_OK;
+}
+
 }  // namespace capgnn
 
 using namespace capgnn;
@@ -137,12 +191,26 @@ extern "C" int capgnn_graph_create(capgnn_graph **out, int64_t n_loc, int64_t n_
     if ((rc = upload(g, order_f.data(), order_f.size(), &f.order))) return fail(rc);
     f.order_sub = f.order;
     for (int64_t i = 0; i < n_loc; ++i) f.max_deg = std::max(f.max_deg, rowptr[i + 1] - rowptr[i]);
+    BlockedHost bh_f;
+    if (build_blocked(rowptr, col, edge_val, col_scale, order_f, n_loc, n_cols, &bh_f) && (rc = upload_blocked(g, bh_f, &f)))
+        return fail(rc);
 
     SpOp &b = g->bwd;
     b.n_out = n_cols; b.n_in = n_loc; b.nnz = nnz; b.out_scale = f.in_scale; b.in_scale = f.out_scale;
     if (share) {
         b.ptr = f.ptr; b.idx = f.idx; b.val = f.val; b.order = f.order; b.n_long = f.n_long;
         b.order_sub = f.order; b.n_sub = n_loc; b.n_long_sub = f.n_long; b.max_deg = f.max_deg;
+        b.ncb = f.ncb; b.b_off = f.b_off; b.b_ew = f.b_ew; b.b_long = f.b_long; b.b_mid = f.b_mid;
+        const bool same_scales = (!row_scale && !col_scale) ||
+                                 (row_scale && col_scale && std::memcmp(row_scale, col_scale, n_loc * sizeof(float)) == 0);
+        if (f.ncb && !same_scales) {   // the transposed product weighs an entry by the other side's scale
+            if (edge_val) {
+                b.ncb = 0;             // rare combination: the transposed product takes the unblocked kernel
+            } else {
+                for (int64_t q = 0; q < nnz; ++q) bh_f.ew[q].y = float_bits(row_scale ? row_scale[bh_f.ew[q].x] : 1.f);
+                if ((rc = upload(g, bh_f.ew.data(), bh_f.ew.size(), &b.b_ew))) return fail(rc);
+            }
+        }
     } else {
         b.n_long = degree_order(colptr, 0, n_cols, order_b);
         b.n_long_sub = degree_order(colptr, 0, n_loc, order_bs);
@@ -153,6 +221,10 @@ extern "C" int capgnn_graph_create(capgnn_graph **out, int64_t n_loc, int64_t n_
         if ((rc = upload(g, order_b.data(), order_b.size(), &b.order))) return fail(rc);
         if ((rc = upload(g, order_bs.data(), order_bs.size(), &b.order_sub))) return fail(rc);
         for (int64_t j = 0; j < n_cols; ++j) b.max_deg = std::max(b.max_deg, colptr[j + 1] - colptr[j]);
+        BlockedHost bh;
+        if (build_blocked(colptr.data(), rowidx.data(), edge_val ? cscval.data() : nullptr, row_scale, order_b, n_cols,
+                          n_loc, &bh) && (rc = upload_blocked(g, bh, &b)))
+            return fail(rc);
     }
     if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) {
         set_error("graph_create: stream synchronisation failed");

@@ -85,9 +85,14 @@ static size_t saved_bytes(const capgnn_graph *g, const capgnn_layer *l, int orde
     return align_up(static_cast<size_t>(g->n_loc) * pad_ld(l->f_in, l->dtype) * elem_bytes(l->dtype), 256);
 }
 
-static size_t fwd_ws_bytes(const capgnn_graph *g, const capgnn_layer *l, int order) {
+// forward scratch: [transformed features T (XFORM_FIRST)] [scratch of the aggregation kernel]
+static size_t fwd_t_bytes(const capgnn_graph *g, const capgnn_layer *l, int order) {
     if (order == CAPGNN_AGG_FIRST) return 0;
     return align_up(static_cast<size_t>(g->n_cols) * pad_ld(l->f_out, l->dtype) * elem_bytes(l->dtype), 256);
+}
+
+static size_t fwd_ws_bytes(const capgnn_graph *g, const capgnn_layer *l, int order) {
+    return fwd_t_bytes(g, l, order) + spmm_ws_bytes(g->fwd, order == CAPGNN_AGG_FIRST ? l->f_in : l->f_out, l->dtype);
 }
 
 static size_t bwd_ws_bytes(const capgnn_graph *g, const capgnn_layer *l, int order) {
@@ -97,6 +102,7 @@ static size_t bwd_ws_bytes(const capgnn_graph *g, const capgnn_layer *l, int ord
     b += std::max(gemm_ws_bytes(1, l->f_in, l->f_out, red_rows), gemm_ws_bytes(1, l->f_in, l->f_out, g->n_loc));
     if (order == CAPGNN_AGG_FIRST) b += align_up(static_cast<size_t>(g->n_loc) * pad_ld(l->f_in, l->dtype) * es, 256);
     else b += align_up(static_cast<size_t>(g->n_cols) * pad_ld(l->f_out, l->dtype) * es, 256);
+    b += spmm_ws_bytes(g->bwd, order == CAPGNN_AGG_FIRST ? l->f_in : l->f_out, l->dtype);
     return b;
 }
 
@@ -112,7 +118,9 @@ static int layer_fwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
         const int64_t ldm = pad_ld(l->f_in, dt);
         {
             Scope s(CAPGNN_K_SPMM_FWD, li, 0, st);
-            CG_TRY(launch_spmm(g->fwd, false, X, ldx, saved, ldm, l->f_in, dt, SpmmEpilogue(), st));
+            SpmmEpilogue ep;
+            ep.ws = ws; ep.ws_bytes = ws ? ws_bytes : 0;
+            CG_TRY(launch_spmm(g->fwd, false, X, ldx, saved, ldm, l->f_in, dt, ep, st));
         }
         Scope s(CAPGNN_K_GEMM, li, 0, st);
         if (sage) {
@@ -125,8 +133,9 @@ static int layer_fwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
     }
     // XFORM_FIRST
     const int64_t ldt = pad_ld(l->f_out, dt);
-    const size_t need = static_cast<size_t>(g->n_cols) * ldt * es;
+    const size_t need = fwd_ws_bytes(g, l, order);
     if (!ws || ws_bytes < need) CG_FAIL(CAPGNN_ENOMEM, "layer_fwd: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+    (void)es;
     {
         Scope s(CAPGNN_K_GEMM, li, 0, st);
         CG_TRY(launch_gemm(0, 0, g->n_cols, l->f_out, l->f_in, X, ldx, l->W, l->f_out, ws, ldt, dt, 0, 0, nullptr, 0,
@@ -138,6 +147,8 @@ static int layer_fwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
     Scope s(CAPGNN_K_SPMM_FWD, li, 0, st);
     SpmmEpilogue ep;
     ep.bias = l->bias; ep.relu = relu; ep.accumulate = sage ? 1 : 0; ep.out_f32 = l->out_f32;
+    ep.ws = static_cast<char *>(ws) + fwd_t_bytes(g, l, order);
+    ep.ws_bytes = ws_bytes - fwd_t_bytes(g, l, order);
     CG_TRY(launch_spmm(g->fwd, false, ws, ldt, H, ldh, l->f_out, dt, ep, st));
     return CAPGNN_OK;
 }
@@ -162,6 +173,11 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
     void *ws_gemm = w;
     w += gw;
     void *tmp = w;   // dM (AGG_FIRST) or dT (XFORM_FIRST)
+    w += order == CAPGNN_AGG_FIRST ? align_up(static_cast<size_t>(g->n_loc) * pad_ld(l->f_in, dt) * elem_bytes(dt), 256)
+                                   : align_up(static_cast<size_t>(g->n_cols) * pad_ld(l->f_out, dt) * elem_bytes(dt), 256);
+    SpmmEpilogue sp_ep;   // scratch of the transposed aggregation
+    sp_ep.ws = w;
+    sp_ep.ws_bytes = ws_bytes - static_cast<size_t>(w - static_cast<char *>(ws));
 
     {   // dZ = dH * sigma'(Z) in place; dbias = column sums of dZ
         Scope s(CAPGNN_K_ELEMENTWISE, li, 1, st);
@@ -184,7 +200,7 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
         if (dX) {
             {
                 Scope s(CAPGNN_K_SPMM_BWD, li, 1, st);
-                CG_TRY(launch_spmm(g->bwd, !need_halo_grad, tmp, ldm, dX, lddx, l->f_in, dt, SpmmEpilogue(), st));
+                CG_TRY(launch_spmm(g->bwd, !need_halo_grad, tmp, ldm, dX, lddx, l->f_in, dt, sp_ep, st));
             }
             if (sage) {
                 Scope s(CAPGNN_K_GEMM, li, 1, st);
@@ -199,7 +215,7 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
     if (dW || dX) {
         Scope s(CAPGNN_K_SPMM_BWD, li, 1, st);
         const bool sub = !dW && !need_halo_grad;
-        CG_TRY(launch_spmm(g->bwd, sub, dH, lddh, tmp, ldt, l->f_out, dt, SpmmEpilogue(), st));
+        CG_TRY(launch_spmm(g->bwd, sub, dH, lddh, tmp, ldt, l->f_out, dt, sp_ep, st));
     }
     Scope s(CAPGNN_K_GEMM, li, 1, st);
     if (dW) CG_TRY(launch_gemm(1, 0, l->f_in, l->f_out, g->n_cols, X, ldx, tmp, ldt, dW, l->f_out, dt, 1, 0, nullptr, 0,

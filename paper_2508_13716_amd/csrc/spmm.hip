@@ -10,6 +10,8 @@
 // combined through LDS in a fixed order, so results are reproducible run to run.
 #include "common.h"
 
+#include <algorithm>
+
 namespace capgnn {
 
 struct SpmmArgs {
@@ -256,6 +258,324 @@ __global__ __launch_bounds__(256) void spmm_kernel(SpmmArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Column-blocked variant for dense-degree operators whose gathered matrix is larger than an L2.
+//
+// A task is (source block cb, output position p, feature slice s): it sums the entries of row order[p] whose
+// source lies in block cb, over one SLICE_BYTES-wide slice of the feature row, and stores the partial row to
+// scratch.  The grid is laid out so that the workgroups running on one L2 domain at any moment share (cb, s):
+// their gathers then address CB_ROWS * SLICE_BYTES = 2 MB, which that L2 holds.  Workgroup b runs on domain
+// b % NUM_XCD; the slices (times H interleaved shares of the rows when there are fewer slices than domains)
+// are dealt to the domains, and each domain sweeps its units block by block.  Within a (unit, block) phase the
+// positions come heaviest first in three classes: a whole workgroup per task, a wave per task, and eight
+// tasks per wave (one per 8-lane group).  A second kernel sums the partials of a row over the blocks in a
+// fixed order and applies the epilogue.
+struct SpmmBlockedArgs {
+    const uint32_t *off;         // [ncb*n_out + 1]
+    const int2 *ew;              // [nnz] {source row, weight bits}
+    int64_t n_out, n_long, n_mid;
+    int ncb, H;                  // source blocks, row shares per slice
+    int64_t RG_long, RG_mid, RG; // workgroups per (unit, block): long class, medium class, all
+    const char *X;
+    uint32_t ld16;               // row pitch of X in 16-byte units
+    int F_lim;
+    float *part;                 // [ncb*n_out][ldp] partial rows
+    int64_t ldp;
+};
+
+constexpr int B_LPR = SLICE_BYTES / 16;      // lanes that cover one slice with 16-byte loads
+constexpr int B_GROUPS = 64 / B_LPR;         // entries (or rows) a wave works on at the same time
+constexpr int B_MID_PER_WAVE = 4;            // consecutive medium positions one wave handles
+constexpr int B_SHORT_PER_GROUP = 2;         // consecutive short positions one lane group handles
+constexpr int B_MID_PER_WG = 4 * B_MID_PER_WAVE;
+constexpr int B_SHORT_PER_WG = 4 * B_GROUPS * B_SHORT_PER_GROUP;
+static_assert(B_LPR == 8, "lane-group shuffles below assume 8-lane groups");
+
+// value of `v` in lane k of the caller's 8-lane group (ds_swizzle, bit-mask mode: lane = (lane & 0x18) | k)
+__device__ __forceinline__ int group_bcast(int v, int k) {
+    switch (k) {
+        case 0: return __builtin_amdgcn_ds_swizzle(v, 0x0018);
+        case 1: return __builtin_amdgcn_ds_swizzle(v, 0x0038);
+        case 2: return __builtin_amdgcn_ds_swizzle(v, 0x0058);
+        case 3: return __builtin_amdgcn_ds_swizzle(v, 0x0078);
+        case 4: return __builtin_amdgcn_ds_swizzle(v, 0x0098);
+        case 5: return __builtin_amdgcn_ds_swizzle(v, 0x00b8);
+        case 6: return __builtin_amdgcn_ds_swizzle(v, 0x00d8);
+        default: return __builtin_amdgcn_ds_swizzle(v, 0x00f8);
+    }
+}
+
+// All 64 lanes work on ONE row: entries [e0, e1) are read 64 at a time (coalesced), lane group g then takes
+// entries g, g+8, ... of the chunk, so up to eight 16-byte-per-lane feature loads are in flight per wave.
+// On return every lane of group g holds the sum over that group's entries; the caller adds the groups.
+template <bool BF16, int E>
+__device__ __forceinline__ void blocked_row_accumulate(const SpmmBlockedArgs &b, uint32_t e0, uint32_t e1, int lane,
+                                                       const char *xbase, bool ok, float (&acc)[E]) {
+    const int grp = lane / B_LPR;
+    int2 pr = make_int2(0, 0);
+    if (e0 + lane < e1) pr = b.ew[e0 + lane];
+    for (uint32_t c0 = e0; c0 < e1; c0 += 64) {
+        const int coff = static_cast<int>(__umul24(static_cast<uint32_t>(pr.x), b.ld16));   // 16-byte units
+        const int wbits = pr.y;                                                               // 0 beyond the end
+        pr = make_int2(0, 0);
+        if (c0 + 64 + lane < e1) pr = b.ew[c0 + 64 + lane];      // next chunk's entries are on their way early
+        const int cnt = static_cast<int>(e1 - c0 < 64u ? e1 - c0 : 64u);
+        float xk[B_GROUPS][E], wk[B_GROUPS];
+#pragma unroll
+        for (int k = 0; k < B_GROUPS; ++k) {
+            if (k * B_GROUPS < cnt) {      // wave-uniform
+                const int src = k * B_GROUPS + grp;
+                const uint32_t ck = static_cast<uint32_t>(__shfl(coff, src));
+                wk[k] = __int_as_float(__shfl(wbits, src));
+                if (src < cnt && ok) {
+                    load_elems<BF16, E>(xbase + (static_cast<uint64_t>(ck) << 4), xk[k]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < E; ++j) xk[k][j] = 0.f;
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < B_GROUPS; ++k)
+            if (k * B_GROUPS < cnt) {
+#pragma unroll
+                for (int j = 0; j < E; ++j) acc[j] = fmaf(wk[k], xk[k][j], acc[j]);
+            }
+    }
+}
+
+template <int E>
+__device__ __forceinline__ void add_groups(float (&acc)[E]) {
+#pragma unroll
+    for (int off = B_LPR; off < 64; off <<= 1)
+#pragma unroll
+        for (int j = 0; j < E; ++j) acc[j] += __shfl_xor(acc[j], off);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void spmm_blocked_kernel(SpmmBlockedArgs b) {
+    constexpr int E = BF16 ? 8 : 4;
+    constexpr int ES = BF16 ? 2 : 4;
+    constexpr int SLICE = B_LPR * E;
+    __shared__ float red[3][E][B_LPR];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int l = lane % B_LPR, grp = lane / B_LPR;
+    const int x = blockIdx.x % NUM_XCD;
+    int64_t q = blockIdx.x / NUM_XCD;
+    int64_t r = q % b.RG;
+    q /= b.RG;
+    const int cb = static_cast<int>(q % b.ncb);
+    const int64_t u = x + NUM_XCD * (q / b.ncb);     // unit = (slice, share)
+    const int s = static_cast<int>(u / b.H), h = static_cast<int>(u % b.H);
+    const int elem0 = s * SLICE + l * E;
+    const bool ok = elem0 < b.F_lim;
+    const char *xbase = b.X + static_cast<int64_t>(elem0) * ES;
+    const int64_t tbase = static_cast<int64_t>(cb) * b.n_out;
+
+    if (r < b.RG_long) {
+        // ---- a whole workgroup on one task: the four waves take quarters of the group, summed through LDS
+        const int64_t p = r * b.H + h;
+        if (p >= b.n_long) return;                   // uniform over the workgroup
+        const uint32_t e0 = b.off[tbase + p], e1 = b.off[tbase + p + 1];
+        if (e0 == e1) return;
+        const uint32_t per = ((e1 - e0 + 3) / 4 + 63) / 64 * 64;
+        uint32_t w0 = e0 + wave * per, w1 = w0 + per;
+        if (w0 > e1) w0 = e1;
+        if (w1 > e1) w1 = e1;
+        float acc[E];
+#pragma unroll
+        for (int j = 0; j < E; ++j) acc[j] = 0.f;
+        blocked_row_accumulate<BF16, E>(b, w0, w1, lane, xbase, ok, acc);
+        add_groups<E>(acc);
+        if (wave > 0 && lane < B_LPR) {
+#pragma unroll
+            for (int j = 0; j < E; ++j) red[wave - 1][j][lane] = acc[j];
+        }
+        __syncthreads();
+        if (wave == 0 && lane < B_LPR) {
+#pragma unroll
+            for (int wv = 0; wv < 3; ++wv)
+#pragma unroll
+                for (int j = 0; j < E; ++j) acc[j] += red[wv][j][lane];
+            store_elems<false, E>(reinterpret_cast<char *>(b.part + (tbase + p) * b.ldp + elem0), acc);
+        }
+        return;
+    }
+    r -= b.RG_long;
+    if (r < b.RG_mid) {
+        // ---- one wave per task
+        const int64_t p0 = b.n_long + (r * b.H + h) * B_MID_PER_WG + wave * B_MID_PER_WAVE;
+        for (int i = 0; i < B_MID_PER_WAVE; ++i) {
+            const int64_t p = p0 + i;
+            if (p >= b.n_mid) break;
+            const uint32_t e0 = b.off[tbase + p], e1 = b.off[tbase + p + 1];
+            if (e0 == e1) continue;
+            float acc[E];
+#pragma unroll
+            for (int j = 0; j < E; ++j) acc[j] = 0.f;
+            blocked_row_accumulate<BF16, E>(b, e0, e1, lane, xbase, ok, acc);
+            add_groups<E>(acc);
+            if (lane < B_LPR) store_elems<false, E>(reinterpret_cast<char *>(b.part + (tbase + p) * b.ldp + elem0), acc);
+        }
+        return;
+    }
+    r -= b.RG_mid;
+    // ---- eight tasks per wave: each 8-lane group owns one position and walks its entries 8 per trip (one index
+    // load per group, then 8 independent feature loads in flight)
+    const int64_t p0 = b.n_mid + (r * b.H + h) * B_SHORT_PER_WG + wave * (B_GROUPS * B_SHORT_PER_GROUP);
+    for (int i = 0; i < B_SHORT_PER_GROUP; ++i) {
+        const int64_t p = p0 + i * B_GROUPS + grp;
+        uint32_t e = 0, e1 = 0;
+        if (p < b.n_out) { e = b.off[tbase + p]; e1 = b.off[tbase + p + 1]; }
+        const bool any_entry = e < e1;
+        float acc[E];
+#pragma unroll
+        for (int j = 0; j < E; ++j) acc[j] = 0.f;
+        int2 pr = make_int2(0, 0);
+        if (e + l < e1) pr = b.ew[e + l];
+        while (__any(e < e1)) {
+            const int coff = static_cast<int>(__umul24(static_cast<uint32_t>(pr.x), b.ld16));   // in 16-byte units
+            const int wbits = pr.y;
+            const int n = e < e1 ? static_cast<int>(e1 - e) : 0;    // entries this group still has (may exceed 8)
+            e += B_LPR;
+            pr = make_int2(0, 0);
+            if (e + l < e1) pr = b.ew[e + l];                       // next trip's entries are on their way early
+            float xk[B_LPR][E], wk[B_LPR];
+#pragma unroll
+            for (int k = 0; k < B_LPR; ++k) {
+                const uint32_t ck = static_cast<uint32_t>(group_bcast(coff, k));
+                wk[k] = __int_as_float(group_bcast(wbits, k));
+                if (k < n && ok) {
+                    load_elems<BF16, E>(xbase + (static_cast<uint64_t>(ck) << 4), xk[k]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < E; ++j) xk[k][j] = 0.f;
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < B_LPR; ++k)
+#pragma unroll
+                for (int j = 0; j < E; ++j) acc[j] = fmaf(wk[k], xk[k][j], acc[j]);
+        }
+        if (any_entry) store_elems<false, E>(reinterpret_cast<char *>(b.part + (tbase + p) * b.ldp + elem0), acc);
+    }
+}
+
+struct SpmmReduceArgs {
+    const uint32_t *off;
+    const int32_t *order;
+    const float *out_scale;
+    const float *part;
+    int64_t ldp, n_out;
+    int ncb;
+    char *Y;
+    int64_t ldy_bytes;
+    int F;
+    const float *bias;
+    int relu, accumulate;
+};
+
+// one thread per (position, four consecutive features)
+template <bool OBF16>
+__global__ __launch_bounds__(256) void spmm_blocked_reduce_kernel(SpmmReduceArgs a) {
+    constexpr int ES = OBF16 ? 2 : 4;
+    const int chunks = (a.F + 3) / 4;
+    const int64_t tid = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t p = tid / chunks;
+    if (p >= a.n_out) return;
+    const int f0 = static_cast<int>(tid % chunks) * 4;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int cb = 0; cb < a.ncb; ++cb) {
+        const int64_t t = static_cast<int64_t>(cb) * a.n_out + p;
+        if (a.off[t + 1] == a.off[t]) continue;      // empty group: its partial row was never written
+        const float4 v = *reinterpret_cast<const float4 *>(a.part + t * a.ldp + f0);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    const int row = a.order[p];
+    const float oscale = a.out_scale ? a.out_scale[row] : 1.f;
+    char *yrow = a.Y + static_cast<int64_t>(row) * a.ldy_bytes;
+    float y[4] = {acc.x * oscale, acc.y * oscale, acc.z * oscale, acc.w * oscale};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (f0 + j < a.F) {
+            if (a.accumulate) y[j] += load_one<OBF16>(yrow + static_cast<int64_t>(f0 + j) * ES);
+            if (a.bias) y[j] += a.bias[f0 + j];
+        }
+        if (a.relu) y[j] = y[j] > 0.f ? y[j] : 0.f;
+    }
+    if (f0 + 4 <= a.F) {
+        if constexpr (OBF16) {
+            uint2 v;
+            v.x = f32_to_bf16_bits(y[0]) | (f32_to_bf16_bits(y[1]) << 16);
+            v.y = f32_to_bf16_bits(y[2]) | (f32_to_bf16_bits(y[3]) << 16);
+            *reinterpret_cast<uint2 *>(yrow + static_cast<int64_t>(f0) * ES) = v;
+        } else {
+            *reinterpret_cast<float4 *>(yrow + static_cast<int64_t>(f0) * ES) = make_float4(y[0], y[1], y[2], y[3]);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (f0 + j < a.F) store_one<OBF16>(yrow + static_cast<int64_t>(f0 + j) * ES, y[j]);
+    }
+}
+
+// Geometry of the blocked launch for a width-F operand; ok == false when the blocked kernel does not apply.
+struct BlockedGeom {
+    bool ok = false;
+    int ns = 0, H = 0;
+    int64_t U = 0, RG_long = 0, RG_mid = 0, RG = 0, ldp = 0, grid = 0;
+    size_t ws = 0;
+};
+
+static BlockedGeom blocked_geom(const SpOp &op, int F, int dtype) {
+    BlockedGeom g;
+    if (op.ncb == 0 || F <= 0) return g;
+    const int slice = SLICE_BYTES / elem_bytes(dtype);
+    if (F < slice) return g;                         // narrow rows: the whole operand is small, one pass does
+    if (op.n_in >= (int64_t(1) << 24)) return g;     // the kernel forms source offsets with 24-bit multiplies
+    g.ns = (F + slice - 1) / slice;
+    int gcd = g.ns, t = NUM_XCD;
+    while (t) { const int m = gcd % t; gcd = t; t = m; }
+    g.H = NUM_XCD / gcd;
+    g.U = static_cast<int64_t>(g.ns) * g.H / NUM_XCD;
+    auto per_share = [&](int64_t positions, int per_wg) { return ((positions + per_wg - 1) / per_wg + g.H - 1) / g.H; };
+    g.RG_long = per_share(op.b_long, 1);
+    g.RG_mid = per_share(op.b_mid - op.b_long, B_MID_PER_WG);
+    g.RG = g.RG_long + g.RG_mid + per_share(op.n_out - op.b_mid, B_SHORT_PER_WG);
+    g.ldp = static_cast<int64_t>(g.ns) * slice;
+    g.grid = NUM_XCD * g.U * op.ncb * g.RG;
+    if (g.grid <= 0 || g.grid >= (int64_t(1) << 31)) return g;
+    g.ws = align_up(static_cast<size_t>(op.ncb) * op.n_out * g.ldp * sizeof(float), 256);
+    g.ok = true;
+    return g;
+}
+
+size_t spmm_ws_bytes(const SpOp &op, int F, int dtype) {
+    const BlockedGeom g = blocked_geom(op, F, dtype);
+    return g.ok ? g.ws : 0;
+}
+
+template <bool BF16, bool OBF16>
+static int launch_blocked(const SpOp &op, const BlockedGeom &g, const SpmmArgs &a, float *part, hipStream_t st) {
+    SpmmBlockedArgs b;
+    b.off = op.b_off; b.ew = op.b_ew; b.n_out = op.n_out; b.n_long = op.b_long; b.n_mid = op.b_mid;
+    b.ncb = op.ncb; b.H = g.H; b.RG_long = g.RG_long; b.RG_mid = g.RG_mid; b.RG = g.RG;
+    b.X = a.X; b.ld16 = static_cast<uint32_t>(a.ldx_bytes >> 4); b.F_lim = a.F_lim;
+    b.part = part; b.ldp = g.ldp;
+    hipLaunchKernelGGL((spmm_blocked_kernel<BF16>), dim3(static_cast<unsigned>(g.grid)), dim3(256), 0, st, b);
+    CG_HIP(hipGetLastError());
+    SpmmReduceArgs r;
+    r.off = op.b_off; r.order = op.order; r.out_scale = op.out_scale; r.part = part; r.ldp = g.ldp; r.n_out = op.n_out;
+    r.ncb = op.ncb; r.Y = a.Y; r.ldy_bytes = a.ldy_bytes; r.F = a.F; r.bias = a.bias; r.relu = a.relu;
+    r.accumulate = a.accumulate;
+    const int64_t threads = op.n_out * ((a.F + 3) / 4);
+    hipLaunchKernelGGL((spmm_blocked_reduce_kernel<OBF16>), dim3(static_cast<unsigned>((threads + 255) / 256)), dim3(256),
+                       0, st, r);
+    CG_HIP(hipGetLastError());
+    return CAPGNN_OK;
+}
+
 template <bool BF16, bool OBF16, int E, int LPR, int NV>
 static int launch_cfg(const SpmmArgs &base, int64_t n_long, int64_t n_rows, hipStream_t st) {
     if (n_long > 0) {
@@ -318,6 +638,18 @@ int launch_spmm(const SpOp &op, bool restrict_sub, const void *X, int64_t ldx, v
     a.F = F; a.F_lim = vec ? f_up : F;
     a.bias = ep.bias; a.relu = ep.relu; a.accumulate = ep.accumulate;
     const int64_t n_long = restrict_sub ? op.n_long_sub : op.n_long;
+    if (vec && !restrict_sub && ep.ws) {
+        // the blocked kernel runs when the operator has a blocked copy and the caller brought the scratch for it
+        const BlockedGeom bg = blocked_geom(op, F, dtype);
+        // source offsets are 32-bit counts of 16-byte units formed by a 24-bit multiply
+        const bool off_ok = (a.ldx_bytes >> 4) < (int64_t(1) << 24) && op.n_in * (a.ldx_bytes >> 4) < (int64_t(1) << 32);
+        if (bg.ok && off_ok && ep.ws_bytes >= bg.ws && (reinterpret_cast<uintptr_t>(ep.ws) & 15u) == 0) {
+            float *part = static_cast<float *>(ep.ws);
+            if (dtype == CAPGNN_F32) return launch_blocked<false, false>(op, bg, a, part, stream);
+            if (out_dtype == CAPGNN_BF16) return launch_blocked<true, true>(op, bg, a, part, stream);
+            return launch_blocked<true, false>(op, bg, a, part, stream);
+        }
+    }
     if (dtype == CAPGNN_F32) return dispatch<false, false>(a, vec, n_long, n_rows, stream);
     if (out_dtype == CAPGNN_BF16) return dispatch<true, true>(a, vec, n_long, n_rows, stream);
     return dispatch<true, false>(a, vec, n_long, n_rows, stream);
@@ -327,16 +659,23 @@ int launch_spmm(const SpOp &op, bool restrict_sub, const void *X, int64_t ldx, v
 
 using namespace capgnn;
 
-extern "C" size_t capgnn_spmm_workspace_bytes(const capgnn_graph *, int, int) { return 0; }
+extern "C" size_t capgnn_spmm_workspace_bytes(const capgnn_graph *g, int F, int dtype) {
+    if (!g || (dtype != CAPGNN_F32 && dtype != CAPGNN_BF16)) return 0;
+    return std::max(spmm_ws_bytes(g->fwd, F, dtype), spmm_ws_bytes(g->bwd, F, dtype));
+}
 
 extern "C" int capgnn_spmm_fwd(const capgnn_graph *g, const void *X, int64_t ldx, void *Y, int64_t ldy, int F,
-                               int dtype, void *, size_t, void *stream) {
+                               int dtype, void *ws, size_t ws_bytes, void *stream) {
     if (!g) CG_FAIL(CAPGNN_EINVAL, "spmm_fwd: graph is NULL");
-    return launch_spmm(g->fwd, false, X, ldx, Y, ldy, F, dtype, SpmmEpilogue(), static_cast<hipStream_t>(stream));
+    SpmmEpilogue ep;
+    ep.ws = ws; ep.ws_bytes = ws_bytes;
+    return launch_spmm(g->fwd, false, X, ldx, Y, ldy, F, dtype, ep, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int capgnn_spmm_bwd(const capgnn_graph *g, const void *dY, int64_t lddy, void *dX, int64_t lddx, int F,
-                               int dtype, void *, size_t, void *stream) {
+                               int dtype, void *ws, size_t ws_bytes, void *stream) {
     if (!g) CG_FAIL(CAPGNN_EINVAL, "spmm_bwd: graph is NULL");
-    return launch_spmm(g->bwd, false, dY, lddy, dX, lddx, F, dtype, SpmmEpilogue(), static_cast<hipStream_t>(stream));
+    SpmmEpilogue ep;
+    ep.ws = ws; ep.ws_bytes = ws_bytes;
+    return launch_spmm(g->bwd, false, dY, lddy, dX, lddx, F, dtype, ep, static_cast<hipStream_t>(stream));
 }

@@ -40,7 +40,7 @@ def adversarial_graphs():
     return gs
 
 
-def run_spmm(env, part, F, ld, dtype, with_vals, seed):
+def run_spmm(env, part, F, ld, dtype, with_vals, seed, blocked=False):
     torch, B, H, O, orc = env["torch"], env["B"], env["H"], env["O"], env["orc"]
     rng = np.random.default_rng(seed)
     r = rng.uniform(0.5, 1.5, part.n_loc).astype(np.float32)
@@ -58,8 +58,13 @@ def run_spmm(env, part, F, ld, dtype, with_vals, seed):
     # sentinel-filled outputs: whatever the kernel must not touch stays recognisable
     Yd = torch.full((part.n_loc, ld), 7.0, dtype=Xd.dtype, device="cuda")
     dXd = torch.full((part.n_cols, ld), 7.0, dtype=Xd.dtype, device="cuda")
-    B.spmm_fwd(g, Xd, ld, Yd, ld, F, dt)
-    B.spmm_bwd(g, dYd, ld, dXd, ld, F, dt)
+    ws, wsb = None, 0
+    if blocked:       # with scratch the column-blocked kernel runs (the graph must qualify for a blocked copy)
+        wsb = B.spmm_workspace_bytes(g, F, dt)
+        assert wsb > 0, "graph or width does not qualify for the column-blocked kernel"
+        ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    B.spmm_fwd(g, Xd, ld, Yd, ld, F, dt, ws=ws, ws_bytes=wsb)
+    B.spmm_bwd(g, dYd, ld, dXd, ld, F, dt, ws=ws, ws_bytes=wsb)
     torch.cuda.synchronize()
     og = orc.Graph(part.n_loc, part.n_cols, part.rowptr, part.col, r.astype(np.float64), c.astype(np.float64),
                    None if v is None else v.astype(np.float64))
@@ -93,6 +98,22 @@ def test_spmm_bf16(env, F, ld):
     for part in adversarial_graphs()[:2] + adversarial_graphs()[4:]:
         say(f"spmm bf16 {part.name} F={F} ld={ld}")
         run_spmm(env, part, F, ld, "bf16", with_vals=False, seed=F)
+
+
+@pytest.mark.parametrize("shape", ["wide", "tall"])
+def test_spmm_column_blocked(env, shape):
+    """Dense-degree operators get a column-blocked copy (several source blocks, long (block,row) groups);
+    with scratch the blocked kernel + its fixed-order reduction run.  'wide' blocks the forward product,
+    'tall' the transposed one; ragged last block, empty groups, partial last slice, edge values."""
+    if shape == "wide":
+        part = synth.make_partition("blk-wide", 2500, 38000, 330000, seed=21, max_deg=9000, halo_edge_frac=0.9)
+    else:
+        part = synth.make_partition("blk-tall", 37000, 2000, 2600000, seed=22, max_deg=4000, halo_edge_frac=0.2)
+    for F, ld, dtype, vals in [(32, 32, "f32", False), (41, 44, "f32", True), (256, 256, "f32", False),
+                               (602, 604, "f32", False), (64, 64, "bf16", False), (200, 200, "bf16", True),
+                               (256, 264, "bf16", False)]:
+        say(f"spmm blocked {part.name} F={F} ld={ld} {dtype}")
+        run_spmm(env, part, F, ld, dtype, vals, seed=F, blocked=True)
 
 
 def test_spmm_exact_on_small_integers(env):
