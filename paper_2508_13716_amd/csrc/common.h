@@ -134,9 +134,12 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
 size_t gemm_ws_bytes(int trans_a, int64_t M, int64_t N, int64_t K);
 
 // dZ = dH * 1[H > 0] in place (when relu) and dbias[f] = sum_i dZ[i,f] (when dbias), fixed summation order.
+// src (of src_dtype, pitch lds), when non-null and different from dH, is the unrounded gradient: dH is then
+// written as its masked, converted copy and the bias gradient is summed from the unrounded values.
 size_t relu_bias_ws_bytes(int64_t n, int F);
-int launch_relu_mask_dbias(int64_t n, int F, void *dH, int64_t lddh, const void *H, int64_t ldh, int dtype,
-                           int h_dtype, int relu, float *dbias, void *ws, size_t ws_bytes, hipStream_t stream);
+int launch_relu_mask_dbias(int64_t n, int F, const void *src, int64_t lds, int src_dtype, void *dH, int64_t lddh,
+                           const void *H, int64_t ldh, int dtype, int h_dtype, int relu, float *dbias, void *ws,
+                           size_t ws_bytes, hipStream_t stream);
 int launch_sgd(float *W, const float *dW, int64_t n, float lr, hipStream_t stream);
 
 uint64_t hash_gid(uint64_t x);

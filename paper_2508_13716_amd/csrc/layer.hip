@@ -156,7 +156,7 @@ static int layer_fwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
 static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int order, int li, const void *X, int64_t ldx,
                           const void *H, int64_t ldh, const void *saved, void *dH, int64_t lddh, float *dW,
                           float *dW_self, float *dbias, void *dX, int64_t lddx, int need_halo_grad, void *ws,
-                          size_t ws_bytes, hipStream_t st) {
+                          size_t ws_bytes, hipStream_t st, const float *dH32 = nullptr, int64_t lddh32 = 0) {
     const int dt = l->dtype;
     const bool sage = l->kind == CAPGNN_SAGE_MEAN;
     const int relu = l->act == CAPGNN_ACT_RELU;
@@ -182,7 +182,10 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
     {   // dZ = dH * sigma'(Z) in place; dbias = column sums of dZ
         Scope s(CAPGNN_K_ELEMENTWISE, li, 1, st);
         const int h_dt = (l->out_f32 ? CAPGNN_F32 : dt);
-        CG_TRY(launch_relu_mask_dbias(g->n_loc, l->f_out, dH, lddh, H, ldh, dt, h_dt, relu, dbias, ws_rb, rb, st));
+        // dH32: the same gradient before it was rounded to the storage type (the loss gradient of a bf16 model);
+        // the bias gradient is then summed from it and dH is (re)written as its masked, rounded copy
+        CG_TRY(launch_relu_mask_dbias(g->n_loc, l->f_out, dH32, lddh32, CAPGNN_F32, dH, lddh, H, ldh, dt, h_dt, relu, dbias,
+                                      ws_rb, rb, st));
     }
     if (order == CAPGNN_AGG_FIRST) {
         if (!saved) CG_FAIL(CAPGNN_EINVAL, "layer_bwd: saved is NULL");
@@ -239,7 +242,7 @@ struct EpochPlan {
     std::vector<int> order;
     std::vector<int64_t> ldx;          // leading dimension of layer l's input
     std::vector<size_t> x_off, saved_off;
-    size_t logits_off = 0, grad_off[2] = {0, 0}, layer_ws_off = 0, layer_ws_bytes = 0, loss_ws_off = 0,
+    size_t logits_off = 0, dz32_off = 0, grad_off[2] = {0, 0}, layer_ws_off = 0, layer_ws_bytes = 0, loss_ws_off = 0,
            loss_val_off = 0, staging_off = 0, total = 0;
     int64_t ld_grad = 0, ldz = 0;
 };
@@ -262,6 +265,8 @@ static int plan_epoch(const capgnn_graph *g, const capgnn_cache *c, const capgnn
     }
     p->ldz = pad_ld(layers[L - 1].f_out, CAPGNN_F32);
     p->logits_off = take(static_cast<size_t>(g->n_loc) * p->ldz * sizeof(float));
+    // a bf16 model keeps the loss gradient in float as well: the last layer's bias gradient is summed from it
+    if (layers[0].dtype == CAPGNN_BF16) p->dz32_off = take(static_cast<size_t>(g->n_loc) * p->ldz * sizeof(float));
     p->ld_grad = max_w;
     p->grad_off[0] = take(static_cast<size_t>(g->n_loc) * max_w * sizeof(float));
     p->grad_off[1] = take(static_cast<size_t>(g->n_loc) * max_w * sizeof(float));
@@ -439,8 +444,12 @@ extern "C" int capgnn_epoch(const capgnn_graph *g, capgnn_cache *c, const capgnn
     int cur = 0;
     {
         Scope s(CAPGNN_K_LOSS, L - 1, 0, st);
-        CG_TRY(capgnn_softmax_ce(g->n_loc, C, Z, ldz, labels, mask, loss_norm, loss_dev, w + p.grad_off[cur], p.ld_grad, dt,
-                                 w + p.loss_ws_off, capgnn_loss_workspace_bytes(g->n_loc), st));
+        if (dt == CAPGNN_BF16)
+            CG_TRY(capgnn_softmax_ce(g->n_loc, C, Z, ldz, labels, mask, loss_norm, loss_dev, w + p.dz32_off, ldz, CAPGNN_F32,
+                                     w + p.loss_ws_off, capgnn_loss_workspace_bytes(g->n_loc), st));
+        else
+            CG_TRY(capgnn_softmax_ce(g->n_loc, C, Z, ldz, labels, mask, loss_norm, loss_dev, w + p.grad_off[cur], p.ld_grad, dt,
+                                     w + p.loss_ws_off, capgnn_loss_workspace_bytes(g->n_loc), st));
     }
     // backward
     for (int l = L - 1; l >= 0; --l) {
@@ -450,7 +459,8 @@ extern "C" int capgnn_epoch(const capgnn_graph *g, capgnn_cache *c, const capgnn
         void *dX = l > 0 ? static_cast<void *>(w + p.grad_off[cur ^ 1]) : nullptr;
         CG_TRY(layer_bwd_impl(g, &layers[l], p.order[l], l, Xl(l), p.ldx[l], Hl, ldh, w + p.saved_off[l],
                               w + p.grad_off[cur], p.ld_grad, dW[l], dW_self ? dW_self[l] : nullptr, dbias[l], dX,
-                              p.ld_grad, 0, w + p.layer_ws_off, p.layer_ws_bytes, st));
+                              p.ld_grad, 0, w + p.layer_ws_off, p.layer_ws_bytes, st,
+                              (last && dt == CAPGNN_BF16) ? reinterpret_cast<const float *>(w + p.dz32_off) : nullptr, ldz));
         cur ^= 1;
     }
     if (lr != 0.f) {

@@ -22,30 +22,36 @@ __device__ __forceinline__ void st_elem(char *p, int64_t i, float v, int bf16) {
 }
 
 // ------------------------------------------------------------------ dZ = dH * 1[H>0], dbias partials
-constexpr int RB_ROWS = 128;   // rows per workgroup
+constexpr int RB_ROWS = 128;          // rows per chunk
+constexpr int RB_MAX_BLOCKS = 1024;   // workgroups (= partial rows); each walks chunks b, b+grid, ...
 
-// blockDim = (TX, 256/TX): threadIdx.x walks the feature columns, threadIdx.y the rows of the chunk.
-__global__ __launch_bounds__(256) void relu_mask_dbias_kernel(int64_t n, int F, char *dH, int64_t lddh, const char *H,
-                                                              int64_t ldh, int bf16, int h_bf16, int relu, float *partial) {
+// blockDim = (TX, 256/TX): threadIdx.x walks the feature columns, threadIdx.y the rows of a chunk.
+// dst = src * 1[H > 0] (all of src when !relu), written in place (only the zeroed elements are stored) or,
+// when dst differs from src, as a converting copy.  partial[b][f] = this workgroup's column sums of dst,
+// formed from the unrounded values.
+__global__ __launch_bounds__(256) void relu_mask_dbias_kernel(int64_t n, int F, const char *src, int64_t lds,
+                                                              int src_bf16, char *dst, int64_t ldd, int dst_bf16,
+                                                              const char *H, int64_t ldh, int h_bf16, int relu,
+                                                              float *partial) {
     __shared__ float red[256];
     const int tx = threadIdx.x, ty = threadIdx.y, TX = blockDim.x, TY = blockDim.y;
-    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * RB_ROWS;
-    const int64_t r1 = r0 + RB_ROWS < n ? r0 + RB_ROWS : n;
+    const bool in_place = src == dst;
     for (int f0 = 0; f0 < F; f0 += TX) {
         const int f = f0 + tx;
         float s = 0.f;
         if (f < F) {
-            for (int64_t r = r0 + ty; r < r1; r += TY) {
-                float g = ld_elem(dH, r * lddh + f, bf16);
-                if (relu) {
-                    const float h = ld_elem(H, r * ldh + f, h_bf16);
-                    if (!(h > 0.f)) {
-                        g = 0.f;
-                        if (bf16) reinterpret_cast<uint16_t *>(dH)[r * lddh + f] = 0;
-                        else reinterpret_cast<float *>(dH)[r * lddh + f] = 0.f;
+            for (int64_t r0 = static_cast<int64_t>(blockIdx.x) * RB_ROWS; r0 < n; r0 += static_cast<int64_t>(gridDim.x) * RB_ROWS) {
+                const int64_t r1 = r0 + RB_ROWS < n ? r0 + RB_ROWS : n;
+                for (int64_t r = r0 + ty; r < r1; r += TY) {
+                    float g = ld_elem(src, r * lds + f, src_bf16);
+                    bool zeroed = false;
+                    if (relu) {
+                        const float h = ld_elem(H, r * ldh + f, h_bf16);
+                        if (!(h > 0.f)) { g = 0.f; zeroed = true; }
                     }
+                    if (!in_place || zeroed) st_elem(dst, r * ldd + f, g, dst_bf16);
+                    s += g;
                 }
-                s += g;
             }
         }
         if (partial) {
@@ -61,45 +67,61 @@ __global__ __launch_bounds__(256) void relu_mask_dbias_kernel(int64_t n, int F, 
     }
 }
 
+// dbias[f] = sum_b partial[b][f]: 32 features x 8 strided groups per workgroup, doubles, fixed order
 __global__ __launch_bounds__(256) void dbias_final_kernel(int64_t nblocks, int F, const float *partial, float *dbias) {
-    const int f = blockIdx.x * 256 + threadIdx.x;
-    if (f >= F) return;
+    __shared__ double red[8][32];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int f = blockIdx.x * 32 + tx;
     double s = 0.0;
-    for (int64_t b = 0; b < nblocks; ++b) s += static_cast<double>(partial[b * F + f]);
-    dbias[f] = static_cast<float>(s);
+    if (f < F)
+        for (int64_t b = ty; b < nblocks; b += 8) s += static_cast<double>(partial[b * F + f]);
+    red[ty][tx] = s;
+    __syncthreads();
+    if (ty == 0 && f < F) {
+        double t = 0.0;
+        for (int y = 0; y < 8; ++y) t += red[y][tx];
+        dbias[f] = static_cast<float>(t);
+    }
+}
+
+static int64_t rb_blocks(int64_t n) {
+    return std::max<int64_t>(1, std::min<int64_t>((n + RB_ROWS - 1) / RB_ROWS, RB_MAX_BLOCKS));
 }
 
 size_t relu_bias_ws_bytes(int64_t n, int F) {
-    const int64_t nb = (n + RB_ROWS - 1) / RB_ROWS;
-    return align_up(static_cast<size_t>(std::max<int64_t>(nb, 1)) * F * sizeof(float), 256);
+    return align_up(static_cast<size_t>(rb_blocks(n)) * F * sizeof(float), 256);
 }
 
-int launch_relu_mask_dbias(int64_t n, int F, void *dH, int64_t lddh, const void *H, int64_t ldh, int dtype,
-                           int h_dtype, int relu, float *dbias, void *ws, size_t ws_bytes, hipStream_t stream) {
+int launch_relu_mask_dbias(int64_t n, int F, const void *src, int64_t lds, int src_dtype, void *dH, int64_t lddh,
+                           const void *H, int64_t ldh, int dtype, int h_dtype, int relu, float *dbias, void *ws,
+                           size_t ws_bytes, hipStream_t stream) {
     if (F <= 0) return CAPGNN_OK;
     if (n <= 0) {   // no rows: the bias gradient is zero (summing zero partial blocks)
         if (dbias) {
-            hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 255) / 256), dim3(256), 0, stream, int64_t(0), F,
+            hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 31) / 32), dim3(256), 0, stream, int64_t(0), F,
                                static_cast<const float *>(nullptr), dbias);
             CG_HIP(hipGetLastError());
         }
         return CAPGNN_OK;
     }
-    if (!relu && !dbias) return CAPGNN_OK;
+    if (!src) { src = dH; lds = lddh; src_dtype = dtype; }
+    const bool converting = src != dH;
+    if (!relu && !dbias && !converting) return CAPGNN_OK;
     if (!dH || (relu && !H)) CG_FAIL(CAPGNN_EINVAL, "relu_mask_dbias: NULL operand");
-    if (lddh < F || (relu && ldh < F)) CG_FAIL(CAPGNN_EINVAL, "relu_mask_dbias: leading dimension smaller than F");
-    const int64_t nb = (n + RB_ROWS - 1) / RB_ROWS;
+    if (lddh < F || lds < F || (relu && ldh < F)) CG_FAIL(CAPGNN_EINVAL, "relu_mask_dbias: leading dimension smaller than F");
+    const int64_t nb = rb_blocks(n);
     if (dbias && (!ws || ws_bytes < static_cast<size_t>(nb) * F * sizeof(float)))
         CG_FAIL(CAPGNN_ENOMEM, "relu_mask_dbias: workspace too small");
     int TX = 1;
     while (TX < F && TX < 256) TX <<= 1;
     dim3 block(TX, 256 / TX);
     hipLaunchKernelGGL(relu_mask_dbias_kernel, dim3(static_cast<unsigned>(nb)), block, 0, stream, n, F,
-                       static_cast<char *>(dH), lddh, static_cast<const char *>(H), ldh, dtype == CAPGNN_BF16 ? 1 : 0,
-                       h_dtype == CAPGNN_BF16 ? 1 : 0, relu, dbias ? static_cast<float *>(ws) : nullptr);
+                       static_cast<const char *>(src), lds, src_dtype == CAPGNN_BF16 ? 1 : 0, static_cast<char *>(dH), lddh,
+                       dtype == CAPGNN_BF16 ? 1 : 0, static_cast<const char *>(H), ldh, h_dtype == CAPGNN_BF16 ? 1 : 0,
+                       relu, dbias ? static_cast<float *>(ws) : nullptr);
     CG_HIP(hipGetLastError());
     if (dbias) {
-        hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 255) / 256), dim3(256), 0, stream, nb, F,
+        hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 31) / 32), dim3(256), 0, stream, nb, F,
                            static_cast<const float *>(ws), dbias);
         CG_HIP(hipGetLastError());
     }

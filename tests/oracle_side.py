@@ -54,3 +54,44 @@ def normwise(gpu: np.ndarray, ref: np.ndarray) -> float:
     if den == 0.0:
         return float(np.abs(gpu).max()) if gpu.size else 0.0
     return float(np.abs(gpu - ref).max() / den)
+
+
+# ----------------------------------------------------------------------------- sampled outputs at full size
+def sampled_fwd_graph(og, rows):
+    """The oracle graph restricted to the output rows `rows` (renumbered 0..k-1) and to the columns those
+    rows touch (renumbered; returned as J).  orc.spmm_fwd on it gives exactly the oracle's rows `rows`."""
+    rows = np.asarray(rows, np.int64)
+    starts, ends = og.rowptr[rows], og.rowptr[rows + 1]
+    rowptr = np.zeros(len(rows) + 1, np.int64)
+    np.cumsum(ends - starts, out=rowptr[1:])
+    eidx = (np.concatenate([np.arange(s, e, dtype=np.int64) for s, e in zip(starts, ends)])
+            if len(rows) else np.zeros(0, np.int64))
+    J, inv = np.unique(og.col[eidx], return_inverse=True)
+    v = None if og.v is None else og.v[eidx]
+    return orc.Graph(len(rows), len(J), rowptr, inv.astype(np.int32), og.r[rows], og.c[J], v), J.astype(np.int64)
+
+
+def sampled_bwd_graph(og, cols):
+    """The oracle graph restricted to the entries whose column is in `cols` (columns renumbered in ascending
+    order, rows that hold such entries renumbered; returned as R).  orc.spmm_bwd on it gives exactly the
+    oracle's transposed product for those columns (entry order inside a column is kept)."""
+    cols = np.unique(np.asarray(cols, np.int64))
+    lut = np.full(og.n_cols, -1, np.int32)
+    lut[cols] = np.arange(len(cols), dtype=np.int32)
+    m = lut[og.col]
+    eidx = np.nonzero(m >= 0)[0]
+    erow = np.searchsorted(og.rowptr, eidx, side="right") - 1
+    R, rinv = np.unique(erow, return_inverse=True)
+    rowptr = np.zeros(len(R) + 1, np.int64)
+    np.cumsum(np.bincount(rinv, minlength=len(R)), out=rowptr[1:])
+    v = None if og.v is None else og.v[eidx]
+    return orc.Graph(len(R), len(cols), rowptr, m[eidx].astype(np.int32), og.r[R], og.c[cols], v), R.astype(np.int64), cols
+
+
+def sample_indices(lengths: np.ndarray, k: int, seed: int) -> np.ndarray:
+    """k indices: the longest and the shortest few plus random ones (sorted, unique)."""
+    n = len(lengths)
+    rng = np.random.default_rng(seed)
+    order = np.argsort(lengths, kind="stable")
+    pick = np.concatenate([order[:8], order[-8:], rng.integers(0, n, size=max(k - 16, 0))])
+    return np.unique(pick.astype(np.int64))
