@@ -64,8 +64,11 @@ extern "C" {
 
 #define CAPGNN_GRAPH_SYMMETRIC 1u  /* n_halo == 0 and A_hat^T == A_hat: backward reuses the CSR */
 
-#define CAPGNN_MISS_ZEROCOPY 0  /* host-tier rows are read by a kernel straight from pinned memory */
-#define CAPGNN_MISS_STAGED   1  /* host tier is DMA-copied into a device staging area, then scattered */
+#define CAPGNN_MISS_ZEROCOPY  0  /* host-tier rows are read by a kernel straight from pinned memory */
+#define CAPGNN_MISS_STAGED    1  /* host tier is DMA-copied into a device staging area, then scattered (default) */
+#define CAPGNN_MISS_PIPELINED 2  /* as STAGED, and capgnn_epoch starts the copy for the NEXT epoch as soon as this
+                                    epoch has consumed a layer's staging area (the prefetch queue of the section
+                                    "Pipeline Design": transfers overlap computation across iterations) */
 
 typedef struct capgnn_graph capgnn_graph;
 typedef struct capgnn_cache capgnn_cache;
@@ -147,12 +150,18 @@ int capgnn_cache_build(capgnn_cache **c, int64_t n_halo, const int64_t *gid, con
                        void *gpu_tier, void *host_tier, int map_kind, void *stream);
 int capgnn_cache_destroy(capgnn_cache *c);
 
-/* How capgnn_epoch moves host-tier rows: CAPGNN_MISS_ZEROCOPY (default) or CAPGNN_MISS_STAGED (then
- * capgnn_epoch_workspace_bytes() includes the staging area). */
+/* How capgnn_epoch moves host-tier rows: CAPGNN_MISS_ZEROCOPY, CAPGNN_MISS_STAGED (default) or
+ * CAPGNN_MISS_PIPELINED (for the last two capgnn_epoch_workspace_bytes() includes the staging area).
+ * CAPGNN_MISS_PIPELINED keeps state between calls of capgnn_epoch: the staging area inside `ws` holds the
+ * host-tier rows prefetched for the next call, so consecutive calls must pass the same ws (a different ws,
+ * capgnn_cache_fill or a mode change make the next call fetch afresh), a side stream must be given, and copies
+ * into ws may still be in flight on the side stream after capgnn_epoch returns: synchronise that stream (or the
+ * device) before freeing or reusing ws, the tiers or the cache.  The rows an epoch consumes are the host
+ * tier's contents at the time of the previous call (or of this call, for the first). */
 int capgnn_cache_set_miss_mode(capgnn_cache *c, int mode);
 
 /* Loads layer `layer`'s logical table (host, [n_halo x ld], halo-local row order) into both tiers.
- * Synchronous (setup call). */
+ * Synchronous (setup call): waits for `stream` and for a prefetch the last capgnn_epoch left in flight. */
 int capgnn_cache_fill(capgnn_cache *c, int layer, const void *rows, int64_t ld, void *stream);
 
 /* check_cache on the host (for tests and planning): ids are halo-local indices, or global ids when

@@ -193,26 +193,44 @@ int gather_all_hits(const capgnn_cache *c, int layer, void *out, int64_t ld, hip
     return CAPGNN_OK;
 }
 
-// Host-tier part of the full-batch gather of one layer, on `st`: either a kernel that reads pinned
-// memory directly, or a DMA copy into `staging` followed by the same scatter from device memory.
-int gather_all_misses(const capgnn_cache *c, int layer, void *out, int64_t ld, void *staging, hipStream_t st) {
+// DMA of layer `layer`'s host tier into its slot of the staging area.
+int stage_misses(const capgnn_cache *c, int layer, void *staging, hipStream_t st) {
     if (c->n_host == 0) return CAPGNN_OK;
-    const char *tab = c->host_tier + c->host_off[layer];
-    if (staging) {
-        char *stg = static_cast<char *>(staging) + c->host_off[layer];
-        CG_HIP(hipMemcpyAsync(stg, tab, static_cast<size_t>(c->n_host) * c->pitch[layer], hipMemcpyHostToDevice, st));
-        tab = stg;
-    }
+    if (!staging) CG_FAIL(CAPGNN_EINVAL, "halo_gather: staging area is NULL");
+    CG_HIP(hipMemcpyAsync(static_cast<char *>(staging) + c->host_off[layer], c->host_tier + c->host_off[layer],
+                          static_cast<size_t>(c->n_host) * c->pitch[layer], hipMemcpyHostToDevice, st));
+    return CAPGNN_OK;
+}
+
+static int scatter_host_rows(const capgnn_cache *c, int layer, const char *tab, bool pinned, void *out, int64_t ld,
+                             hipStream_t st) {
     CopyGeom g;
     CG_TRY(copy_geom(c, layer, out, ld, tab, &g));
     // A kernel that reads pinned memory is bound by the host link, not by the CUs: a small grid keeps enough
     // requests in flight and leaves the compute units to the kernels of the main stream.
     unsigned blocks = blocks_for(c->n_host, g.lpr);
-    if (!staging && blocks > HOST_READ_BLOCKS) blocks = HOST_READ_BLOCKS;
+    if (pinned && blocks > HOST_READ_BLOCKS) blocks = HOST_READ_BLOCKS;
     hipLaunchKernelGGL(scatter_tier_kernel, dim3(blocks), dim3(256), 0, st, tab, c->pitch[layer],
                        c->host_list_d, c->n_host, static_cast<char *>(out), g.out_pitch, g.row_bytes, g.lpr, g.vec16, g.es);
     CG_HIP(hipGetLastError());
     return CAPGNN_OK;
+}
+
+// Scatter of a staged host tier into the halo rows it belongs to.
+int scatter_staged(const capgnn_cache *c, int layer, void *out, int64_t ld, void *staging, hipStream_t st) {
+    if (c->n_host == 0) return CAPGNN_OK;
+    return scatter_host_rows(c, layer, static_cast<const char *>(staging) + c->host_off[layer], false, out, ld, st);
+}
+
+// Host-tier part of the full-batch gather of one layer, on `st`: either a kernel that reads pinned
+// memory directly, or a DMA copy into `staging` followed by the same scatter from device memory.
+int gather_all_misses(const capgnn_cache *c, int layer, void *out, int64_t ld, void *staging, hipStream_t st) {
+    if (c->n_host == 0) return CAPGNN_OK;
+    if (staging) {
+        CG_TRY(stage_misses(c, layer, staging, st));
+        return scatter_staged(c, layer, out, ld, staging, st);
+    }
+    return scatter_host_rows(c, layer, c->host_tier + c->host_off[layer], true, out, ld, st);
 }
 
 template <typename T>
@@ -354,8 +372,11 @@ extern "C" int capgnn_cache_build(capgnn_cache **out, int64_t n_halo, const int6
         return fail(CAPGNN_EHIP);
     }
     c->ev_layer.assign(n_layers, nullptr);
+    c->ev_consumed.assign(n_layers, nullptr);
+    c->staged_valid.assign(n_layers, 0);
     for (int l = 0; l < n_layers; ++l)
-        if (hipEventCreateWithFlags(&c->ev_layer[l], hipEventDisableTiming) != hipSuccess) {
+        if (hipEventCreateWithFlags(&c->ev_layer[l], hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&c->ev_consumed[l], hipEventDisableTiming) != hipSuccess) {
             set_error("cache_build: hipEventCreate failed");
             return fail(CAPGNN_EHIP);
         }
@@ -369,17 +390,21 @@ extern "C" int capgnn_cache_build(capgnn_cache **out, int64_t n_halo, const int6
 
 extern "C" int capgnn_cache_destroy(capgnn_cache *c) {
     if (!c) return CAPGNN_OK;
+    if (c->last_side) (void)hipStreamSynchronize(c->last_side);   // a prefetch may still be reading the host tier
     for (void *p : c->dev_allocs) (void)hipFree(p);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     for (hipEvent_t e : c->ev_layer) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->ev_consumed) if (e) (void)hipEventDestroy(e);
     delete c;
     return CAPGNN_OK;
 }
 
 extern "C" int capgnn_cache_set_miss_mode(capgnn_cache *c, int mode) {
-    if (!c || (mode != CAPGNN_MISS_ZEROCOPY && mode != CAPGNN_MISS_STAGED)) CG_FAIL(CAPGNN_EINVAL, "cache_set_miss_mode: bad argument");
+    if (!c || mode < CAPGNN_MISS_ZEROCOPY || mode > CAPGNN_MISS_PIPELINED) CG_FAIL(CAPGNN_EINVAL, "cache_set_miss_mode: bad argument");
+    if (c->last_side) CG_HIP(hipStreamSynchronize(c->last_side));
     c->miss_mode = mode;
+    std::fill(c->staged_valid.begin(), c->staged_valid.end(), 0);
     return CAPGNN_OK;
 }
 
@@ -387,6 +412,7 @@ extern "C" int capgnn_cache_fill(capgnn_cache *c, int layer, const void *rows, i
     if (!c || layer < 0 || layer >= c->n_layers) CG_FAIL(CAPGNN_EINVAL, "cache_fill: bad cache or layer");
     if (c->n_halo == 0) return CAPGNN_OK;
     if (!rows || ld < c->dims[layer]) CG_FAIL(CAPGNN_EINVAL, "cache_fill: rows is NULL or ld too small");
+    if (c->last_side) CG_HIP(hipStreamSynchronize(c->last_side));   // a prefetch may be reading the host tier
     const int es = elem_bytes(c->dtype);
     const size_t rb = static_cast<size_t>(c->dims[layer]) * es;
     const int64_t pitch = c->pitch[layer];
@@ -402,6 +428,7 @@ extern "C" int capgnn_cache_fill(capgnn_cache *c, int layer, const void *rows, i
     CG_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
     if (c->cap_gpu > 0)
         CG_HIP(hipMemcpy(c->gpu_tier + c->gpu_off[layer], pack.data(), pack.size(), hipMemcpyHostToDevice));
+    c->staged_valid[layer] = 0;      // rows prefetched for the next epoch are out of date now
     return CAPGNN_OK;
 }
 

@@ -106,7 +106,11 @@ struct capgnn_cache {
     int64_t *counters_d = nullptr;      // [4] hits, misses, absent
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     std::vector<hipEvent_t> ev_layer;   // one per layer: host-tier rows of that layer have landed
-    int miss_mode = CAPGNN_MISS_ZEROCOPY;
+    std::vector<hipEvent_t> ev_consumed;  // one per layer: the layer's staging area has been scattered (pipelined mode)
+    std::vector<uint8_t> staged_valid;  // pipelined mode: staging area of layer l holds rows copied for the next epoch
+    void *staged_base = nullptr;        // ... inside this staging area
+    hipStream_t last_side = nullptr;    // stream that may still carry such a copy
+    int miss_mode = CAPGNN_MISS_STAGED;
     std::vector<void *> dev_allocs;
 };
 
@@ -147,5 +151,8 @@ uint64_t hash_gid(uint64_t x);
 // full-batch gather of one layer's halo rows, one tier at a time (used by the epoch's two-stream schedule)
 int gather_all_hits(const capgnn_cache *c, int layer, void *out, int64_t ld, hipStream_t st);
 int gather_all_misses(const capgnn_cache *c, int layer, void *out, int64_t ld, void *staging, hipStream_t st);
+// the two halves of the staged path: DMA of the layer's host tier into the staging area, scatter from there
+int stage_misses(const capgnn_cache *c, int layer, void *staging, hipStream_t st);
+int scatter_staged(const capgnn_cache *c, int layer, void *out, int64_t ld, void *staging, hipStream_t st);
 
 }  // namespace capgnn

@@ -274,7 +274,7 @@ static int plan_epoch(const capgnn_graph *g, const capgnn_cache *c, const capgnn
     p->layer_ws_off = take(lws);
     p->loss_ws_off = take(capgnn_loss_workspace_bytes(g->n_loc));
     p->loss_val_off = take(256);
-    if (c && c->miss_mode == CAPGNN_MISS_STAGED) {
+    if (c && c->miss_mode != CAPGNN_MISS_ZEROCOPY) {
         size_t hb = 0;
         for (int l = 0; l < c->n_layers; ++l) hb += align_up(static_cast<size_t>(c->n_host) * c->pitch[l], 256);
         p->staging_off = take(hb);
@@ -386,7 +386,7 @@ extern "C" int capgnn_epoch(const capgnn_graph *g, capgnn_cache *c, const capgnn
     const int C = layers[L - 1].f_out;
     float *Z = reinterpret_cast<float *>(w + p.logits_off);   // padded pitch keeps the vector paths usable
     const int64_t ldz = p.ldz;
-    void *staging = (c && c->miss_mode == CAPGNN_MISS_STAGED) ? w + p.staging_off : nullptr;
+    void *staging = (c && c->miss_mode != CAPGNN_MISS_ZEROCOPY) ? w + p.staging_off : nullptr;
     g_rec.reset(times != nullptr);
     hipEvent_t ev_t0 = nullptr, ev_t1 = nullptr;
     if (times) {
@@ -398,13 +398,30 @@ extern "C" int capgnn_epoch(const capgnn_graph *g, capgnn_cache *c, const capgnn
 
     // host-tier rows of every layer start moving now, on the side stream, ahead of the layers that use them
     const bool has_miss = c && c->n_host > 0;
-    if (has_miss) {
-        if (side != st) {
-            CG_HIP(hipEventRecord(c->ev_fork, st));
-            CG_HIP(hipStreamWaitEvent(side, c->ev_fork, 0));
+    // pipelined: the rows were copied into the staging area while the previous epoch ran; each area is
+    // refilled for the next epoch as soon as this epoch has scattered it
+    const bool pipelined = has_miss && c->miss_mode == CAPGNN_MISS_PIPELINED && side != st;
+    auto halo_rows = [&](int l) -> char * { return Xl(l) + static_cast<size_t>(g->n_loc) * p.ldx[l] * es; };
+    if (has_miss && side != st) {
+        CG_HIP(hipEventRecord(c->ev_fork, st));
+        CG_HIP(hipStreamWaitEvent(side, c->ev_fork, 0));
+        c->last_side = side;
+        if (pipelined) {
+            if (c->staged_base != staging) {
+                std::fill(c->staged_valid.begin(), c->staged_valid.end(), 0);
+                c->staged_base = staging;
+            }
+            for (int l = 0; l < L; ++l) {
+                if (c->staged_valid[l]) continue;
+                Scope s(CAPGNN_K_GATHER_MISS, l, 0, side);     // cold start: nothing was prefetched for this layer
+                CG_TRY(stage_misses(c, l, staging, side));
+                CG_HIP(hipEventRecord(c->ev_layer[l], side));
+                c->staged_valid[l] = 1;
+            }
+        } else {
             for (int l = 0; l < L; ++l) {
                 Scope s(CAPGNN_K_GATHER_MISS, l, 0, side);
-                CG_TRY(gather_all_misses(c, l, Xl(l) + static_cast<size_t>(g->n_loc) * p.ldx[l] * es, p.ldx[l], staging, side));
+                CG_TRY(gather_all_misses(c, l, halo_rows(l), p.ldx[l], staging, side));
                 if (!g_rec.on) CG_HIP(hipEventRecord(c->ev_layer[l], side));
             }
         }
@@ -412,13 +429,24 @@ extern "C" int capgnn_epoch(const capgnn_graph *g, capgnn_cache *c, const capgnn
     // forward
     for (int l = 0; l < L; ++l) {
         char *X = Xl(l);
-        char *halo = X + static_cast<size_t>(g->n_loc) * p.ldx[l] * es;
+        char *halo = halo_rows(l);
         if (c) {
             {
                 Scope s(CAPGNN_K_GATHER_HIT, l, 0, st);
                 CG_TRY(gather_all_hits(c, l, halo, p.ldx[l], st));
             }
-            if (has_miss) {
+            if (pipelined) {
+                CG_HIP(hipStreamWaitEvent(st, c->ev_layer[l], 0));
+                {
+                    Scope s(CAPGNN_K_GATHER_HIT, l, 0, st);    // a device copy, like the GPU tier's
+                    CG_TRY(scatter_staged(c, l, halo, p.ldx[l], staging, st));
+                }
+                CG_HIP(hipEventRecord(c->ev_consumed[l], st));
+                CG_HIP(hipStreamWaitEvent(side, c->ev_consumed[l], 0));
+                Scope s(CAPGNN_K_GATHER_MISS, l, 0, side);     // the next epoch's rows of this layer
+                CG_TRY(stage_misses(c, l, staging, side));
+                CG_HIP(hipEventRecord(c->ev_layer[l], side));
+            } else if (has_miss) {
                 if (side != st) {
                     if (g_rec.on) {
                         // the recorder's stop event of this layer's transfer doubles as the join point

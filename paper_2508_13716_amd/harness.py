@@ -77,10 +77,11 @@ def padded_matrix(a: np.ndarray, ld: int, rows: Optional[int] = None):
 class DeviceProblem:
     """Library handles + device buffers for one Problem."""
 
-    def __init__(self, prob: Problem, orders: Optional[List[int]] = None, miss_mode: int = B.MISS_ZEROCOPY,
+    def __init__(self, prob: Problem, orders: Optional[List[int]] = None, miss_mode: int = B.MISS_STAGED,
                  map_kind: int = B.MAP_DIRECT, use_side_stream: bool = True):
         torch = _torch()
         self.prob = prob
+        self.miss_mode = miss_mode
         cfg, part = prob.cfg, prob.part
         self.dtype = B.BF16 if cfg.dtype == "bf16" else B.F32
         self.es = 2 if self.dtype == B.BF16 else 4
@@ -161,6 +162,7 @@ class DeviceProblem:
                 "db": [dev_to_np(t) for t in self.dbias]}
 
     def close(self):
+        _torch().cuda.synchronize()     # a pipelined epoch may have left a prefetch into the workspace in flight
         if self.cache is not None:
             self.cache.close()
         self.graph.close()

@@ -48,7 +48,7 @@ def compare_epoch(env, prob, dp, ref, loss, tol, tag, **oracle_kw):
 
 
 @pytest.mark.parametrize("orders", ["auto", "agg", "xform"])
-@pytest.mark.parametrize("miss_mode", [0, 1])
+@pytest.mark.parametrize("miss_mode", [0, 1, 2])
 def test_epoch_config1_matches_oracle(env, orders, miss_mode):
     B, H, O = env["B"], env["H"], env["O"]
     import copy
@@ -58,7 +58,7 @@ def test_epoch_config1_matches_oracle(env, orders, miss_mode):
     ords = None if orders == "auto" else [B.AGG_FIRST if orders == "agg" else B.XFORM_FIRST] * 2
     dp = H.DeviceProblem(prob, orders=ords, miss_mode=miss_mode)
     ref = O.oracle_epoch(prob)
-    for rep in range(2):                                # second run: buffers are reused, result unchanged
+    for rep in range(3 if miss_mode == 2 else 2):       # later runs: buffers (and prefetched rows) are reused
         loss, _ = dp.run_epoch()
         compare_epoch(env, prob, dp, ref, loss, TOL["f32"], f"C1 {orders} miss_mode={miss_mode} rep={rep}")
     dp.close()
@@ -82,6 +82,28 @@ def test_epoch_scaled_configs_match_oracle(env, name, scale):
     compare_epoch(env, prob, dp2, ref, loss2, TOL[cfg.dtype], cfg.name + " single-stream, mixed orders")
     dp.close()
     dp2.close()
+
+
+def test_epoch_pipelined_host_tier_sees_refilled_tables(env):
+    """Pipelined mode copies the host tier for the next epoch while the current one runs.  Every epoch must
+    still consume exactly the tables last loaded: after capgnn_cache_fill the prefetched rows are dropped."""
+    B, H, O = env["B"], env["H"], env["O"]
+    cfg = synth.CONFIGS["C3"].scaled(0.01)
+    prob = H.make_problem(cfg, mask_frac=0.5)
+    dp = H.DeviceProblem(prob, miss_mode=B.MISS_PIPELINED)
+    ref = O.oracle_epoch(prob)
+    for rep in range(3):
+        loss, times = dp.run_epoch(want_times=(rep == 1))
+        compare_epoch(env, prob, dp, ref, loss, TOL["f32"], f"pipelined rep={rep}")
+    for l in (1, 0):
+        prob.tables[l] = synth.make_features(prob.part.n_halo, cfg.dims[l], seed=991, stream=70 + l, dtype=cfg.dtype)
+        dp.cache.fill(l, prob.tables[l])
+    ref2 = O.oracle_epoch(prob)
+    assert O.normwise(ref2["logits"], ref["logits"]) > 1e-2          # the new tables do change the result
+    for rep in range(2):
+        loss, _ = dp.run_epoch()
+        compare_epoch(env, prob, dp, ref2, loss, TOL["f32"], f"pipelined after refill rep={rep}")
+    dp.close()
 
 
 @pytest.mark.parametrize("kind", ["gcn", "sage"])
