@@ -67,6 +67,43 @@ __device__ __forceinline__ float4 load4(const char *base, int64_t off, int nvali
     return r;
 }
 
+// Writes one wave's TM x TN grid of 32x32 accumulator tiles (top-left corner (row0, col0)) with the epilogue.
+// D layout of the 32x32 MFMAs: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+template <int TM, int TN>
+__device__ __forceinline__ void store_tile(const GemmArgs &g, const floatx16 (&acc)[TM][TN], int64_t row0, int64_t col0,
+                                           int l32, int half) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int64_t col = col0 + j * 32 + l32;
+            if (col >= g.N) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = row0 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (row >= g.M) continue;
+                float v = acc[i][j][r];
+                if (g.part) {
+                    g.part[(static_cast<int64_t>(blockIdx.z) * g.M + row) * g.N + col] = v;
+                    continue;
+                }
+                if (g.accumulate) {
+                    v += g.out_bf16 ? __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t *>(g.C)[row * g.ldc + col]) << 16)
+                                    : reinterpret_cast<const float *>(g.C)[row * g.ldc + col];
+                }
+                if (g.bias) v += g.bias[col];
+                if (g.relu) v = v > 0.f ? v : 0.f;
+                if (g.mask) {
+                    const float mv = g.mask_bf16 ? __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t *>(g.mask)[row * g.ldm + col]) << 16)
+                                                 : reinterpret_cast<const float *>(g.mask)[row * g.ldm + col];
+                    if (!(mv > 0.f)) v = 0.f;
+                }
+                if (g.out_bf16) reinterpret_cast<uint16_t *>(g.C)[row * g.ldc + col] = static_cast<uint16_t>(f32_to_bf16_rne(v));
+                else reinterpret_cast<float *>(g.C)[row * g.ldc + col] = v;
+            }
+        }
+}
+
 constexpr int BK = 16;
 constexpr int PAD = 4;
 
@@ -177,68 +214,186 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
         __syncthreads();
     }
 
-    // D layout of the 32x32 MFMA: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
+    store_tile<TM, TN>(g, acc, m0 + wm * WM, n0 + wn * WN, l32, half);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// bf16 operands on the bf16 matrix cores (v_mfma_f32_32x32x16_bf16: lane l supplies A[i = l%32][k = 8*(l/32) ..+7]
+// and B[k = 8*(l/32) ..+7][j = l%32], eight consecutive k per lane).  Both operand tiles are kept in LDS with
+// the reduction index contiguous (S[row][k], 32 k per step, rows padded to 80 bytes so the 16-byte operand
+// reads of 8 neighbouring lanes fall into distinct banks).  An operand stored with the reduction index
+// contiguous is moved with 16-byte loads and stores; one stored the other way (the vertex dimension of the
+// weight gradient) is loaded 16 bytes along its rows and transposed by 2-byte LDS stores.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+constexpr int HBK = 32;            // k per step of the bf16 kernel
+constexpr int HPAD = 8;            // bf16 elements of row padding
+
+template <bool KC, int BT>
+struct HalfTileLoader {
+    static constexpr int NLD = BT * HBK / 8 / 256;   // 16-byte chunks per thread
+    uint4 r[NLD];
+
+    // eight consecutive bf16 starting at element `off`; only the first nvalid are read
+    static __device__ __forceinline__ uint4 load8(const char *base, int64_t off, int nvalid) {
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (nvalid <= 0) return v;
+        const uint16_t *p = reinterpret_cast<const uint16_t *>(base) + off;
+        if (nvalid >= 8) return *reinterpret_cast<const uint4 *>(p);
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        for (int e = 0; e < nvalid; ++e) w[e >> 1] |= static_cast<uint32_t>(p[e]) << (16 * (e & 1));
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    }
+
+    __device__ __forceinline__ void fetch(const char *base, int64_t ld, int64_t t0, int64_t T, int64_t k0, int64_t k_end,
+                                          int tid) {
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const int idx = tid + 256 * q;
+            if constexpr (KC) {
+                const int row = idx >> 2, kq = idx & 3;
+                const int64_t t = t0 + row, k = k0 + 8 * kq;
+                const int nv = (t < T) ? static_cast<int>(k_end - k < 8 ? k_end - k : 8) : 0;
+                r[q] = load8(base, t * ld + k, nv);
+            } else {
+                constexpr int CPR = BT / 8;
+                const int kk = idx / CPR, tq = idx % CPR;
+                const int64_t k = k0 + kk, t = t0 + 8 * tq;
+                const int nv = (k < k_end) ? static_cast<int>(T - t < 8 ? T - t : 8) : 0;
+                r[q] = load8(base, k * ld + t, nv);
+            }
+        }
+    }
+
+    __device__ __forceinline__ void stash(uint16_t (*s)[HBK + HPAD], int tid) const {
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const int idx = tid + 256 * q;
+            if constexpr (KC) {
+                const int row = idx >> 2, kq = idx & 3;
+                *reinterpret_cast<uint4 *>(&s[row][8 * kq]) = r[q];
+            } else {
+                constexpr int CPR = BT / 8;
+                const int kk = idx / CPR, tq = idx % CPR;
+                const uint32_t w[4] = {r[q].x, r[q].y, r[q].z, r[q].w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s[8 * tq + e][kk] = static_cast<uint16_t>(w[e >> 1] >> (16 * (e & 1)));
+            }
+        }
+    }
+};
+
+template <bool A_KC, bool B_KC, int BM, int BN>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
+    constexpr int WM = BM / 2, WN = BN / 2;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][BM][HBK + HPAD];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN][HBK + HPAD];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int64_t m0 = static_cast<int64_t>(blockIdx.y) * BM;
+    const int64_t n0 = static_cast<int64_t>(blockIdx.x) * BN;
+    const int64_t k_begin = static_cast<int64_t>(blockIdx.z) * g.k_chunk;
+    const int64_t k_end = (k_begin + g.k_chunk < g.K) ? k_begin + g.k_chunk : g.K;
+
+    floatx16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int64_t col = n0 + wn * WN + j * 32 + l32;
-            if (col >= g.N) continue;
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t row = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                if (row >= g.M) continue;
-                float v = acc[i][j][r];
-                if (g.part) {
-                    g.part[(static_cast<int64_t>(blockIdx.z) * g.M + row) * g.N + col] = v;
-                    continue;
-                }
-                if (g.accumulate) {
-                    v += g.out_bf16 ? __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t *>(g.C)[row * g.ldc + col]) << 16)
-                                    : reinterpret_cast<const float *>(g.C)[row * g.ldc + col];
-                }
-                if (g.bias) v += g.bias[col];
-                if (g.relu) v = v > 0.f ? v : 0.f;
-                if (g.mask) {
-                    const float mv = g.mask_bf16 ? __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t *>(g.mask)[row * g.ldm + col]) << 16)
-                                                 : reinterpret_cast<const float *>(g.mask)[row * g.ldm + col];
-                    if (!(mv > 0.f)) v = 0.f;
-                }
-                if (g.out_bf16) reinterpret_cast<uint16_t *>(g.C)[row * g.ldc + col] = static_cast<uint16_t>(f32_to_bf16_rne(v));
-                else reinterpret_cast<float *>(g.C)[row * g.ldc + col] = v;
-            }
-        }
-}
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-// Sums the split partials in order z = 0..S-1 and applies the epilogue.
-__global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmArgs g, int S) {
-    const int64_t total = g.M * g.N;
-    for (int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; t < total;
-         t += static_cast<int64_t>(gridDim.x) * 256) {
-        const int64_t row = t / g.N, col = t % g.N;
-        float v = 0.f;
-        for (int z = 0; z < S; ++z) v += g.part[static_cast<int64_t>(z) * total + t];
-        if (g.accumulate) {
-            v += g.out_bf16 ? __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t *>(g.C)[row * g.ldc + col]) << 16)
-                            : reinterpret_cast<const float *>(g.C)[row * g.ldc + col];
-        }
-        if (g.bias) v += g.bias[col];
-        if (g.relu) v = v > 0.f ? v : 0.f;
-        if (g.mask) {
-            const float mv = g.mask_bf16 ? __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t *>(g.mask)[row * g.ldm + col]) << 16)
-                                         : reinterpret_cast<const float *>(g.mask)[row * g.ldm + col];
-            if (!(mv > 0.f)) v = 0.f;
-        }
-        if (g.out_bf16) reinterpret_cast<uint16_t *>(g.C)[row * g.ldc + col] = static_cast<uint16_t>(f32_to_bf16_rne(v));
-        else reinterpret_cast<float *>(g.C)[row * g.ldc + col] = v;
+    HalfTileLoader<A_KC, BM> la;
+    HalfTileLoader<B_KC, BN> lb;
+    const int64_t nk = (k_end > k_begin) ? (k_end - k_begin + HBK - 1) / HBK : 0;
+    if (nk > 0) {
+        la.fetch(g.A, g.lda, m0, g.M, k_begin, k_end, tid);
+        lb.fetch(g.B, g.ldb, n0, g.N, k_begin, k_end, tid);
+        la.stash(As[0], tid);
+        lb.stash(Bs[0], tid);
     }
+    __syncthreads();
+    for (int64_t kt = 0; kt < nk; ++kt) {
+        const int buf = static_cast<int>(kt & 1);
+        const bool more = kt + 1 < nk;
+        if (more) {
+            la.fetch(g.A, g.lda, m0, g.M, k_begin + (kt + 1) * HBK, k_end, tid);
+            lb.fetch(g.B, g.ldb, n0, g.N, k_begin + (kt + 1) * HBK, k_end, tid);
+        }
+#pragma unroll
+        for (int ks = 0; ks < HBK; ks += 16) {
+            bf16x8 a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&As[buf][wm * WM + i * 32 + l32][ks + 8 * half]));
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&Bs[buf][wn * WN + j * 32 + l32][ks + 8 * half]));
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) {
+            la.stash(As[buf ^ 1], tid);
+            lb.stash(Bs[buf ^ 1], tid);
+        }
+        __syncthreads();
+    }
+    store_tile<TM, TN>(g, acc, m0 + wm * WM, n0 + wn * WN, l32, half);
 }
 
-static int choose_split(int trans_a, int64_t M, int64_t N, int64_t K, int bm, int bn) {
+// Lays the (small) second operand of a product out as Wt[n][k], k contiguous, rows padded to 16 bytes, for the
+// bf16 kernel.  kc: the source already is [n][k] (pitch ldw), else it is [k][n].
+__global__ __launch_bounds__(256) void repack_bf16_kernel(const uint16_t *W, int64_t ldw, int kc, int64_t K, int64_t N,
+                                                          uint16_t *Wt, int64_t ldt) {
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (t >= N * ldt) return;
+    const int64_t n = t / ldt, k = t % ldt;
+    Wt[t] = k < K ? (kc ? W[n * ldw + k] : W[k * ldw + n]) : static_cast<uint16_t>(0);
+}
+
+// Sums the split partials and applies the epilogue.  A workgroup covers 32 consecutive output elements with 8
+// groups of threads; group y adds the partials z = y, y+8, ... in that order, then the 8 group sums are added
+// in group order: a fixed summation order, whatever the launch geometry.
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmArgs g, int S) {
+    __shared__ float red[8][32];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int64_t total = g.M * g.N;
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 32 + tx;
+    float v = 0.f;
+    if (t < total)
+        for (int z = ty; z < S; z += 8) v += g.part[static_cast<int64_t>(z) * total + t];
+    red[ty][tx] = v;
+    __syncthreads();
+    if (ty != 0 || t >= total) return;
+    v = 0.f;
+    for (int y = 0; y < 8; ++y) v += red[y][tx];
+    const int64_t row = t / g.N, col = t % g.N;
+    if (g.accumulate) {
+        v += g.out_bf16 ? __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t *>(g.C)[row * g.ldc + col]) << 16)
+                        : reinterpret_cast<const float *>(g.C)[row * g.ldc + col];
+    }
+    if (g.bias) v += g.bias[col];
+    if (g.relu) v = v > 0.f ? v : 0.f;
+    if (g.mask) {
+        const float mv = g.mask_bf16 ? __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t *>(g.mask)[row * g.ldm + col]) << 16)
+                                     : reinterpret_cast<const float *>(g.mask)[row * g.ldm + col];
+        if (!(mv > 0.f)) v = 0.f;
+    }
+    if (g.out_bf16) reinterpret_cast<uint16_t *>(g.C)[row * g.ldc + col] = static_cast<uint16_t>(f32_to_bf16_rne(v));
+    else reinterpret_cast<float *>(g.C)[row * g.ldc + col] = v;
+}
+
+static int choose_split(int trans_a, int64_t M, int64_t N, int64_t K, int bm, int bn, int bk) {
     if (!trans_a) return 1;
     const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
     int64_t s = 1536 / (tiles > 0 ? tiles : 1);
-    const int64_t max_by_k = K / (BK * 16) > 0 ? K / (BK * 16) : 1;   // at least 16 k-steps per split
+    const int64_t max_by_k = K / (bk * 16) > 0 ? K / (bk * 16) : 1;   // at least 16 k-steps per split
     if (s > max_by_k) s = max_by_k;
     if (s > 512) s = 512;
     if (s < 1) s = 1;
@@ -250,17 +405,30 @@ static void tile_for(int64_t N, int *bm, int *bn) {
     *bn = (N <= 64) ? 64 : 128;
 }
 
+static size_t transposed_b_bytes(int64_t N, int64_t K) {
+    return align_up(static_cast<size_t>(N) * ((K + 7) / 8 * 8) * sizeof(uint16_t), 256);
+}
+
 size_t gemm_ws_bytes(int trans_a, int64_t M, int64_t N, int64_t K) {
     int bm, bn;
     tile_for(N, &bm, &bn);
-    const int s = choose_split(trans_a, M, N, K, bm, bn);
-    return s > 1 ? align_up(static_cast<size_t>(s) * M * N * sizeof(float), 256) : 0;
+    // the larger split of the two kernels (they step through K in 16s and 32s)
+    const int s = std::max(choose_split(trans_a, M, N, K, bm, bn, BK), choose_split(trans_a, M, N, K, bm, bn, HBK));
+    size_t b = s > 1 ? align_up(static_cast<size_t>(s) * M * N * sizeof(float), 256) : 0;
+    if (!trans_a) b = std::max(b, transposed_b_bytes(N, K));    // room to lay a bf16 weight out for the bf16 kernel
+    return b;
 }
 
 template <bool BF16, bool A_KC, bool B_KC>
 static void launch_tiles(const GemmArgs &g, int bn, dim3 grid, hipStream_t st) {
     if (bn == 64) hipLaunchKernelGGL((gemm_kernel<BF16, A_KC, B_KC, 128, 64>), grid, dim3(256), 0, st, g);
     else hipLaunchKernelGGL((gemm_kernel<BF16, A_KC, B_KC, 128, 128>), grid, dim3(256), 0, st, g);
+}
+
+template <bool A_KC, bool B_KC>
+static void launch_bf16_tiles(const GemmArgs &g, int bn, dim3 grid, hipStream_t st) {
+    if (bn == 64) hipLaunchKernelGGL((gemm_bf16_kernel<A_KC, B_KC, 128, 64>), grid, dim3(256), 0, st, g);
+    else hipLaunchKernelGGL((gemm_bf16_kernel<A_KC, B_KC, 128, 128>), grid, dim3(256), 0, st, g);
 }
 
 int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
@@ -277,7 +445,13 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
     const int es = elem_bytes(dtype);
     int bm, bn;
     tile_for(N, &bm, &bn);
-    const int S = choose_split(trans_a, M, N, K, bm, bn);
+    // bf16 operands whose rows start on 16-byte boundaries run on the bf16 matrix cores; the second operand of a
+    // product with a plain first operand is a weight matrix, small enough to be repacked into the workspace
+    const bool repack_b = dtype == CAPGNN_BF16 && !trans_a && ws && ws_bytes >= transposed_b_bytes(N, K);
+    const bool half_path = dtype == CAPGNN_BF16 && aligned16(A) && (lda * 2) % 16 == 0 &&
+                           (repack_b || (aligned16(B) && (ldb * 2) % 16 == 0));
+    const int bk = half_path ? HBK : BK;
+    const int S = choose_split(trans_a, M, N, K, bm, bn, bk);
     GemmArgs g;
     g.M = M; g.N = N; g.K = K;
     g.A = static_cast<const char *>(A); g.lda = lda;
@@ -295,25 +469,49 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
         const size_t need = static_cast<size_t>(S) * M * N * sizeof(float);
         if (!ws || ws_bytes < need) CG_FAIL(CAPGNN_ENOMEM, "gemm: workspace of %zu bytes needed, %zu given", need, ws_bytes);
         g.part = static_cast<float *>(ws);
-        const int64_t steps = (K + BK - 1) / BK;
-        g.k_chunk = (steps + S - 1) / S * BK;
+        const int64_t steps = (K + bk - 1) / bk;
+        g.k_chunk = (steps + S - 1) / S * bk;
     }
     const int64_t gy = (M + bm - 1) / bm, gx = (N + bn - 1) / bn;
-    if (gy > 65535) CG_FAIL(CAPGNN_EINVAL, "gemm: M=%lld needs more than 65535 row tiles", (long long)M);
+    if (gy > 65535) {
+        // more row tiles than grid.y holds: the caller splits the rows (outputs of different row ranges are independent)
+        if (trans_a) CG_FAIL(CAPGNN_EINVAL, "gemm: M=%lld needs more than 65535 row tiles", (long long)M);
+        const int64_t rows_per = static_cast<int64_t>(65535) * bm;
+        for (int64_t r0 = 0; r0 < M; r0 += rows_per) {
+            const int64_t mr = std::min(rows_per, M - r0);
+            CG_TRY(launch_gemm(0, trans_b, mr, N, K, static_cast<const char *>(A) + r0 * lda * es, lda, B, ldb,
+                               static_cast<char *>(C) + r0 * ldc * (g.out_bf16 ? 2 : 4), ldc, dtype, out_f32, accumulate, bias, relu,
+                               relu_mask ? static_cast<const char *>(relu_mask) + r0 * ldm * es : nullptr, ldm, ws, ws_bytes, stream));
+        }
+        return CAPGNN_OK;
+    }
     dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(S));
-    const bool bf = dtype == CAPGNN_BF16;
-    const bool akc = !trans_a, bkc = trans_b != 0;
+    bool akc = !trans_a, bkc = trans_b != 0;
+    if (half_path) {
+        if (repack_b) {
+            const int64_t ldt = (K + 7) / 8 * 8;
+            hipLaunchKernelGGL(repack_bf16_kernel, dim3(static_cast<unsigned>((N * ldt + 255) / 256)), dim3(256), 0, stream,
+                               static_cast<const uint16_t *>(B), ldb, bkc ? 1 : 0, K, N, static_cast<uint16_t *>(ws), ldt);
+            g.B = static_cast<const char *>(ws); g.ldb = ldt;
+            bkc = true;
+        }
+        if (akc && bkc) launch_bf16_tiles<true, true>(g, bn, grid, stream);
+        else if (akc) launch_bf16_tiles<true, false>(g, bn, grid, stream);
+        else if (bkc) launch_bf16_tiles<false, true>(g, bn, grid, stream);
+        else launch_bf16_tiles<false, false>(g, bn, grid, stream);
+    } else {
+        const bool bf = dtype == CAPGNN_BF16;
 #define CG_GEMM_CASE(BF, AK, BKC_) if (bf == BF && akc == AK && bkc == BKC_) launch_tiles<BF, AK, BKC_>(g, bn, grid, stream);
-    CG_GEMM_CASE(false, true, false) CG_GEMM_CASE(false, true, true)
-    CG_GEMM_CASE(false, false, false) CG_GEMM_CASE(false, false, true)
-    CG_GEMM_CASE(true, true, false) CG_GEMM_CASE(true, true, true)
-    CG_GEMM_CASE(true, false, false) CG_GEMM_CASE(true, false, true)
+        CG_GEMM_CASE(false, true, false) CG_GEMM_CASE(false, true, true)
+        CG_GEMM_CASE(false, false, false) CG_GEMM_CASE(false, false, true)
+        CG_GEMM_CASE(true, true, false) CG_GEMM_CASE(true, true, true)
+        CG_GEMM_CASE(true, false, false) CG_GEMM_CASE(true, false, true)
 #undef CG_GEMM_CASE
+    }
     CG_HIP(hipGetLastError());
     if (S > 1) {
         const int64_t total = M * N;
-        const unsigned blocks = static_cast<unsigned>(std::min<int64_t>((total + 255) / 256, 4096));
-        hipLaunchKernelGGL(gemm_reduce_kernel, dim3(blocks), dim3(256), 0, stream, g, S);
+        hipLaunchKernelGGL(gemm_reduce_kernel, dim3(static_cast<unsigned>((total + 31) / 32)), dim3(256), 0, stream, g, S);
         CG_HIP(hipGetLastError());
     }
     return CAPGNN_OK;

@@ -91,15 +91,22 @@ static size_t fwd_t_bytes(const capgnn_graph *g, const capgnn_layer *l, int orde
     return align_up(static_cast<size_t>(g->n_cols) * pad_ld(l->f_out, l->dtype) * elem_bytes(l->dtype), 256);
 }
 
+// scratch of the transform GEMMs (the bf16 kernel lays the weight out with the reduction index contiguous)
+static size_t fwd_g_bytes(const capgnn_graph *g, const capgnn_layer *l) {
+    return gemm_ws_bytes(0, g->n_cols, l->f_out, l->f_in);
+}
+
 static size_t fwd_ws_bytes(const capgnn_graph *g, const capgnn_layer *l, int order) {
-    return fwd_t_bytes(g, l, order) + spmm_ws_bytes(g->fwd, order == CAPGNN_AGG_FIRST ? l->f_in : l->f_out, l->dtype);
+    return fwd_t_bytes(g, l, order) + fwd_g_bytes(g, l) +
+           spmm_ws_bytes(g->fwd, order == CAPGNN_AGG_FIRST ? l->f_in : l->f_out, l->dtype);
 }
 
 static size_t bwd_ws_bytes(const capgnn_graph *g, const capgnn_layer *l, int order) {
     const int es = elem_bytes(l->dtype);
     size_t b = relu_bias_ws_bytes(g->n_loc, l->f_out);
     const int64_t red_rows = order == CAPGNN_AGG_FIRST ? g->n_loc : g->n_cols;
-    b += std::max(gemm_ws_bytes(1, l->f_in, l->f_out, red_rows), gemm_ws_bytes(1, l->f_in, l->f_out, g->n_loc));
+    b += std::max(std::max(gemm_ws_bytes(1, l->f_in, l->f_out, red_rows), gemm_ws_bytes(1, l->f_in, l->f_out, g->n_loc)),
+                  gemm_ws_bytes(0, g->n_cols, l->f_in, l->f_out));
     if (order == CAPGNN_AGG_FIRST) b += align_up(static_cast<size_t>(g->n_loc) * pad_ld(l->f_in, l->dtype) * es, 256);
     else b += align_up(static_cast<size_t>(g->n_cols) * pad_ld(l->f_out, l->dtype) * es, 256);
     b += spmm_ws_bytes(g->bwd, order == CAPGNN_AGG_FIRST ? l->f_in : l->f_out, l->dtype);
@@ -119,16 +126,21 @@ static int layer_fwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
         {
             Scope s(CAPGNN_K_SPMM_FWD, li, 0, st);
             SpmmEpilogue ep;
-            ep.ws = ws; ep.ws_bytes = ws ? ws_bytes : 0;
+            if (ws && ws_bytes >= fwd_ws_bytes(g, l, order)) {
+                ep.ws = static_cast<char *>(ws) + fwd_g_bytes(g, l);
+                ep.ws_bytes = ws_bytes - fwd_g_bytes(g, l);
+            }
             CG_TRY(launch_spmm(g->fwd, false, X, ldx, saved, ldm, l->f_in, dt, ep, st));
         }
         Scope s(CAPGNN_K_GEMM, li, 0, st);
+        void *gws = (ws && ws_bytes >= fwd_g_bytes(g, l)) ? ws : nullptr;
+        const size_t gwb = gws ? fwd_g_bytes(g, l) : 0;
         if (sage) {
             CG_TRY(launch_gemm(0, 0, g->n_loc, l->f_out, l->f_in, X, ldx, l->W_self, l->f_out, H, ldh, dt, l->out_f32, 0,
-                               nullptr, 0, nullptr, 0, nullptr, 0, st));
+                               nullptr, 0, nullptr, 0, gws, gwb, st));
         }
         CG_TRY(launch_gemm(0, 0, g->n_loc, l->f_out, l->f_in, saved, ldm, l->W, l->f_out, H, ldh, dt, l->out_f32,
-                           sage ? 1 : 0, l->bias, relu, nullptr, 0, nullptr, 0, st));
+                           sage ? 1 : 0, l->bias, relu, nullptr, 0, gws, gwb, st));
         return CAPGNN_OK;
     }
     // XFORM_FIRST
@@ -138,17 +150,18 @@ static int layer_fwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
     (void)es;
     {
         Scope s(CAPGNN_K_GEMM, li, 0, st);
+        void *gws = static_cast<char *>(ws) + fwd_t_bytes(g, l, order);
         CG_TRY(launch_gemm(0, 0, g->n_cols, l->f_out, l->f_in, X, ldx, l->W, l->f_out, ws, ldt, dt, 0, 0, nullptr, 0,
-                           nullptr, 0, nullptr, 0, st));
+                           nullptr, 0, gws, fwd_g_bytes(g, l), st));
         if (sage)
             CG_TRY(launch_gemm(0, 0, g->n_loc, l->f_out, l->f_in, X, ldx, l->W_self, l->f_out, H, ldh, dt, l->out_f32, 0,
-                               nullptr, 0, nullptr, 0, nullptr, 0, st));
+                               nullptr, 0, nullptr, 0, gws, fwd_g_bytes(g, l), st));
     }
     Scope s(CAPGNN_K_SPMM_FWD, li, 0, st);
     SpmmEpilogue ep;
     ep.bias = l->bias; ep.relu = relu; ep.accumulate = sage ? 1 : 0; ep.out_f32 = l->out_f32;
-    ep.ws = static_cast<char *>(ws) + fwd_t_bytes(g, l, order);
-    ep.ws_bytes = ws_bytes - fwd_t_bytes(g, l, order);
+    ep.ws = static_cast<char *>(ws) + fwd_t_bytes(g, l, order) + fwd_g_bytes(g, l);
+    ep.ws_bytes = ws_bytes - fwd_t_bytes(g, l, order) - fwd_g_bytes(g, l);
     CG_TRY(launch_spmm(g->fwd, false, ws, ldt, H, ldh, l->f_out, dt, ep, st));
     return CAPGNN_OK;
 }
@@ -169,7 +182,8 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
     const size_t rb = relu_bias_ws_bytes(g->n_loc, l->f_out);
     w += rb;
     const int64_t red_rows = order == CAPGNN_AGG_FIRST ? g->n_loc : g->n_cols;
-    const size_t gw = std::max(gemm_ws_bytes(1, l->f_in, l->f_out, red_rows), gemm_ws_bytes(1, l->f_in, l->f_out, g->n_loc));
+    const size_t gw = std::max(std::max(gemm_ws_bytes(1, l->f_in, l->f_out, red_rows), gemm_ws_bytes(1, l->f_in, l->f_out, g->n_loc)),
+                               gemm_ws_bytes(0, g->n_cols, l->f_in, l->f_out));
     void *ws_gemm = w;
     w += gw;
     void *tmp = w;   // dM (AGG_FIRST) or dT (XFORM_FIRST)
@@ -198,7 +212,7 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
                 CG_TRY(launch_gemm(1, 0, l->f_in, l->f_out, g->n_loc, X, ldx, dH, lddh, dW_self, l->f_out, dt, 1, 0,
                                    nullptr, 0, nullptr, 0, ws_gemm, gw, st));
             if (dX) CG_TRY(launch_gemm(0, 1, g->n_loc, l->f_in, l->f_out, dH, lddh, l->W, l->f_out, tmp, ldm, dt, 0, 0,
-                                       nullptr, 0, nullptr, 0, nullptr, 0, st));
+                                       nullptr, 0, nullptr, 0, ws_gemm, gw, st));
         }
         if (dX) {
             {
@@ -208,7 +222,7 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
             if (sage) {
                 Scope s(CAPGNN_K_GEMM, li, 1, st);
                 CG_TRY(launch_gemm(0, 1, g->n_loc, l->f_in, l->f_out, dH, lddh, l->W_self, l->f_out, dX, lddx, dt, 0, 1,
-                                   nullptr, 0, nullptr, 0, nullptr, 0, st));
+                                   nullptr, 0, nullptr, 0, ws_gemm, gw, st));
             }
         }
         return CAPGNN_OK;
@@ -229,10 +243,10 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
     if (dX) {
         const int64_t rows = need_halo_grad ? g->n_cols : g->n_loc;
         CG_TRY(launch_gemm(0, 1, rows, l->f_in, l->f_out, tmp, ldt, l->W, l->f_out, dX, lddx, dt, 0, 0, nullptr, 0,
-                           nullptr, 0, nullptr, 0, st));
+                           nullptr, 0, ws_gemm, gw, st));
         if (sage)
             CG_TRY(launch_gemm(0, 1, g->n_loc, l->f_in, l->f_out, dH, lddh, l->W_self, l->f_out, dX, lddx, dt, 0, 1,
-                               nullptr, 0, nullptr, 0, nullptr, 0, st));
+                               nullptr, 0, nullptr, 0, ws_gemm, gw, st));
     }
     return CAPGNN_OK;
 }

@@ -294,6 +294,43 @@ def test_gemm_vs_oracle(env, dtype, ta, tb):
             assert O.normwise(O.widen(H.dev_to_np(Cd2))[:, :N], ref2) <= tol
 
 
+@pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_gemm_bf16_matrix_core_path(env, ta, tb):
+    """bf16 operands with 16-byte aligned rows take the bf16 MFMA kernel (weights of plain products are
+    repacked, so their pitch may be anything).  Small-integer operands make every product and partial sum
+    exactly representable: the result must equal the oracle exactly, which pins the operand lane layout;
+    random operands are compared within the bf16 tolerance.  Sizes span several tiles and ragged tails."""
+    torch, B, H, O, orc = env["torch"], env["B"], env["H"], env["O"], env["orc"]
+    rng = np.random.default_rng(10 + ta * 2 + tb)
+    for (M, N, K) in [(333, 47, 256), (130, 256, 40), (257, 130, 1000), (64, 64, 32), (500, 41, 4100)]:
+        for ints in (True, False):
+            say(f"gemm bf16 mfma ta={ta} tb={tb} M={M} N={N} K={K} ints={ints}")
+            shapeA, shapeB = ((K, M) if ta else (M, K)), ((N, K) if tb else (K, N))
+            if ints:
+                A = rng.integers(-2, 3, shapeA).astype(np.float32)
+                Bm = rng.integers(-2, 3, shapeB).astype(np.float32)
+            else:
+                A = rng.standard_normal(shapeA).astype(np.float32)
+                Bm = rng.standard_normal(shapeB).astype(np.float32)
+            A, Bm = synth.f32_to_bf16_rne(A).reshape(A.shape), synth.f32_to_bf16_rne(Bm).reshape(Bm.shape)
+            ref = orc.matmul(O.widen(A), O.widen(Bm), ta=bool(ta), tb=bool(tb))
+            lda = synth.pad_to(A.shape[1], 8)
+            ldb = synth.pad_to(Bm.shape[1], 8) if ta else Bm.shape[1] + 1     # a weight's pitch is free
+            ldc = N + 3
+            Ad, Bd = H.padded_matrix(A, lda), H.padded_matrix(Bm, ldb)
+            wsb = B.gemm_workspace_bytes(ta, M, N, K)
+            ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+            Cd = torch.full((M, ldc), 2.0, dtype=torch.float32, device="cuda")
+            B.gemm(ta, tb, M, N, K, Ad, lda, Bd, ldb, Cd, ldc, B.BF16, out_f32=1, ws=ws, ws_bytes=wsb)
+            torch.cuda.synchronize()
+            got = Cd.cpu().numpy()
+            if ints:
+                assert np.array_equal(got[:, :N].astype(np.float64), ref)
+            else:
+                assert O.normwise(got[:, :N], ref) <= TOL_BF16
+            assert (got[:, N:] == 2.0).all()
+
+
 def test_gemm_relu_mask_epilogue(env):
     torch, B, H, O, orc = env["torch"], env["B"], env["H"], env["O"], env["orc"]
     rng = np.random.default_rng(3)
