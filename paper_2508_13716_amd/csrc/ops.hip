@@ -67,6 +67,79 @@ __global__ __launch_bounds__(256) void relu_mask_dbias_kernel(int64_t n, int F, 
     }
 }
 
+__device__ __forceinline__ float4 ld4(const char *p, int64_t i, int bf16) {
+    if (bf16) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(p) + i);
+        return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
+                           __uint_as_float(v.y & 0xffff0000u));
+    }
+    return *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(p) + i);
+}
+
+__device__ __forceinline__ uint32_t bf16_rne_bits(float v) {
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// The same operation with four consecutive features per thread (8- or 16-byte accesses); needs rows that start on
+// 16-byte boundaries.  blockDim = (TX, 256/TX), TX = ceil(F/4) rounded up to a power of two (F <= 1024).
+__global__ __launch_bounds__(256) void relu_mask_dbias_vec4_kernel(int64_t n, int F, const char *src, int64_t lds,
+                                                                   int src_bf16, char *dst, int64_t ldd, int dst_bf16,
+                                                                   const char *H, int64_t ldh, int h_bf16, int relu,
+                                                                   float *partial) {
+    __shared__ float red[256][4];
+    const int tx = threadIdx.x, ty = threadIdx.y, TX = blockDim.x, TY = blockDim.y;
+    const bool in_place = src == dst;
+    const int f = 4 * tx;
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    if (f < F) {
+        const int nv = F - f < 4 ? F - f : 4;    // valid features of this thread's vector (the rest is row padding)
+        for (int64_t r0 = static_cast<int64_t>(blockIdx.x) * RB_ROWS; r0 < n; r0 += static_cast<int64_t>(gridDim.x) * RB_ROWS) {
+            const int64_t r1 = r0 + RB_ROWS < n ? r0 + RB_ROWS : n;
+            for (int64_t r = r0 + ty; r < r1; r += TY) {
+                const float4 gv = ld4(src, r * lds + f, src_bf16);
+                float g[4] = {gv.x, gv.y, gv.z, gv.w};
+                bool zeroed = false;
+                if (relu) {
+                    const float4 hv = ld4(H, r * ldh + f, h_bf16);
+                    const float h[4] = {hv.x, hv.y, hv.z, hv.w};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (!(h[j] > 0.f) && g[j] != 0.f) { g[j] = 0.f; zeroed = true; }
+                }
+                if (!in_place || zeroed) {
+                    if (nv == 4) {
+                        if (dst_bf16) {
+                            uint2 o;
+                            o.x = bf16_rne_bits(g[0]) | (bf16_rne_bits(g[1]) << 16);
+                            o.y = bf16_rne_bits(g[2]) | (bf16_rne_bits(g[3]) << 16);
+                            *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(dst) + r * ldd + f) = o;
+                        } else {
+                            *reinterpret_cast<float4 *>(reinterpret_cast<float *>(dst) + r * ldd + f) = make_float4(g[0], g[1], g[2], g[3]);
+                        }
+                    } else {
+                        for (int j = 0; j < nv; ++j) st_elem(dst, r * ldd + f + j, g[j], dst_bf16);
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) s[j] += g[j];
+            }
+        }
+    }
+    if (!partial) return;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) red[ty * TX + tx][j] = s[j];
+    __syncthreads();
+    if (ty == 0 && f < F) {
+        for (int j = 0; j < 4 && f + j < F; ++j) {
+            float t = 0.f;
+            for (int y = 0; y < TY; ++y) t += red[y * TX + tx][j];
+            partial[static_cast<int64_t>(blockIdx.x) * F + f + j] = t;
+        }
+    }
+}
+
 // dbias[f] = sum_b partial[b][f]: 32 features x 8 strided groups per workgroup, doubles, fixed order
 __global__ __launch_bounds__(256) void dbias_final_kernel(int64_t nblocks, int F, const float *partial, float *dbias) {
     __shared__ double red[8][32];
@@ -112,6 +185,25 @@ int launch_relu_mask_dbias(int64_t n, int F, const void *src, int64_t lds, int s
     const int64_t nb = rb_blocks(n);
     if (dbias && (!ws || ws_bytes < static_cast<size_t>(nb) * F * sizeof(float)))
         CG_FAIL(CAPGNN_ENOMEM, "relu_mask_dbias: workspace too small");
+    const int ses = elem_bytes(src_dtype), des = elem_bytes(dtype), hes = elem_bytes(h_dtype);
+    const bool vec = F <= 1024 && aligned16(src) && aligned16(dH) && (lds * ses) % 16 == 0 && (lddh * des) % 16 == 0 &&
+                     (!relu || (aligned16(H) && (ldh * hes) % 16 == 0));
+    if (vec) {
+        int TX = 1;
+        while (TX < (F + 3) / 4) TX <<= 1;
+        dim3 block(TX, 256 / TX);
+        hipLaunchKernelGGL(relu_mask_dbias_vec4_kernel, dim3(static_cast<unsigned>(nb)), block, 0, stream, n, F,
+                           static_cast<const char *>(src), lds, src_dtype == CAPGNN_BF16 ? 1 : 0, static_cast<char *>(dH), lddh,
+                           dtype == CAPGNN_BF16 ? 1 : 0, static_cast<const char *>(H), ldh, h_dtype == CAPGNN_BF16 ? 1 : 0,
+                           relu, dbias ? static_cast<float *>(ws) : nullptr);
+        CG_HIP(hipGetLastError());
+        if (dbias) {
+            hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 31) / 32), dim3(256), 0, stream, nb, F,
+                               static_cast<const float *>(ws), dbias);
+            CG_HIP(hipGetLastError());
+        }
+        return CAPGNN_OK;
+    }
     int TX = 1;
     while (TX < F && TX < 256) TX <<= 1;
     dim3 block(TX, 256 / TX);
@@ -145,18 +237,37 @@ int launch_sgd(float *W, const float *dW, int64_t n, float lr, hipStream_t strea
 }
 
 // ------------------------------------------------------------------ masked softmax cross-entropy
-// scratch layout: [0] = normaliser (float), [64 ..] = per-row loss terms
-__global__ __launch_bounds__(1024) void count_mask_kernel(int64_t n, const uint8_t *mask, float *norm_out) {
-    __shared__ unsigned long long red[1024];
-    unsigned long long c = 0;
-    for (int64_t i = threadIdx.x; i < n; i += 1024) c += mask[i] ? 1 : 0;
+// scratch layout (bytes): [0] normaliser (float); [256, 256 + 8*LOSS_PARTS) per-workgroup partial sums (double);
+// [LOSS_HEADER ..] per-row loss terms (float).  Both reductions are two-level with fixed summation orders.
+constexpr int LOSS_PARTS = 512;
+constexpr size_t LOSS_HEADER = 8192;
+
+__device__ __forceinline__ double block_sum_1024(double c, double *red) {
     red[threadIdx.x] = c;
     __syncthreads();
     for (int s = 512; s > 0; s >>= 1) {
         if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
         __syncthreads();
     }
-    if (threadIdx.x == 0) norm_out[0] = red[0] > 0 ? static_cast<float>(red[0]) : 1.f;
+    return red[0];
+}
+
+// part[b] = number of masked rows in workgroup b's contiguous slice
+__global__ __launch_bounds__(1024) void count_mask_kernel(int64_t n, const uint8_t *mask, double *part) {
+    __shared__ double red[1024];
+    const int64_t per = (n + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = blockIdx.x * per, hi = lo + per < n ? lo + per : n;
+    double c = 0.0;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += 1024) c += mask[i] ? 1.0 : 0.0;
+    c = block_sum_1024(c, red);
+    if (threadIdx.x == 0) part[blockIdx.x] = c;
+}
+
+__global__ __launch_bounds__(64) void count_final_kernel(int parts, const double *part, float *norm_out) {
+    if (threadIdx.x != 0) return;
+    double c = 0.0;
+    for (int b = 0; b < parts; ++b) c += part[b];
+    norm_out[0] = c > 0.0 ? static_cast<float>(c) : 1.f;
 }
 
 // one wave per row; lanes stride over the classes
@@ -194,21 +305,23 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(int64_t n, int C, const
     }
 }
 
-__global__ __launch_bounds__(1024) void loss_reduce_kernel(int64_t n, const float *row_loss, float norm_val,
-                                                           const float *norm_dev, float *loss_out) {
+__global__ __launch_bounds__(1024) void loss_partial_kernel(int64_t n, const float *row_loss, double *part) {
     __shared__ double red[1024];
+    const int64_t per = (n + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = blockIdx.x * per, hi = lo + per < n ? lo + per : n;
     double c = 0.0;
-    for (int64_t i = threadIdx.x; i < n; i += 1024) c += static_cast<double>(row_loss[i]);
-    red[threadIdx.x] = c;
-    __syncthreads();
-    for (int s = 512; s > 0; s >>= 1) {
-        if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) {
-        const double norm = norm_dev ? static_cast<double>(norm_dev[0]) : static_cast<double>(norm_val);
-        loss_out[0] = static_cast<float>(red[0] / norm);
-    }
+    for (int64_t i = lo + threadIdx.x; i < hi; i += 1024) c += static_cast<double>(row_loss[i]);
+    c = block_sum_1024(c, red);
+    if (threadIdx.x == 0) part[blockIdx.x] = c;
+}
+
+__global__ __launch_bounds__(64) void loss_final_kernel(int parts, const double *part, float norm_val, const float *norm_dev,
+                                                        float *loss_out) {
+    if (threadIdx.x != 0) return;
+    double c = 0.0;
+    for (int b = 0; b < parts; ++b) c += part[b];
+    const double norm = norm_dev ? static_cast<double>(norm_dev[0]) : static_cast<double>(norm_val);
+    loss_out[0] = static_cast<float>(c / norm);
 }
 
 }  // namespace capgnn
@@ -216,7 +329,7 @@ __global__ __launch_bounds__(1024) void loss_reduce_kernel(int64_t n, const floa
 using namespace capgnn;
 
 extern "C" size_t capgnn_loss_workspace_bytes(int64_t n) {
-    return align_up(256 + static_cast<size_t>(n > 0 ? n : 1) * sizeof(float), 256);
+    return align_up(LOSS_HEADER + static_cast<size_t>(n > 0 ? n : 1) * sizeof(float), 256);
 }
 
 extern "C" int capgnn_softmax_ce(int64_t n, int C, const float *Z, int64_t ldz, const int32_t *labels,
@@ -232,16 +345,20 @@ extern "C" int capgnn_softmax_ce(int64_t n, int C, const float *Z, int64_t ldz, 
     float *norm_dev = nullptr;
     float norm_val = 1.f;
     float *scratch = static_cast<float *>(ws);
+    double *part = reinterpret_cast<double *>(static_cast<char *>(ws) + 256);
+    const int parts = static_cast<int>(std::max<int64_t>(1, std::min<int64_t>((n + 4095) / 4096, LOSS_PARTS)));
     if (loss_norm > 0.0) norm_val = static_cast<float>(loss_norm);
     else if (!mask) norm_val = static_cast<float>(n);
     else {
         norm_dev = scratch;
-        hipLaunchKernelGGL(count_mask_kernel, dim3(1), dim3(1024), 0, st, n, mask, norm_dev);
+        hipLaunchKernelGGL(count_mask_kernel, dim3(parts), dim3(1024), 0, st, n, mask, part);
+        hipLaunchKernelGGL(count_final_kernel, dim3(1), dim3(64), 0, st, parts, part, norm_dev);
     }
-    float *row_loss = scratch + 64;
+    float *row_loss = reinterpret_cast<float *>(static_cast<char *>(ws) + LOSS_HEADER);
     hipLaunchKernelGGL(softmax_ce_kernel, dim3(static_cast<unsigned>((n + 3) / 4)), dim3(256), 0, st, n, C, Z, ldz,
                        labels, mask, norm_val, norm_dev, row_loss, static_cast<char *>(dZ), lddz, dz_dtype == CAPGNN_BF16 ? 1 : 0);
-    hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, st, n, row_loss, norm_val, norm_dev, loss_dev);
+    hipLaunchKernelGGL(loss_partial_kernel, dim3(parts), dim3(1024), 0, st, n, row_loss, part);
+    hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(64), 0, st, parts, part, norm_val, norm_dev, loss_dev);
     CG_HIP(hipGetLastError());
     return CAPGNN_OK;
 }
