@@ -15,6 +15,10 @@
  *                     first (Eq. 2 gives the priority; Alg. 1 "sort R(v_k) and select top k").
  *   orc_gather        JACA workflow: the receiving worker looks the halo rows up in the
  *                     local / global cache and places them in the layer input.
+ *   orc_cache_update  "Vertex Importance and Vertex Update" / "Staleness in CaPGNN": cached rows are
+ *                     overwritten with newer representations and carry the iteration they were written in.
+ *   orc_stale_ids     bounded staleness: the rows that have not been refreshed for more than a
+ *                     configured number of iterations.
  *   orc_gcn_scales    notation table: A-hat is the symmetrically normalised adjacency.
  *   orc_spmm_fwd      aggregation step of Eq. 1; A-hat * H in the GCN rule of Lemma 2's proof.
  *   orc_spmm_bwd      the transposed product the chain rule of that rule needs
@@ -91,6 +95,38 @@ int64_t orc_gather(const uint8_t *table, int64_t n_rows, int64_t row_bytes,
         }
     }
     return absent;
+}
+
+/* table[ids[r], :] = rows[r, :] and stamp[ids[r]] = epoch, for r = 0..n-1 in this order (of several
+ * updates of one row the last one stays); ids outside [0, n_rows) are skipped.  Returns how many were. */
+int64_t orc_cache_update(uint8_t *table, int64_t *stamp, int64_t n_rows, int64_t row_bytes,
+                         const int64_t *ids, int64_t n, const uint8_t *rows, int64_t epoch)
+{
+    int64_t absent = 0;
+    for (int64_t r = 0; r < n; ++r) {
+        int64_t id = ids[r];
+        if (id < 0 || id >= n_rows) {
+            ++absent;
+            continue;
+        }
+        memcpy(table + id * row_bytes, rows + r * row_bytes, (size_t)row_bytes);
+        stamp[id] = epoch;
+    }
+    return absent;
+}
+
+/* Rows whose stamp is more than max_age iterations behind epoch_now, in ascending order.
+ * Returns their number; *oldest receives the smallest stamp (epoch_now if there are no rows). */
+int64_t orc_stale_ids(const int64_t *stamp, int64_t n_rows, int64_t epoch_now, int64_t max_age,
+                      int64_t *ids_out, int64_t *oldest)
+{
+    int64_t n = 0, lo = epoch_now;
+    for (int64_t h = 0; h < n_rows; ++h) {
+        if (stamp[h] < lo) lo = stamp[h];
+        if (epoch_now - stamp[h] > max_age) ids_out[n++] = h;
+    }
+    *oldest = lo;
+    return n;
 }
 
 /* ---------------------------------------------------------------- normalisation scales */

@@ -56,6 +56,10 @@ def _lib():
         L.orc_placement.argtypes = [i64, p, p, i64, p, p]
         L.orc_gather.argtypes = [p, i64, i64, p, i64, p]
         L.orc_gather.restype = i64
+        L.orc_cache_update.argtypes = [p, p, i64, i64, p, i64, p, i64]
+        L.orc_cache_update.restype = i64
+        L.orc_stale_ids.argtypes = [p, i64, i64, i64, p, p]
+        L.orc_stale_ids.restype = i64
         L.orc_gcn_scales.argtypes = [i64, i64, p, p, p, p]
         L.orc_mean_scales.argtypes = [i64, i64, p, p, p]
         L.orc_spmm_fwd.argtypes = [i64, p, p, p, p, p, p, i64, p]
@@ -113,6 +117,28 @@ def gather(table: np.ndarray, ids: np.ndarray):
     out = np.zeros((len(ids), table.shape[1]), dtype=table.dtype)
     absent = _lib().orc_gather(_ptr(table), table.shape[0], row_bytes, _ptr(ids), len(ids), _ptr(out))
     return out, int(absent)
+
+
+def cache_update(table: np.ndarray, stamp: np.ndarray, ids, rows: np.ndarray, epoch: int) -> int:
+    """Vertex update: table[ids[r], :] = rows[r, :] and stamp[ids[r]] = epoch, r ascending (the last of several
+    updates of one row stays); ids outside the table are skipped.  In place; returns the number skipped."""
+    assert table.flags.c_contiguous and stamp.dtype == np.int64 and stamp.flags.c_contiguous
+    ids = np.ascontiguousarray(ids, np.int64)
+    rows = np.ascontiguousarray(rows, dtype=table.dtype)
+    assert rows.shape == (len(ids), table.shape[1])
+    row_bytes = table.shape[1] * table.itemsize
+    return int(_lib().orc_cache_update(_ptr(table), _ptr(stamp), table.shape[0], row_bytes, _ptr(ids), len(ids),
+                                       _ptr(rows), int(epoch)))
+
+
+def stale_ids(stamp: np.ndarray, epoch_now: int, max_age: int):
+    """Bounded staleness: ascending ids of the rows not refreshed for more than max_age iterations, and the
+    oldest stamp."""
+    stamp = np.ascontiguousarray(stamp, np.int64)
+    out = np.zeros(len(stamp), np.int64)
+    oldest = np.zeros(1, np.int64)
+    n = _lib().orc_stale_ids(_ptr(stamp), len(stamp), int(epoch_now), int(max_age), _ptr(out), _ptr(oldest))
+    return out[:n].copy(), int(oldest[0])
 
 
 def overlap_ratio(halo_sets: Sequence[np.ndarray]):

@@ -301,6 +301,44 @@ def test_stale_halo_rows_obey_lemma2_bound(orc):
 
 
 # ----------------------------------------------------------------------------- cache side
+def test_cache_update_and_staleness_vs_bruteforce(orc):
+    """Vertex update and the bounded-staleness list against plain Python loops, plus what must hold whatever the
+    input: untouched rows keep their bytes and stamps, the last of repeated updates stays, absent ids are
+    counted and ignored, and the stale list is exactly {h : epoch_now - stamp[h] > max_age} in ascending order."""
+    rng = np.random.default_rng(12)
+    for dtype in (np.float32, np.uint16):
+        n_rows, f = 57, 5
+        table = (rng.standard_normal((n_rows, f)) * 100).astype(dtype)
+        stamp = np.zeros(n_rows, np.int64)
+        ref_t, ref_s = table.copy(), stamp.copy()
+        for epoch in range(1, 9):
+            n = int(rng.integers(0, 40))
+            ids = rng.integers(-3, n_rows + 3, n).astype(np.int64)         # repeats and absent ids
+            rows = (rng.standard_normal((n, f)) * 100).astype(dtype)
+            absent = orc.cache_update(table, stamp, ids, rows, epoch)
+            miss = 0
+            for r in range(n):                                            # the definition, spelled out
+                if 0 <= ids[r] < n_rows:
+                    ref_t[ids[r]] = rows[r]
+                    ref_s[ids[r]] = epoch
+                else:
+                    miss += 1
+            assert absent == miss
+            assert table.tobytes() == ref_t.tobytes() and np.array_equal(stamp, ref_s)
+            for max_age in (0, 1, 3, 100):
+                got, oldest = orc.stale_ids(stamp, epoch, max_age)
+                want = [h for h in range(n_rows) if epoch - ref_s[h] > max_age]
+                assert got.tolist() == want and oldest == ref_s.min()
+            # a gather right after the update returns the rows just written (last occurrence of each id)
+            ok = (ids >= 0) & (ids < n_rows)
+            out, _ = orc.gather(table, ids[ok])
+            last = {int(i): r for r, i in enumerate(ids) if 0 <= i < n_rows}
+            for pos, i in enumerate(ids[ok]):
+                assert out[pos].tobytes() == rows[last[int(i)]].tobytes()
+    got, oldest = orc.stale_ids(np.zeros(0, np.int64), 7, 0)
+    assert len(got) == 0 and oldest == 7
+
+
 def test_placement_vs_bruteforce_and_invariants(orc):
     rng = np.random.default_rng(10)
     for n, cap in [(0, 5), (1, 0), (37, 10), (1000, 1000), (5000, 1234), (300, 400)]:
