@@ -61,12 +61,68 @@ def cpu_baseline(cfg, scale, full_prob):
     return prob, ref, dt, orc.max_threads()
 
 
+def bench_cache_update(args):
+    """Throughput of the cache write path (vertex update into both tiers, bounded-staleness list) on the
+    configuration's halo set; one JSON line.  Not the headline metric: a measurement of its own."""
+    import numpy as np
+    import torch
+    from paper_2508_13716_amd import binding as B, synth
+    cfg = synth.CONFIGS[args.config]
+    part = synth.partition_for(cfg)
+    L = len(cfg.dims) - 1
+    dt = B.BF16 if cfg.dtype == "bf16" else B.F32
+    es = 2 if cfg.dtype == "bf16" else 4
+    cap = synth.cap_gpu_for(cfg, part)
+    c = B.Cache(part.halo_gid, part.halo_prio, cap, cfg.dims[:L], dt, B.MAP_DIRECT)
+    tier, _ = c.query(np.arange(part.n_halo))
+    st = torch.cuda.Stream()
+    ids_out = torch.empty(max(part.n_halo, 1), dtype=torch.int64, device="cuda")
+
+    def timeit(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(st):
+            e0.record(st)
+            for _ in range(args.steps):
+                fn()
+            e1.record(st)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    layers = []
+    for l in range(L):
+        F = cfg.dims[l]
+        ld = synth.pad_to(F, 16 // es)
+        rec = {"layer": l, "F": F}
+        for key, sel in (("gpu_tier", np.nonzero(tier == 0)[0]), ("host_tier", np.nonzero(tier == 1)[0])):
+            if len(sel) == 0:
+                continue
+            ids = torch.from_numpy(np.random.default_rng(l).permutation(sel).astype(np.int64)).cuda()
+            rows = torch.randn(len(sel), ld, device="cuda").to(torch.bfloat16 if es == 2 else torch.float32)
+            torch.cuda.synchronize()
+            ms = timeit(lambda: B.cache_update(c, l, ids, len(sel), rows, ld, 3, stream=st))
+            nbytes = len(sel) * F * es
+            rec[key] = {"rows": int(len(sel)), "ms": ms, "written_GBps": nbytes / ms / 1e6,
+                        "read_plus_written_GBps": 2 * nbytes / ms / 1e6}
+        rec["stale_list_ms"] = timeit(lambda: B.cache_stale(c, l, 10, 2, ids_out, stream=st))
+        layers.append(rec)
+    print(json.dumps({"metric": "cache update throughput", "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "data": "synthetic",
+                      "config": {"workload": f"{cfg.name}: {part.n_halo} halo vertices, GPU tier {cap} rows, dims {cfg.dims[:L]}, {cfg.dtype}"},
+                      "hbm_peak_GBps": HBM_PEAK_GBPS, "layers": layers}))
+    c.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C2")
+    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update"],
+                    help="epoch (default): the headline benchmark; cache_update: throughput of the cache write path")
     ap.add_argument("--miss-mode", type=int, default=None, help="0 zero-copy kernel, 1 staged DMA, 2 staged DMA prefetched one epoch ahead (default 2)")
     ap.add_argument("--orders", default=None, help="comma list of 1 (aggregate first) / 2 (transform first) per layer")
     ap.add_argument("--cpu-scale", type=float, default=None,
@@ -84,6 +140,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     B.lib()
+    if args.what == "cache_update":
+        return bench_cache_update(args)
 
     cfg = synth.CONFIGS[args.config]
     t_gen = time.perf_counter()

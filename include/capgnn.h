@@ -195,6 +195,29 @@ int capgnn_halo_gather(capgnn_cache *c, int layer, const int64_t *ids, int64_t n
                        void *out, int64_t ld, void *stream, void *side_stream, void *staging,
                        capgnn_gather_stats *stats);
 
+/* Vertex update (sections "Vertex Importance and Vertex Update" and "Staleness in CaPGNN": cached halo
+ * representations are overwritten by newer ones and must not stay stale for an unbounded number of
+ * iterations).  For k = 0..n-1: the cached row of ids[k] in `layer`'s table becomes rows[k, 0:dims[layer]], in
+ * whichever tier holds it (GPU-tier rows are written in device memory, host-tier rows through the pinned
+ * mapping), and is stamped with `epoch`.  Of several updates of one vertex in a call the last one stays.  No
+ * lock is taken: rows and stamps of a call become visible together, in stream order, to the gathers and
+ * epochs enqueued after it (the lock-free update of the section "Pipeline Design"; there is no reader inside
+ * this library that runs concurrently with an update on the same stream).
+ * ids: device int64[n] (halo-local indices, or global ids when by_gid); rows: device [n x ld] of the cache's
+ * dtype.  Absent ids are skipped.  Asynchronous on `stream` unless stats != NULL (then it synchronises and
+ * reports hits = rows written to the GPU tier, misses = rows written to the host tier, absent).
+ * In CAPGNN_MISS_PIPELINED mode the rows prefetched for the next epoch are dropped.  Every table starts with
+ * stamp 0 (capgnn_cache_fill resets the layer's stamps to 0). */
+int capgnn_cache_update(capgnn_cache *c, int layer, const int64_t *ids, int64_t n, int by_gid,
+                        const void *rows, int64_t ld, int64_t epoch, void *stream,
+                        capgnn_gather_stats *stats);
+
+/* Bounded staleness: the halo-local indices h (ascending) of `layer`'s rows with epoch_now - stamp[h] > max_age,
+ * i.e. the rows a periodic synchronisation has to refresh.  ids_out: device int64[n_halo]; *n_out (host) = how
+ * many; *oldest (host, may be NULL) = the smallest stamp.  Synchronises `stream`. */
+int capgnn_cache_stale(capgnn_cache *c, int layer, int64_t epoch_now, int64_t max_age,
+                       int64_t *ids_out, int64_t *n_out, int64_t *oldest, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * Dense products on the matrix cores ("MM is related to the number of vertices").
  * C[M x N] (+)= op(A) op(B) with fp32 accumulation; optional fused bias / ReLU epilogue.

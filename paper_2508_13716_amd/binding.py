@@ -77,6 +77,8 @@ SIGNATURES = {
     "capgnn_cache_build": (_i32, [C.POINTER(_vp), _i64, _vp, _vp, _i64, _vp, _i32, _i32, _vp, _vp, _i32, _vp]),
     "capgnn_cache_destroy": (_i32, [_vp]),
     "capgnn_cache_set_miss_mode": (_i32, [_vp, _i32]),
+    "capgnn_cache_update": (_i32, [_vp, _i32, _vp, _i64, _i32, _vp, _i64, _i64, _vp, _vp]),
+    "capgnn_cache_stale": (_i32, [_vp, _i32, _i64, _i64, _vp, _vp, _vp, _vp]),
     "capgnn_cache_fill": (_i32, [_vp, _i32, _vp, _i64, _vp]),
     "capgnn_cache_query": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp]),
     "capgnn_cache_lookup": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _vp]),
@@ -280,6 +282,21 @@ def halo_gather(c: Cache, layer: int, ids, n: int, out, ld: int, by_gid: bool = 
     if rc != OK and (check or rc != ENOTFOUND):
         _check(rc)
     return (rc, st) if want_stats else rc
+
+
+def cache_update(c: Cache, layer: int, ids, n: int, rows, ld: int, epoch: int, by_gid: bool = False, stream=None,
+                 want_stats: bool = False):
+    st = GatherStats() if want_stats else None
+    _check(lib().capgnn_cache_update(c.h, layer, _p(ids), n, int(by_gid), _p(rows), ld, epoch, _stream(stream),
+                                     C.byref(st) if st is not None else None))
+    return st
+
+
+def cache_stale(c: Cache, layer: int, epoch_now: int, max_age: int, ids_out, stream=None):
+    """Returns (number of stale rows, oldest stamp); ids_out (device int64[n_halo]) receives their indices."""
+    n, lo = C.c_int64(0), C.c_int64(0)
+    _check(lib().capgnn_cache_stale(c.h, layer, epoch_now, max_age, _p(ids_out), C.byref(n), C.byref(lo), _stream(stream)))
+    return int(n.value), int(lo.value)
 
 
 # --------------------------------------------------------------------------- dense, layer, loss, epoch

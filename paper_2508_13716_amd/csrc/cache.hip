@@ -133,6 +133,119 @@ __global__ __launch_bounds__(256) void gather_ids_kernel(MapView m, const int64_
     }
 }
 
+// ---- vertex update.  Pass 1 finds, for every vertex named in the call, the position of its last update;
+// pass 2 lets exactly that position write the row, then the stamp, and clears the scratch again.
+__global__ __launch_bounds__(256) void update_owner_kernel(MapView m, const int64_t *ids, int64_t n, int by_gid,
+                                                           long long *owner) {
+    const int64_t k = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (k >= n) return;
+    const int64_t h = resolve(m, ids[k], by_gid);
+    if (h >= 0) atomicMax(&owner[h], static_cast<long long>(k));
+}
+
+__global__ __launch_bounds__(256) void update_rows_kernel(MapView m, const int64_t *ids, int64_t n, int by_gid,
+                                                          const char *rows, int64_t rows_pitch, char *gpu_table,
+                                                          char *host_table, int64_t pitch, int row_bytes, int lpr,
+                                                          int vec16, int es, const long long *owner, int64_t *stamp,
+                                                          int64_t epoch, unsigned long long *counters) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int64_t k = wave * (64 / lpr) + lane / lpr;
+    if (k >= n) return;
+    const int l = lane % lpr;
+    const int64_t h = resolve(m, ids[k], by_gid);
+    if (h < 0) {
+        if (counters && l == 0) atomicAdd(&counters[2], 1ull);
+        return;
+    }
+    if (owner[h] != static_cast<long long>(k)) return;        // a later position updates the same vertex
+    const int32_t s = m.slot[h];
+    char *d = s >= 0 ? gpu_table + static_cast<int64_t>(s) * pitch : host_table + (-1 - static_cast<int64_t>(s)) * pitch;
+    copy_row(rows + k * rows_pitch, d, row_bytes, l, lpr, vec16, es);
+    if (counters && l == 0) atomicAdd(&counters[s >= 0 ? 0 : 1], 1ull);
+    if (l == 0) stamp[h] = epoch;
+}
+
+__global__ __launch_bounds__(256) void update_clear_kernel(MapView m, const int64_t *ids, int64_t n, int by_gid,
+                                                           long long *owner) {
+    const int64_t k = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (k >= n) return;
+    const int64_t h = resolve(m, ids[k], by_gid);
+    if (h >= 0) owner[h] = -1;
+}
+
+__global__ __launch_bounds__(256) void fill_i64_kernel(int64_t *p, int64_t n, int64_t v) {
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < n; i += static_cast<int64_t>(gridDim.x) * 256)
+        p[i] = v;
+}
+
+// ---- stale list: ordered compaction in three steps (count per 1024-row block, scan of the counts, write)
+constexpr int STALE_BLOCK = 1024;
+
+__global__ __launch_bounds__(STALE_BLOCK) void stale_count_kernel(const int64_t *stamp, int64_t n, int64_t epoch_now,
+                                                                   int64_t max_age, int64_t *counts, long long *oldest) {
+    __shared__ int red[STALE_BLOCK];
+    __shared__ long long lo[STALE_BLOCK];
+    const int64_t h = static_cast<int64_t>(blockIdx.x) * STALE_BLOCK + threadIdx.x;
+    const bool in = h < n;
+    const int64_t st = in ? stamp[h] : epoch_now;
+    red[threadIdx.x] = (in && epoch_now - st > max_age) ? 1 : 0;
+    lo[threadIdx.x] = st;
+    __syncthreads();
+    for (int s = STALE_BLOCK / 2; s > 0; s >>= 1) {
+        if (threadIdx.x < s) {
+            red[threadIdx.x] += red[threadIdx.x + s];
+            lo[threadIdx.x] = lo[threadIdx.x] < lo[threadIdx.x + s] ? lo[threadIdx.x] : lo[threadIdx.x + s];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        counts[blockIdx.x] = red[0];
+        atomicMin(oldest, lo[0]);
+    }
+}
+
+// counts[b] <- number of stale rows before block b; counts[nb] <- total.  One workgroup: every thread sums a
+// contiguous run of counts, the run totals are scanned through LDS, then each thread writes its run's offsets.
+__global__ __launch_bounds__(STALE_BLOCK) void stale_scan_kernel(int64_t *counts, int64_t nb) {
+    __shared__ long long tot[STALE_BLOCK];
+    const int64_t per = (nb + STALE_BLOCK - 1) / STALE_BLOCK;
+    const int64_t lo = threadIdx.x * per, hi = lo + per < nb ? lo + per : nb;
+    long long sum = 0;
+    for (int64_t b = lo; b < hi; ++b) sum += counts[b];
+    tot[threadIdx.x] = sum;
+    __syncthreads();
+    for (int off = 1; off < STALE_BLOCK; off <<= 1) {
+        const long long v = threadIdx.x >= off ? tot[threadIdx.x - off] : 0;
+        __syncthreads();
+        tot[threadIdx.x] += v;
+        __syncthreads();
+    }
+    long long run = tot[threadIdx.x] - sum;      // exclusive prefix of this thread's run
+    for (int64_t b = lo; b < hi; ++b) {
+        const int64_t c = counts[b];
+        counts[b] = run;
+        run += c;
+    }
+    if (threadIdx.x == STALE_BLOCK - 1) counts[nb] = tot[STALE_BLOCK - 1];
+}
+
+__global__ __launch_bounds__(STALE_BLOCK) void stale_write_kernel(const int64_t *stamp, int64_t n, int64_t epoch_now,
+                                                                   int64_t max_age, const int64_t *counts, int64_t *ids_out) {
+    __shared__ int pre[STALE_BLOCK];
+    const int64_t h = static_cast<int64_t>(blockIdx.x) * STALE_BLOCK + threadIdx.x;
+    const int flag = (h < n && epoch_now - stamp[h] > max_age) ? 1 : 0;
+    pre[threadIdx.x] = flag;
+    __syncthreads();
+    for (int off = 1; off < STALE_BLOCK; off <<= 1) {          // inclusive prefix sum of the flags
+        const int v = threadIdx.x >= off ? pre[threadIdx.x - off] : 0;
+        __syncthreads();
+        pre[threadIdx.x] += v;
+        __syncthreads();
+    }
+    if (flag) ids_out[counts[blockIdx.x] + pre[threadIdx.x] - 1] = h;
+}
+
 __global__ void zero_counters_kernel(unsigned long long *c) {
     if (threadIdx.x < 4) c[threadIdx.x] = 0ull;
 }
@@ -366,6 +479,14 @@ extern "C" int capgnn_cache_build(capgnn_cache **out, int64_t n_halo, const int6
     }
     std::vector<int64_t> zeros(4, 0);
     if ((rc = dev_copy(c, zeros, &c->counters_d))) return fail(rc);
+    {
+        std::vector<int64_t> stamps(static_cast<size_t>(n_layers) * n_halo, 0);
+        std::vector<long long> owners(n_halo, -1);
+        std::vector<int64_t> scan(n_halo / STALE_BLOCK + 3, 0);
+        if ((rc = dev_copy(c, stamps, &c->stamp_d))) return fail(rc);
+        if ((rc = dev_copy(c, owners, &c->owner_d))) return fail(rc);
+        if ((rc = dev_copy(c, scan, &c->scan_d))) return fail(rc);
+    }
     if (hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
         set_error("cache_build: hipEventCreate failed");
@@ -429,6 +550,11 @@ extern "C" int capgnn_cache_fill(capgnn_cache *c, int layer, const void *rows, i
     if (c->cap_gpu > 0)
         CG_HIP(hipMemcpy(c->gpu_tier + c->gpu_off[layer], pack.data(), pack.size(), hipMemcpyHostToDevice));
     c->staged_valid[layer] = 0;      // rows prefetched for the next epoch are out of date now
+    hipLaunchKernelGGL(fill_i64_kernel, dim3(256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       c->stamp_d + static_cast<size_t>(layer) * c->n_halo, c->n_halo, int64_t(0));
+    CG_HIP(hipGetLastError());
+    CG_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+    CG_HIP(hipDeviceSynchronize());   // setup call: the tables and stamps are in place for work on any stream
     return CAPGNN_OK;
 }
 
@@ -526,5 +652,73 @@ extern "C" int capgnn_halo_gather(capgnn_cache *c, int layer, const int64_t *ids
         stats->absent = static_cast<int64_t>(h[2]);
         if (h[2]) CG_FAIL(CAPGNN_ENOTFOUND, "halo_gather: %llu ids are in neither tier", h[2]);
     }
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_cache_update(capgnn_cache *c, int layer, const int64_t *ids, int64_t n, int by_gid,
+                                   const void *rows, int64_t ld, int64_t epoch, void *stream,
+                                   capgnn_gather_stats *stats) {
+    if (!c || layer < 0 || layer >= c->n_layers) CG_FAIL(CAPGNN_EINVAL, "cache_update: bad cache or layer");
+    if (n < 0) CG_FAIL(CAPGNN_EINVAL, "cache_update: n < 0");
+    if (by_gid && c->map_kind != CAPGNN_MAP_HASH) CG_FAIL(CAPGNN_EINVAL, "cache_update: by_gid needs a cache built with MAP_HASH");
+    if (stats) stats->hits = stats->misses = stats->absent = 0;
+    if (n == 0 || c->n_halo == 0) return CAPGNN_OK;
+    if (!ids || !rows) CG_FAIL(CAPGNN_EINVAL, "cache_update: ids or rows is NULL");
+    if (ld < c->dims[layer]) CG_FAIL(CAPGNN_EINVAL, "cache_update: ld=%lld smaller than the row width %d", (long long)ld, c->dims[layer]);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // a prefetch of the previous epoch may still be reading the host tier: let it finish, then drop its copy
+    if (c->last_side) CG_HIP(hipStreamSynchronize(c->last_side));
+    c->staged_valid[layer] = 0;
+    const int es = elem_bytes(c->dtype);
+    char *gtab = c->gpu_tier + c->gpu_off[layer];
+    char *htab = c->host_tier + c->host_off[layer];
+    const int row_bytes = c->dims[layer] * es;
+    const int64_t rows_pitch = ld * es;
+    const int vec16 = aligned16(rows) && rows_pitch % 16 == 0 && aligned16(gtab) && aligned16(htab) && c->pitch[layer] % 16 == 0;
+    const int lpr = lanes_per_row(row_bytes, vec16, es);
+    const MapView m = view_dev(c);
+    unsigned long long *ctr = stats ? reinterpret_cast<unsigned long long *>(c->counters_d) : nullptr;
+    if (ctr) hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, st, ctr);
+    const unsigned b1 = static_cast<unsigned>((n + 255) / 256);
+    hipLaunchKernelGGL(update_owner_kernel, dim3(b1), dim3(256), 0, st, m, ids, n, by_gid, c->owner_d);
+    hipLaunchKernelGGL(update_rows_kernel, dim3(blocks_for(n, lpr)), dim3(256), 0, st, m, ids, n, by_gid,
+                       static_cast<const char *>(rows), rows_pitch, gtab, htab, c->pitch[layer], row_bytes, lpr, vec16, es,
+                       c->owner_d, c->stamp_d + static_cast<size_t>(layer) * c->n_halo, epoch, ctr);
+    hipLaunchKernelGGL(update_clear_kernel, dim3(b1), dim3(256), 0, st, m, ids, n, by_gid, c->owner_d);
+    CG_HIP(hipGetLastError());
+    if (stats) {
+        unsigned long long h[4] = {0, 0, 0, 0};
+        CG_HIP(hipMemcpyAsync(h, ctr, sizeof(h), hipMemcpyDeviceToHost, st));
+        CG_HIP(hipStreamSynchronize(st));
+        stats->hits = static_cast<int64_t>(h[0]);
+        stats->misses = static_cast<int64_t>(h[1]);
+        stats->absent = static_cast<int64_t>(h[2]);
+    }
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_cache_stale(capgnn_cache *c, int layer, int64_t epoch_now, int64_t max_age, int64_t *ids_out,
+                                  int64_t *n_out, int64_t *oldest, void *stream) {
+    if (!c || layer < 0 || layer >= c->n_layers || !n_out) CG_FAIL(CAPGNN_EINVAL, "cache_stale: bad argument");
+    *n_out = 0;
+    if (oldest) *oldest = epoch_now;
+    if (c->n_halo == 0) return CAPGNN_OK;
+    if (!ids_out) CG_FAIL(CAPGNN_EINVAL, "cache_stale: ids_out is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t nb = (c->n_halo + STALE_BLOCK - 1) / STALE_BLOCK;
+    const int64_t *stamp = c->stamp_d + static_cast<size_t>(layer) * c->n_halo;
+    long long *lo = reinterpret_cast<long long *>(c->scan_d + nb + 1);
+    hipLaunchKernelGGL(fill_i64_kernel, dim3(1), dim3(256), 0, st, c->scan_d + nb + 1, int64_t(1), epoch_now);
+    hipLaunchKernelGGL(stale_count_kernel, dim3(static_cast<unsigned>(nb)), dim3(STALE_BLOCK), 0, st, stamp, c->n_halo,
+                       epoch_now, max_age, c->scan_d, lo);
+    hipLaunchKernelGGL(stale_scan_kernel, dim3(1), dim3(STALE_BLOCK), 0, st, c->scan_d, nb);
+    hipLaunchKernelGGL(stale_write_kernel, dim3(static_cast<unsigned>(nb)), dim3(STALE_BLOCK), 0, st, stamp, c->n_halo,
+                       epoch_now, max_age, c->scan_d, ids_out);
+    CG_HIP(hipGetLastError());
+    int64_t tail[2] = {0, 0};
+    CG_HIP(hipMemcpyAsync(tail, c->scan_d + nb, sizeof(tail), hipMemcpyDeviceToHost, st));
+    CG_HIP(hipStreamSynchronize(st));
+    *n_out = tail[0];
+    if (oldest) *oldest = tail[1];
     return CAPGNN_OK;
 }

@@ -104,6 +104,9 @@ struct capgnn_cache {
     int64_t *hkeys_d = nullptr;
     int32_t *hvals_d = nullptr;
     int64_t *counters_d = nullptr;      // [4] hits, misses, absent
+    int64_t *stamp_d = nullptr;         // [n_layers][n_halo] iteration in which each cached row was last written
+    long long *owner_d = nullptr;       // [n_halo] scratch of an update call: position of the last update of a vertex
+    int64_t *scan_d = nullptr;          // [n_halo/1024 + 2] scratch of the stale-list compaction
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     std::vector<hipEvent_t> ev_layer;   // one per layer: host-tier rows of that layer have landed
     std::vector<hipEvent_t> ev_consumed;  // one per layer: the layer's staging area has been scattered (pipelined mode)

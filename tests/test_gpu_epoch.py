@@ -106,6 +106,48 @@ def test_epoch_pipelined_host_tier_sees_refilled_tables(env):
     dp.close()
 
 
+@pytest.mark.parametrize("miss_mode", [1, 2])
+def test_epoch_after_vertex_update_and_staleness_bound(env, miss_mode):
+    """Cached halo rows are overwritten between epochs (capgnn_cache_update).  The next epoch must consume
+    exactly the updated tables (also when the previous epoch had already prefetched the old ones), and when
+    the update moves the last layer's halo rows by at most eps the logits move by at most the staleness
+    bound of Lemma 2, eta^2 beta^2 eps (and by the sharper row-wise bound its chain of inequalities gives)."""
+    torch, B, H, O = env["torch"], env["B"], env["H"], env["O"]
+    cfg = synth.CONFIGS["C2"].scaled(0.02)
+    prob = H.make_problem(cfg, mask_frac=0.5)
+    part = prob.part
+    dp = H.DeviceProblem(prob, miss_mode=miss_mode)
+    ref = O.oracle_epoch(prob)
+    for rep in range(2):
+        loss, _ = dp.run_epoch()
+    compare_epoch(env, prob, dp, ref, loss, TOL["f32"], f"before update (miss_mode {miss_mode})")
+    logits_before = dp.results()["logits"].astype(np.float64)
+    # stale rows: the last layer's halo inputs move by at most eps
+    eps, l = 1e-2, dp.L - 1
+    rng = np.random.default_rng(3)
+    ids = rng.permutation(part.n_halo)[: part.n_halo // 2].astype(np.int64)
+    new_rows = (prob.tables[l][ids] + rng.uniform(-eps, eps, (len(ids), cfg.dims[l]))).astype(np.float32)
+    moved = float(np.abs(new_rows.astype(np.float64) - prob.tables[l][ids]).max())
+    rows_d = H.np_to_dev(new_rows)
+    torch.cuda.synchronize()
+    B.cache_update(dp.cache, l, torch.from_numpy(ids).cuda(), len(ids), rows_d, cfg.dims[l], 7, stream=dp.stream)
+    prob.tables[l][ids] = new_rows
+    ref2 = O.oracle_epoch(prob)
+    loss2, _ = dp.run_epoch()
+    compare_epoch(env, prob, dp, ref2, loss2, TOL["f32"], f"after update (miss_mode {miss_mode})")
+    delta = float(np.abs(dp.results()["logits"].astype(np.float64) - logits_before).max())
+    W = prob.model[l].W.astype(np.float64)
+    eta = max(part.n_cols, W.shape[0], W.shape[1])
+    beta = max(1.0, float(np.abs(ref["hidden"][l - 1]).max()), float(np.abs(prob.tables[l]).max()), float(np.abs(W).max()))
+    og = O.oracle_graph(part, cfg.kind)
+    halo_rowsum = np.array([og.r[i] * og.c[part.col[part.rowptr[i]:part.rowptr[i + 1]]][part.col[part.rowptr[i]:part.rowptr[i + 1]] >= part.n_loc].sum()
+                            for i in range(part.n_loc)])
+    sharp = halo_rowsum.max() * W.shape[0] * np.abs(W).max() * moved
+    say(f"stale rows moved by {moved:.3e}: logits moved by {delta:.3e}; row-wise bound {sharp:.3e}; Lemma 2 bound {eta ** 2 * beta ** 2 * moved:.3e}")
+    assert 0 < delta <= sharp * (1 + 1e-3) + 1e-5 <= eta ** 2 * beta ** 2 * moved
+    dp.close()
+
+
 @pytest.mark.parametrize("kind", ["gcn", "sage"])
 @pytest.mark.parametrize("order", ["agg", "xform"])
 def test_layer_fwd_bwd_with_halo_gradient(env, kind, order):

@@ -226,6 +226,64 @@ def test_cache_placement_lookup_gather_bit_exact(env, dtype, cap_frac):
     c.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("cap_frac", [0.0, 0.37, 1.0])
+def test_cache_update_and_stale_list_bit_exact(env, dtype, cap_frac):
+    """Vertex update (both tiers, repeated and absent ids, by index and by global id) and the
+    bounded-staleness list against the oracle: every cached byte and every stamp afterwards."""
+    torch, B, H, O, orc = env["torch"], env["B"], env["H"], env["O"], env["orc"]
+    part = synth.make_partition("cache-upd", 300, 5000, 30000, seed=23, max_deg=200)
+    n = part.n_halo
+    cap = int(cap_frac * n)
+    dims = [70, 256]
+    dt = B.BF16 if dtype == "bf16" else B.F32
+    tables = [synth.make_features(n, d, seed=5, stream=40 + i, dtype=dtype) for i, d in enumerate(dims)]
+    stamps = [np.zeros(n, np.int64) for _ in dims]
+    c = B.Cache(part.halo_gid, part.halo_prio, cap, dims, dt, B.MAP_HASH)
+    for l in range(len(dims)):
+        c.fill(l, tables[l])
+    tier, _ = c.query(np.arange(n))
+    rng = np.random.default_rng(6)
+    main = torch.cuda.Stream()
+    ids_out = torch.empty(n, dtype=torch.int64, device="cuda")
+    for epoch in range(1, 6):
+        for l, d in enumerate(dims):
+            per16 = 16 // (2 if dtype == "bf16" else 4)
+            ld = d if epoch % 2 else synth.pad_to(d, per16) + per16
+            m = int(rng.integers(1, 3000))
+            ids = rng.integers(-2, n + 2, m).astype(np.int64)                      # repeats and absent ids
+            by_gid = bool(epoch % 2 == 0)
+            ids_call = np.where((ids >= 0) & (ids < n), part.halo_gid[np.clip(ids, 0, n - 1)], (1 << 45) + ids) if by_gid else ids
+            rows = synth.make_features(m, d, seed=100 + epoch, stream=50 + l, dtype=dtype)
+            say(f"cache update dtype={dtype} cap={cap}/{n} epoch={epoch} layer={l} m={m} ld={ld} by_gid={by_gid}")
+            rows_d = H.padded_matrix(rows, ld)
+            torch.cuda.synchronize()
+            st = B.cache_update(c, l, torch.from_numpy(ids_call).cuda(), m, rows_d, ld, epoch, by_gid=by_gid, stream=main,
+                                want_stats=True)
+            n_abs = orc.cache_update(tables[l], stamps[l], ids, rows, epoch)
+            last = np.full(n, -1, np.int64)
+            ok = (ids >= 0) & (ids < n)
+            last[ids[ok]] = np.nonzero(ok)[0]                                      # one write per distinct vertex
+            touched = np.nonzero(last >= 0)[0]
+            assert st.absent == n_abs
+            assert st.hits == int((tier[touched] == 0).sum()) and st.misses == int((tier[touched] == 1).sum())
+            out = torch.full((n, ld), 3.0, dtype=rows_d.dtype, device="cuda")
+            torch.cuda.synchronize()
+            B.halo_gather(c, l, None, n, out, ld, stream=main)
+            torch.cuda.synchronize()
+            assert H.dev_to_np(out)[:, :d].tobytes() == tables[l].tobytes()
+            for max_age in (0, 2):
+                cnt, oldest = B.cache_stale(c, l, epoch, max_age, ids_out, stream=main)
+                ref_ids, ref_old = orc.stale_ids(stamps[l], epoch, max_age)
+                assert cnt == len(ref_ids) and oldest == ref_old
+                assert np.array_equal(ids_out[:cnt].cpu().numpy(), ref_ids)
+    # a refill starts the layer's history again
+    c.fill(0, tables[0])
+    cnt, oldest = B.cache_stale(c, 0, 5, 0, ids_out, stream=main)
+    assert cnt == n and oldest == 0
+    c.close()
+
+
 def test_cache_edge_cases(env):
     torch, B = env["torch"], env["B"]
     with pytest.raises(B.CapgnnError):
