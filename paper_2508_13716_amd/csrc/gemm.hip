@@ -27,7 +27,30 @@ struct GemmArgs {
     int out_bf16, accumulate, relu;
     const float *bias;
     const char *mask; int64_t ldm; int mask_bf16;
+    int gx, gy, S;                  // tiles along N, along M, reduction splits
 };
+
+// Tile of a workgroup in the one-dimensional grid.  Workgroup b runs on L2 domain b % NUM_XCD; the order is
+// chosen so that workgroups that read the same operand data share a domain and follow one another there: the
+// tiles of one reduction split (they read the same slab of both operands), or the tiles along N of one row
+// block (they read the same rows of A).  Returns false for the padding workgroups at the end of the grid.
+__device__ __forceinline__ bool tile_coords(const GemmArgs &g, int *bx, int *by, int *bz) {
+    const int64_t b = blockIdx.x;
+    const int xcd = static_cast<int>(b % NUM_XCD);
+    const int64_t seq = b / NUM_XCD;
+    if (g.S > 1) {
+        const int64_t tiles = static_cast<int64_t>(g.gx) * g.gy;
+        const int64_t z = (seq / tiles) * NUM_XCD + xcd;
+        const int64_t t = seq % tiles;
+        *bz = static_cast<int>(z); *bx = static_cast<int>(t % g.gx); *by = static_cast<int>(t / g.gx);
+        return z < g.S;
+    }
+    *bz = 0;
+    *bx = static_cast<int>(seq % g.gx);
+    const int64_t y = (seq / g.gx) * NUM_XCD + xcd;
+    *by = static_cast<int>(y);
+    return y < g.gy;
+}
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
     uint32_t u = __float_as_uint(f);
@@ -71,7 +94,7 @@ __device__ __forceinline__ float4 load4(const char *base, int64_t off, int nvali
 // D layout of the 32x32 MFMAs: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
 template <int TM, int TN>
 __device__ __forceinline__ void store_tile(const GemmArgs &g, const floatx16 (&acc)[TM][TN], int64_t row0, int64_t col0,
-                                           int l32, int half) {
+                                           int l32, int half, int bz) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -84,7 +107,7 @@ __device__ __forceinline__ void store_tile(const GemmArgs &g, const floatx16 (&a
                 if (row >= g.M) continue;
                 float v = acc[i][j][r];
                 if (g.part) {
-                    g.part[(static_cast<int64_t>(blockIdx.z) * g.M + row) * g.N + col] = v;
+                    g.part[(static_cast<int64_t>(bz) * g.M + row) * g.N + col] = v;
                     continue;
                 }
                 if (g.accumulate) {
@@ -164,9 +187,11 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, half = lane >> 5;
-    const int64_t m0 = static_cast<int64_t>(blockIdx.y) * BM;
-    const int64_t n0 = static_cast<int64_t>(blockIdx.x) * BN;
-    const int64_t k_begin = static_cast<int64_t>(blockIdx.z) * g.k_chunk;
+    int bx, by, bz;
+    if (!tile_coords(g, &bx, &by, &bz)) return;      // uniform over the workgroup
+    const int64_t m0 = static_cast<int64_t>(by) * BM;
+    const int64_t n0 = static_cast<int64_t>(bx) * BN;
+    const int64_t k_begin = static_cast<int64_t>(bz) * g.k_chunk;
     const int64_t k_end = (k_begin + g.k_chunk < g.K) ? k_begin + g.k_chunk : g.K;
 
     floatx16 acc[TM][TN];
@@ -214,7 +239,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
         __syncthreads();
     }
 
-    store_tile<TM, TN>(g, acc, m0 + wm * WM, n0 + wn * WN, l32, half);
+    store_tile<TM, TN>(g, acc, m0 + wm * WM, n0 + wn * WN, l32, half, bz);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -293,9 +318,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, half = lane >> 5;
-    const int64_t m0 = static_cast<int64_t>(blockIdx.y) * BM;
-    const int64_t n0 = static_cast<int64_t>(blockIdx.x) * BN;
-    const int64_t k_begin = static_cast<int64_t>(blockIdx.z) * g.k_chunk;
+    int bx, by, bz;
+    if (!tile_coords(g, &bx, &by, &bz)) return;      // uniform over the workgroup
+    const int64_t m0 = static_cast<int64_t>(by) * BM;
+    const int64_t n0 = static_cast<int64_t>(bx) * BN;
+    const int64_t k_begin = static_cast<int64_t>(bz) * g.k_chunk;
     const int64_t k_end = (k_begin + g.k_chunk < g.K) ? k_begin + g.k_chunk : g.K;
 
     floatx16 acc[TM][TN];
@@ -344,7 +371,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         }
         __syncthreads();
     }
-    store_tile<TM, TN>(g, acc, m0 + wm * WM, n0 + wn * WN, l32, half);
+    store_tile<TM, TN>(g, acc, m0 + wm * WM, n0 + wn * WN, l32, half, bz);
 }
 
 // Lays the (small) second operand of a product out as Wt[n][k], k contiguous, rows padded to 16 bytes, for the
@@ -473,19 +500,11 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
         g.k_chunk = (steps + S - 1) / S * bk;
     }
     const int64_t gy = (M + bm - 1) / bm, gx = (N + bn - 1) / bn;
-    if (gy > 65535) {
-        // more row tiles than grid.y holds: the caller splits the rows (outputs of different row ranges are independent)
-        if (trans_a) CG_FAIL(CAPGNN_EINVAL, "gemm: M=%lld needs more than 65535 row tiles", (long long)M);
-        const int64_t rows_per = static_cast<int64_t>(65535) * bm;
-        for (int64_t r0 = 0; r0 < M; r0 += rows_per) {
-            const int64_t mr = std::min(rows_per, M - r0);
-            CG_TRY(launch_gemm(0, trans_b, mr, N, K, static_cast<const char *>(A) + r0 * lda * es, lda, B, ldb,
-                               static_cast<char *>(C) + r0 * ldc * (g.out_bf16 ? 2 : 4), ldc, dtype, out_f32, accumulate, bias, relu,
-                               relu_mask ? static_cast<const char *>(relu_mask) + r0 * ldm * es : nullptr, ldm, ws, ws_bytes, stream));
-        }
-        return CAPGNN_OK;
-    }
-    dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(S));
+    const int64_t n_wg = S > 1 ? NUM_XCD * ((S + NUM_XCD - 1) / NUM_XCD) * gx * gy : NUM_XCD * ((gy + NUM_XCD - 1) / NUM_XCD) * gx;
+    if (n_wg >= (int64_t(1) << 31) || gx >= (int64_t(1) << 24) || gy >= (int64_t(1) << 30))
+        CG_FAIL(CAPGNN_EINVAL, "gemm: %lld x %lld tiles exceed the grid", (long long)gy, (long long)gx);
+    g.gx = static_cast<int>(gx); g.gy = static_cast<int>(gy); g.S = S;
+    dim3 grid(static_cast<unsigned>(n_wg), 1, 1);
     bool akc = !trans_a, bkc = trans_b != 0;
     if (half_path) {
         if (repack_b) {
