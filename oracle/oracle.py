@@ -149,6 +149,78 @@ def overlap_ratio(halo_sets: Sequence[np.ndarray]):
     return ids, cnt.astype(np.int64)
 
 
+def policy_hit_counts(halo_sets: Sequence[np.ndarray], policy: str, cap_local: int, cap_global: int,
+                      epochs: int, warmup: int = 1):
+    """Two-level cache policy comparison (evaluation sections on the vertex overlap ratio and on cache
+    capacity: JACA against FIFO and LRU, all on the same local + global structure).
+
+    Model (the paper gives no listing; this is the reading the design notes record): in every epoch the
+    partitions i = 0..P-1 take turns, and partition i asks for every vertex of its halo set in ascending id
+    order.  A request is served by the partition's local cache, else by the shared global cache, else it is a
+    miss (the vertex has to be communicated).
+      'jaca' / 'jaca_low': static contents chosen by the vertex overlap ratio R (Eq. 2) - local cache i holds the
+          cap_local vertices of H_i with the highest (lowest) R, the global cache the cap_global vertices of the
+          union with the highest (lowest) R, ties by ascending vertex id.
+      'fifo' / 'lru': both levels start empty; a global hit or a miss inserts the vertex into the local cache, a
+          miss also into the global cache, evicting the first-inserted / least-recently-used entry of a full
+          cache (an LRU hit refreshes the entry; capacity 0 holds nothing).
+    Requests of the first `warmup` epochs fill the caches and are not counted.  Returns (local hits, global
+    hits, misses) over the remaining epochs."""
+    from collections import OrderedDict
+    sets = [np.unique(np.asarray(h, np.int64)) for h in halo_sets]
+    P = len(sets)
+    hits_l = hits_g = misses = 0
+    if policy in ("jaca", "jaca_low"):
+        ids, cnt = overlap_ratio(sets)
+        R = dict(zip(ids.tolist(), cnt.tolist()))
+        sign = -1 if policy == "jaca" else 1
+        key = lambda v: (sign * R[v], v)
+        glob = set(sorted(ids.tolist(), key=key)[:max(cap_global, 0)])
+        loc = [set(sorted(h.tolist(), key=key)[:max(cap_local, 0)]) for h in sets]
+        for e in range(epochs):
+            for i in range(P):
+                for v in sets[i].tolist():
+                    if e < warmup:
+                        continue
+                    if v in loc[i]:
+                        hits_l += 1
+                    elif v in glob:
+                        hits_g += 1
+                    else:
+                        misses += 1
+        return hits_l, hits_g, misses
+    assert policy in ("fifo", "lru")
+    lru = policy == "lru"
+
+    def insert(cache: "OrderedDict", cap: int, v: int):
+        if cap <= 0 or v in cache:
+            return
+        if len(cache) >= cap:
+            cache.popitem(last=False)            # oldest insertion (FIFO) / least recent use (LRU)
+        cache[v] = True
+
+    glob: "OrderedDict" = OrderedDict()
+    loc = [OrderedDict() for _ in range(P)]
+    for e in range(epochs):
+        for i in range(P):
+            for v in sets[i].tolist():
+                counted = e >= warmup
+                if v in loc[i]:
+                    if lru:
+                        loc[i].move_to_end(v)
+                    hits_l += counted
+                elif v in glob:
+                    if lru:
+                        glob.move_to_end(v)
+                    insert(loc[i], cap_local, v)
+                    hits_g += counted
+                else:
+                    insert(glob, cap_global, v)
+                    insert(loc[i], cap_local, v)
+                    misses += counted
+    return int(hits_l), int(hits_g), int(misses)
+
+
 # ------------------------------------------------------------------ graph
 @dataclass
 class Graph:

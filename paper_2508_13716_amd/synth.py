@@ -195,6 +195,23 @@ def make_partition(name: str, n_loc: int, n_halo: int, nnz: int, *, seed: int,
     return Partition(name, n_loc, n_halo, rowptr, col, gid, prio, degree, self_loops, symmetric)
 
 
+def make_halo_sets(n: int, nnz: int, n_parts: int, *, seed: int, gamma: float = 2.1, max_deg: Optional[int] = None):
+    """Halo sets of a random n_parts-way vertex partition of one power-law graph (the paper's "Random"
+    pre-partitioning): H_i = the vertices outside part i that are sources of edges into part i.  Returns
+    (list of sorted unique int64 arrays of global vertex ids, part id of every vertex)."""
+    alpha = 1.0 / (gamma - 1.0)
+    rng = rng_for(seed, 7)
+    md = max_deg if max_deg is not None else max(8, min(n // 4, int(40 * nnz / max(n, 1))))
+    law = _calibrated(n, alpha, nnz, md)
+    dst = law.draw(rng, rng.permutation(n), nnz)
+    src = law.draw(rng, rng.permutation(n), nnz)
+    part = rng.integers(0, n_parts, size=n, dtype=np.int64)
+    cut = part[dst] != part[src]
+    dst_part, src_v = part[dst[cut]], src[cut]
+    sets = [np.unique(src_v[dst_part == i]).astype(np.int64) for i in range(n_parts)]
+    return sets, part
+
+
 def hand_partition(n_loc: int, n_halo: int, edges, *, seed: int = 7, self_loops: bool = False,
                    name: str = "hand") -> Partition:
     """Partition from an explicit (row, col) edge list (duplicates kept: they act as multiplicity)."""

@@ -339,6 +339,51 @@ def test_cache_update_and_staleness_vs_bruteforce(orc):
     assert len(got) == 0 and oldest == 7
 
 
+def test_policy_hit_counts_closed_forms_and_invariants(orc):
+    """The policy model against cases whose answer is known without simulating:
+    - disjoint halo sets, full-batch sweeps: a cyclic sweep over more vertices than an LRU or FIFO cache holds
+      never hits; with room for all of them every counted request hits locally;
+    - JACA with static contents hits exactly |local set| + |global set minus local set| per sweep;
+    - one vertex shared by all partitions, capacity 1 globally and 0 locally: every request after the first hits;
+    - hits + misses = counted requests, capacity 0 everywhere = all misses, and hit counts never decrease
+      when JACA's capacities grow."""
+    A, Bs = np.arange(0, 50), np.arange(100, 130)
+    for pol in ("fifo", "lru"):
+        assert orc.policy_hit_counts([A, Bs], pol, 10, 0, epochs=4) == (0, 0, 3 * 80)        # cyclic sweep, cache too small
+        assert orc.policy_hit_counts([A, Bs], pol, 50, 0, epochs=4) == (3 * 80, 0, 0)        # everything fits locally
+        assert orc.policy_hit_counts([A, Bs], pol, 0, 80, epochs=4) == (0, 3 * 80, 0)        # ... or globally
+        assert orc.policy_hit_counts([A, Bs], pol, 0, 0, epochs=3) == (0, 0, 2 * 80)
+    # shared vertex 7: R = 3; everything else R = 1
+    sets = [np.array([1, 2, 7]), np.array([7, 20]), np.array([7, 30, 31])]
+    ids, R = orc.overlap_ratio(sets)
+    assert dict(zip(ids.tolist(), R.tolist())) == {1: 1, 2: 1, 7: 3, 20: 1, 30: 1, 31: 1}
+    assert orc.policy_hit_counts(sets, "jaca", 0, 1, epochs=2) == (0, 3, 5)                 # the global slot goes to vertex 7
+    assert orc.policy_hit_counts(sets, "jaca_low", 0, 1, epochs=2) == (0, 1, 7)             # ... or to vertex 1 (lowest R, lowest id)
+    assert orc.policy_hit_counts(sets, "jaca", 1, 1, epochs=2) == (3, 0, 5)                 # each local slot holds 7 as well
+    assert orc.policy_hit_counts(sets, "jaca", 2, 0, epochs=3) == (2 * 6, 0, 2 * 2)         # {7,1} {7,20} {7,30}
+    # FIFO/LRU, global capacity 1, no local cache: 7 survives only from the end of partition 0's sweep to the
+    # start of partition 1's, so each epoch has exactly one hit (by hand: 7 misses + 1 hit per epoch)
+    for pol in ("fifo", "lru"):
+        assert orc.policy_hit_counts(sets, pol, 0, 1, epochs=2, warmup=0) == (0, 2, 14)
+    rng = np.random.default_rng(14)
+    sets = [np.unique(rng.integers(0, 300, 120)) for _ in range(4)]
+    total = sum(len(h) for h in sets)
+    prev = -1
+    for cap in (0, 5, 20, 60, 150, 400):
+        for pol in ("jaca", "jaca_low", "fifo", "lru"):
+            hl, hg, ms = orc.policy_hit_counts(sets, pol, cap, cap, epochs=3)
+            assert hl + hg + ms == 2 * total and min(hl, hg, ms) >= 0
+            if cap == 0:
+                assert (hl, hg) == (0, 0)
+            if cap >= 400:
+                assert ms == 0
+        hl, hg, _ = orc.policy_hit_counts(sets, "jaca", cap, cap, epochs=3)
+        assert hl + hg >= prev
+        prev = hl + hg
+        # high overlap first never does worse than low overlap first on the shared level
+        assert hl + hg >= sum(orc.policy_hit_counts(sets, "jaca_low", cap, cap, epochs=3)[:2]) or cap >= 150
+
+
 def test_placement_vs_bruteforce_and_invariants(orc):
     rng = np.random.default_rng(10)
     for n, cap in [(0, 5), (1, 0), (37, 10), (1000, 1000), (5000, 1234), (300, 400)]:
