@@ -115,14 +115,50 @@ def bench_cache_update(args):
     c.close()
 
 
+def bench_policy(args):
+    """Hit-rate curves of the policy layer (overlap-ratio priority against FIFO and LRU on the two-level
+    structure) on a random 4-way partition of a synthetic power-law graph; one JSON line."""
+    import numpy as np
+    import torch
+    from paper_2508_13716_amd import binding as B, synth
+    n, nnz, P = 233_000, 11_500_000, 4          # Reddit's vertex count, a tenth of its edges
+    sets, _ = synth.make_halo_sets(n, nnz, P, seed=synth.BASE_SEED * 10 + 9)
+    flat = np.concatenate(sets)
+    ids_d = torch.from_numpy(flat).cuda()
+    R = torch.empty(n, dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    B.overlap_ratio(ids_d, len(flat), n, R)
+    torch.cuda.synchronize()
+    t_overlap = time.perf_counter() - t0
+    hist = np.bincount(R.cpu().numpy(), minlength=P + 1).tolist()
+    union = int((R > 0).sum().item())
+    rate = lambda c: (c[0] + c[1]) / max(1, sum(c))
+    curves = []
+    for frac in (0.02, 0.05, 0.1, 0.2, 0.4, 0.6, 0.8, 1.0):
+        cap_g = int(frac * union)
+        cap_l = cap_g // 8 if frac < 1.0 else cap_g
+        t0 = time.perf_counter()
+        row = {"global_capacity": cap_g, "local_capacity": cap_l}
+        for name, pid in (("jaca", B.POLICY_JACA), ("low_overlap_first", B.POLICY_JACA_LOW), ("fifo", B.POLICY_FIFO), ("lru", B.POLICY_LRU)):
+            row[name] = round(rate(B.policy_simulate(sets, pid, cap_l, cap_g, 3)), 4)
+        row["simulate_s"] = round(time.perf_counter() - t0, 3)
+        curves.append(row)
+    print(json.dumps({"metric": "cache hit rate by policy", "unit": "fraction of halo requests served by a cache", "n_gpus": 1,
+                      "data": "synthetic", "config": {"workload": f"random {P}-way partition of a power-law graph, {n} vertices, {nnz} edges; "
+                                                                  f"{len(flat)} halo requests per epoch, {union} distinct halo vertices"},
+                      "overlap_ratio_histogram": hist, "overlap_ratio_kernel_ms": t_overlap * 1e3, "curves": curves}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C2")
-    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update"],
-                    help="epoch (default): the headline benchmark; cache_update: throughput of the cache write path")
+    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy"],
+                    help="epoch (default): the headline benchmark; cache_update: throughput of the cache write path; "
+                         "policy: hit-rate curves of the cache policies")
     ap.add_argument("--miss-mode", type=int, default=None, help="0 zero-copy kernel, 1 staged DMA, 2 staged DMA prefetched one epoch ahead (default 2)")
     ap.add_argument("--orders", default=None, help="comma list of 1 (aggregate first) / 2 (transform first) per layer")
     ap.add_argument("--cpu-scale", type=float, default=None,
@@ -142,6 +178,8 @@ def main():
     B.lib()
     if args.what == "cache_update":
         return bench_cache_update(args)
+    if args.what == "policy":
+        return bench_policy(args)
 
     cfg = synth.CONFIGS[args.config]
     t_gen = time.perf_counter()

@@ -218,6 +218,30 @@ int capgnn_cache_update(capgnn_cache *c, int layer, const int64_t *ids, int64_t 
 int capgnn_cache_stale(capgnn_cache *c, int layer, int64_t epoch_now, int64_t max_age,
                        int64_t *ids_out, int64_t *n_out, int64_t *oldest, void *stream);
 
+/* Vertex overlap ratio, Eq. 2: R[v] = number of partitions whose halo set contains v.  halo_ids: device
+ * int64[n_ids], the halo sets of all partitions one after another (every set duplicate-free; ids outside
+ * [0, n_vertices) are ignored); R: device int32[n_vertices], overwritten (0 for vertices in no halo set).
+ * Asynchronous on `stream`. */
+int capgnn_overlap_ratio(const int64_t *halo_ids, int64_t n_ids, int64_t n_vertices, int32_t *R, void *stream);
+
+#define CAPGNN_POLICY_JACA      0  /* static contents, highest overlap ratio first (ties: ascending vertex id) */
+#define CAPGNN_POLICY_JACA_LOW  1  /* the same with the lowest overlap ratio first (the evaluation's counter-test) */
+#define CAPGNN_POLICY_FIFO      2
+#define CAPGNN_POLICY_LRU       3
+
+/* Two-level cache policy comparison (evaluation sections "Impact of Vertex Overlap Ratio on Cache Hit Rate" and
+ * "Impact of Cache Capacity and Partition on Cache Hit Rate": JACA against FIFO and LRU on one local cache per
+ * partition plus one shared global cache).  Host only.  In every epoch the partitions take turns; partition i
+ * requests every vertex of its halo set halo_ids[halo_ptr[i] .. halo_ptr[i+1]) (ascending, duplicate-free) in
+ * that order.  A request is served by the partition's local cache, else by the global cache, else it is a miss.
+ * JACA: local cache i holds the cap_local vertices of H_i with the highest overlap ratio, the global cache the
+ * cap_global vertices of the union with the highest ratio.  FIFO / LRU: both levels start empty; a global hit or
+ * a miss inserts the vertex into the local cache, a miss also into the global cache, evicting the
+ * first-inserted / least-recently-used entry of a full cache.  Requests of the first `warmup` epochs are not
+ * counted.  counts[3] (host) = local hits, global hits, misses. */
+int capgnn_policy_simulate(int n_parts, const int64_t *halo_ptr, const int64_t *halo_ids, int policy,
+                           int64_t cap_local, int64_t cap_global, int epochs, int warmup, int64_t *counts);
+
 /* ------------------------------------------------------------------------------------------
  * Dense products on the matrix cores ("MM is related to the number of vertices").
  * C[M x N] (+)= op(A) op(B) with fp32 accumulation; optional fused bias / ReLU epilogue.

@@ -77,6 +77,8 @@ SIGNATURES = {
     "capgnn_cache_build": (_i32, [C.POINTER(_vp), _i64, _vp, _vp, _i64, _vp, _i32, _i32, _vp, _vp, _i32, _vp]),
     "capgnn_cache_destroy": (_i32, [_vp]),
     "capgnn_cache_set_miss_mode": (_i32, [_vp, _i32]),
+    "capgnn_overlap_ratio": (_i32, [_vp, _i64, _i64, _vp, _vp]),
+    "capgnn_policy_simulate": (_i32, [_i32, _vp, _vp, _i32, _i64, _i64, _i32, _i32, _vp]),
     "capgnn_cache_update": (_i32, [_vp, _i32, _vp, _i64, _i32, _vp, _i64, _i64, _vp, _vp]),
     "capgnn_cache_stale": (_i32, [_vp, _i32, _i64, _i64, _vp, _vp, _vp, _vp]),
     "capgnn_cache_fill": (_i32, [_vp, _i32, _vp, _i64, _vp]),
@@ -110,6 +112,9 @@ def lib():
     if _lib is None:
         if not os.path.exists(SO_PATH):
             raise RuntimeError(f"{SO_PATH} is missing: build it with `python -m paper_2508_13716_amd.build`")
+        # torch first: the library must bind to the HIP runtime torch has loaded (its own copy), else a second
+        # runtime would be pulled in from the system path and the device memory torch hands over would be foreign
+        import torch  # noqa: F401
         L = C.CDLL(SO_PATH)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(L, name)
@@ -297,6 +302,23 @@ def cache_stale(c: Cache, layer: int, epoch_now: int, max_age: int, ids_out, str
     n, lo = C.c_int64(0), C.c_int64(0)
     _check(lib().capgnn_cache_stale(c.h, layer, epoch_now, max_age, _p(ids_out), C.byref(n), C.byref(lo), _stream(stream)))
     return int(n.value), int(lo.value)
+
+
+POLICY_JACA, POLICY_JACA_LOW, POLICY_FIFO, POLICY_LRU = 0, 1, 2, 3
+
+
+def overlap_ratio(halo_ids, n_ids: int, n_vertices: int, R, stream=None):
+    _check(lib().capgnn_overlap_ratio(_p(halo_ids), n_ids, n_vertices, _p(R), _stream(stream)))
+
+
+def policy_simulate(halo_sets, policy: int, cap_local: int, cap_global: int, epochs: int, warmup: int = 1):
+    """halo_sets: list of ascending, duplicate-free int64 arrays.  Returns (local hits, global hits, misses)."""
+    ptr = np.zeros(len(halo_sets) + 1, np.int64)
+    np.cumsum([len(h) for h in halo_sets], out=ptr[1:])
+    ids = np.ascontiguousarray(np.concatenate(halo_sets) if len(halo_sets) else np.zeros(0, np.int64), np.int64)
+    out = np.zeros(3, np.int64)
+    _check(lib().capgnn_policy_simulate(len(halo_sets), _p(ptr), _p(ids), policy, cap_local, cap_global, epochs, warmup, _p(out)))
+    return int(out[0]), int(out[1]), int(out[2])
 
 
 # --------------------------------------------------------------------------- dense, layer, loss, epoch
