@@ -19,6 +19,8 @@
  *                     overwritten with newer representations and carry the iteration they were written in.
  *   orc_stale_ids     bounded staleness: the rows that have not been refreshed for more than a
  *                     configured number of iterations.
+ *   orc_influence     RAPA's vertex influence score (Eq. 6): degree-normalised sums over a vertex's outgoing
+ *                     and incoming neighbours, times its repetition count.
  *   orc_gcn_scales    notation table: A-hat is the symmetrically normalised adjacency.
  *   orc_spmm_fwd      aggregation step of Eq. 1; A-hat * H in the GCN rule of Lemma 2's proof.
  *   orc_spmm_bwd      the transposed product the chain rule of that rule needs
@@ -127,6 +129,27 @@ int64_t orc_stale_ids(const int64_t *stamp, int64_t n_rows, int64_t epoch_now, i
     }
     *oldest = lo;
     return n;
+}
+
+/* Vertex influence score, Eq. 6, on a partition graph (rows = local vertices, entry (i, j) = edge j -> i):
+ *   S_v = ( sum_{j in N_out(v)} 1/sqrt(Din_j) * 1/sqrt(Dout_v) + sum_{j in N_in(v)} 1/sqrt(Dout_j) * 1/sqrt(Din_v) ) * C_v
+ * for every column vertex v (local vertices have both kinds of neighbours, halo vertices only outgoing ones).
+ * din: in-degree of the local vertices [n_loc]; dout: out-degree of the column vertices [n_cols]; count: C [n_cols]. */
+void orc_influence(int64_t n_loc, int64_t n_cols, const int64_t *rowptr, const int32_t *col,
+                   const double *din, const double *dout, const double *count, double *S)
+{
+    for (int64_t v = 0; v < n_cols; ++v) S[v] = 0.0;
+    /* outgoing neighbours of v: the rows i that hold an entry (i, v) */
+    for (int64_t i = 0; i < n_loc; ++i)
+        for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+            int64_t v = col[e];
+            S[v] += (1.0 / sqrt(din[i])) * (1.0 / sqrt(dout[v]));
+        }
+    /* incoming neighbours of a local vertex i: the columns of its row */
+    for (int64_t i = 0; i < n_loc; ++i)
+        for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e)
+            S[i] += (1.0 / sqrt(dout[col[e]])) * (1.0 / sqrt(din[i]));
+    for (int64_t v = 0; v < n_cols; ++v) S[v] *= count[v];
 }
 
 /* ---------------------------------------------------------------- normalisation scales */

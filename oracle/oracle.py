@@ -60,6 +60,7 @@ def _lib():
         L.orc_cache_update.restype = i64
         L.orc_stale_ids.argtypes = [p, i64, i64, i64, p, p]
         L.orc_stale_ids.restype = i64
+        L.orc_influence.argtypes = [i64, i64, p, p, p, p, p, p]
         L.orc_gcn_scales.argtypes = [i64, i64, p, p, p, p]
         L.orc_mean_scales.argtypes = [i64, i64, p, p, p]
         L.orc_spmm_fwd.argtypes = [i64, p, p, p, p, p, p, i64, p]
@@ -219,6 +220,19 @@ def policy_hit_counts(halo_sets: Sequence[np.ndarray], policy: str, cap_local: i
                     insert(loc[i], cap_local, v)
                     misses += counted
     return int(hits_l), int(hits_g), int(misses)
+
+
+def influence_score(n_loc: int, n_cols: int, rowptr, col, din, dout, count=None) -> np.ndarray:
+    """RAPA's vertex influence score (Eq. 6) of every column vertex of a partition graph.  din[n_loc]: in-degrees
+    of the local vertices, dout[n_cols]: out-degrees of the column vertices, count[n_cols]: repetition counts
+    (1 when omitted).  A vertex without incident edges scores 0; degrees must be positive where they are used."""
+    rowptr = np.ascontiguousarray(rowptr, np.int64)
+    col = np.ascontiguousarray(col, np.int32)
+    din, dout = _f64(din), _f64(dout)
+    cnt = np.ones(n_cols) if count is None else _f64(count)
+    S = np.zeros(n_cols, np.float64)
+    _lib().orc_influence(n_loc, n_cols, _ptr(rowptr), _ptr(col), _ptr(din), _ptr(dout), _ptr(cnt), _ptr(S))
+    return S
 
 
 # ------------------------------------------------------------------ graph

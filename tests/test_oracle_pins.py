@@ -300,6 +300,47 @@ def test_stale_halo_rows_obey_lemma2_bound(orc):
     assert np.abs(Zs - Z).max() <= rowsum.max() * fi * np.abs(W).max() * eps * (1 + 1e-12)
 
 
+# ----------------------------------------------------------------------------- Eq. 6
+def test_influence_score_vs_dense_bruteforce_and_closed_forms(orc):
+    """Eq. 6 from a dense adjacency matrix, term by term as printed; a directed ring where every degree is 1
+    (score = 2 C); a star whose centre feeds d leaves (centre d/sqrt(d) = sqrt(d), each leaf 1/sqrt(d)); and the
+    identity sum_v S_v / C_v = 2 sum_e 1/sqrt(Din Dout) (every edge is one outgoing and one incoming term)."""
+    rng = np.random.default_rng(15)
+    part = synth.make_partition("infl", 40, 25, 400, seed=33, max_deg=20, self_loops=False)
+    n_loc, n_cols = part.n_loc, part.n_cols
+    A = np.zeros((n_loc, n_cols))                                   # A[i, j] = number of edges j -> i
+    for i in range(n_loc):
+        for e in range(part.rowptr[i], part.rowptr[i + 1]):
+            A[i, part.col[e]] += 1
+    din = np.maximum(A.sum(axis=1), 1) * rng.integers(1, 3, n_loc)  # "in the original graph": at least the local count
+    dout = np.maximum(A.sum(axis=0), 1)
+    C = rng.integers(1, 5, n_cols).astype(np.float64)
+    want = np.zeros(n_cols)
+    for v in range(n_cols):
+        out_part = sum(A[j, v] / np.sqrt(din[j]) / np.sqrt(dout[v]) for j in range(n_loc))
+        in_part = sum(A[v, j] / np.sqrt(dout[j]) / np.sqrt(din[v]) for j in range(n_cols)) if v < n_loc else 0.0
+        want[v] = (out_part + in_part) * C[v]
+    got = orc.influence_score(n_loc, n_cols, part.rowptr, part.col, din, dout, C)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-14)
+    edge_terms = sum(A[i, j] / np.sqrt(din[i] * dout[j]) for i in range(n_loc) for j in range(n_cols))
+    np.testing.assert_allclose((got / C).sum(), 2 * edge_terms, rtol=1e-12)
+    # directed ring on n vertices, no halo: entry (i, i-1)
+    n = 9
+    rowptr = np.arange(n + 1, dtype=np.int64)
+    col = ((np.arange(n) - 1) % n).astype(np.int32)
+    C = np.arange(1, n + 1, dtype=np.float64)
+    np.testing.assert_allclose(orc.influence_score(n, n, rowptr, col, np.ones(n), np.ones(n), C), 2 * C, rtol=1e-15)
+    # star: halo vertex 0 (column d) feeds the d local leaves
+    d = 16
+    rowptr = np.arange(d + 1, dtype=np.int64)
+    col = np.full(d, d, np.int32)
+    dout = np.ones(d + 1)
+    dout[d] = d
+    S = orc.influence_score(d, d + 1, rowptr, col, np.ones(d), dout)
+    np.testing.assert_allclose(S[d], np.sqrt(d), rtol=1e-15)
+    np.testing.assert_allclose(S[:d], 1 / np.sqrt(d), rtol=1e-15)
+
+
 # ----------------------------------------------------------------------------- cache side
 def test_cache_update_and_staleness_vs_bruteforce(orc):
     """Vertex update and the bounded-staleness list against plain Python loops, plus what must hold whatever the
