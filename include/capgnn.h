@@ -224,6 +224,17 @@ int capgnn_cache_stale(capgnn_cache *c, int layer, int64_t epoch_now, int64_t ma
  * Asynchronous on `stream`. */
 int capgnn_overlap_ratio(const int64_t *halo_ids, int64_t n_ids, int64_t n_vertices, int32_t *R, void *stream);
 
+/* RAPA's vertex influence score, Eq. 6, of every column vertex v of the partition graph (local vertices have
+ * outgoing and incoming neighbours, halo vertices only outgoing ones):
+ *   S[v] = ( inv_sqrt_dout[v] * sum_{rows i with an entry (i,v)} inv_sqrt_din[i]
+ *          + [v local] inv_sqrt_din[v] * sum_{entries (v,j) of row v} inv_sqrt_dout[j] ) * count[v].
+ * inv_sqrt_din: device float[n_loc], 1/sqrt of the in-degrees the caller wants (Eq. 6: of the original graph);
+ * inv_sqrt_dout: device float[n_cols], 1/sqrt of the out-degrees (Eq. 6: in the subgraph); count: device
+ * float[n_cols], how often the vertex appears across subgraphs, or NULL (= 1); S: device float[n_cols].
+ * Edge values and the graph's own scales are not used.  Asynchronous on `stream`. */
+int capgnn_influence_score(const capgnn_graph *g, const float *inv_sqrt_din, const float *inv_sqrt_dout,
+                           const float *count, float *S, void *stream);
+
 #define CAPGNN_POLICY_JACA      0  /* static contents, highest overlap ratio first (ties: ascending vertex id) */
 #define CAPGNN_POLICY_JACA_LOW  1  /* the same with the lowest overlap ratio first (the evaluation's counter-test) */
 #define CAPGNN_POLICY_FIFO      2

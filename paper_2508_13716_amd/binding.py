@@ -78,6 +78,7 @@ SIGNATURES = {
     "capgnn_cache_destroy": (_i32, [_vp]),
     "capgnn_cache_set_miss_mode": (_i32, [_vp, _i32]),
     "capgnn_overlap_ratio": (_i32, [_vp, _i64, _i64, _vp, _vp]),
+    "capgnn_influence_score": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp]),
     "capgnn_policy_simulate": (_i32, [_i32, _vp, _vp, _i32, _i64, _i64, _i32, _i32, _vp]),
     "capgnn_cache_update": (_i32, [_vp, _i32, _vp, _i64, _i32, _vp, _i64, _i64, _vp, _vp]),
     "capgnn_cache_stale": (_i32, [_vp, _i32, _i64, _i64, _vp, _vp, _vp, _vp]),
@@ -309,6 +310,10 @@ POLICY_JACA, POLICY_JACA_LOW, POLICY_FIFO, POLICY_LRU = 0, 1, 2, 3
 
 def overlap_ratio(halo_ids, n_ids: int, n_vertices: int, R, stream=None):
     _check(lib().capgnn_overlap_ratio(_p(halo_ids), n_ids, n_vertices, _p(R), _stream(stream)))
+
+
+def influence_score(g: Graph, inv_sqrt_din, inv_sqrt_dout, count, S, stream=None):
+    _check(lib().capgnn_influence_score(g.h, _p(inv_sqrt_din), _p(inv_sqrt_dout), _p(count), _p(S), _stream(stream)))
 
 
 def policy_simulate(halo_sets, policy: int, cap_local: int, cap_global: int, epochs: int, warmup: int = 1):

@@ -19,6 +19,40 @@ __global__ __launch_bounds__(256) void fill_i32_kernel(int32_t *p, int64_t n, in
         p[i] = v;
 }
 
+// Vertex influence score (Eq. 6): one wave per column vertex v (heaviest first).  The lanes stride over the
+// entries of column v (outgoing neighbours: 1/sqrt(Din_row)) and, for a local vertex, over the entries of its
+// row (incoming neighbours: 1/sqrt(Dout_col)); lane sums are combined by a butterfly in a fixed order.
+struct InfluenceArgs {
+    const int64_t *colptr; const int32_t *rowidx;     // CSC: entries of column v
+    const int64_t *rowptr; const int32_t *col;        // CSR: entries of row i
+    const int32_t *order;                              // column vertices, heaviest first
+    int64_t n_loc, n_cols;
+    const float *rs_din;                               // [n_loc]  1/sqrt(in-degree)
+    const float *rs_dout;                              // [n_cols] 1/sqrt(out-degree)
+    const float *count;                                // [n_cols] or null
+    float *S;
+};
+
+__global__ __launch_bounds__(256) void influence_kernel(InfluenceArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int64_t p = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (p >= a.n_cols) return;
+    const int64_t v = a.order[p];
+    float out_sum = 0.f, in_sum = 0.f;
+    for (int64_t e = a.colptr[v] + lane; e < a.colptr[v + 1]; e += 64) out_sum += a.rs_din[a.rowidx[e]];
+    if (v < a.n_loc)
+        for (int64_t e = a.rowptr[v] + lane; e < a.rowptr[v + 1]; e += 64) in_sum += a.rs_dout[a.col[e]];
+    for (int off = 32; off > 0; off >>= 1) {
+        out_sum += __shfl_xor(out_sum, off);
+        in_sum += __shfl_xor(in_sum, off);
+    }
+    if (lane == 0) {
+        float s = out_sum * a.rs_dout[v];
+        if (v < a.n_loc) s += in_sum * a.rs_din[v];
+        a.S[v] = a.count ? s * a.count[v] : s;
+    }
+}
+
 // A cache over the dense ids 0..n-1 with FIFO or LRU replacement: an intrusive doubly linked list from the
 // next victim (head) to the newest entry (tail).
 struct ListCache {
@@ -70,6 +104,19 @@ extern "C" int capgnn_overlap_ratio(const int64_t *halo_ids, int64_t n_ids, int6
     if (n_ids > 0)
         hipLaunchKernelGGL(overlap_count_kernel, dim3(static_cast<unsigned>(std::min<int64_t>((n_ids + 255) / 256, 8192))), dim3(256), 0,
                            st, halo_ids, n_ids, n_vertices, R);
+    CG_HIP(hipGetLastError());
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_influence_score(const capgnn_graph *g, const float *inv_sqrt_din, const float *inv_sqrt_dout,
+                                      const float *count, float *S, void *stream) {
+    if (!g || !inv_sqrt_din || !inv_sqrt_dout || !S) CG_FAIL(CAPGNN_EINVAL, "influence_score: NULL argument");
+    if (g->n_cols == 0) return CAPGNN_OK;
+    InfluenceArgs a;
+    a.colptr = g->bwd.ptr; a.rowidx = g->bwd.idx; a.rowptr = g->fwd.ptr; a.col = g->fwd.idx; a.order = g->bwd.order;
+    a.n_loc = g->n_loc; a.n_cols = g->n_cols; a.rs_din = inv_sqrt_din; a.rs_dout = inv_sqrt_dout; a.count = count; a.S = S;
+    hipLaunchKernelGGL(influence_kernel, dim3(static_cast<unsigned>((g->n_cols + 3) / 4)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), a);
     CG_HIP(hipGetLastError());
     return CAPGNN_OK;
 }
