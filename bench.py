@@ -21,6 +21,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 FP32_MATRIX_PEAK_TFLOPS = 157.3
+BF16_MATRIX_PEAK_TFLOPS = 2500.0
 
 
 def spmm_launches(cfg, part, orders):
@@ -46,6 +47,21 @@ def spmm_min_bytes(part, F, n_out, n_in_touched, es):
     """Compulsory traffic of one SpMM launch: every index once, every needed source row once, every
     output row once (nnz*4 + (n_out+1)*8 + touched*F*s + n_out*F*s)."""
     return part.nnz * 4 + (n_out + 1) * 8 + n_in_touched * F * es + n_out * F * es
+
+
+def gemm_report(cfg, part, orders, kernels):
+    """FLOP rate of the first layer's forward transform against the matrix-core peak of its operand type."""
+    rec = [k for k in kernels if k["kind"] == "gemm" and k["layer"] == 0 and not k["backward"]]
+    if not rec:
+        return None
+    rows = part.n_loc if orders[0] == 1 else part.n_cols
+    mult = 2 if cfg.kind == "sage" else 1                    # GraphSAGE adds the self transform over the local rows
+    flops = 2.0 * rows * cfg.dims[0] * cfg.dims[1] + (mult - 1) * 2.0 * part.n_loc * cfg.dims[0] * cfg.dims[1]
+    peak = FP32_MATRIX_PEAK_TFLOPS if cfg.dtype == "f32" else BF16_MATRIX_PEAK_TFLOPS
+    tf = flops / (rec[0]["ms"] * 1e-3) / 1e12
+    return {"kernel": "transform of layer 0 (forward)", "gflop": flops / 1e9, "ms": rec[0]["ms"], "tflops": tf,
+            "peak_tflops": peak, "frac_of_matrix_peak": tf / peak,
+            "note": "matrix-core busy cycles of the same kernels: profiles/gemm_C2_C4_mfma_counters.txt"}
 
 
 def cpu_baseline(cfg, scale, full_prob):
@@ -255,6 +271,7 @@ def main():
         "gather": {"hit_GBps": hit_bytes / (hit_ms * 1e-3) / 1e9 if hit_ms else None, "hit_bytes": hit_bytes,
                    "miss_host_link_GBps": miss_bytes / (miss_ms * 1e-3) / 1e9 if miss_ms else None,
                    "miss_bytes": miss_bytes},
+        "gemm": gemm_report(cfg, part, res_orders, kernels),
         "kernels": kernels[:12],
         "roofline": {"kernel": f"{dom['kind']} layer {dom['layer']} F={F}", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
