@@ -40,6 +40,16 @@ static inline int elem_bytes(int dtype) { return dtype == CAPGNN_BF16 ? 2 : 4; }
 static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // One direction of the sparse operator: output row k sums over entries [ptr[k], ptr[k+1]).
+// Rows of a work list that are too long for one workgroup: the first n_rows positions of the list.  Each is cut
+// into pieces of GIANT_PIECE entries (the last one shorter); piece q belongs to position piece_pos[q], and the
+// pieces of position p are [piece_first[p], piece_first[p+1]).
+struct GiantList {
+    int64_t n_rows = 0;
+    int64_t n_pieces = 0;
+    const int32_t *piece_pos = nullptr;    // device [n_pieces]
+    const int32_t *piece_first = nullptr;  // device [n_rows + 1]
+};
+
 struct SpOp {
     int64_t n_out = 0;          // rows of the output
     int64_t n_in = 0;           // rows of the gathered operand
@@ -56,6 +66,7 @@ struct SpOp {
     const int32_t *order_sub = nullptr;
     int64_t n_long_sub = 0;
     int64_t max_deg = 0;
+    GiantList giant, giant_sub;       // of `order` and of `order_sub`
     // Column-blocked copy of the entries (built for dense-degree operators whose gathered operand does not
     // fit an L2): entries regrouped by (source block cb = idx / CB_ROWS, position p in `order`), original
     // entry order kept inside a group.  Group (cb, p) = entries [b_off[cb*n_out+p], b_off[cb*n_out+p+1]).
@@ -68,6 +79,8 @@ struct SpOp {
 };
 
 constexpr int LONG_ROW = 2048;  // rows at least this long are reduced by a whole workgroup
+constexpr int GIANT_ROW = 16384;  // rows at least this long are cut into pieces when the caller brings scratch
+constexpr int GIANT_PIECE = 4096; // entries per piece: one workgroup each, partial sums combined in piece order
 constexpr int CB_ROWS = 16384;  // source rows per column block: 16384 x 128-byte slices = 2 MB, half an XCD's L2
 constexpr int B_LONG_GROUP = 512; // rows with at least this many entries per source block on average: workgroup per group
 constexpr int B_MID_GROUP = 128;  // ... at least this many: wave per group
@@ -125,7 +138,7 @@ struct SpmmEpilogue {
     int relu = 0;
     int accumulate = 0;            // add the previous contents of Y
     int out_f32 = 0;               // store Y as float although X is bf16
-    void *ws = nullptr;            // scratch for the column-blocked kernel (spmm_ws_bytes), may be null
+    void *ws = nullptr;            // scratch for the column-blocked kernel or for cut rows (spmm_ws_bytes), may be null
     size_t ws_bytes = 0;
 };
 

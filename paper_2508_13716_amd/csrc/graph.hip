@@ -42,6 +42,25 @@ static int64_t degree_order(const std::vector<int64_t> &ptr, int64_t lo, int64_t
     return n_long;
 }
 
+// Cuts the leading rows of a degree-ordered work list that have at least GIANT_ROW entries into pieces.
+static int upload_giant(capgnn_graph *g, const int64_t *ptr, const std::vector<int32_t> &order, GiantList *out) {
+    std::vector<int32_t> pos, first(1, 0);
+    int64_t n = 0;
+    for (; n < static_cast<int64_t>(order.size()); ++n) {
+        const int64_t len = ptr[order[n] + 1] - ptr[order[n]];
+        if (len < GIANT_ROW) break;
+        const int64_t pieces = (len + GIANT_PIECE - 1) / GIANT_PIECE;
+        pos.insert(pos.end(), pieces, static_cast<int32_t>(n));
+        first.push_back(static_cast<int32_t>(pos.size()));
+    }
+    if (n == 0) return CAPGNN_OK;
+    CG_TRY(upload(g, pos.data(), pos.size(), &out->piece_pos));
+    CG_TRY(upload(g, first.data(), first.size(), &out->piece_first));
+    out->n_rows = n;
+    out->n_pieces = static_cast<int64_t>(pos.size());
+    return CAPGNN_OK;
+}
+
 // Column-blocked copy of one direction of the operator (see SpOp).  Worth building only when the gathered
 // operand spans several blocks and a (block, row) group holds enough entries to amortise its overhead.
 struct BlockedHost {
@@ -190,6 +209,8 @@ extern "C" int capgnn_graph_create(capgnn_graph **out, int64_t n_loc, int64_t n_
     if (col_scale && (rc = upload(g, col_scale, n_cols, &f.in_scale))) return fail(rc);
     if ((rc = upload(g, order_f.data(), order_f.size(), &f.order))) return fail(rc);
     f.order_sub = f.order;
+    if ((rc = upload_giant(g, rowptr, order_f, &f.giant))) return fail(rc);
+    f.giant_sub = f.giant;
     for (int64_t i = 0; i < n_loc; ++i) f.max_deg = std::max(f.max_deg, rowptr[i + 1] - rowptr[i]);
     BlockedHost bh_f;
     if (build_blocked(rowptr, col, edge_val, col_scale, order_f, n_loc, n_cols, &bh_f) && (rc = upload_blocked(g, bh_f, &f)))
@@ -200,6 +221,7 @@ extern "C" int capgnn_graph_create(capgnn_graph **out, int64_t n_loc, int64_t n_
     if (share) {
         b.ptr = f.ptr; b.idx = f.idx; b.val = f.val; b.order = f.order; b.n_long = f.n_long;
         b.order_sub = f.order; b.n_sub = n_loc; b.n_long_sub = f.n_long; b.max_deg = f.max_deg;
+        b.giant = f.giant; b.giant_sub = f.giant;
         b.ncb = f.ncb; b.b_off = f.b_off; b.b_ew = f.b_ew; b.b_long = f.b_long; b.b_mid = f.b_mid;
         const bool same_scales = (!row_scale && !col_scale) ||
                                  (row_scale && col_scale && std::memcmp(row_scale, col_scale, n_loc * sizeof(float)) == 0);
@@ -220,6 +242,8 @@ extern "C" int capgnn_graph_create(capgnn_graph **out, int64_t n_loc, int64_t n_
         if (edge_val && (rc = upload(g, cscval.data(), nnz, &b.val))) return fail(rc);
         if ((rc = upload(g, order_b.data(), order_b.size(), &b.order))) return fail(rc);
         if ((rc = upload(g, order_bs.data(), order_bs.size(), &b.order_sub))) return fail(rc);
+        if ((rc = upload_giant(g, colptr.data(), order_b, &b.giant))) return fail(rc);
+        if ((rc = upload_giant(g, colptr.data(), order_bs, &b.giant_sub))) return fail(rc);
         for (int64_t j = 0; j < n_cols; ++j) b.max_deg = std::max(b.max_deg, colptr[j + 1] - colptr[j]);
         BlockedHost bh;
         if (build_blocked(colptr.data(), rowidx.data(), edge_val ? cscval.data() : nullptr, row_scale, order_b, n_cols,

@@ -31,6 +31,11 @@ struct SpmmArgs {
     const float *bias;
     int relu;
     int accumulate;
+    // cut rows: piece lists and the fp32 partial sums [n_pieces][ldp]
+    const int32_t *piece_pos;
+    const int32_t *piece_first;
+    float *part;
+    int64_t ldp;
 };
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
@@ -171,8 +176,11 @@ __device__ __forceinline__ void accumulate_range(const SpmmArgs &a, int64_t e_be
     }
 }
 
-template <bool BF16, bool OBF16, int E, int LPR, int NV, bool LONG>
+// MODE 0: one wave per output row.  MODE 1: one workgroup per row.  MODE 2: one workgroup per piece of a cut row;
+// the raw fp32 sum of the piece goes to a.part and spmm_pieces_finish_kernel completes the row.
+template <bool BF16, bool OBF16, int E, int LPR, int NV, int MODE>
 __global__ __launch_bounds__(256) void spmm_kernel(SpmmArgs a) {
+    constexpr bool LONG = MODE >= 1;
     constexpr int G = 64 / LPR;
     constexpr int ES = OBF16 ? 2 : 4;   // element size of the output
     constexpr int U = (NV == 1) ? 8 : 4;
@@ -183,8 +191,12 @@ __global__ __launch_bounds__(256) void spmm_kernel(SpmmArgs a) {
     const int64_t slot = a.list_begin + (LONG ? static_cast<int64_t>(blockIdx.x)
                                               : static_cast<int64_t>(blockIdx.x) * 4 + wave);
     if (slot >= a.list_end) return;   // LONG: uniform over the workgroup
-    const int row = a.order[slot];
+    const int row = a.order[MODE == 2 ? a.piece_pos[slot] : slot];
     int64_t beg = a.ptr[row], end = a.ptr[row + 1];
+    if constexpr (MODE == 2) {
+        beg += static_cast<int64_t>(slot - a.piece_first[a.piece_pos[slot]]) * GIANT_PIECE;
+        if (beg + GIANT_PIECE < end) end = beg + GIANT_PIECE;
+    }
     if constexpr (LONG) {
         const int64_t len = end - beg;
         const int64_t per = ((len + 3) / 4 + 63) / 64 * 64;
@@ -228,6 +240,19 @@ __global__ __launch_bounds__(256) void spmm_kernel(SpmmArgs a) {
 #pragma unroll
                         for (int j = 0; j < E; ++j) acc[v][j] += red[wv][v * E + j][lane];
             }
+        }
+        if constexpr (MODE == 2) {
+            if (wave == 0 && lane < LPR) {
+                float *prow = a.part + slot * a.ldp;
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    const int f0 = elem0 + v * LPR * E;
+#pragma unroll
+                    for (int j = 0; j < E; ++j)
+                        if (f0 + j < a.F) prow[f0 + j] = acc[v][j];
+                }
+            }
+            continue;
         }
         if ((!LONG || wave == 0) && lane < LPR) {
             char *yrow = a.Y + static_cast<int64_t>(row) * a.ldy_bytes;
@@ -551,9 +576,13 @@ static BlockedGeom blocked_geom(const SpOp &op, int F, int dtype) {
     return g;
 }
 
+static int64_t pieces_ldp(int F) { return (static_cast<int64_t>(F) + 7) / 8 * 8; }
+
 size_t spmm_ws_bytes(const SpOp &op, int F, int dtype) {
     const BlockedGeom g = blocked_geom(op, F, dtype);
-    return g.ok ? g.ws : 0;
+    const int64_t pieces = std::max(op.giant.n_pieces, op.giant_sub.n_pieces);
+    const size_t cut = F > 0 ? static_cast<size_t>(pieces) * pieces_ldp(F) * sizeof(float) : 0;
+    return std::max<size_t>(g.ok ? g.ws : 0, cut);
 }
 
 template <bool BF16, bool OBF16>
@@ -576,21 +605,52 @@ static int launch_blocked(const SpOp &op, const BlockedGeom &g, const SpmmArgs &
     return CAPGNN_OK;
 }
 
+// Completes the cut rows: sums the pieces of a row in piece order and applies the same epilogue as spmm_kernel.
+template <bool OBF16>
+__global__ __launch_bounds__(256) void spmm_pieces_finish_kernel(SpmmArgs a, int64_t n_giant) {
+    constexpr int ES = OBF16 ? 2 : 4;
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (t >= n_giant * a.F) return;
+    const int64_t pos = t / a.F;
+    const int f = static_cast<int>(t - pos * a.F);
+    const int row = a.order[pos];
+    float acc = 0.f;
+    for (int q = a.piece_first[pos]; q < a.piece_first[pos + 1]; ++q) acc += a.part[q * a.ldp + f];
+    acc *= a.out_scale ? a.out_scale[row] : 1.f;
+    char *y = a.Y + static_cast<int64_t>(row) * a.ldy_bytes + static_cast<int64_t>(f) * ES;
+    if (a.accumulate) acc += load_one<OBF16>(y);
+    if (a.bias) acc += a.bias[f];
+    if (a.relu) acc = acc > 0.f ? acc : 0.f;
+    store_one<OBF16>(y, acc);
+}
+
 template <bool BF16, bool OBF16, int E, int LPR, int NV>
-static int launch_cfg(const SpmmArgs &base, int64_t n_long, int64_t n_rows, hipStream_t st) {
-    if (n_long > 0) {
+static int launch_cfg(const SpmmArgs &base, const GiantList *giant, int64_t n_long, int64_t n_rows, hipStream_t st) {
+    int64_t n_giant = 0;
+    if (giant) {
+        n_giant = giant->n_rows;
         SpmmArgs a = base;
         a.list_begin = 0;
+        a.list_end = giant->n_pieces;
+        hipLaunchKernelGGL((spmm_kernel<BF16, OBF16, E, LPR, NV, 2>), dim3(static_cast<unsigned>(giant->n_pieces)),
+                           dim3(256), 0, st, a);
+        const int64_t threads = n_giant * a.F;
+        hipLaunchKernelGGL((spmm_pieces_finish_kernel<OBF16>), dim3(static_cast<unsigned>((threads + 255) / 256)),
+                           dim3(256), 0, st, a, n_giant);
+    }
+    if (n_long > n_giant) {
+        SpmmArgs a = base;
+        a.list_begin = n_giant;
         a.list_end = n_long;
-        hipLaunchKernelGGL((spmm_kernel<BF16, OBF16, E, LPR, NV, true>), dim3(static_cast<unsigned>(n_long)), dim3(256), 0,
-                           st, a);
+        hipLaunchKernelGGL((spmm_kernel<BF16, OBF16, E, LPR, NV, 1>), dim3(static_cast<unsigned>(n_long - n_giant)),
+                           dim3(256), 0, st, a);
     }
     if (n_rows > n_long) {
         SpmmArgs a = base;
         a.list_begin = n_long;
         a.list_end = n_rows;
         const int64_t blocks = (n_rows - n_long + 3) / 4;
-        hipLaunchKernelGGL((spmm_kernel<BF16, OBF16, E, LPR, NV, false>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
+        hipLaunchKernelGGL((spmm_kernel<BF16, OBF16, E, LPR, NV, 0>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
                            st, a);
     }
     CG_HIP(hipGetLastError());
@@ -598,21 +658,21 @@ static int launch_cfg(const SpmmArgs &base, int64_t n_long, int64_t n_rows, hipS
 }
 
 template <bool BF16, bool OBF16>
-static int dispatch(const SpmmArgs &a, bool vec, int64_t n_long, int64_t n_rows, hipStream_t st) {
+static int dispatch(const SpmmArgs &a, bool vec, const GiantList *gl, int64_t n_long, int64_t n_rows, hipStream_t st) {
     constexpr int EV = BF16 ? 8 : 4;
     if (vec) {
         const int nvec = a.F_lim / EV;
-        if (nvec <= 4) return launch_cfg<BF16, OBF16, EV, 4, 1>(a, n_long, n_rows, st);
-        if (nvec <= 8) return launch_cfg<BF16, OBF16, EV, 8, 1>(a, n_long, n_rows, st);
-        if (nvec <= 16) return launch_cfg<BF16, OBF16, EV, 16, 1>(a, n_long, n_rows, st);
-        if (nvec <= 32) return launch_cfg<BF16, OBF16, EV, 32, 1>(a, n_long, n_rows, st);
-        if (nvec <= 64) return launch_cfg<BF16, OBF16, EV, 64, 1>(a, n_long, n_rows, st);
-        if (nvec <= 128) return launch_cfg<BF16, OBF16, EV, 64, 2>(a, n_long, n_rows, st);
-        return launch_cfg<BF16, OBF16, EV, 64, 3>(a, n_long, n_rows, st);   // wider rows take several passes
+        if (nvec <= 4) return launch_cfg<BF16, OBF16, EV, 4, 1>(a, gl, n_long, n_rows, st);
+        if (nvec <= 8) return launch_cfg<BF16, OBF16, EV, 8, 1>(a, gl, n_long, n_rows, st);
+        if (nvec <= 16) return launch_cfg<BF16, OBF16, EV, 16, 1>(a, gl, n_long, n_rows, st);
+        if (nvec <= 32) return launch_cfg<BF16, OBF16, EV, 32, 1>(a, gl, n_long, n_rows, st);
+        if (nvec <= 64) return launch_cfg<BF16, OBF16, EV, 64, 1>(a, gl, n_long, n_rows, st);
+        if (nvec <= 128) return launch_cfg<BF16, OBF16, EV, 64, 2>(a, gl, n_long, n_rows, st);
+        return launch_cfg<BF16, OBF16, EV, 64, 3>(a, gl, n_long, n_rows, st);   // wider rows take several passes
     }
-    if (a.F <= 64) return launch_cfg<BF16, OBF16, 1, 64, 1>(a, n_long, n_rows, st);
-    if (a.F <= 128) return launch_cfg<BF16, OBF16, 1, 64, 2>(a, n_long, n_rows, st);
-    return launch_cfg<BF16, OBF16, 1, 64, 4>(a, n_long, n_rows, st);
+    if (a.F <= 64) return launch_cfg<BF16, OBF16, 1, 64, 1>(a, gl, n_long, n_rows, st);
+    if (a.F <= 128) return launch_cfg<BF16, OBF16, 1, 64, 2>(a, gl, n_long, n_rows, st);
+    return launch_cfg<BF16, OBF16, 1, 64, 4>(a, gl, n_long, n_rows, st);
 }
 
 int launch_spmm(const SpOp &op, bool restrict_sub, const void *X, int64_t ldx, void *Y, int64_t ldy, int F,
@@ -650,9 +710,17 @@ int launch_spmm(const SpOp &op, bool restrict_sub, const void *X, int64_t ldx, v
             return launch_blocked<true, false>(op, bg, a, part, stream);
         }
     }
-    if (dtype == CAPGNN_F32) return dispatch<false, false>(a, vec, n_long, n_rows, stream);
-    if (out_dtype == CAPGNN_BF16) return dispatch<true, true>(a, vec, n_long, n_rows, stream);
-    return dispatch<true, false>(a, vec, n_long, n_rows, stream);
+    // rows too long for one workgroup are cut into pieces when the caller brought scratch for their partial sums
+    const GiantList &gl = restrict_sub ? op.giant_sub : op.giant;
+    const GiantList *cut = nullptr;
+    a.piece_pos = gl.piece_pos; a.piece_first = gl.piece_first;
+    a.part = static_cast<float *>(ep.ws); a.ldp = pieces_ldp(F);
+    if (gl.n_rows > 0 && ep.ws && (reinterpret_cast<uintptr_t>(ep.ws) & 15u) == 0 &&
+        ep.ws_bytes >= static_cast<size_t>(gl.n_pieces) * a.ldp * sizeof(float))
+        cut = &gl;
+    if (dtype == CAPGNN_F32) return dispatch<false, false>(a, vec, cut, n_long, n_rows, stream);
+    if (out_dtype == CAPGNN_BF16) return dispatch<true, true>(a, vec, cut, n_long, n_rows, stream);
+    return dispatch<true, false>(a, vec, cut, n_long, n_rows, stream);
 }
 
 }  // namespace capgnn

@@ -59,9 +59,9 @@ def run_spmm(env, part, F, ld, dtype, with_vals, seed, blocked=False):
     Yd = torch.full((part.n_loc, ld), 7.0, dtype=Xd.dtype, device="cuda")
     dXd = torch.full((part.n_cols, ld), 7.0, dtype=Xd.dtype, device="cuda")
     ws, wsb = None, 0
-    if blocked:       # with scratch the column-blocked kernel runs (the graph must qualify for a blocked copy)
+    if blocked:       # with scratch the column-blocked kernel runs, or very long rows are cut into pieces
         wsb = B.spmm_workspace_bytes(g, F, dt)
-        assert wsb > 0, "graph or width does not qualify for the column-blocked kernel"
+        assert wsb > 0, "graph or width qualifies neither for the column-blocked kernel nor for cut rows"
         ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
     B.spmm_fwd(g, Xd, ld, Yd, ld, F, dt, ws=ws, ws_bytes=wsb)
     B.spmm_bwd(g, dYd, ld, dXd, ld, F, dt, ws=ws, ws_bytes=wsb)
@@ -113,6 +113,28 @@ def test_spmm_column_blocked(env, shape):
                                (602, 604, "f32", False), (64, 64, "bf16", False), (200, 200, "bf16", True),
                                (256, 264, "bf16", False)]:
         say(f"spmm blocked {part.name} F={F} ld={ld} {dtype}")
+        run_spmm(env, part, F, ld, dtype, vals, seed=F, blocked=True)
+
+
+def test_spmm_rows_cut_into_pieces(env):
+    """Rows and columns far longer than one workgroup's share: with scratch they are cut into pieces whose
+    partial sums are combined in a fixed order.  One row of 40000 entries, one exactly at the cutting
+    threshold plus one, two halo columns referenced by 33000 rows (ragged last piece), the rest short."""
+    rng = np.random.default_rng(5)
+    n_loc, n_halo = 45000, 50
+    n_cols = n_loc + n_halo
+    rows = [rng.integers(0, n_cols, 40000), rng.integers(0, n_cols, 16385)]
+    for i in range(2, n_loc):
+        extra = [n_loc, n_loc + 1] if i < 33002 else []
+        rows.append(np.array(list(rng.integers(0, n_cols, 3)) + extra))
+    rowptr = np.zeros(n_loc + 1, np.int64)
+    np.cumsum([len(r) for r in rows], out=rowptr[1:])
+    col = np.concatenate(rows).astype(np.int32)
+    part = synth.Partition("cut", n_loc, n_halo, rowptr, col, np.arange(n_halo, dtype=np.int64),
+                           np.ones(n_halo, np.int64), np.ones(n_halo, np.int64), False, False)
+    for F, ld, dtype, vals in [(32, 32, "f32", False), (41, 44, "f32", True), (256, 256, "bf16", False),
+                               (100, 104, "bf16", True), (7, 7, "f32", False)]:
+        say(f"spmm cut rows F={F} ld={ld} {dtype}")
         run_spmm(env, part, F, ld, dtype, vals, seed=F, blocked=True)
 
 
