@@ -21,6 +21,8 @@
  *                     configured number of iterations.
  *   orc_influence     RAPA's vertex influence score (Eq. 6): degree-normalised sums over a vertex's outgoing
  *                     and incoming neighbours, times its repetition count.
+ *   orc_locality_order  "we reorder the subgraphs" (end of the RAPA section, reorder figure): a new storage order
+ *                     of the partition's vertices.  The paper names no algorithm; two orders are defined here.
  *   orc_gcn_scales    notation table: A-hat is the symmetrically normalised adjacency.
  *   orc_spmm_fwd      aggregation step of Eq. 1; A-hat * H in the GCN rule of Lemma 2's proof.
  *   orc_spmm_bwd      the transposed product the chain rule of that rule needs
@@ -150,6 +152,72 @@ void orc_influence(int64_t n_loc, int64_t n_cols, const int64_t *rowptr, const i
         for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e)
             S[i] += (1.0 / sqrt(dout[col[e]])) * (1.0 / sqrt(din[i]));
     for (int64_t v = 0; v < n_cols; ++v) S[v] *= count[v];
+}
+
+/* ---------------------------------------------------------------- storage order of the vertices */
+/* new2old[k] = the vertex stored at place k.  Local vertices keep places [0, n_loc), halo vertices the places
+ * after them, so the partition keeps its shape and every result is the old one with rows permuted.
+ *
+ * method 0, by popularity: inside each of the two ranges, vertices referenced by more entries come first
+ * (ties: smaller old index first).
+ *
+ * method 1, breadth first: local vertices in the order a breadth-first search over the local-to-local entries
+ * reaches them.  A search starts at the unreached vertex with the longest row (ties: smaller index), a reached
+ * vertex's row is scanned in stored order, and when a search dies out the next one starts the same way.
+ * Halo vertices follow in the order in which the rows, walked in the new local order, first mention them;
+ * halo vertices no row mentions come last, by index. */
+typedef struct { int64_t key, idx; } orc_pair_t;
+
+static int orc_pair_desc(const void *a, const void *b)
+{
+    const orc_pair_t *x = (const orc_pair_t *)a, *y = (const orc_pair_t *)b;
+    if (x->key != y->key) return x->key > y->key ? -1 : 1;
+    return x->idx < y->idx ? -1 : (x->idx > y->idx ? 1 : 0);
+}
+
+int orc_locality_order(int method, int64_t n_loc, int64_t n_halo, const int64_t *rowptr, const int32_t *col,
+                       int32_t *new2old)
+{
+    const int64_t n_cols = n_loc + n_halo;
+    orc_pair_t *byk = (orc_pair_t *)malloc((size_t)(n_cols > 0 ? n_cols : 1) * sizeof(orc_pair_t));
+    char *seen = (char *)calloc((size_t)(n_cols > 0 ? n_cols : 1), 1);
+    if (!byk || !seen) { free(byk); free(seen); return -1; }
+    if (method == 0) {
+        for (int64_t j = 0; j < n_cols; ++j) { byk[j].key = 0; byk[j].idx = j; }
+        for (int64_t e = 0; e < rowptr[n_loc]; ++e) byk[col[e]].key += 1;
+        qsort(byk, (size_t)n_loc, sizeof(orc_pair_t), orc_pair_desc);
+        qsort(byk + n_loc, (size_t)n_halo, sizeof(orc_pair_t), orc_pair_desc);
+        for (int64_t k = 0; k < n_cols; ++k) new2old[k] = (int32_t)byk[k].idx;
+    } else {
+        for (int64_t i = 0; i < n_loc; ++i) { byk[i].key = rowptr[i + 1] - rowptr[i]; byk[i].idx = i; }
+        qsort(byk, (size_t)n_loc, sizeof(orc_pair_t), orc_pair_desc);
+        int64_t placed = 0, head = 0;           /* new2old[0..placed) doubles as the search queue */
+        for (int64_t s = 0; s < n_loc; ++s) {
+            int64_t root = byk[s].idx;
+            if (seen[root]) continue;
+            seen[root] = 1;
+            new2old[placed++] = (int32_t)root;
+            while (head < placed) {
+                int64_t u = new2old[head++];
+                for (int64_t e = rowptr[u]; e < rowptr[u + 1]; ++e) {
+                    int64_t v = col[e];
+                    if (v < n_loc && !seen[v]) { seen[v] = 1; new2old[placed++] = (int32_t)v; }
+                }
+            }
+        }
+        for (int64_t k = 0; k < n_loc; ++k) {
+            int64_t u = new2old[k];
+            for (int64_t e = rowptr[u]; e < rowptr[u + 1]; ++e) {
+                int64_t v = col[e];
+                if (v >= n_loc && !seen[v]) { seen[v] = 1; new2old[placed++] = (int32_t)v; }
+            }
+        }
+        for (int64_t v = n_loc; v < n_cols; ++v)
+            if (!seen[v]) new2old[placed++] = (int32_t)v;
+    }
+    free(byk);
+    free(seen);
+    return 0;
 }
 
 /* ---------------------------------------------------------------- normalisation scales */

@@ -54,6 +54,8 @@ def _lib():
         L.orc_max_threads.restype = C.c_int
         L.orc_set_threads.argtypes = [C.c_int]
         L.orc_placement.argtypes = [i64, p, p, i64, p, p]
+        L.orc_locality_order.argtypes = [C.c_int, i64, i64, p, p, p]
+        L.orc_locality_order.restype = C.c_int
         L.orc_gather.argtypes = [p, i64, i64, p, i64, p]
         L.orc_gather.restype = i64
         L.orc_cache_update.argtypes = [p, p, i64, i64, p, i64, p, i64]
@@ -233,6 +235,41 @@ def influence_score(n_loc: int, n_cols: int, rowptr, col, din, dout, count=None)
     S = np.zeros(n_cols, np.float64)
     _lib().orc_influence(n_loc, n_cols, _ptr(rowptr), _ptr(col), _ptr(din), _ptr(dout), _ptr(cnt), _ptr(S))
     return S
+
+
+def locality_order(method: str, n_loc: int, n_halo: int, rowptr, col) -> np.ndarray:
+    """A storage order of the partition's vertices ("we reorder the subgraphs", reorder figure): new2old, a
+    permutation that keeps local vertices in [0, n_loc) and halo vertices after them.  method "popularity":
+    most referenced first inside each range; "bfs": breadth-first over the local-to-local entries from the
+    longest rows, halo vertices by first mention (both defined in full in capgnn_oracle.c)."""
+    rowptr = np.ascontiguousarray(rowptr, np.int64)
+    col = np.ascontiguousarray(col, np.int32)
+    out = np.zeros(n_loc + n_halo, np.int32)
+    rc = _lib().orc_locality_order({"popularity": 0, "bfs": 1}[method], n_loc, n_halo, _ptr(rowptr), _ptr(col), _ptr(out))
+    if rc != 0:
+        raise MemoryError("orc_locality_order")
+    return out
+
+
+def relabel_csr(n_loc: int, rowptr, col, new2old, val=None):
+    """The partition's CSR after its vertices moved to the places new2old names: row k of the result is old row
+    new2old[k] with every column index replaced by its new place; entries keep their order inside a row."""
+    rowptr = np.asarray(rowptr, np.int64)
+    col = np.asarray(col, np.int64)
+    new2old = np.asarray(new2old, np.int64)
+    old2new = np.zeros(len(new2old), np.int64)
+    for k, o in enumerate(new2old):
+        old2new[o] = k
+    new_ptr, new_col, new_val = [0], [], []
+    for k in range(n_loc):
+        o = new2old[k]
+        for e in range(rowptr[o], rowptr[o + 1]):
+            new_col.append(old2new[col[e]])
+            if val is not None:
+                new_val.append(val[e])
+        new_ptr.append(len(new_col))
+    return (np.array(new_ptr, np.int64), np.array(new_col, np.int32),
+            None if val is None else np.array(new_val, np.asarray(val).dtype))
 
 
 # ------------------------------------------------------------------ graph

@@ -95,3 +95,20 @@ def sample_indices(lengths: np.ndarray, k: int, seed: int) -> np.ndarray:
     order = np.argsort(lengths, kind="stable")
     pick = np.concatenate([order[:8], order[-8:], rng.integers(0, n, size=max(k - 16, 0))])
     return np.unique(pick.astype(np.int64))
+
+
+# ----------------------------------------------------------------------------- relabelled problems
+def relabelled_problem(prob, new2old):
+    """The same training problem with its vertices stored in the order new2old (CSR through the oracle's relabel;
+    rows of the features, labels, mask, cache tables and halo attributes moved alike)."""
+    import dataclasses
+    part = prob.part
+    nl = part.n_loc
+    new2old = np.asarray(new2old, np.int64)
+    pl, ph = new2old[:nl], new2old[nl:] - nl
+    rowptr, col, _ = orc.relabel_csr(nl, part.rowptr, part.col, new2old)
+    part2 = dataclasses.replace(part, name=part.name + "-relabelled", rowptr=rowptr, col=col,
+                                halo_gid=part.halo_gid[ph], halo_prio=part.halo_prio[ph],
+                                halo_degree=part.halo_degree[ph])
+    return dataclasses.replace(prob, part=part2, X0=prob.X0[pl], tables=[t[ph] for t in prob.tables],
+                               labels=prob.labels[pl], mask=prob.mask[pl])

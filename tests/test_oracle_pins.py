@@ -342,6 +342,90 @@ def test_influence_score_vs_dense_bruteforce_and_closed_forms(orc):
 
 
 # ----------------------------------------------------------------------------- cache side
+def _sym_partition(n, edges, n_halo=0, halo_edges=()):
+    """Undirected local graph (both directions stored, rows sorted, no duplicates) plus local->halo entries."""
+    und = {(a, b) for a, b in edges if a != b} | {(b, a) for a, b in edges if a != b}
+    return synth.hand_partition(n, n_halo, sorted(und) + [(i, n + h) for i, h in halo_edges], name="sym")
+
+
+def test_locality_order_is_a_valid_order_and_matches_library_bfs(orc):
+    """The vertex storage order: a permutation that keeps the local / halo ranges; 'popularity' is checked
+    against its definition by brute force; 'bfs' on a connected graph with sorted rows is the textbook
+    breadth-first order, taken here from scipy's graph routines; on a relabelled ring it restores bandwidth 2;
+    components stay contiguous; halo vertices follow their first mention."""
+    from scipy.sparse import csr_matrix
+    from scipy.sparse.csgraph import breadth_first_order
+    rng = np.random.default_rng(12)
+    # validity + popularity on random partitions (duplicates, empty rows, unreferenced halo vertices)
+    for seed in range(4):
+        part = synth.make_partition("ord", 300, 200, 2500, seed=seed, max_deg=60)
+        refs = np.bincount(part.col, minlength=part.n_cols)
+        for method in ("popularity", "bfs"):
+            o = orc.locality_order(method, part.n_loc, part.n_halo, part.rowptr, part.col)
+            assert sorted(o.tolist()) == list(range(part.n_cols))
+            assert (o[: part.n_loc] < part.n_loc).all() and (o[part.n_loc:] >= part.n_loc).all()
+        o = orc.locality_order("popularity", part.n_loc, part.n_halo, part.rowptr, part.col)
+        for seg in (o[: part.n_loc], o[part.n_loc:]):
+            key = [(-int(refs[v]), int(v)) for v in seg]
+            assert key == sorted(key)
+    # bfs == scipy's breadth-first order from the longest row on a connected undirected graph
+    n = 400
+    ring = [(i, (i + 1) % n) for i in range(n)]
+    chords = [(int(a), int(b)) for a, b in rng.integers(0, n, (300, 2))]
+    part = _sym_partition(n, ring + chords)
+    deg = np.diff(part.rowptr)
+    root = int(np.flatnonzero(deg == deg.max())[0])
+    A = csr_matrix((np.ones(part.nnz), part.col, part.rowptr), shape=(n, n))
+    want = breadth_first_order(A, root, directed=True, return_predecessors=False)
+    got = orc.locality_order("bfs", n, 0, part.rowptr, part.col)
+    assert len(want) == n and np.array_equal(got, want)
+    # a ring whose labels were shuffled: breadth-first relabelling brings every edge within distance 2
+    n = 257
+    lab = rng.permutation(n)
+    part = _sym_partition(n, [(int(lab[i]), int(lab[(i + 1) % n])) for i in range(n)])
+    o = orc.locality_order("bfs", n, 0, part.rowptr, part.col)
+    ptr2, col2, _ = orc.relabel_csr(n, part.rowptr, part.col, o)
+    rows2 = np.repeat(np.arange(n), np.diff(ptr2))
+    assert np.abs(rows2 - col2).max() == 2
+    ptr0_rows = np.repeat(np.arange(n), np.diff(part.rowptr))
+    assert np.abs(ptr0_rows - part.col).max() > 50            # the shuffled labelling had no such locality
+    # two rings and an isolated vertex: every component occupies a contiguous range of the new order;
+    # halo vertices: first mention decides, never-mentioned ones come last in index order
+    a, b = list(range(0, 30)), list(range(30, 50))
+    edges = [(a[i], a[(i + 1) % 30]) for i in range(30)] + [(b[i], b[(i + 1) % 20]) for i in range(20)]
+    part = _sym_partition(51, edges, n_halo=6, halo_edges=[(35, 4), (2, 1), (50, 0), (2, 3)])
+    o = orc.locality_order("bfs", 51, 6, part.rowptr, part.col)
+    comp = np.array([0] * 30 + [1] * 20 + [2])[o[:51]]
+    assert (np.diff(np.flatnonzero(np.diff(comp) != 0)) > 0).all() and len(np.flatnonzero(np.diff(comp) != 0)) == 2
+    where = {int(v): k for k, v in enumerate(o[:51])}
+    mentioned = sorted([(where[35], 4), (where[2], 1), (where[50], 0), (where[2], 3)])   # rows are sorted by column
+    assert o[51:].tolist() == [51 + h for _, h in mentioned] + [51 + 2, 51 + 5]
+
+
+def test_relabelled_problem_gives_the_same_epoch_with_rows_permuted(orc):
+    """Moving the vertices to new places changes no result: loss and weight gradients stay, per-vertex
+    outputs move with their vertex (checked on a GCN and a GraphSAGE problem, both orders)."""
+    from tests import oracle_side as O
+    from paper_2508_13716_amd import harness as H
+    for name in ("C1", "C3"):
+        cfg = synth.CONFIGS[name].scaled(0.004) if name == "C3" else synth.CONFIGS[name].scaled(0.25)
+        prob = H.make_problem(cfg, mask_frac=0.6)
+        ref = O.oracle_epoch(prob, halo_grad=True)
+        for method in ("popularity", "bfs"):
+            part = prob.part
+            o = orc.locality_order(method, part.n_loc, part.n_halo, part.rowptr, part.col)
+            assert not np.array_equal(o, np.arange(part.n_cols))
+            got = O.oracle_epoch(O.relabelled_problem(prob, o), halo_grad=True)
+            pl, ph = o[: part.n_loc], o[part.n_loc:] - part.n_loc
+            assert abs(got["loss"] - ref["loss"]) <= 1e-12 * abs(ref["loss"])
+            assert O.normwise(got["logits"], ref["logits"][pl]) <= 1e-12
+            for l in range(len(prob.model)):
+                assert O.normwise(got["hidden"][l], ref["hidden"][l][pl]) <= 1e-12
+                assert O.normwise(got["dW"][l], ref["dW"][l]) <= 1e-11
+                assert O.normwise(got["db"][l], ref["db"][l]) <= 1e-11
+                assert O.normwise(got["dX_halo"][l], ref["dX_halo"][l][ph]) <= 1e-11
+
+
 def test_cache_update_and_staleness_vs_bruteforce(orc):
     """Vertex update and the bounded-staleness list against plain Python loops, plus what must hold whatever the
     input: untouched rows keep their bytes and stamps, the last of repeated updates stays, absent ids are
