@@ -166,15 +166,77 @@ def bench_policy(args):
                       "overlap_ratio_histogram": hist, "overlap_ratio_kernel_ms": t_overlap * 1e3, "curves": curves}))
 
 
+def bench_reorder(args):
+    """Aggregation time of one SpMM launch (forward and transposed, hidden width 256) before and after the
+    vertices are stored in a locality order, on the named config's graph (--config; 'clustered' = a graph with
+    geometric locality whose numbering hides it); one JSON line."""
+    import torch
+    from paper_2508_13716_amd import binding as B, synth
+    F = 256
+    if args.config == "clustered":
+        part = synth.make_clustered_partition("clustered", 1_300_000, 26, 4000, seed=synth.BASE_SEED * 10 + 7)
+        kind, bf = B.NORM_SYM, True
+        workload = f"clustered ring-window graph, labels shuffled: {part.n_loc} vertices, {part.nnz} entries"
+    else:
+        cfg = synth.CONFIGS[args.config]
+        part = synth.partition_for(cfg)
+        kind, bf = (B.NORM_SYM if cfg.kind == "gcn" else B.NORM_MEAN), cfg.dtype == "bf16"
+        workload = f"{args.config}: {part.n_loc} local + {part.n_halo} halo vertices, {part.nnz} entries"
+    dt, tdt, es = (B.BF16, torch.bfloat16, 2) if bf else (B.F32, torch.float32, 4)
+    st = torch.cuda.Stream()
+
+    def timeit(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(args.steps):
+            fn()
+        e1.record(st)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    def measure(rowptr, col, halo_degree):
+        r, c = B.norm_scales(kind, part.n_loc, part.n_halo, rowptr, halo_degree)
+        g = B.Graph(part.n_loc, part.n_halo, rowptr, col, r, c, None, B.GRAPH_SYMMETRIC if part.symmetric else 0)
+        X = torch.randn(part.n_cols, F, device="cuda").to(tdt)
+        Y = torch.empty(part.n_loc, F, device="cuda", dtype=tdt)
+        dY = torch.randn(part.n_loc, F, device="cuda").to(tdt)
+        dX = torch.empty(part.n_cols, F, device="cuda", dtype=tdt)
+        wsb = B.spmm_workspace_bytes(g, F, dt)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+        tf = timeit(lambda: B.spmm_fwd(g, X, F, Y, F, F, dt, st, ws=ws, ws_bytes=wsb))
+        tb = timeit(lambda: B.spmm_bwd(g, dY, F, dX, F, F, dt, st, ws=ws, ws_bytes=wsb))
+        g.close()
+        gathered = part.nnz * F * es
+        return {"spmm_fwd_ms": round(tf, 4), "spmm_bwd_ms": round(tb, 4), "fwd_gather_GBps": round(gathered / tf / 1e6, 1),
+                "bwd_gather_GBps": round(gathered / tb / 1e6, 1)}
+
+    hd = part.halo_degree if part.n_halo else None
+    out = {"original": measure(part.rowptr, part.col, hd)}
+    for name, mid in (("popularity", B.RELABEL_POPULARITY), ("bfs", B.RELABEL_BFS)):
+        t0 = time.perf_counter()
+        o = B.locality_order(mid, part.n_loc, part.n_halo, part.rowptr, part.col)
+        rp, cl, _ = B.relabel_csr(part.n_loc, part.n_halo, part.rowptr, part.col, o)
+        host_s = time.perf_counter() - t0
+        out[name] = measure(rp, cl, None if hd is None else hd[o[part.n_loc:] - part.n_loc])
+        out[name]["host_order_and_relabel_s"] = round(host_s, 2)
+    print(json.dumps({"metric": "SpMM time before / after vertex reordering", "unit": "ms per launch", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "dtype": "bf16" if bf else "f32", "data": "synthetic",
+                      "config": {"workload": workload, "F": F}, "orders": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C2")
-    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy"],
+    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder"],
                     help="epoch (default): the headline benchmark; cache_update: throughput of the cache write path; "
-                         "policy: hit-rate curves of the cache policies")
+                         "policy: hit-rate curves of the cache policies; reorder: SpMM before / after vertex reordering "
+                         "(--config C2..C5 or clustered)")
     ap.add_argument("--miss-mode", type=int, default=None, help="0 zero-copy kernel, 1 staged DMA, 2 staged DMA prefetched one epoch ahead (default 2)")
     ap.add_argument("--orders", default=None, help="comma list of 1 (aggregate first) / 2 (transform first) per layer")
     ap.add_argument("--cpu-scale", type=float, default=None,
@@ -194,6 +256,8 @@ def main():
     B.lib()
     if args.what == "cache_update":
         return bench_cache_update(args)
+    if args.what == "reorder":
+        return bench_reorder(args)
     if args.what == "policy":
         return bench_policy(args)
 

@@ -254,6 +254,32 @@ int capgnn_policy_simulate(int n_parts, const int64_t *halo_ptr, const int64_t *
                            int64_t cap_local, int64_t cap_global, int epochs, int warmup, int64_t *counts);
 
 /* ------------------------------------------------------------------------------------------
+ * Storage order of the vertices (the subgraph reordering that follows RAPA; the reorder figure).  The paper
+ * names no algorithm, so any order is admissible as long as results only move with their vertex.  Host code.
+ *
+ * capgnn_locality_order: new2old[n_loc + n_halo] (host, written) = the vertex to store at each place; local
+ * vertices keep places [0, n_loc), halo vertices the places after them.
+ *   CAPGNN_RELABEL_POPULARITY  inside each range, vertices referenced by more entries first (ties: lower index)
+ *   CAPGNN_RELABEL_BFS         local vertices in breadth-first order over the local-to-local entries: a search
+ *                              starts at the unreached vertex with the longest row (ties: lower index) and scans
+ *                              rows in stored order; halo vertices in the order in which the rows, walked in
+ *                              the new local order, first mention them; unmentioned ones last, by index.
+ * capgnn_relabel_csr: the CSR with vertices moved to those places: row k of the result is old row new2old[k]
+ * with columns renumbered and its entries (edge_val with them, may be NULL) sorted by the new column, equal
+ * columns in their old order: a sorted CSR stays sorted, a symmetric one equal to its transpose.  Outputs are host
+ * arrays of the input's sizes, owned by the caller.  The caller moves the rows of its features, labels, masks
+ * and halo attributes the same way (row k <- old row new2old[k]).
+ * Errors: CAPGNN_EINVAL for malformed CSR, an unknown method, or a new2old that is no such permutation.
+ * ---------------------------------------------------------------------------------------- */
+#define CAPGNN_RELABEL_POPULARITY 0
+#define CAPGNN_RELABEL_BFS 1
+int capgnn_locality_order(int method, int64_t n_loc, int64_t n_halo, const int64_t *rowptr, const int32_t *col,
+                          int32_t *new2old);
+int capgnn_relabel_csr(int64_t n_loc, int64_t n_halo, const int64_t *rowptr, const int32_t *col,
+                       const float *edge_val, const int32_t *new2old, int64_t *rowptr_out, int32_t *col_out,
+                       float *val_out);
+
+/* ------------------------------------------------------------------------------------------
  * Dense products on the matrix cores ("MM is related to the number of vertices").
  * C[M x N] (+)= op(A) op(B) with fp32 accumulation; optional fused bias / ReLU epilogue.
  * trans_a: A is stored [K x M];  trans_b: B is stored [N x K].  bias: device float[N] or NULL.

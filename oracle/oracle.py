@@ -253,7 +253,8 @@ def locality_order(method: str, n_loc: int, n_halo: int, rowptr, col) -> np.ndar
 
 def relabel_csr(n_loc: int, rowptr, col, new2old, val=None):
     """The partition's CSR after its vertices moved to the places new2old names: row k of the result is old row
-    new2old[k] with every column index replaced by its new place; entries keep their order inside a row."""
+    new2old[k] with every column index replaced by its new place, its entries sorted by that new index (equal
+    indices keep their order), so a sorted CSR stays sorted and a symmetric one stays equal to its transpose."""
     rowptr = np.asarray(rowptr, np.int64)
     col = np.asarray(col, np.int64)
     new2old = np.asarray(new2old, np.int64)
@@ -263,7 +264,8 @@ def relabel_csr(n_loc: int, rowptr, col, new2old, val=None):
     new_ptr, new_col, new_val = [0], [], []
     for k in range(n_loc):
         o = new2old[k]
-        for e in range(rowptr[o], rowptr[o + 1]):
+        entries = sorted(range(rowptr[o], rowptr[o + 1]), key=lambda e: old2new[col[e]])   # sorted() is stable
+        for e in entries:
             new_col.append(old2new[col[e]])
             if val is not None:
                 new_val.append(val[e])

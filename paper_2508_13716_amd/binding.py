@@ -80,6 +80,8 @@ SIGNATURES = {
     "capgnn_overlap_ratio": (_i32, [_vp, _i64, _i64, _vp, _vp]),
     "capgnn_influence_score": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp]),
     "capgnn_policy_simulate": (_i32, [_i32, _vp, _vp, _i32, _i64, _i64, _i32, _i32, _vp]),
+    "capgnn_locality_order": (_i32, [_i32, _i64, _i64, _vp, _vp, _vp]),
+    "capgnn_relabel_csr": (_i32, [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "capgnn_cache_update": (_i32, [_vp, _i32, _vp, _i64, _i32, _vp, _i64, _i64, _vp, _vp]),
     "capgnn_cache_stale": (_i32, [_vp, _i32, _i64, _i64, _vp, _vp, _vp, _vp]),
     "capgnn_cache_fill": (_i32, [_vp, _i32, _vp, _i64, _vp]),
@@ -324,6 +326,30 @@ def policy_simulate(halo_sets, policy: int, cap_local: int, cap_global: int, epo
     out = np.zeros(3, np.int64)
     _check(lib().capgnn_policy_simulate(len(halo_sets), _p(ptr), _p(ids), policy, cap_local, cap_global, epochs, warmup, _p(out)))
     return int(out[0]), int(out[1]), int(out[2])
+
+
+RELABEL_POPULARITY, RELABEL_BFS = 0, 1
+
+
+def locality_order(method: int, n_loc: int, n_halo: int, rowptr, col) -> np.ndarray:
+    """new2old (int32 [n_loc + n_halo]): the vertex to store at each place."""
+    rowptr = np.ascontiguousarray(rowptr, np.int64)
+    col = np.ascontiguousarray(col, np.int32)
+    out = np.zeros(n_loc + n_halo, np.int32)
+    _check(lib().capgnn_locality_order(method, n_loc, n_halo, _p(rowptr), _p(col), _p(out)))
+    return out
+
+
+def relabel_csr(n_loc: int, n_halo: int, rowptr, col, new2old, edge_val=None):
+    """(rowptr, col, edge_val) of the partition with its vertices moved to the places new2old names."""
+    rowptr = np.ascontiguousarray(rowptr, np.int64)
+    col = np.ascontiguousarray(col, np.int32)
+    new2old = np.ascontiguousarray(new2old, np.int32)
+    val = None if edge_val is None else np.ascontiguousarray(edge_val, np.float32)
+    rp, cl = np.zeros_like(rowptr), np.zeros_like(col)
+    vl = None if val is None else np.zeros_like(val)
+    _check(lib().capgnn_relabel_csr(n_loc, n_halo, _p(rowptr), _p(col), _p(val), _p(new2old), _p(rp), _p(cl), _p(vl)))
+    return rp, cl, vl
 
 
 # --------------------------------------------------------------------------- dense, layer, loss, epoch

@@ -59,7 +59,8 @@ struct SpOp {
     const float *val = nullptr;       // device [nnz] or null
     const float *out_scale = nullptr; // device [n_out] or null
     const float *in_scale = nullptr;  // device [n_in]  or null
-    // work lists: output rows ordered by entry count, descending
+    // work lists: output rows by entry count, descending; rows shorter than EXACT_ROW only by power-of-two class,
+    // in index order inside a class
     const int32_t *order = nullptr;   // device [n_out]
     int64_t n_long = 0;               // first n_long entries of `order` have >= LONG_ROW entries
     int64_t n_sub = 0;                // rows [0, n_sub) of the output restricted list (bwd: local columns only)
@@ -78,6 +79,7 @@ struct SpOp {
     int64_t b_long = 0, b_mid = 0;
 };
 
+constexpr int EXACT_ROW = 256;  // work lists sort rows at least this long by their exact entry count
 constexpr int LONG_ROW = 2048;  // rows at least this long are reduced by a whole workgroup
 constexpr int GIANT_ROW = 16384;  // rows at least this long are cut into pieces when the caller brings scratch
 constexpr int GIANT_PIECE = 4096; // entries per piece: one workgroup each, partial sums combined in piece order

@@ -28,12 +28,23 @@ static int upload(capgnn_graph *g, const T *host, size_t n, const T **dev_out) {
     return CAPGNN_OK;
 }
 
-// Output rows ordered by entry count (descending, ties by index); returns how many are "long".
+// Sorting key of a row in the work lists: its entry count when that is at least EXACT_ROW, else the power of two
+// below it.  Long rows are thus in exact descending order (the class limits of the kernels cut that part), and
+// the many short rows of one power-of-two class stay in index order, so whatever locality the caller's vertex
+// numbering has survives into the order in which rows are processed.
+static int64_t order_key(int64_t len) {
+    if (len >= EXACT_ROW || len <= 0) return len;
+    int64_t k = 1;
+    while (2 * k <= len) k *= 2;
+    return k;
+}
+
+// Output rows [lo, hi) ordered by order_key (descending, ties by index); returns how many are "long".
 static int64_t degree_order(const std::vector<int64_t> &ptr, int64_t lo, int64_t hi, std::vector<int32_t> &order) {
     order.resize(hi - lo);
     std::iota(order.begin(), order.end(), static_cast<int32_t>(lo));
     std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
-        return (ptr[a + 1] - ptr[a]) > (ptr[b + 1] - ptr[b]);
+        return order_key(ptr[a + 1] - ptr[a]) > order_key(ptr[b + 1] - ptr[b]);
     });
     int64_t n_long = 0;
     while (n_long < static_cast<int64_t>(order.size()) &&

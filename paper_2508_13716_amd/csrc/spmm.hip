@@ -176,10 +176,11 @@ __device__ __forceinline__ void accumulate_range(const SpmmArgs &a, int64_t e_be
     }
 }
 
-// MODE 0: one wave per output row.  MODE 1: one workgroup per row.  MODE 2: one workgroup per piece of a cut row;
+// MODE 0: one single-wave workgroup per output row (rows of one work-list class differ in length, and a wave that
+// shares a workgroup with a longer row would hold its slot until that one ends).  MODE 1: one workgroup per row.  MODE 2: one workgroup per piece of a cut row;
 // the raw fp32 sum of the piece goes to a.part and spmm_pieces_finish_kernel completes the row.
 template <bool BF16, bool OBF16, int E, int LPR, int NV, int MODE>
-__global__ __launch_bounds__(256) void spmm_kernel(SpmmArgs a) {
+__global__ __launch_bounds__(MODE == 0 ? 64 : 256) void spmm_kernel(SpmmArgs a) {
     constexpr bool LONG = MODE >= 1;
     constexpr int G = 64 / LPR;
     constexpr int ES = OBF16 ? 2 : 4;   // element size of the output
@@ -188,8 +189,7 @@ __global__ __launch_bounds__(256) void spmm_kernel(SpmmArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int l = lane % LPR;
-    const int64_t slot = a.list_begin + (LONG ? static_cast<int64_t>(blockIdx.x)
-                                              : static_cast<int64_t>(blockIdx.x) * 4 + wave);
+    const int64_t slot = a.list_begin + blockIdx.x;
     if (slot >= a.list_end) return;   // LONG: uniform over the workgroup
     const int row = a.order[MODE == 2 ? a.piece_pos[slot] : slot];
     int64_t beg = a.ptr[row], end = a.ptr[row + 1];
@@ -649,9 +649,8 @@ static int launch_cfg(const SpmmArgs &base, const GiantList *giant, int64_t n_lo
         SpmmArgs a = base;
         a.list_begin = n_long;
         a.list_end = n_rows;
-        const int64_t blocks = (n_rows - n_long + 3) / 4;
-        hipLaunchKernelGGL((spmm_kernel<BF16, OBF16, E, LPR, NV, 0>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
-                           st, a);
+        hipLaunchKernelGGL((spmm_kernel<BF16, OBF16, E, LPR, NV, 0>), dim3(static_cast<unsigned>(n_rows - n_long)),
+                           dim3(64), 0, st, a);
     }
     CG_HIP(hipGetLastError());
     return CAPGNN_OK;

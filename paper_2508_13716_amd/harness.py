@@ -39,6 +39,23 @@ def make_problem(cfg: synth.Config, mask_frac: float = 1.0, part: Optional[synth
     return Problem(cfg, part, X0, tables, model, labels, mask, synth.cap_gpu_for(cfg, part))
 
 
+def relabel_problem(prob: Problem, method: int):
+    """The same problem with its vertices stored in the library's locality order.  Returns (problem, new2old);
+    per-vertex rows of the result k correspond to old rows new2old[k]."""
+    import dataclasses
+    part = prob.part
+    nl = part.n_loc
+    new2old = B.locality_order(method, nl, part.n_halo, part.rowptr, part.col)
+    rowptr, col, _ = B.relabel_csr(nl, part.n_halo, part.rowptr, part.col, new2old)
+    pl, ph = new2old[:nl].astype(np.int64), new2old[nl:].astype(np.int64) - nl
+    part2 = dataclasses.replace(part, name=part.name + "-relabelled", rowptr=rowptr, col=col,
+                                halo_gid=part.halo_gid[ph], halo_prio=part.halo_prio[ph],
+                                halo_degree=part.halo_degree[ph])
+    prob2 = dataclasses.replace(prob, part=part2, X0=prob.X0[pl], tables=[t[ph] for t in prob.tables],
+                                labels=prob.labels[pl], mask=prob.mask[pl])
+    return prob2, new2old
+
+
 def _torch():
     import torch
     return torch

@@ -195,6 +195,32 @@ def make_partition(name: str, n_loc: int, n_halo: int, nnz: int, *, seed: int,
     return Partition(name, n_loc, n_halo, rowptr, col, gid, prio, degree, self_loops, symmetric)
 
 
+def make_clustered_partition(name: str, n_loc: int, avg_deg: int, window: int, *, seed: int,
+                             shuffle: bool = True) -> Partition:
+    """Undirected graph with geometric locality and a numbering that hides it: vertex u is joined to about
+    avg_deg vertices drawn uniformly from u's `window` nearest positions on a ring, then (with ``shuffle``) the
+    vertex labels are permuted at random.  Stand-in for a graph with community structure stored in arrival order,
+    the case a locality reordering is for.  No halo, self loops added, both directions stored."""
+    rng = rng_for(seed, 5)
+    m = n_loc * avg_deg // 2
+    u = rng.integers(0, n_loc, size=m, dtype=np.int64)
+    off = rng.integers(1, window // 2 + 1, size=m, dtype=np.int64) * rng.choice(np.array([-1, 1], np.int64), size=m)
+    v = (u + off) % n_loc
+    if shuffle:
+        lab = rng.permutation(n_loc).astype(np.int64)
+        u, v = lab[u], lab[v]
+    d = np.arange(n_loc, dtype=np.int64)
+    rows = np.concatenate([u, v, d])
+    cols = np.concatenate([v, u, d])
+    key = np.unique(rows * np.int64(n_loc) + cols)
+    rows = key // np.int64(n_loc)
+    col = (key - rows * np.int64(n_loc)).astype(np.int32)
+    rowptr = np.zeros(n_loc + 1, dtype=np.int64)
+    np.cumsum(np.bincount(rows, minlength=n_loc), out=rowptr[1:])
+    z = np.zeros(0, np.int64)
+    return Partition(name, n_loc, 0, rowptr, col, z, z, z, True, True)
+
+
 def make_halo_sets(n: int, nnz: int, n_parts: int, *, seed: int, gamma: float = 2.1, max_deg: Optional[int] = None):
     """Halo sets of a random n_parts-way vertex partition of one power-law graph (the paper's "Random"
     pre-partitioning): H_i = the vertices outside part i that are sources of edges into part i.  Returns
