@@ -344,6 +344,43 @@ def softmax_ce(Z, y, mask=None, norm: float = 0.0):
     return float(loss), dZ
 
 
+def sigmoid_bce(Z, Y, mask=None, norm: float = 0.0):
+    """Binary cross-entropy on logits, the loss of the multi-label tasks (evaluation setup): per element
+    -[y log s(z) + (1-y) log(1-s(z))] with s the logistic function, written in the overflow-free form
+    max(z,0) - z y + log(1 + exp(-|z|)); summed over the masked rows and all classes and divided by `norm`
+    (default: masked rows x classes, the mean over elements).  Returns (loss, dloss/dZ)."""
+    Z, Y = _f64(Z), _f64(Y)
+    n, C = Z.shape
+    on = np.ones(n, bool) if mask is None else np.asarray(mask).astype(bool)
+    if norm <= 0.0:
+        norm = float(max(int(on.sum()), 1) * C)
+    per = np.maximum(Z, 0.0) - Z * Y + np.log1p(np.exp(-np.abs(Z)))
+    loss = float(per[on].sum() / norm)
+    e = np.exp(-np.abs(Z))
+    s = np.where(Z >= 0, 1.0 / (1.0 + e), e / (1.0 + e))
+    dZ = (s - Y) / norm
+    dZ[~on] = 0.0
+    return loss, dZ
+
+
+def gin_graph(n_loc: int, n_halo: int, rowptr, col, eps: float = 0.0):
+    """Operator of a GIN layer's aggregation, (1 + eps) x_i + sum_{j in N(i)} x_j: the stored entries with unit
+    weight plus a diagonal entry (1 + eps) appended to every row; no normalisation.  The layer itself is then
+    sigma(A X W + b), i.e. kind 'gcn' on this operator (GIN with a one-layer update function)."""
+    rowptr = np.asarray(rowptr, np.int64)
+    col = np.asarray(col, np.int32)
+    new_ptr = rowptr + np.arange(n_loc + 1, dtype=np.int64)
+    new_col = np.zeros(int(new_ptr[-1]), np.int32)
+    val = np.ones(int(new_ptr[-1]), np.float64)
+    for i in range(n_loc):
+        a, b = int(rowptr[i]), int(rowptr[i + 1])
+        q = int(new_ptr[i])
+        new_col[q: q + b - a] = col[a:b]
+        new_col[q + b - a] = i
+        val[q + b - a] = 1.0 + eps
+    return Graph(n_loc, n_loc + n_halo, new_ptr, new_col, np.ones(n_loc), np.ones(n_loc + n_halo), val)
+
+
 # ------------------------------------------------------------------ layers
 @dataclass
 class Layer:
@@ -401,12 +438,13 @@ def layer_bwd(g: Graph, l: Layer, X, saved, dH, need_dx: bool = True, relu_on=No
 
 def epoch(g: Graph, layers: List[Layer], X0_local, halo_tables: Sequence[Optional[np.ndarray]],
           labels, mask=None, loss_norm: float = 0.0, lr: float = 0.0, halo_grad: bool = False,
-          relu_on: Optional[Sequence] = None):
+          relu_on: Optional[Sequence] = None, loss_kind: str = "ce"):
     """One full-batch forward + backward over the partition.
 
     halo_tables[l] is the logical [n_halo, f_in(l)] cache table feeding layer l (None when the
     partition has no halo).  relu_on[l], when given, overrides layer l's backward decision 1[Z > 0]
-    (see layer_bwd).  Returns dict(loss, logits, dW, dW_self, db, dX_halo, hidden, new_W ...).
+    (see layer_bwd).  loss_kind "ce": labels are class indices (single-label tasks); "bce": labels is the
+    [n_loc, classes] 0/1 target matrix (multi-label tasks).  Returns dict(loss, logits, dW, dW_self, db, dX_halo, hidden, new_W ...).
     """
     n_halo = g.n_cols - g.n_loc
     ids = np.arange(n_halo, dtype=np.int64)
@@ -423,7 +461,7 @@ def epoch(g: Graph, layers: List[Layer], X0_local, halo_tables: Sequence[Optiona
         Xs.append(X)
         saves.append(sv)
     logits = H
-    loss, dH = softmax_ce(logits, labels, mask, loss_norm)
+    loss, dH = (softmax_ce if loss_kind == "ce" else sigmoid_bce)(logits, labels, mask, loss_norm)
     res = {"loss": loss, "logits": logits, "dW": [None] * len(layers), "dW_self": [None] * len(layers),
            "db": [None] * len(layers), "dX_halo": [None] * len(layers), "hidden": [s["Z"] for s in saves]}
     for li in range(len(layers) - 1, -1, -1):

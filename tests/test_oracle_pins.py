@@ -267,6 +267,90 @@ def test_gradients_vs_central_finite_differences(orc, kind):
         check(T, res["dX_halo"][li], pick)
 
 
+def test_sigmoid_bce_textbook_two_class_equivalence_and_finite_differences(orc):
+    """Multi-label loss: log 2 at zero logits; the textbook -[y log s + (1-y) log(1-s)] at moderate logits; for a
+    single class it is the (already pinned) softmax cross-entropy of the two-class logits (z, 0); extreme logits
+    neither overflow nor lose the linear tail; masked-off rows contribute nothing; gradient by central differences."""
+    rng = np.random.default_rng(31)
+    n, C = 11, 5
+    Y = (rng.random((n, C)) < 0.4).astype(np.float64)
+    loss, dZ = orc.sigmoid_bce(np.zeros((n, C)), Y)
+    assert abs(loss - math.log(2.0)) < 1e-15 and np.allclose(dZ, (0.5 - Y) / (n * C), atol=1e-17)
+    Z = rng.standard_normal((n, C)) * 3.0
+    mask = (rng.random(n) < 0.6).astype(np.uint8)
+    mask[0], mask[1] = 1, 0
+    loss, dZ = orc.sigmoid_bce(Z, Y, mask)
+    sig = 1.0 / (1.0 + np.exp(-Z))
+    per = -(Y * np.log(sig) + (1.0 - Y) * np.log(1.0 - sig))
+    on = mask.astype(bool)
+    assert abs(loss - per[on].sum() / (on.sum() * C)) < 1e-13
+    assert np.all(dZ[~on] == 0.0)
+    loss_n, dZ_n = orc.sigmoid_bce(Z, Y, mask, norm=7.0)                       # explicit normaliser
+    assert abs(loss_n * 7.0 - loss * on.sum() * C) < 1e-12 and np.allclose(dZ_n * 7.0, dZ * on.sum() * C, atol=1e-15)
+    # one class: BCE(z, y) == CE([z, 0], class 0 if y else class 1)
+    z1 = rng.standard_normal((n, 1)) * 4.0
+    y1 = (rng.random((n, 1)) < 0.5).astype(np.float64)
+    l_b, g_b = orc.sigmoid_bce(z1, y1, mask)
+    l_c, g_c = orc.softmax_ce(np.concatenate([z1, np.zeros((n, 1))], 1), (1 - y1[:, 0]).astype(np.int32), mask)
+    assert abs(l_b - l_c) < 1e-13 and np.allclose(g_b[:, 0], g_c[:, 0], atol=1e-15)
+    # extreme logits
+    Ze = np.array([[800.0, -800.0, 800.0, -800.0]])
+    Ye = np.array([[1.0, 0.0, 0.0, 1.0]])
+    le, ge = orc.sigmoid_bce(Ze, Ye)
+    assert np.isfinite(le) and abs(le - 1600.0 / 4.0) < 1e-9
+    assert np.allclose(ge, np.array([[0.0, 0.0, 1.0, -1.0]]) / 4.0, atol=1e-15)
+    # central differences
+    h = 1e-6
+    for idx in [(0, 0), (0, 4), (5, 2), (10, 1), (1, 3)]:
+        Zp, Zm = Z.copy(), Z.copy()
+        Zp[idx] += h
+        Zm[idx] -= h
+        fd = (orc.sigmoid_bce(Zp, Y, mask)[0] - orc.sigmoid_bce(Zm, Y, mask)[0]) / (2 * h)
+        assert abs(fd - dZ[idx]) < 1e-9
+
+
+def test_gin_operator_vs_edge_loops_and_epoch_gradients(orc):
+    """GIN aggregation (1+eps) x_i + sum over the stored neighbours, against loops over the edges; eps = -1 leaves
+    the neighbour sum, an edgeless graph leaves (1+eps) X; a GIN network trained with the multi-label loss has
+    gradients that match central differences (also pins the epoch's loss switch and edge-valued operators)."""
+    rng = np.random.default_rng(33)
+    part = synth.make_partition("gin", 14, 9, 60, seed=5, max_deg=8, self_loops=False)
+    X = rng.standard_normal((part.n_cols, 6))
+    for eps in (0.0, 0.3, -1.0):
+        g = orc.gin_graph(part.n_loc, part.n_halo, part.rowptr, part.col, eps)
+        want = np.zeros((part.n_loc, 6))
+        for i in range(part.n_loc):
+            want[i] = (1.0 + eps) * X[i]
+            for e in range(part.rowptr[i], part.rowptr[i + 1]):
+                want[i] += X[part.col[e]]
+        assert np.allclose(orc.spmm_fwd(g, X), want, atol=1e-13)
+    g0 = orc.gin_graph(4, 0, np.zeros(5, np.int64), np.zeros(0, np.int32), 0.25)
+    assert np.allclose(orc.spmm_fwd(g0, X[:4]), 1.25 * X[:4], atol=1e-15)
+    g = orc.gin_graph(part.n_loc, part.n_halo, part.rowptr, part.col, 0.3)
+    dims = [6, 4, 3]
+    layers = [orc.Layer("gcn", rng.standard_normal((dims[l], dims[l + 1])) * 0.5, rng.standard_normal(dims[l + 1]) * 0.2,
+                        "relu" if l == 0 else "none") for l in range(2)]
+    X0 = rng.standard_normal((part.n_loc, dims[0]))
+    tables = [rng.standard_normal((part.n_halo, dims[l])) for l in range(2)]
+    Y = (rng.random((part.n_loc, 3)) < 0.4).astype(np.float64)
+    mask = (rng.random(part.n_loc) < 0.7).astype(np.uint8)
+    mask[0] = 1
+    res = orc.epoch(g, layers, X0, tables, Y, mask, loss_kind="bce", halo_grad=True)
+    h = 1e-6
+    for arr, grad, idxs in [(layers[0].W, res["dW"][0], [(0, 0), (5, 3), (2, 1)]), (layers[1].W, res["dW"][1], [(0, 0), (3, 2)]),
+                            (layers[1].bias, res["db"][1], [(1,)]), (tables[1], res["dX_halo"][1], [(0, 0), (8, 3)]),
+                            (tables[0], res["dX_halo"][0], [(4, 5)])]:
+        for idx in idxs:
+            old = arr[idx]
+            arr[idx] = old + h
+            lp = orc.epoch(g, layers, X0, tables, Y, mask, loss_kind="bce")["loss"]
+            arr[idx] = old - h
+            lm = orc.epoch(g, layers, X0, tables, Y, mask, loss_kind="bce")["loss"]
+            arr[idx] = old
+            fd = (lp - lm) / (2 * h)
+            assert abs(fd - grad[idx]) <= 1e-6 * max(1.0, abs(fd)), (idx, fd, grad[idx])
+
+
 def test_sgd_step_is_plain_descent(orc):
     g, layers, X0, tables, y, mask = _tiny_problem(orc, "gcn", 22)
     res = orc.epoch(g, layers, X0, tables, y, mask, lr=0.01)
