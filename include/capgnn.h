@@ -93,6 +93,15 @@ int capgnn_version(void);
 int capgnn_norm_scales(int kind, int64_t n_loc, int64_t n_halo, const int64_t *rowptr,
                        const int64_t *halo_degree, float *row_scale, float *col_scale);
 
+/* Host helper: the operator of a GIN layer's aggregation, (1 + eps) x_i + sum_{j in N(i)} x_j (the paper's
+ * convergence analysis names GIN among the covered architectures: neighbour aggregation, a linear transform, a
+ * Lipschitz nonlinearity).  Output CSR = the input's entries with value 1 plus one diagonal entry of value 1 + eps
+ * appended to every row: rowptr_out host int64[n_loc+1], col_out host int32[nnz+n_loc], val_out host float[nnz+n_loc].
+ * Pass it to capgnn_graph_create with edge_val = val_out and no scales; a CAPGNN_GCN layer on that graph is a GIN
+ * layer with a one-layer update function.  No GPU work. */
+int capgnn_gin_operator(int64_t n_loc, int64_t n_halo, const int64_t *rowptr, const int32_t *col, float eps,
+                        int64_t *rowptr_out, int32_t *col_out, float *val_out);
+
 /* Uploads the CSR, builds the CSC (= CSR of A_hat^T) and the degree-ordered work lists.
  * rowptr: host int64[n_loc+1], rowptr[0]==0, non-decreasing; col: host int32[nnz], each in
  * [0, n_loc+n_halo); nnz < 2^31.  row_scale/col_scale: host float arrays or NULL (= 1).
@@ -345,6 +354,15 @@ int capgnn_softmax_ce(int64_t n, int C, const float *Z, int64_t ldz, const int32
                       const uint8_t *mask, double loss_norm, float *loss_dev, void *dZ, int64_t lddz,
                       int dz_dtype, void *ws, size_t ws_bytes, void *stream);
 
+/* Masked binary cross-entropy on logits (evaluation setup: binary cross-entropy for multi-label tasks) and its
+ * gradient: loss = (1/norm) sum_{mask} sum_k ( max(z,0) - z*y + log(1 + exp(-|z|)) ), which equals
+ * -[y log s(z) + (1-y) log(1 - s(z))] with s the logistic function; dZ = (s(Z) - Y)/norm, zero in unmasked rows.
+ * targets: device uint8 [n x ldt], nonzero = the label is set.  loss_norm <= 0 means "masked rows x C" (the mean over
+ * elements).  Other arguments, workspace and errors as capgnn_softmax_ce. */
+int capgnn_sigmoid_bce(int64_t n, int C, const float *Z, int64_t ldz, const uint8_t *targets, int64_t ldt,
+                       const uint8_t *mask, double loss_norm, float *loss_dev, void *dZ, int64_t lddz,
+                       int dz_dtype, void *ws, size_t ws_bytes, void *stream);
+
 #define CAPGNN_MAX_RECORDS 96
 #define CAPGNN_K_GATHER_HIT   1
 #define CAPGNN_K_GATHER_MISS  2
@@ -381,6 +399,14 @@ int capgnn_epoch(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer *lay
                  float *logits, float **dW, float **dW_self, float **dbias, float lr,
                  float *loss_out, capgnn_epoch_times *times,
                  void *ws, size_t ws_bytes, void *stream, void *side_stream);
+
+/* The same epoch for a multi-label task: the loss is capgnn_sigmoid_bce on targets (device uint8 [n_loc x ldt])
+ * instead of the softmax cross-entropy on labels.  Everything else as capgnn_epoch. */
+int capgnn_epoch_multilabel(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer *layers, int L,
+                            void *X0, int64_t ld0, const uint8_t *targets, int64_t ldt, const uint8_t *mask,
+                            double loss_norm, float *logits, float **dW, float **dW_self, float **dbias, float lr,
+                            float *loss_out, capgnn_epoch_times *times,
+                            void *ws, size_t ws_bytes, void *stream, void *side_stream);
 
 /* Where capgnn_epoch leaves the output of hidden layer l (0 <= l < L-1) inside ws: *ptr = device
  * address of H_l ([n_loc x *ld] of the layers' dtype), valid until ws is reused.  Same arguments as

@@ -67,6 +67,7 @@ SIGNATURES = {
     "capgnn_last_error": (C.c_char_p, []),
     "capgnn_version": (_i32, []),
     "capgnn_norm_scales": (_i32, [_i32, _i64, _i64, _vp, _vp, _vp, _vp]),
+    "capgnn_gin_operator": (_i32, [_i64, _i64, _vp, _vp, C.c_float, _vp, _vp, _vp]),
     "capgnn_graph_create": (_i32, [C.POINTER(_vp), _i64, _i64, _vp, _vp, _vp, _vp, _vp, C.c_uint32, _vp]),
     "capgnn_graph_destroy": (_i32, [_vp]),
     "capgnn_spmm_workspace_bytes": (_sz, [_vp, _i32, _i32]),
@@ -99,6 +100,10 @@ SIGNATURES = {
                                 _i32, _vp, _sz, _vp]),
     "capgnn_loss_workspace_bytes": (_sz, [_i64]),
     "capgnn_softmax_ce": (_i32, [_i64, _i32, _vp, _i64, _vp, _vp, C.c_double, _vp, _vp, _i64, _i32, _vp, _sz, _vp]),
+    "capgnn_sigmoid_bce": (_i32, [_i64, _i32, _vp, _i64, _vp, _i64, _vp, C.c_double, _vp, _vp, _i64, _i32, _vp, _sz, _vp]),
+    "capgnn_epoch_multilabel": (_i32, [_vp, _vp, C.POINTER(Layer), _i32, _vp, _i64, _vp, _i64, _vp, C.c_double, _vp,
+                                       C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_vp), C.c_float, C.POINTER(C.c_float),
+                                       C.POINTER(EpochTimes), _vp, _sz, _vp, _vp]),
     "capgnn_epoch_workspace_bytes": (_sz, [_vp, _vp, C.POINTER(Layer), _i32]),
     "capgnn_epoch_activation": (_i32, [_vp, _vp, C.POINTER(Layer), _i32, _i32, _vp, C.POINTER(_vp), C.POINTER(_i64)]),
     "capgnn_epoch": (_i32, [_vp, _vp, C.POINTER(Layer), _i32, _vp, _i64, _vp, _vp, C.c_double, _vp, C.POINTER(_vp),
@@ -404,6 +409,22 @@ def softmax_ce(n: int, n_classes: int, Z, ldz: int, labels, mask, loss_norm: flo
                                    dz_dtype, _p(ws), ws_bytes, _stream(stream)))
 
 
+def sigmoid_bce(n: int, n_classes: int, Z, ldz: int, targets, ldt: int, mask, loss_norm: float, loss_dev, dZ, lddz: int,
+                dz_dtype: int, ws, ws_bytes: int, stream=None):
+    _check(lib().capgnn_sigmoid_bce(n, n_classes, _p(Z), ldz, _p(targets), ldt, _p(mask), loss_norm, _p(loss_dev), _p(dZ),
+                                    lddz, dz_dtype, _p(ws), ws_bytes, _stream(stream)))
+
+
+def gin_operator(n_loc: int, n_halo: int, rowptr, col, eps: float):
+    """(rowptr, col, edge_val) of the GIN aggregation operator: unit entries plus a diagonal of 1 + eps."""
+    rowptr = np.ascontiguousarray(rowptr, np.int64)
+    col = np.ascontiguousarray(col, np.int32)
+    nnz = int(rowptr[n_loc]) + n_loc
+    rp, cl, vl = np.zeros(n_loc + 1, np.int64), np.zeros(nnz, np.int32), np.zeros(nnz, np.float32)
+    _check(lib().capgnn_gin_operator(n_loc, n_halo, _p(rowptr), _p(col), eps, _p(rp), _p(cl), _p(vl)))
+    return rp, cl, vl
+
+
 def epoch_workspace_bytes(g: Graph, c: Optional[Cache], layers: List[Layer]) -> int:
     arr = (Layer * len(layers))(*layers)
     return int(lib().capgnn_epoch_workspace_bytes(g.h, c.h if c is not None else None, arr, len(layers)))
@@ -420,7 +441,8 @@ def epoch_activation(g: Graph, c: Optional[Cache], layers: List[Layer], l: int, 
 
 def epoch(g: Graph, c: Optional[Cache], layers: List[Layer], X0, ld0: int, labels, mask, loss_norm: float, logits,
           dW: Sequence, dW_self: Optional[Sequence], dbias: Sequence, lr: float, ws, ws_bytes: int, stream=None,
-          side_stream=None, want_loss: bool = True, want_times: bool = False):
+          side_stream=None, want_loss: bool = True, want_times: bool = False, targets=None, ldt: int = 0):
+    """One epoch; with `targets` (device uint8 [n_loc x ldt]) the multi-label entry point runs and `labels` is unused."""
     L = len(layers)
     arr = (Layer * L)(*layers)
     pw = (C.c_void_p * L)(*[_p(t) for t in dW])
@@ -428,8 +450,10 @@ def epoch(g: Graph, c: Optional[Cache], layers: List[Layer], X0, ld0: int, label
     pb = (C.c_void_p * L)(*[_p(t) for t in dbias])
     loss = C.c_float(float("nan"))
     times = EpochTimes() if want_times else None
-    _check(lib().capgnn_epoch(g.h, c.h if c is not None else None, arr, L, _p(X0), ld0, _p(labels), _p(mask), loss_norm,
-                              _p(logits), pw, ps, pb, lr, C.byref(loss) if want_loss else None,
-                              C.byref(times) if times is not None else None, _p(ws), ws_bytes, _stream(stream),
-                              _stream(side_stream)))
+    tail = (_p(mask), loss_norm, _p(logits), pw, ps, pb, lr, C.byref(loss) if want_loss else None,
+            C.byref(times) if times is not None else None, _p(ws), ws_bytes, _stream(stream), _stream(side_stream))
+    if targets is not None:
+        _check(lib().capgnn_epoch_multilabel(g.h, c.h if c is not None else None, arr, L, _p(X0), ld0, _p(targets), ldt, *tail))
+    else:
+        _check(lib().capgnn_epoch(g.h, c.h if c is not None else None, arr, L, _p(X0), ld0, _p(labels), *tail))
     return (float(loss.value) if want_loss else None), (times.as_dict() if times is not None else None)

@@ -158,6 +158,26 @@ extern "C" int capgnn_norm_scales(int kind, int64_t n_loc, int64_t n_halo, const
     return CAPGNN_OK;
 }
 
+extern "C" int capgnn_gin_operator(int64_t n_loc, int64_t n_halo, const int64_t *rowptr, const int32_t *col, float eps,
+                                   int64_t *rowptr_out, int32_t *col_out, float *val_out) {
+    if (n_loc < 0 || n_halo < 0 || !rowptr || !rowptr_out) CG_FAIL(CAPGNN_EINVAL, "gin_operator: bad argument");
+    if (n_loc > 0 && (!col_out || !val_out)) CG_FAIL(CAPGNN_EINVAL, "gin_operator: NULL output");
+    if (rowptr[0] != 0 || (rowptr[n_loc] > 0 && !col)) CG_FAIL(CAPGNN_EINVAL, "gin_operator: malformed CSR");
+    rowptr_out[0] = 0;
+    for (int64_t i = 0; i < n_loc; ++i) {
+        if (rowptr[i + 1] < rowptr[i]) CG_FAIL(CAPGNN_EINVAL, "gin_operator: rowptr decreases at row %lld", (long long)i);
+        int64_t q = rowptr_out[i];
+        for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e, ++q) {
+            col_out[q] = col[e];
+            val_out[q] = 1.f;
+        }
+        col_out[q] = static_cast<int32_t>(i);
+        val_out[q] = 1.f + eps;
+        rowptr_out[i + 1] = q + 1;
+    }
+    return CAPGNN_OK;
+}
+
 extern "C" int capgnn_graph_create(capgnn_graph **out, int64_t n_loc, int64_t n_halo, const int64_t *rowptr,
                                    const int32_t *col, const float *row_scale, const float *col_scale,
                                    const float *edge_val, uint32_t flags, void *stream) {

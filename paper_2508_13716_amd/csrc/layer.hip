@@ -380,12 +380,14 @@ extern "C" int capgnn_epoch_activation(const capgnn_graph *g, const capgnn_cache
     return CAPGNN_OK;
 }
 
-extern "C" int capgnn_epoch(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer *layers, int L, void *X0,
-                            int64_t ld0, const int32_t *labels, const uint8_t *mask, double loss_norm, float *logits,
-                            float **dW, float **dW_self, float **dbias, float lr, float *loss_out,
-                            capgnn_epoch_times *times, void *ws, size_t ws_bytes, void *stream, void *side_stream) {
+// labels (class indices, softmax cross-entropy) or targets (0/1 matrix, binary cross-entropy): exactly one is given
+static int epoch_impl(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer *layers, int L, void *X0,
+                      int64_t ld0, const int32_t *labels, const uint8_t *targets, int64_t ldt, const uint8_t *mask,
+                      double loss_norm, float *logits, float **dW, float **dW_self, float **dbias, float lr, float *loss_out,
+                      capgnn_epoch_times *times, void *ws, size_t ws_bytes, void *stream, void *side_stream) {
     CG_TRY(check_epoch_args(g, c, layers, L));
-    if (!X0 || !labels || !dW || !dbias) CG_FAIL(CAPGNN_EINVAL, "epoch: NULL argument");
+    if (!X0 || (!labels && !targets) || !dW || !dbias) CG_FAIL(CAPGNN_EINVAL, "epoch: NULL argument");
+    if (targets && ldt < layers[L - 1].f_out) CG_FAIL(CAPGNN_EINVAL, "epoch: ldt smaller than the number of classes");
     if (ld0 < layers[0].f_in) CG_FAIL(CAPGNN_EINVAL, "epoch: ld0 smaller than the input width");
     const int dt = layers[0].dtype, es = elem_bytes(dt);
     if (dt == CAPGNN_BF16 && !layers[L - 1].out_f32) CG_FAIL(CAPGNN_EINVAL, "epoch: the last bf16 layer must set out_f32 (the loss reads float logits)");
@@ -486,11 +488,15 @@ extern "C" int capgnn_epoch(const capgnn_graph *g, capgnn_cache *c, const capgnn
     int cur = 0;
     {
         Scope s(CAPGNN_K_LOSS, L - 1, 0, st);
-        if (dt == CAPGNN_BF16)
-            CG_TRY(capgnn_softmax_ce(g->n_loc, C, Z, ldz, labels, mask, loss_norm, loss_dev, w + p.dz32_off, ldz, CAPGNN_F32,
-                                     w + p.loss_ws_off, capgnn_loss_workspace_bytes(g->n_loc), st));
+        // a bf16 model gets the gradient in fp32 first (the bias gradient is summed before rounding)
+        void *dz = dt == CAPGNN_BF16 ? static_cast<void *>(w + p.dz32_off) : static_cast<void *>(w + p.grad_off[cur]);
+        const int64_t lddz = dt == CAPGNN_BF16 ? ldz : p.ld_grad;
+        const int dzt = dt == CAPGNN_BF16 ? CAPGNN_F32 : dt;
+        if (targets)
+            CG_TRY(capgnn_sigmoid_bce(g->n_loc, C, Z, ldz, targets, ldt, mask, loss_norm, loss_dev, dz, lddz, dzt,
+                                      w + p.loss_ws_off, capgnn_loss_workspace_bytes(g->n_loc), st));
         else
-            CG_TRY(capgnn_softmax_ce(g->n_loc, C, Z, ldz, labels, mask, loss_norm, loss_dev, w + p.grad_off[cur], p.ld_grad, dt,
+            CG_TRY(capgnn_softmax_ce(g->n_loc, C, Z, ldz, labels, mask, loss_norm, loss_dev, dz, lddz, dzt,
                                      w + p.loss_ws_off, capgnn_loss_workspace_bytes(g->n_loc), st));
     }
     // backward
@@ -548,4 +554,23 @@ extern "C" int capgnn_epoch(const capgnn_graph *g, capgnn_cache *c, const capgnn
         g_rec.reset(false);
     }
     return CAPGNN_OK;
+}
+
+extern "C" int capgnn_epoch(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer *layers, int L, void *X0,
+                            int64_t ld0, const int32_t *labels, const uint8_t *mask, double loss_norm, float *logits,
+                            float **dW, float **dW_self, float **dbias, float lr, float *loss_out,
+                            capgnn_epoch_times *times, void *ws, size_t ws_bytes, void *stream, void *side_stream) {
+    if (!labels) CG_FAIL(CAPGNN_EINVAL, "epoch: labels is NULL");
+    return epoch_impl(g, c, layers, L, X0, ld0, labels, nullptr, 0, mask, loss_norm, logits, dW, dW_self, dbias, lr, loss_out,
+                      times, ws, ws_bytes, stream, side_stream);
+}
+
+extern "C" int capgnn_epoch_multilabel(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer *layers, int L, void *X0,
+                                       int64_t ld0, const uint8_t *targets, int64_t ldt, const uint8_t *mask,
+                                       double loss_norm, float *logits, float **dW, float **dW_self, float **dbias,
+                                       float lr, float *loss_out, capgnn_epoch_times *times, void *ws, size_t ws_bytes,
+                                       void *stream, void *side_stream) {
+    if (!targets) CG_FAIL(CAPGNN_EINVAL, "epoch_multilabel: targets is NULL");
+    return epoch_impl(g, c, layers, L, X0, ld0, nullptr, targets, ldt, mask, loss_norm, logits, dW, dW_self, dbias, lr,
+                      loss_out, times, ws, ws_bytes, stream, side_stream);
 }

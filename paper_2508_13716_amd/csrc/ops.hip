@@ -263,11 +263,11 @@ __global__ __launch_bounds__(1024) void count_mask_kernel(int64_t n, const uint8
     if (threadIdx.x == 0) part[blockIdx.x] = c;
 }
 
-__global__ __launch_bounds__(64) void count_final_kernel(int parts, const double *part, float *norm_out) {
+__global__ __launch_bounds__(64) void count_final_kernel(int parts, const double *part, float times, float *norm_out) {
     if (threadIdx.x != 0) return;
     double c = 0.0;
     for (int b = 0; b < parts; ++b) c += part[b];
-    norm_out[0] = c > 0.0 ? static_cast<float>(c) : 1.f;
+    norm_out[0] = (c > 0.0 ? static_cast<float>(c) : 1.f) * times;
 }
 
 // one wave per row; lanes stride over the classes
@@ -305,6 +305,38 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(int64_t n, int C, const
     }
 }
 
+// Binary cross-entropy on logits, one wave per row, lanes stride over the classes: the element's loss in the form
+// max(z,0) - z*y + log(1 + exp(-|z|)), which neither overflows nor cancels, and its derivative s(z) - y.
+__global__ __launch_bounds__(256) void sigmoid_bce_kernel(int64_t n, int C, const float *Z, int64_t ldz,
+                                                          const uint8_t *targets, int64_t ldt, const uint8_t *mask,
+                                                          float norm_val, const float *norm_dev, float *row_loss, char *dZ,
+                                                          int64_t lddz, int dz_bf16) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (row >= n) return;
+    const bool on = !mask || mask[row];
+    if (!on) {
+        if (lane == 0) row_loss[row] = 0.f;
+        if (dZ) for (int k = lane; k < C; k += 64) st_elem(dZ, row * lddz + k, 0.f, dz_bf16);
+        return;
+    }
+    const float inv = 1.f / (norm_dev ? norm_dev[0] : norm_val);
+    const float *z = Z + row * ldz;
+    const uint8_t *t = targets + row * ldt;
+    float s = 0.f;
+    for (int k = lane; k < C; k += 64) {
+        const float zk = z[k], y = t[k] ? 1.f : 0.f;
+        const float e = expf(-fabsf(zk));
+        s += fmaxf(zk, 0.f) - zk * y + log1pf(e);
+        if (dZ) {
+            const float sig = zk >= 0.f ? 1.f / (1.f + e) : e / (1.f + e);
+            st_elem(dZ, row * lddz + k, (sig - y) * inv, dz_bf16);
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    if (lane == 0) row_loss[row] = s;
+}
+
 __global__ __launch_bounds__(1024) void loss_partial_kernel(int64_t n, const float *row_loss, double *part) {
     __shared__ double red[1024];
     const int64_t per = (n + gridDim.x - 1) / gridDim.x;
@@ -332,6 +364,36 @@ extern "C" size_t capgnn_loss_workspace_bytes(int64_t n) {
     return align_up(LOSS_HEADER + static_cast<size_t>(n > 0 ? n : 1) * sizeof(float), 256);
 }
 
+extern "C" int capgnn_sigmoid_bce(int64_t n, int C, const float *Z, int64_t ldz, const uint8_t *targets, int64_t ldt,
+                                  const uint8_t *mask, double loss_norm, float *loss_dev, void *dZ, int64_t lddz,
+                                  int dz_dtype, void *ws, size_t ws_bytes, void *stream) {
+    if (dz_dtype != CAPGNN_F32 && dz_dtype != CAPGNN_BF16) CG_FAIL(CAPGNN_EINVAL, "sigmoid_bce: unknown dz_dtype");
+    if (n < 0 || C <= 0) CG_FAIL(CAPGNN_EINVAL, "sigmoid_bce: bad sizes");
+    if (n == 0) return CAPGNN_OK;
+    if (!Z || !targets || !loss_dev) CG_FAIL(CAPGNN_EINVAL, "sigmoid_bce: NULL operand");
+    if (ldz < C || ldt < C || (dZ && lddz < C)) CG_FAIL(CAPGNN_EINVAL, "sigmoid_bce: leading dimension smaller than C");
+    if (!ws || ws_bytes < capgnn_loss_workspace_bytes(n)) CG_FAIL(CAPGNN_ENOMEM, "sigmoid_bce: workspace too small");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *norm_dev = nullptr;
+    float norm_val = 1.f;
+    double *part = reinterpret_cast<double *>(static_cast<char *>(ws) + 256);
+    const int parts = static_cast<int>(std::max<int64_t>(1, std::min<int64_t>((n + 4095) / 4096, LOSS_PARTS)));
+    if (loss_norm > 0.0) norm_val = static_cast<float>(loss_norm);
+    else if (!mask) norm_val = static_cast<float>(n) * static_cast<float>(C);
+    else {   // masked rows x classes
+        norm_dev = static_cast<float *>(ws);
+        hipLaunchKernelGGL(count_mask_kernel, dim3(parts), dim3(1024), 0, st, n, mask, part);
+        hipLaunchKernelGGL(count_final_kernel, dim3(1), dim3(64), 0, st, parts, part, static_cast<float>(C), norm_dev);
+    }
+    float *row_loss = reinterpret_cast<float *>(static_cast<char *>(ws) + LOSS_HEADER);
+    hipLaunchKernelGGL(sigmoid_bce_kernel, dim3(static_cast<unsigned>((n + 3) / 4)), dim3(256), 0, st, n, C, Z, ldz, targets,
+                       ldt, mask, norm_val, norm_dev, row_loss, static_cast<char *>(dZ), lddz, dz_dtype == CAPGNN_BF16 ? 1 : 0);
+    hipLaunchKernelGGL(loss_partial_kernel, dim3(parts), dim3(1024), 0, st, n, row_loss, part);
+    hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(64), 0, st, parts, part, norm_val, norm_dev, loss_dev);
+    CG_HIP(hipGetLastError());
+    return CAPGNN_OK;
+}
+
 extern "C" int capgnn_softmax_ce(int64_t n, int C, const float *Z, int64_t ldz, const int32_t *labels,
                                  const uint8_t *mask, double loss_norm, float *loss_dev, void *dZ, int64_t lddz,
                                  int dz_dtype, void *ws, size_t ws_bytes, void *stream) {
@@ -352,7 +414,7 @@ extern "C" int capgnn_softmax_ce(int64_t n, int C, const float *Z, int64_t ldz, 
     else {
         norm_dev = scratch;
         hipLaunchKernelGGL(count_mask_kernel, dim3(parts), dim3(1024), 0, st, n, mask, part);
-        hipLaunchKernelGGL(count_final_kernel, dim3(1), dim3(64), 0, st, parts, part, norm_dev);
+        hipLaunchKernelGGL(count_final_kernel, dim3(1), dim3(64), 0, st, parts, part, 1.f, norm_dev);
     }
     float *row_loss = reinterpret_cast<float *>(static_cast<char *>(ws) + LOSS_HEADER);
     hipLaunchKernelGGL(softmax_ce_kernel, dim3(static_cast<unsigned>((n + 3) / 4)), dim3(256), 0, st, n, C, Z, ldz,

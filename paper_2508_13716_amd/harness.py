@@ -26,6 +26,7 @@ class Problem:
     labels: np.ndarray                 # int32 [n_loc]
     mask: np.ndarray                   # uint8 [n_loc]
     cap_gpu: int
+    targets: Optional[np.ndarray] = None   # uint8 [n_loc, classes]: multi-label task (binary cross-entropy)
 
 
 def make_problem(cfg: synth.Config, mask_frac: float = 1.0, part: Optional[synth.Partition] = None) -> Problem:
@@ -36,7 +37,10 @@ def make_problem(cfg: synth.Config, mask_frac: float = 1.0, part: Optional[synth
               for l in range(L)]
     model = synth.make_model(cfg.kind, cfg.dims, seed=cfg.seed, dtype=cfg.dtype)
     labels, mask = synth.make_labels(part.n_loc, cfg.dims[-1], seed=cfg.seed, mask_frac=mask_frac)
-    return Problem(cfg, part, X0, tables, model, labels, mask, synth.cap_gpu_for(cfg, part))
+    targets = None
+    if cfg.extra.get("loss") == "bce":
+        targets = synth.make_multilabels(part.n_loc, cfg.dims[-1], seed=cfg.seed)
+    return Problem(cfg, part, X0, tables, model, labels, mask, synth.cap_gpu_for(cfg, part), targets)
 
 
 def relabel_problem(prob: Problem, method: int):
@@ -108,10 +112,14 @@ class DeviceProblem:
         self.stream = torch.cuda.Stream()
         self.side = torch.cuda.Stream() if (use_side_stream and part.n_halo > 0) else None
 
-        kind = B.NORM_SYM if cfg.kind == "gcn" else B.NORM_MEAN
-        r, c = B.norm_scales(kind, part.n_loc, part.n_halo, part.rowptr, part.halo_degree)
-        flags = B.GRAPH_SYMMETRIC if part.symmetric else 0
-        self.graph = B.Graph(part.n_loc, part.n_halo, part.rowptr, part.col, r, c, None, flags)
+        if cfg.kind == "gin":
+            rp, cl, vl = B.gin_operator(part.n_loc, part.n_halo, part.rowptr, part.col, float(cfg.extra.get("gin_eps", 0.0)))
+            self.graph = B.Graph(part.n_loc, part.n_halo, rp, cl, None, None, vl, 0)
+        else:
+            kind = B.NORM_SYM if cfg.kind == "gcn" else B.NORM_MEAN
+            r, c = B.norm_scales(kind, part.n_loc, part.n_halo, part.rowptr, part.halo_degree)
+            flags = B.GRAPH_SYMMETRIC if part.symmetric else 0
+            self.graph = B.Graph(part.n_loc, part.n_halo, part.rowptr, part.col, r, c, None, flags)
 
         self.cache = None
         if part.n_halo > 0:
@@ -140,11 +148,12 @@ class DeviceProblem:
             self.dW_self.append(torch.zeros(p.W.shape, dtype=torch.float32, device="cuda") if Ws is not None else None)
             self.dbias.append(torch.zeros(p.f_out, dtype=torch.float32, device="cuda"))
             order = B.ORDER_AUTO if orders is None else orders[l]
-            self.layers.append(B.make_layer(B.GCN if p.kind == "gcn" else B.SAGE_MEAN, p.f_in, p.f_out,
+            self.layers.append(B.make_layer(B.SAGE_MEAN if p.kind == "sage" else B.GCN, p.f_in, p.f_out,
                                             B.ACT_RELU if p.act == "relu" else B.ACT_NONE, self.dtype, W, Ws, b, order,
                                             out_f32=1 if (l == L - 1 and self.dtype == B.BF16) else 0))
         self.labels = torch.from_numpy(prob.labels).cuda()
         self.mask = torch.from_numpy(prob.mask).cuda()
+        self.targets = None if prob.targets is None else torch.from_numpy(np.ascontiguousarray(prob.targets)).cuda()
         self.logits = torch.zeros((part.n_loc, cfg.dims[-1]), dtype=torch.float32, device="cuda")
         self.ws_bytes = B.epoch_workspace_bytes(self.graph, self.cache, self.layers)
         if self.ws_bytes == 0:
@@ -159,7 +168,8 @@ class DeviceProblem:
         return B.epoch(self.graph, self.cache, self.layers, self.X0, self.ld0, self.labels,
                        self.mask if mask else None, 0.0, self.logits, self.dW,
                        self.dW_self if any(t is not None for t in self.dW_self) else None, self.dbias, lr,
-                       self.ws, self.ws_bytes, self.stream, self.side, want_loss=want_loss, want_times=want_times)
+                       self.ws, self.ws_bytes, self.stream, self.side, want_loss=want_loss, want_times=want_times,
+                       targets=self.targets, ldt=0 if self.targets is None else self.targets.shape[1])
 
     def hidden(self, l: int) -> np.ndarray:
         """Output of hidden layer l after the last epoch, [n_loc, f_out(l)] (bf16 as uint16 bits)."""

@@ -320,11 +320,17 @@ def make_labels(n: int, n_classes: int, *, seed: int, mask_frac: float = 1.0):
     return y, mask
 
 
+def make_multilabels(n: int, n_classes: int, *, seed: int, density: float = 0.3) -> np.ndarray:
+    """0/1 target matrix of a multi-label task, uint8 [n, n_classes]; every label set independently."""
+    rng = rng_for(seed, 61)
+    return (rng.random((n, n_classes)) < density).astype(np.uint8)
+
+
 # --------------------------------------------------------------------------- named configs
 @dataclass
 class Config:
     name: str
-    kind: str                    # 'gcn' | 'sage'
+    kind: str                    # 'gcn' | 'sage' | 'gin' (sum aggregation, extra["gin_eps"]; stored without self loops)
     n_loc: int
     n_halo: int
     nnz: int
@@ -337,7 +343,7 @@ class Config:
     symmetric: bool = False
     oversample: float = 1.0      # extra draws that make up for duplicate removal
     seed: int = BASE_SEED * 10
-    extra: Dict = field(default_factory=dict)
+    extra: Dict = field(default_factory=dict)   # "loss": "bce" (multi-label targets), "gin_eps": float
 
     def scaled(self, s: float) -> "Config":
         """Same shape statistics at s times the vertex and edge counts (for quick parity runs)."""
@@ -368,7 +374,7 @@ CONFIGS: Dict[str, Config] = {
 
 def partition_for(cfg: Config) -> Partition:
     return make_partition(cfg.name, cfg.n_loc, cfg.n_halo, int(cfg.nnz * cfg.oversample), seed=cfg.seed, max_deg=cfg.max_deg,
-                          halo_edge_frac=cfg.halo_edge_frac, self_loops=(cfg.kind == "gcn"),
+                          halo_edge_frac=cfg.halo_edge_frac, self_loops=(cfg.kind == "gcn"),   # GIN's self term is its own
                           symmetric=cfg.symmetric, halo_zipf=cfg.halo_zipf)
 
 

@@ -12,16 +12,24 @@ def widen(a: np.ndarray) -> np.ndarray:
     return a.astype(np.float64)
 
 
-def oracle_graph(part, kind: str):
+def oracle_graph(part, kind: str, gin_eps: float = 0.0):
+    if kind == "gin":
+        return orc.gin_graph(part.n_loc, part.n_halo, part.rowptr, part.col, gin_eps)
     if kind == "gcn":
         return orc.gcn_graph(part.n_loc, part.n_halo, part.rowptr, part.col, part.halo_degree)
     return orc.mean_graph(part.n_loc, part.n_halo, part.rowptr, part.col)
 
 
 def oracle_epoch(prob, lr: float = 0.0, use_mask: bool = True, halo_grad: bool = False, relu_on=None):
-    g = oracle_graph(prob.part, prob.cfg.kind)
+    g = oracle_graph(prob.part, prob.cfg.kind, float(prob.cfg.extra.get("gin_eps", 0.0)))
     layers = [orc.Layer.of(p) for p in prob.model]
+    for l in layers:
+        if l.kind == "gin":
+            l.kind = "gcn"                    # sigma(A X W + b) on the GIN operator
     tables = [widen(t) for t in prob.tables]
+    if prob.targets is not None:
+        return orc.epoch(g, layers, widen(prob.X0), tables, prob.targets.astype(np.float64), prob.mask if use_mask else None,
+                         0.0, lr, halo_grad=halo_grad, relu_on=relu_on, loss_kind="bce")
     return orc.epoch(g, layers, widen(prob.X0), tables, prob.labels, prob.mask if use_mask else None, 0.0, lr,
                      halo_grad=halo_grad, relu_on=relu_on)
 
