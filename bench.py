@@ -279,8 +279,12 @@ def main():
     t0 = time.perf_counter()
     for _ in range(args.steps):
         loss, times = dp.run_epoch(want_times=True)
-        for r in times["records"]:
-            acc.setdefault((r["kind"], r["layer"], r["backward"]), []).append(r["ms"])
+        per_epoch = {}
+        for r in times["records"]:      # several records of one epoch may share a key (the GEMMs of one layer)
+            key = (r["kind"], r["layer"], r["backward"])
+            per_epoch[key] = per_epoch.get(key, 0.0) + r["ms"]
+        for key, ms in per_epoch.items():
+            acc.setdefault(key, []).append(ms)
         for k in ("pick_cache_ms", "communication_ms", "aggregation_ms", "combine_ms", "loss_ms", "other_ms", "total_ms"):
             stage[k] = stage.get(k, 0.0) + times[k] / args.steps
     torch.cuda.synchronize()
@@ -314,6 +318,7 @@ def main():
     hit_bytes = sum(2 * dp.cache.cap_gpu * cfg.dims[l] * es for l in range(dp.L)) if dp.cache else 0
     miss_bytes = sum((part.n_halo - dp.cache.cap_gpu) * cfg.dims[l] * es for l in range(dp.L)) if dp.cache else 0
     hit_ms = sum(k["ms"] for k in kernels if k["kind"] == "gather_hit")
+    staged_ms = sum(k["ms"] for k in kernels if k["kind"] == "gather_staged")
     miss_ms = sum(k["ms"] for k in kernels if k["kind"] == "gather_miss")
 
     out = {
@@ -333,6 +338,7 @@ def main():
         "stages_ms": {k: round(v, 4) for k, v in stage.items()},
         "aggregation_gedges_s_kernel_only": part.nnz * len(launches) / (spmm_ms * 1e-3) / 1e9 if spmm_ms else None,
         "gather": {"hit_GBps": hit_bytes / (hit_ms * 1e-3) / 1e9 if hit_ms else None, "hit_bytes": hit_bytes,
+                   "staged_scatter_GBps": 2 * miss_bytes / (staged_ms * 1e-3) / 1e9 if staged_ms else None,
                    "miss_host_link_GBps": miss_bytes / (miss_ms * 1e-3) / 1e9 if miss_ms else None,
                    "miss_bytes": miss_bytes},
         "gemm": gemm_report(cfg, part, res_orders, kernels),

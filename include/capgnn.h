@@ -371,6 +371,7 @@ int capgnn_sigmoid_bce(int64_t n, int C, const float *Z, int64_t ldz, const uint
 #define CAPGNN_K_GEMM         5
 #define CAPGNN_K_LOSS         6
 #define CAPGNN_K_ELEMENTWISE  7
+#define CAPGNN_K_GATHER_STAGED 8   /* device copy of host-tier rows out of the staging area into the layer input */
 
 typedef struct {
     /* stage names follow the evaluation's breakdown: check_cache, pick_cache, communication,

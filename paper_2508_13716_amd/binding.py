@@ -25,7 +25,8 @@ NORM_SYM, NORM_MEAN = 0, 1
 GRAPH_SYMMETRIC = 1
 MISS_ZEROCOPY, MISS_STAGED, MISS_PIPELINED = 0, 1, 2
 MAX_RECORDS = 96
-KIND_NAMES = {1: "gather_hit", 2: "gather_miss", 3: "spmm_fwd", 4: "spmm_bwd", 5: "gemm", 6: "loss", 7: "elementwise"}
+KIND_NAMES = {1: "gather_hit", 2: "gather_miss", 3: "spmm_fwd", 4: "spmm_bwd", 5: "gemm", 6: "loss", 7: "elementwise",
+              8: "gather_staged"}
 
 
 class CapgnnError(RuntimeError):

@@ -89,17 +89,65 @@ __device__ __forceinline__ void zero_row(char *d, int row_bytes, int l, int lpr,
     else for (int b = l * 2; b < row_bytes; b += lpr * 2) *reinterpret_cast<uint16_t *>(d + b) = 0;
 }
 
-// out[dst_list[k]] = table[k]  (full-batch gather of one tier; dst_list = halo-local index of slot k)
+// out[dst_list[k]] = table[k]  (full-batch gather of one tier; dst_list = halo-local index of slot k).
+// A lane group moves SCATTER_ROWS rows at a time: their destination indices are fetched together, then one 16-byte
+// load per row is issued before the first store, so that a wave keeps several kilobytes in flight even when a row
+// is a single load wide (the copy is latency-bound otherwise: index, row, store are three dependent round trips).
+constexpr int SCATTER_ROWS = 4;
+
 __global__ __launch_bounds__(256) void scatter_tier_kernel(const char *table, int64_t pitch, const int32_t *dst_list,
                                                            int64_t n, char *out, int64_t out_pitch, int row_bytes,
                                                            int lpr, int vec16, int es) {
     const int lane = threadIdx.x & 63;
+    const int l = lane % lpr;
     const int rows_per_wave = 64 / lpr;
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * 4 * rows_per_wave;
-    int64_t k = (static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6)) * rows_per_wave + lane / lpr;
-    for (; k < n; k += stride)
-        copy_row(table + k * pitch, out + static_cast<int64_t>(dst_list[k]) * out_pitch, row_bytes, lane % lpr, lpr,
-                 vec16, es);
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int64_t per_wave = static_cast<int64_t>(rows_per_wave) * SCATTER_ROWS;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * 4 * per_wave;   // a capped grid walks the list in strides
+    for (int64_t base = wave * per_wave; base < n; base += stride) {
+        const int64_t k0 = base + lane / lpr;
+        const char *src[SCATTER_ROWS];
+        char *dst[SCATTER_ROWS];
+        int32_t di[SCATTER_ROWS];
+#pragma unroll
+        for (int u = 0; u < SCATTER_ROWS; ++u) {
+            const int64_t k = k0 + static_cast<int64_t>(u) * rows_per_wave;
+            di[u] = k < n ? dst_list[k] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < SCATTER_ROWS; ++u) {
+            const int64_t k = k0 + static_cast<int64_t>(u) * rows_per_wave;
+            src[u] = table + k * pitch;
+            dst[u] = out + static_cast<int64_t>(di[u]) * out_pitch;
+        }
+        int done = 0;
+        if (vec16) {
+            const int nfull = row_bytes >> 4;
+            for (int c = l; c < nfull; c += lpr) {
+                uint4 a[SCATTER_ROWS];
+#pragma unroll
+                for (int u = 0; u < SCATTER_ROWS; ++u)
+                    if (di[u] >= 0) a[u] = reinterpret_cast<const uint4 *>(src[u])[c];
+#pragma unroll
+                for (int u = 0; u < SCATTER_ROWS; ++u)
+                    if (di[u] >= 0) reinterpret_cast<uint4 *>(dst[u])[c] = a[u];
+            }
+            done = nfull << 4;
+        }
+        if (done < row_bytes) {   // the last few elements of a row, or rows that are not 16-byte aligned
+#pragma unroll
+            for (int u = 0; u < SCATTER_ROWS; ++u) {
+                if (di[u] < 0) continue;
+                if (es == 4) {
+                    for (int b = done + l * 4; b < row_bytes; b += lpr * 4)
+                        *reinterpret_cast<uint32_t *>(dst[u] + b) = *reinterpret_cast<const uint32_t *>(src[u] + b);
+                } else {
+                    for (int b = done + l * 2; b < row_bytes; b += lpr * 2)
+                        *reinterpret_cast<uint16_t *>(dst[u] + b) = *reinterpret_cast<const uint16_t *>(src[u] + b);
+                }
+            }
+        }
+    }
 }
 
 // request-list gather with lookup; which: bit0 = serve GPU-tier rows (and absent ids), bit1 = serve host-tier rows
@@ -294,13 +342,18 @@ static unsigned blocks_for(int64_t n, int lpr) {
     return static_cast<unsigned>((n + rows_per_block - 1) / rows_per_block);
 }
 
+static unsigned scatter_blocks_for(int64_t n, int lpr) {
+    const int64_t rows_per_block = 4 * (64 / lpr) * SCATTER_ROWS;
+    return static_cast<unsigned>((n + rows_per_block - 1) / rows_per_block);
+}
+
 // GPU-tier part of the full-batch gather of one layer, on `st`.
 int gather_all_hits(const capgnn_cache *c, int layer, void *out, int64_t ld, hipStream_t st) {
     if (c->cap_gpu == 0) return CAPGNN_OK;
     CopyGeom g;
     const char *tab = c->gpu_tier + c->gpu_off[layer];
     CG_TRY(copy_geom(c, layer, out, ld, tab, &g));
-    hipLaunchKernelGGL(scatter_tier_kernel, dim3(blocks_for(c->cap_gpu, g.lpr)), dim3(256), 0, st, tab, c->pitch[layer],
+    hipLaunchKernelGGL(scatter_tier_kernel, dim3(scatter_blocks_for(c->cap_gpu, g.lpr)), dim3(256), 0, st, tab, c->pitch[layer],
                        c->gpu_list_d, c->cap_gpu, static_cast<char *>(out), g.out_pitch, g.row_bytes, g.lpr, g.vec16, g.es);
     CG_HIP(hipGetLastError());
     return CAPGNN_OK;
@@ -321,7 +374,7 @@ static int scatter_host_rows(const capgnn_cache *c, int layer, const char *tab, 
     CG_TRY(copy_geom(c, layer, out, ld, tab, &g));
     // A kernel that reads pinned memory is bound by the host link, not by the CUs: a small grid keeps enough
     // requests in flight and leaves the compute units to the kernels of the main stream.
-    unsigned blocks = blocks_for(c->n_host, g.lpr);
+    unsigned blocks = scatter_blocks_for(c->n_host, g.lpr);
     if (pinned && blocks > HOST_READ_BLOCKS) blocks = HOST_READ_BLOCKS;
     hipLaunchKernelGGL(scatter_tier_kernel, dim3(blocks), dim3(256), 0, st, tab, c->pitch[layer],
                        c->host_list_d, c->n_host, static_cast<char *>(out), g.out_pitch, g.row_bytes, g.lpr, g.vec16, g.es);

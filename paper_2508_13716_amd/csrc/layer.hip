@@ -454,7 +454,7 @@ static int epoch_impl(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer
             if (pipelined) {
                 CG_HIP(hipStreamWaitEvent(st, c->ev_layer[l], 0));
                 {
-                    Scope s(CAPGNN_K_GATHER_HIT, l, 0, st);    // a device copy, like the GPU tier's
+                    Scope s(CAPGNN_K_GATHER_STAGED, l, 0, st);   // a device copy, like the GPU tier's
                     CG_TRY(scatter_staged(c, l, halo, p.ldx[l], staging, st));
                 }
                 CG_HIP(hipEventRecord(c->ev_consumed[l], st));
@@ -539,7 +539,7 @@ static int epoch_impl(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer
             float ms = 0.f;
             CG_HIP(hipEventElapsedTime(&ms, r.e0, r.e1));
             switch (r.kind) {
-                case CAPGNN_K_GATHER_HIT: times->pick_cache_ms += ms; break;
+                case CAPGNN_K_GATHER_HIT: case CAPGNN_K_GATHER_STAGED: times->pick_cache_ms += ms; break;
                 case CAPGNN_K_GATHER_MISS: times->communication_ms += ms; break;
                 case CAPGNN_K_SPMM_FWD: case CAPGNN_K_SPMM_BWD: times->aggregation_ms += ms; break;
                 case CAPGNN_K_GEMM: times->combine_ms += ms; break;
