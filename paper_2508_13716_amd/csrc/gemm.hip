@@ -28,6 +28,7 @@ struct GemmArgs {
     const float *bias;
     const char *mask; int64_t ldm; int mask_bf16;
     int gx, gy, S;                  // tiles along N, along M, reduction splits
+    int c_staged;                   // bf16 kernel: write C through LDS in 16-byte pieces (no mask / accumulate / split)
 };
 
 // Tile of a workgroup in the one-dimensional grid.  Workgroup b runs on L2 domain b % NUM_XCD; the order is
@@ -219,18 +220,30 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
             la.fetch(g.A, g.lda, m0, g.M, k_begin + (kt + 1) * BK, k_end, g.a_vec, tid);
             lb.fetch(g.B, g.ldb, n0, g.N, k_begin + (kt + 1) * BK, k_end, g.b_vec, tid);
         }
+        // operands of step kk+2 are read from LDS before the products of step kk are issued
+        float a[2][TM], b[2][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[0][i] = As[buf][half][wm * WM + i * 32 + l32];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[0][j] = Bs[buf][half][wn * WN + j * 32 + l32];
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
-            float a[TM], b[TN];
+            const int cur = (kk >> 1) & 1;
+            if (kk + 2 < BK) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = As[buf][kk + half][wm * WM + i * 32 + l32];
+                for (int i = 0; i < TM; ++i) a[cur ^ 1][i] = As[buf][kk + 2 + half][wm * WM + i * 32 + l32];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = Bs[buf][kk + half][wn * WN + j * 32 + l32];
+                for (int j = 0; j < TN; ++j) b[cur ^ 1][j] = Bs[buf][kk + 2 + half][wn * WN + j * 32 + l32];
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
+            // keep that order in the schedule: LDS reads of the next step, then this step's matrix instructions
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
         }
         if (more) {
             la.stash(As[buf ^ 1], tid);
@@ -245,17 +258,25 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
 // ---------------------------------------------------------------------------------------------------
 // bf16 operands on the bf16 matrix cores (v_mfma_f32_32x32x16_bf16: lane l supplies A[i = l%32][k = 8*(l/32) ..+7]
 // and B[k = 8*(l/32) ..+7][j = l%32], eight consecutive k per lane).  Both operand tiles are kept in LDS with
-// the reduction index contiguous (S[row][k], 32 k per step, rows padded to 80 bytes so the 16-byte operand
-// reads of 8 neighbouring lanes fall into distinct banks).  An operand stored with the reduction index
-// contiguous is moved with 16-byte loads and stores; one stored the other way (the vertex dimension of the
-// weight gradient) is loaded 16 bytes along its rows and transposed by 2-byte LDS stores.
+// the reduction index contiguous (S[row][k], 32 k per step = four 16-byte chunks, rows padded to 80 bytes; the
+// chunk position is XOR-ed with bits of the row so that neither the operand reads nor the transposing stores pile
+// up on a few banks).  An operand stored with the reduction index contiguous is moved with 16-byte loads and
+// stores.  One stored the other way (the vertex dimension of the weight gradient X^T G) is loaded 16 bytes along
+// its rows, four consecutive k per thread, transposed in registers (byte permutes pair up the values of two k)
+// and stored as 8-byte pieces: no 2-byte LDS traffic.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int HBK = 32;            // k per step of the bf16 kernel
 constexpr int HPAD = 8;            // bf16 elements of row padding
 
-template <bool KC, int BT>
+// position (in elements) of 16-byte chunk `chunk` (0..3) inside LDS row `row`
+__device__ __forceinline__ int chunk_pos(int row, int chunk) { return 8 * (chunk ^ ((row >> 3) & 3)); }
+
+// TOFF: first thread of the workgroup that works on this tile when the operand needs the transposing path
+// (that path keeps (HBK/4) * (BT/8) threads busy; the two operands of X^T G take disjoint thread ranges).
+template <bool KC, int BT, int TOFF>
 struct HalfTileLoader {
-    static constexpr int NLD = BT * HBK / 8 / 256;   // 16-byte chunks per thread
+    static constexpr int NLD = KC ? BT * HBK / 8 / 256 : 4;   // 16-byte chunks per thread
+    static constexpr int NTH = (HBK / 4) * (BT / 8);          // threads of the transposing path
     uint4 r[NLD];
 
     // eight consecutive bf16 starting at element `off`; only the first nvalid are read
@@ -271,37 +292,54 @@ struct HalfTileLoader {
 
     __device__ __forceinline__ void fetch(const char *base, int64_t ld, int64_t t0, int64_t T, int64_t k0, int64_t k_end,
                                           int tid) {
+        if constexpr (KC) {
 #pragma unroll
-        for (int q = 0; q < NLD; ++q) {
-            const int idx = tid + 256 * q;
-            if constexpr (KC) {
+            for (int q = 0; q < NLD; ++q) {
+                const int idx = tid + 256 * q;
                 const int row = idx >> 2, kq = idx & 3;
                 const int64_t t = t0 + row, k = k0 + 8 * kq;
                 const int nv = (t < T) ? static_cast<int>(k_end - k < 8 ? k_end - k : 8) : 0;
                 r[q] = load8(base, t * ld + k, nv);
-            } else {
-                constexpr int CPR = BT / 8;
-                const int kk = idx / CPR, tq = idx % CPR;
-                const int64_t k = k0 + kk, t = t0 + 8 * tq;
-                const int nv = (k < k_end) ? static_cast<int>(T - t < 8 ? T - t : 8) : 0;
-                r[q] = load8(base, k * ld + t, nv);
+            }
+        } else {
+            const int tt = tid - TOFF;
+            if (tt < 0 || tt >= NTH) return;
+            constexpr int CPR = BT / 8;
+            const int kb = tt / CPR, tq = tt % CPR;       // four k starting at 4*kb, eight columns starting at 8*tq
+            const int64_t t = t0 + 8 * tq;
+            const int ncol = static_cast<int>(T - t < 8 ? T - t : 8);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int64_t k = k0 + 4 * kb + j;
+                r[j] = load8(base, k * ld + t, k < k_end ? ncol : 0);
             }
         }
     }
 
     __device__ __forceinline__ void stash(uint16_t (*s)[HBK + HPAD], int tid) const {
+        if constexpr (KC) {
 #pragma unroll
-        for (int q = 0; q < NLD; ++q) {
-            const int idx = tid + 256 * q;
-            if constexpr (KC) {
+            for (int q = 0; q < NLD; ++q) {
+                const int idx = tid + 256 * q;
                 const int row = idx >> 2, kq = idx & 3;
-                *reinterpret_cast<uint4 *>(&s[row][8 * kq]) = r[q];
-            } else {
-                constexpr int CPR = BT / 8;
-                const int kk = idx / CPR, tq = idx % CPR;
-                const uint32_t w[4] = {r[q].x, r[q].y, r[q].z, r[q].w};
+                *reinterpret_cast<uint4 *>(&s[row][chunk_pos(row, kq)]) = r[q];
+            }
+        } else {
+            const int tt = tid - TOFF;
+            if (tt < 0 || tt >= NTH) return;
+            constexpr int CPR = BT / 8;
+            const int kb = tt / CPR, tq = tt % CPR;
+            const uint32_t w[4][4] = {{r[0].x, r[0].y, r[0].z, r[0].w}, {r[1].x, r[1].y, r[1].z, r[1].w},
+                                      {r[2].x, r[2].y, r[2].z, r[2].w}, {r[3].x, r[3].y, r[3].z, r[3].w}};
 #pragma unroll
-                for (int e = 0; e < 8; ++e) s[8 * tq + e][kk] = static_cast<uint16_t>(w[e >> 1] >> (16 * (e & 1)));
+            for (int e = 0; e < 8; ++e) {
+                // column 8*tq+e of the four k: the low (e even) or high (e odd) halves of word e/2 of the four rows
+                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                uint2 v;
+                v.x = __builtin_amdgcn_perm(w[1][e >> 1], w[0][e >> 1], sel);
+                v.y = __builtin_amdgcn_perm(w[3][e >> 1], w[2][e >> 1], sel);
+                const int row = 8 * tq + e;
+                *reinterpret_cast<uint2 *>(&s[row][chunk_pos(row, kb >> 1) + 4 * (kb & 1)]) = v;
             }
         }
     }
@@ -311,8 +349,12 @@ template <bool A_KC, bool B_KC, int BM, int BN>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     constexpr int WM = BM / 2, WN = BN / 2;
     constexpr int TM = WM / 32, TN = WN / 32;
-    __shared__ __attribute__((aligned(16))) uint16_t As[2][BM][HBK + HPAD];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN][HBK + HPAD];
+    constexpr int LDSROW = HBK + HPAD;
+    constexpr int CPITCH = BN + 8;          // row pitch of the staged output tile (16-byte multiple)
+    static_assert(BM * CPITCH <= 2 * (BM + BN) * LDSROW, "the staged output tile must fit the operand buffers");
+    __shared__ __attribute__((aligned(16))) uint16_t smem[2 * (BM + BN) * LDSROW];
+    uint16_t (*As)[BM][LDSROW] = reinterpret_cast<uint16_t (*)[BM][LDSROW]>(smem);
+    uint16_t (*Bs)[BN][LDSROW] = reinterpret_cast<uint16_t (*)[BN][LDSROW]>(smem + 2 * BM * LDSROW);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -333,8 +375,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    HalfTileLoader<A_KC, BM> la;
-    HalfTileLoader<B_KC, BN> lb;
+    HalfTileLoader<A_KC, BM, 0> la;
+    HalfTileLoader<B_KC, BN, A_KC ? 0 : 128> lb;     // when both operands are transposed they split the threads
     const int64_t nk = (k_end > k_begin) ? (k_end - k_begin + HBK - 1) / HBK : 0;
     if (nk > 0) {
         la.fetch(g.A, g.lda, m0, g.M, k_begin, k_end, tid);
@@ -354,11 +396,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         for (int ks = 0; ks < HBK; ks += 16) {
             bf16x8 a[TM], b[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&As[buf][wm * WM + i * 32 + l32][ks + 8 * half]));
+            for (int i = 0; i < TM; ++i) {
+                const int row = wm * WM + i * 32 + l32;
+                a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&As[buf][row][chunk_pos(row, ks / 8 + half)]));
+            }
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&Bs[buf][wn * WN + j * 32 + l32][ks + 8 * half]));
+            for (int j = 0; j < TN; ++j) {
+                const int row = wn * WN + j * 32 + l32;
+                b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&Bs[buf][row][chunk_pos(row, ks / 8 + half)]));
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -371,7 +417,40 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         }
         __syncthreads();
     }
-    store_tile<TM, TN>(g, acc, m0 + wm * WM, n0 + wn * WN, l32, half, bz);
+    if (!g.c_staged) {
+        store_tile<TM, TN>(g, acc, m0 + wm * WM, n0 + wn * WN, l32, half, bz);
+        return;
+    }
+    // bf16 output without a read-modify-write epilogue: the tile is rounded into LDS (the operand buffers are free
+    // after the last barrier) and leaves in 16-byte pieces along the rows, instead of 2 bytes per lane.
+    uint16_t (*Cs)[CPITCH] = reinterpret_cast<uint16_t (*)[CPITCH]>(smem);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = wn * WN + j * 32 + l32;
+            const float bv = (g.bias && n0 + col < g.N) ? g.bias[n0 + col] : 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = wm * WM + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                float v = acc[i][j][r] + bv;
+                if (g.relu) v = v > 0.f ? v : 0.f;
+                Cs[row][col] = static_cast<uint16_t>(f32_to_bf16_rne(v));
+            }
+        }
+    __syncthreads();
+    constexpr int CQ = BN / 8;
+    for (int c = tid; c < BM * CQ; c += 256) {
+        const int row = c / CQ, cq = c % CQ;
+        const int64_t grow = m0 + row, gcol = n0 + 8 * cq;
+        if (grow >= g.M || gcol >= g.N) continue;
+        uint16_t *dst = reinterpret_cast<uint16_t *>(g.C) + grow * g.ldc + gcol;
+        if (gcol + 8 <= g.N) {
+            *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(&Cs[row][8 * cq]);
+        } else {
+            for (int e = 0; gcol + e < g.N; ++e) dst[e] = Cs[row][8 * cq + e];
+        }
+    }
 }
 
 // Lays the (small) second operand of a product out as Wt[n][k], k contiguous, rows padded to 16 bytes, for the
@@ -504,6 +583,7 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
     if (n_wg >= (int64_t(1) << 31) || gx >= (int64_t(1) << 24) || gy >= (int64_t(1) << 30))
         CG_FAIL(CAPGNN_EINVAL, "gemm: %lld x %lld tiles exceed the grid", (long long)gy, (long long)gx);
     g.gx = static_cast<int>(gx); g.gy = static_cast<int>(gy); g.S = S;
+    g.c_staged = half_path && g.out_bf16 && !g.part && !g.mask && !g.accumulate && aligned16(C) && (ldc * 2) % 16 == 0;
     dim3 grid(static_cast<unsigned>(n_wg), 1, 1);
     bool akc = !trans_a, bkc = trans_b != 0;
     if (half_path) {

@@ -270,61 +270,70 @@ __global__ __launch_bounds__(64) void count_final_kernel(int parts, const double
     norm_out[0] = (c > 0.0 ? static_cast<float>(c) : 1.f) * times;
 }
 
-// one wave per row; lanes stride over the classes
-__global__ __launch_bounds__(256) void softmax_ce_kernel(int64_t n, int C, const float *Z, int64_t ldz,
+// A group of lpr lanes (a power of two, 4..64, about a quarter of the classes) per row, so that narrow class counts
+// still keep 64/lpr rows in flight per wave; the lanes of a group stride over the classes.
+static int loss_lanes_per_row_host(int C) {
+    int lpr = 4;
+    while (lpr < 64 && lpr * 4 < C) lpr *= 2;
+    return lpr;
+}
+
+__global__ __launch_bounds__(256) void softmax_ce_kernel(int64_t n, int C, int lpr, const float *Z, int64_t ldz,
                                                          const int32_t *labels, const uint8_t *mask, float norm_val,
                                                          const float *norm_dev, float *row_loss, char *dZ,
                                                          int64_t lddz, int dz_bf16) {
     const int lane = threadIdx.x & 63;
-    const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    if (row >= n) return;
+    const int l = lane % lpr;
+    const int64_t row = (static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6)) * (64 / lpr) + lane / lpr;
+    if (row >= n) return;          // whole lane groups leave; the shuffles below stay inside a group
     const float norm = norm_dev ? norm_dev[0] : norm_val;
     const bool on = !mask || mask[row];
     if (!on) {
-        if (lane == 0) row_loss[row] = 0.f;
-        if (dZ) for (int k = lane; k < C; k += 64) st_elem(dZ, row * lddz + k, 0.f, dz_bf16);
+        if (l == 0) row_loss[row] = 0.f;
+        if (dZ) for (int k = l; k < C; k += lpr) st_elem(dZ, row * lddz + k, 0.f, dz_bf16);
         return;
     }
     const float *z = Z + row * ldz;
     float m = -INFINITY;
-    for (int k = lane; k < C; k += 64) m = fmaxf(m, z[k]);
-    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    for (int k = l; k < C; k += lpr) m = fmaxf(m, z[k]);
+    for (int off = lpr >> 1; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
     float s = 0.f;
-    for (int k = lane; k < C; k += 64) s += expf(z[k] - m);
-    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    for (int k = l; k < C; k += lpr) s += expf(z[k] - m);
+    for (int off = lpr >> 1; off > 0; off >>= 1) s += __shfl_xor(s, off);
     const float lse = m + logf(s);
     int y = labels[row];
     y = y < 0 ? 0 : (y >= C ? C - 1 : y);
-    if (lane == 0) row_loss[row] = lse - z[y];
+    if (l == 0) row_loss[row] = lse - z[y];
     if (dZ) {
         const float inv = 1.f / norm;
-        for (int k = lane; k < C; k += 64) {
+        for (int k = l; k < C; k += lpr) {
             float p = expf(z[k] - lse);
             st_elem(dZ, row * lddz + k, (p - (k == y ? 1.f : 0.f)) * inv, dz_bf16);
         }
     }
 }
 
-// Binary cross-entropy on logits, one wave per row, lanes stride over the classes: the element's loss in the form
+// Binary cross-entropy on logits, one lane group per row like the softmax kernel: the element's loss in the form
 // max(z,0) - z*y + log(1 + exp(-|z|)), which neither overflows nor cancels, and its derivative s(z) - y.
-__global__ __launch_bounds__(256) void sigmoid_bce_kernel(int64_t n, int C, const float *Z, int64_t ldz,
+__global__ __launch_bounds__(256) void sigmoid_bce_kernel(int64_t n, int C, int lpr, const float *Z, int64_t ldz,
                                                           const uint8_t *targets, int64_t ldt, const uint8_t *mask,
                                                           float norm_val, const float *norm_dev, float *row_loss, char *dZ,
                                                           int64_t lddz, int dz_bf16) {
     const int lane = threadIdx.x & 63;
-    const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int l = lane % lpr;
+    const int64_t row = (static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6)) * (64 / lpr) + lane / lpr;
     if (row >= n) return;
     const bool on = !mask || mask[row];
     if (!on) {
-        if (lane == 0) row_loss[row] = 0.f;
-        if (dZ) for (int k = lane; k < C; k += 64) st_elem(dZ, row * lddz + k, 0.f, dz_bf16);
+        if (l == 0) row_loss[row] = 0.f;
+        if (dZ) for (int k = l; k < C; k += lpr) st_elem(dZ, row * lddz + k, 0.f, dz_bf16);
         return;
     }
     const float inv = 1.f / (norm_dev ? norm_dev[0] : norm_val);
     const float *z = Z + row * ldz;
     const uint8_t *t = targets + row * ldt;
     float s = 0.f;
-    for (int k = lane; k < C; k += 64) {
+    for (int k = l; k < C; k += lpr) {
         const float zk = z[k], y = t[k] ? 1.f : 0.f;
         const float e = expf(-fabsf(zk));
         s += fmaxf(zk, 0.f) - zk * y + log1pf(e);
@@ -333,8 +342,8 @@ __global__ __launch_bounds__(256) void sigmoid_bce_kernel(int64_t n, int C, cons
             st_elem(dZ, row * lddz + k, (sig - y) * inv, dz_bf16);
         }
     }
-    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
-    if (lane == 0) row_loss[row] = s;
+    for (int off = lpr >> 1; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    if (l == 0) row_loss[row] = s;
 }
 
 __global__ __launch_bounds__(1024) void loss_partial_kernel(int64_t n, const float *row_loss, double *part) {
@@ -386,7 +395,9 @@ extern "C" int capgnn_sigmoid_bce(int64_t n, int C, const float *Z, int64_t ldz,
         hipLaunchKernelGGL(count_final_kernel, dim3(1), dim3(64), 0, st, parts, part, static_cast<float>(C), norm_dev);
     }
     float *row_loss = reinterpret_cast<float *>(static_cast<char *>(ws) + LOSS_HEADER);
-    hipLaunchKernelGGL(sigmoid_bce_kernel, dim3(static_cast<unsigned>((n + 3) / 4)), dim3(256), 0, st, n, C, Z, ldz, targets,
+    const int lpr = loss_lanes_per_row_host(C);
+    const int64_t rows_per_block = 4 * (64 / lpr);
+    hipLaunchKernelGGL(sigmoid_bce_kernel, dim3(static_cast<unsigned>((n + rows_per_block - 1) / rows_per_block)), dim3(256), 0, st, n, C, lpr, Z, ldz, targets,
                        ldt, mask, norm_val, norm_dev, row_loss, static_cast<char *>(dZ), lddz, dz_dtype == CAPGNN_BF16 ? 1 : 0);
     hipLaunchKernelGGL(loss_partial_kernel, dim3(parts), dim3(1024), 0, st, n, row_loss, part);
     hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(64), 0, st, parts, part, norm_val, norm_dev, loss_dev);
@@ -417,7 +428,9 @@ extern "C" int capgnn_softmax_ce(int64_t n, int C, const float *Z, int64_t ldz, 
         hipLaunchKernelGGL(count_final_kernel, dim3(1), dim3(64), 0, st, parts, part, 1.f, norm_dev);
     }
     float *row_loss = reinterpret_cast<float *>(static_cast<char *>(ws) + LOSS_HEADER);
-    hipLaunchKernelGGL(softmax_ce_kernel, dim3(static_cast<unsigned>((n + 3) / 4)), dim3(256), 0, st, n, C, Z, ldz,
+    const int lpr = loss_lanes_per_row_host(C);
+    const int64_t rows_per_block = 4 * (64 / lpr);
+    hipLaunchKernelGGL(softmax_ce_kernel, dim3(static_cast<unsigned>((n + rows_per_block - 1) / rows_per_block)), dim3(256), 0, st, n, C, lpr, Z, ldz,
                        labels, mask, norm_val, norm_dev, row_loss, static_cast<char *>(dZ), lddz, dz_dtype == CAPGNN_BF16 ? 1 : 0);
     hipLaunchKernelGGL(loss_partial_kernel, dim3(parts), dim3(1024), 0, st, n, row_loss, part);
     hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(64), 0, st, parts, part, norm_val, norm_dev, loss_dev);
