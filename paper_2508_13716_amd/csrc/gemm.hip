@@ -158,6 +158,36 @@ struct TileLoader {
         }
     }
 
+    // Interior tiles (every row of the tile exists, vector loads allowed) skip all range checks: the address of
+    // each of the thread's vectors is formed once and then only stepped along the reduction index.
+    const char *pf[NLD];
+
+    __device__ __forceinline__ void fast_begin(const char *base, int64_t ld, int64_t t0, int64_t k0, int tid) {
+        constexpr int ES = BF16 ? 2 : 4;
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const int idx = tid + 256 * q;
+            if constexpr (KC) pf[q] = base + ((t0 + (idx >> 2)) * ld + k0 + 4 * (idx & 3)) * ES;
+            else pf[q] = base + ((k0 + idx / (BT / 4)) * ld + t0 + 4 * (idx % (BT / 4))) * ES;
+        }
+    }
+
+    __device__ __forceinline__ void fetch_fast(int64_t ld) {
+        constexpr int ES = BF16 ? 2 : 4;
+        const int64_t step = KC ? static_cast<int64_t>(BK) * ES : static_cast<int64_t>(BK) * ld * ES;
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            if constexpr (BF16) {
+                const uint2 v = *reinterpret_cast<const uint2 *>(pf[q]);
+                r[q] = make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
+                                   __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
+            } else {
+                r[q] = *reinterpret_cast<const float4 *>(pf[q]);
+            }
+            pf[q] += step;
+        }
+    }
+
     __device__ __forceinline__ void stash(float (*s)[BT + PAD], int tid) const {
 #pragma unroll
         for (int q = 0; q < NLD; ++q) {
@@ -206,19 +236,32 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
     TileLoader<BF16, A_KC, BM> la;
     TileLoader<BF16, B_KC, BN> lb;
     const int64_t nk = (k_end > k_begin) ? (k_end - k_begin + BK - 1) / BK : 0;
+    // uniform over the workgroup: the tile lies inside the matrices and both operands allow vector loads (measured
+    // to pay only when the first operand is stored along the reduction index; X^T G keeps the checked loads)
+    const bool interior = A_KC && m0 + BM <= g.M && n0 + BN <= g.N && g.a_vec && g.b_vec;
+    const int64_t nk_full = (k_end > k_begin) ? (k_end - k_begin) / BK : 0;     // steps that need no check along k either
     if (nk > 0) {
         la.fetch(g.A, g.lda, m0, g.M, k_begin, k_end, g.a_vec, tid);
         lb.fetch(g.B, g.ldb, n0, g.N, k_begin, k_end, g.b_vec, tid);
         la.stash(As[0], tid);
         lb.stash(Bs[0], tid);
     }
+    if (interior) {
+        la.fast_begin(g.A, g.lda, m0, k_begin + BK, tid);
+        lb.fast_begin(g.B, g.ldb, n0, k_begin + BK, tid);
+    }
     __syncthreads();
     for (int64_t kt = 0; kt < nk; ++kt) {
         const int buf = static_cast<int>(kt & 1);
         const bool more = kt + 1 < nk;
         if (more) {
-            la.fetch(g.A, g.lda, m0, g.M, k_begin + (kt + 1) * BK, k_end, g.a_vec, tid);
-            lb.fetch(g.B, g.ldb, n0, g.N, k_begin + (kt + 1) * BK, k_end, g.b_vec, tid);
+            if (interior && kt + 1 < nk_full) {
+                la.fetch_fast(g.lda);
+                lb.fetch_fast(g.ldb);
+            } else {
+                la.fetch(g.A, g.lda, m0, g.M, k_begin + (kt + 1) * BK, k_end, g.a_vec, tid);
+                lb.fetch(g.B, g.ldb, n0, g.N, k_begin + (kt + 1) * BK, k_end, g.b_vec, tid);
+            }
         }
         // operands of step kk+2 are read from LDS before the products of step kk are issued
         float a[2][TM], b[2][TN];
