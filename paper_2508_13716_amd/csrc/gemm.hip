@@ -359,6 +359,26 @@ struct HalfTileLoader {
         }
     }
 
+    // check-free loads of interior tiles (operand stored along the reduction index): addresses formed once
+    const char *pf[NLD];
+
+    __device__ __forceinline__ void fast_begin(const char *base, int64_t ld, int64_t t0, int64_t k0, int tid) {
+        static_assert(KC, "the check-free path serves operands stored along the reduction index");
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const int idx = tid + 256 * q;
+            pf[q] = base + ((t0 + (idx >> 2)) * ld + k0 + 8 * (idx & 3)) * 2;
+        }
+    }
+
+    __device__ __forceinline__ void fetch_fast() {
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            r[q] = *reinterpret_cast<const uint4 *>(pf[q]);
+            pf[q] += HBK * 2;
+        }
+    }
+
     __device__ __forceinline__ void stash(uint16_t (*s)[HBK + HPAD], int tid) const {
         if constexpr (KC) {
 #pragma unroll
@@ -427,13 +447,33 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         la.stash(As[0], tid);
         lb.stash(Bs[0], tid);
     }
+    // uniform over the workgroup: both operands are stored along the reduction index and the tile lies inside
+    constexpr bool FAST = A_KC && B_KC;
+    const bool interior = FAST && m0 + BM <= g.M && n0 + BN <= g.N;
+    const int64_t nk_full = (k_end > k_begin) ? (k_end - k_begin) / HBK : 0;
+    if constexpr (FAST) {
+        if (interior) {
+            la.fast_begin(g.A, g.lda, m0, k_begin + HBK, tid);
+            lb.fast_begin(g.B, g.ldb, n0, k_begin + HBK, tid);
+        }
+    }
     __syncthreads();
     for (int64_t kt = 0; kt < nk; ++kt) {
         const int buf = static_cast<int>(kt & 1);
         const bool more = kt + 1 < nk;
         if (more) {
-            la.fetch(g.A, g.lda, m0, g.M, k_begin + (kt + 1) * HBK, k_end, tid);
-            lb.fetch(g.B, g.ldb, n0, g.N, k_begin + (kt + 1) * HBK, k_end, tid);
+            bool done = false;
+            if constexpr (FAST) {
+                if (interior && kt + 1 < nk_full) {
+                    la.fetch_fast();
+                    lb.fetch_fast();
+                    done = true;
+                }
+            }
+            if (!done) {
+                la.fetch(g.A, g.lda, m0, g.M, k_begin + (kt + 1) * HBK, k_end, tid);
+                lb.fetch(g.B, g.ldb, n0, g.N, k_begin + (kt + 1) * HBK, k_end, tid);
+            }
         }
 #pragma unroll
         for (int ks = 0; ks < HBK; ks += 16) {
