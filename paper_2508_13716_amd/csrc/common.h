@@ -57,6 +57,9 @@ struct SpOp {
     const int64_t *ptr = nullptr;     // device [n_out+1]
     const int32_t *idx = nullptr;     // device [nnz]   source row of each entry
     const float *val = nullptr;       // device [nnz] or null
+    // device [nnz]: weight of each entry, val * in_scale[source] formed once (a sequential read in the kernels
+    // instead of a gather from in_scale per entry); null when every weight is 1
+    const float *wt = nullptr;
     const float *out_scale = nullptr; // device [n_out] or null
     const float *in_scale = nullptr;  // device [n_in]  or null
     // work lists: output rows by entry count, descending; rows shorter than EXACT_ROW only by power-of-two class,

@@ -53,6 +53,24 @@ static int64_t degree_order(const std::vector<int64_t> &ptr, int64_t lo, int64_t
     return n_long;
 }
 
+// Per-entry weights val * in_scale[source] (the float product the kernels would otherwise form per entry).
+// Leaves *dev null when every weight is 1.
+static int upload_weights(capgnn_graph *g, int64_t nnz, const int32_t *idx, const float *val, const float *in_scale,
+                          const float **dev) {
+    *dev = nullptr;
+    if (nnz == 0 || (!val && !in_scale)) return CAPGNN_OK;
+    std::vector<float> w(nnz);
+    bool all_one = true;
+    for (int64_t e = 0; e < nnz; ++e) {
+        float x = in_scale ? in_scale[idx[e]] : 1.f;
+        if (val) x *= val[e];
+        w[e] = x;
+        all_one = all_one && x == 1.f;
+    }
+    if (all_one) return CAPGNN_OK;
+    return upload(g, w.data(), w.size(), dev);
+}
+
 // Cuts the leading rows of a degree-ordered work list that have at least GIANT_ROW entries into pieces.
 static int upload_giant(capgnn_graph *g, const int64_t *ptr, const std::vector<int32_t> &order, GiantList *out) {
     std::vector<int32_t> pos, first(1, 0);
@@ -236,6 +254,7 @@ extern "C" int capgnn_graph_create(capgnn_graph **out, int64_t n_loc, int64_t n_
     if ((rc = upload(g, rowptr, n_loc + 1, &f.ptr))) return fail(rc);
     if ((rc = upload(g, col, nnz, &f.idx))) return fail(rc);
     if (edge_val && (rc = upload(g, edge_val, nnz, &f.val))) return fail(rc);
+    if ((rc = upload_weights(g, nnz, col, edge_val, col_scale, &f.wt))) return fail(rc);
     if (row_scale && (rc = upload(g, row_scale, n_loc, &f.out_scale))) return fail(rc);
     if (col_scale && (rc = upload(g, col_scale, n_cols, &f.in_scale))) return fail(rc);
     if ((rc = upload(g, order_f.data(), order_f.size(), &f.order))) return fail(rc);
@@ -256,6 +275,8 @@ extern "C" int capgnn_graph_create(capgnn_graph **out, int64_t n_loc, int64_t n_
         b.ncb = f.ncb; b.b_off = f.b_off; b.b_ew = f.b_ew; b.b_long = f.b_long; b.b_mid = f.b_mid;
         const bool same_scales = (!row_scale && !col_scale) ||
                                  (row_scale && col_scale && std::memcmp(row_scale, col_scale, n_loc * sizeof(float)) == 0);
+        b.wt = f.wt;
+        if (!same_scales && (rc = upload_weights(g, nnz, col, edge_val, row_scale, &b.wt))) return fail(rc);
         if (f.ncb && !same_scales) {   // the transposed product weighs an entry by the other side's scale
             if (edge_val) {
                 b.ncb = 0;             // rare combination: the transposed product takes the unblocked kernel
@@ -271,6 +292,7 @@ extern "C" int capgnn_graph_create(capgnn_graph **out, int64_t n_loc, int64_t n_
         if ((rc = upload(g, colptr.data(), n_cols + 1, &b.ptr))) return fail(rc);
         if ((rc = upload(g, rowidx.data(), nnz, &b.idx))) return fail(rc);
         if (edge_val && (rc = upload(g, cscval.data(), nnz, &b.val))) return fail(rc);
+        if ((rc = upload_weights(g, nnz, rowidx.data(), edge_val ? cscval.data() : nullptr, row_scale, &b.wt))) return fail(rc);
         if ((rc = upload(g, order_b.data(), order_b.size(), &b.order))) return fail(rc);
         if ((rc = upload(g, order_bs.data(), order_bs.size(), &b.order_sub))) return fail(rc);
         if ((rc = upload_giant(g, colptr.data(), order_b, &b.giant))) return fail(rc);

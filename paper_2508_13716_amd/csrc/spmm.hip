@@ -1,7 +1,7 @@
 // Normalised sparse aggregation Y = A_hat X (and, over the CSC, dX = A_hat^T dY) for gfx950.
 //
 // One 64-wide wavefront owns one output row.  The row's column indices are read 64 at a time,
-// one per lane (coalesced), together with the per-edge weight edge_val * in_scale[col]; the
+// one per lane (coalesced), together with the per-entry weight (edge_val * in_scale[col], formed at graph creation); the
 // indices are then handed from lane to lane (v_readlane / ds_bpermute) so that every feature-row
 // load is a contiguous, 16-byte-per-lane access with a wave-uniform base address.  Several loads
 // are kept in flight per wave before any is consumed.  Narrow feature rows (fewer than 64 vectors)
@@ -20,6 +20,7 @@ struct SpmmArgs {
     const float *val;
     const float *out_scale;
     const float *in_scale;
+    const float *wt;          // per-entry weights, or null: every weight is 1
     const int32_t *order;
     int64_t list_begin, list_end;
     const char *X;
@@ -116,8 +117,7 @@ __device__ __forceinline__ void accumulate_range(const SpmmArgs &a, int64_t e_be
         float w = 0.f;
         if (my < e_end) {
             c = a.idx[my];
-            w = a.in_scale ? a.in_scale[c] : 1.f;
-            if (a.val) w *= a.val[my];
+            w = a.wt ? a.wt[my] : 1.f;
         }
         const int cnt = static_cast<int>(e_end - e0 < 64 ? e_end - e0 : 64);
         const int nsteps = (cnt + G - 1) / G;
@@ -690,6 +690,7 @@ int launch_spmm(const SpOp &op, bool restrict_sub, const void *X, int64_t ldx, v
     const bool vec = aligned16(X) && aligned16(Y) && (ldx * es) % 16 == 0 && (ldy * es_out) % 16 == 0 && ldx >= f_up;
     SpmmArgs a;
     a.ptr = op.ptr; a.idx = op.idx; a.val = op.val; a.out_scale = op.out_scale; a.in_scale = op.in_scale;
+    a.wt = op.wt;
     a.order = restrict_sub ? op.order_sub : op.order;
     a.list_begin = 0; a.list_end = n_rows;
     a.X = static_cast<const char *>(X); a.ldx_bytes = ldx * es;
