@@ -238,6 +238,8 @@ def main():
                          "policy: hit-rate curves of the cache policies; reorder: SpMM before / after vertex reordering "
                          "(--config C2..C5 or clustered)")
     ap.add_argument("--miss-mode", type=int, default=None, help="0 zero-copy kernel, 1 staged DMA, 2 staged DMA prefetched one epoch ahead (default 2)")
+    ap.add_argument("--reorder", default="none", choices=["none", "popularity", "bfs"],
+                    help="store the vertices in a locality order before the graph handle is built (epoch benchmark)")
     ap.add_argument("--orders", default=None, help="comma list of 1 (aggregate first) / 2 (transform first) per layer")
     ap.add_argument("--cpu-scale", type=float, default=None,
                     help="share of the workload the oracle is timed on (0 = skip; default: sized for 10-30 s of CPU work)")
@@ -264,6 +266,8 @@ def main():
     cfg = synth.CONFIGS[args.config]
     t_gen = time.perf_counter()
     prob = H.make_problem(cfg)
+    if args.reorder != "none":
+        prob, _ = H.relabel_problem(prob, B.RELABEL_POPULARITY if args.reorder == "popularity" else B.RELABEL_BFS)
     part = prob.part
     t_gen = time.perf_counter() - t_gen
     orders = [int(x) for x in args.orders.split(",")] if args.orders else None
@@ -331,7 +335,7 @@ def main():
         "config": {"workload": f"{cfg.name}: {part.n_loc} local + {part.n_halo} halo vertices, {part.nnz} edges, "
                                f"{cfg.kind} dims {cfg.dims}, GPU tier {dp.cache.cap_gpu if dp.cache else 0} halo rows",
                    "orders": ["agg_first" if o == 1 else "xform_first" for o in res_orders],
-                   "spmm_launches_per_epoch": len(launches), "loss": loss,
+                   "spmm_launches_per_epoch": len(launches), "loss": loss, "vertex_order": args.reorder,
                    "host_tier": {0: "kernel reads pinned memory", 1: "DMA into a staging area, same epoch",
                                  2: "DMA into a staging area, one epoch ahead (pipelined)"}[dp.miss_mode] if dp.cache else None},
         "epoch_ms_device": stage.get("total_ms"),
