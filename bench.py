@@ -311,13 +311,13 @@ def main():
     bgather = part.nnz * (4 + F * es) + n_out * F * es
     achieved = bmin / (dom["ms"] * 1e-3) / 1e9
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "traffic_per_launch.txt")
     if os.path.exists(tpath):
-        try:
-            tj = json.load(open(tpath))
-            traffic = tj.get(f"{cfg.name}:{dom['kind']}:L{dom['layer']}:F{F}")
-        except Exception:
-            traffic = None
+        want = f"{cfg.name}:{dom['kind']}:L{dom['layer']}:F{F}"
+        for line in open(tpath):
+            parts = line.split()
+            if len(parts) == 2 and parts[0] == want:
+                traffic = float(parts[1])
     spmm_ms = sum(k["ms"] for k in spmm_recs)
     hit_bytes = sum(2 * dp.cache.cap_gpu * cfg.dims[l] * es for l in range(dp.L)) if dp.cache else 0
     miss_bytes = sum((part.n_halo - dp.cache.cap_gpu) * cfg.dims[l] * es for l in range(dp.L)) if dp.cache else 0
