@@ -166,6 +166,49 @@ def bench_policy(args):
                       "overlap_ratio_histogram": hist, "overlap_ratio_kernel_ms": t_overlap * 1e3, "curves": curves}))
 
 
+def bench_zipf_requests(args):
+    """C5's second reading: a request list of 2 M ids drawn with replacement, Zipf(1.1) over the halo vertices ranked
+    by priority, served from a cache whose GPU tier holds the top 10 %.  Reports the measured hit fraction next to
+    the closed form H_{k,s} / H_{N,s}, and the rate of the request-list gather (lookup + copy); one JSON line."""
+    import numpy as np
+    import torch
+    from paper_2508_13716_amd import binding as B, synth
+    N, k, s_exp, F = 2_000_000, 200_000, 1.1, 512
+    p = np.arange(1, N + 1, dtype=np.float64) ** -s_exp
+    p /= p.sum()
+    rng = synth.rng_for(synth.BASE_SEED * 10 + 5, 90)
+    gid = rng.permutation(N).astype(np.int64) * 3 + 11
+    prio = (1e15 * p).astype(np.int64)                      # strictly decreasing: rank = halo-local index
+    c = B.Cache(gid, prio, k, [F], B.BF16, B.MAP_HASH)
+    c.set_miss_mode(B.MISS_ZEROCOPY)                         # a request list is served by one kernel, misses read pinned memory
+    req_h = rng.choice(N, size=N, p=p)
+    hits_expected = float((p[:k]).sum())
+    st = torch.cuda.Stream()
+    out = torch.empty((N, F), dtype=torch.bfloat16, device="cuda")
+    res = {}
+    for name, ids_h, by_gid in (("halo_local_index_direct", req_h.astype(np.int64), False), ("global_id_hash", gid[req_h], True)):
+        ids = torch.from_numpy(ids_h).cuda()
+        rc, stats = B.halo_gather(c, 0, ids, N, out, F, by_gid=by_gid, stream=st, want_stats=True)
+        for _ in range(args.warmup):
+            B.halo_gather(c, 0, ids, N, out, F, by_gid=by_gid, stream=st)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(args.steps):
+            B.halo_gather(c, 0, ids, N, out, F, by_gid=by_gid, stream=st)
+        e1.record(st)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        res[name] = {"ms": round(ms, 3), "hit_fraction": stats.hits / N, "rows_per_s": N / ms * 1e3,
+                     "out_GBps": N * F * 2 / ms / 1e6}
+    c.close()
+    print(json.dumps({"metric": "request-list halo gather, Zipf(1.1) requests", "unit": "ms per 2 M requests", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "dtype": "bf16 rows (bit copies)", "data": "synthetic",
+                      "config": {"workload": f"{N} halo vertices, GPU tier = top {k} by priority, {N} requests with replacement, "
+                                             f"rows of {F} bf16; host-tier rows are read from pinned memory by the same kernel"},
+                      "hit_fraction_closed_form": hits_expected, "lookups": res}))
+
+
 def bench_reorder(args):
     """Aggregation time of one SpMM launch (forward and transposed, hidden width 256) before and after the
     vertices are stored in a locality order, on the named config's graph (--config; 'clustered' = a graph with
@@ -233,10 +276,10 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C2")
-    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder"],
+    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder", "zipf_requests"],
                     help="epoch (default): the headline benchmark; cache_update: throughput of the cache write path; "
                          "policy: hit-rate curves of the cache policies; reorder: SpMM before / after vertex reordering "
-                         "(--config C2..C5 or clustered)")
+                         "(--config C2..C5 or clustered); zipf_requests: request-list gather under Zipf(1.1) requests")
     ap.add_argument("--miss-mode", type=int, default=None, help="0 zero-copy kernel, 1 staged DMA, 2 staged DMA prefetched one epoch ahead (default 2)")
     ap.add_argument("--reorder", default="none", choices=["none", "popularity", "bfs"],
                     help="store the vertices in a locality order before the graph handle is built (epoch benchmark)")
@@ -260,6 +303,8 @@ def main():
         return bench_cache_update(args)
     if args.what == "reorder":
         return bench_reorder(args)
+    if args.what == "zipf_requests":
+        return bench_zipf_requests(args)
     if args.what == "policy":
         return bench_policy(args)
 
@@ -280,6 +325,7 @@ def main():
     torch.cuda.synchronize()
     acc = {}
     stage = {}
+    dev_epochs = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
         loss, times = dp.run_epoch(want_times=True)
@@ -289,6 +335,7 @@ def main():
             per_epoch[key] = per_epoch.get(key, 0.0) + r["ms"]
         for key, ms in per_epoch.items():
             acc.setdefault(key, []).append(ms)
+        dev_epochs.append(times["total_ms"])
         for k in ("pick_cache_ms", "communication_ms", "aggregation_ms", "combine_ms", "loss_ms", "other_ms", "total_ms"):
             stage[k] = stage.get(k, 0.0) + times[k] / args.steps
     torch.cuda.synchronize()
@@ -339,6 +386,9 @@ def main():
                    "host_tier": {0: "kernel reads pinned memory", 1: "DMA into a staging area, same epoch",
                                  2: "DMA into a staging area, one epoch ahead (pipelined)"}[dp.miss_mode] if dp.cache else None},
         "epoch_ms_device": stage.get("total_ms"),
+        "epoch_ms_device_median": float(np.median(dev_epochs)), "epoch_ms_device_min": float(np.min(dev_epochs)),
+        "env": {"device": torch.cuda.get_device_name(0), "hip": torch.version.hip, "torch": torch.__version__,
+                "host_cores": os.cpu_count()},
         "stages_ms": {k: round(v, 4) for k, v in stage.items()},
         "aggregation_gedges_s_kernel_only": part.nnz * len(launches) / (spmm_ms * 1e-3) / 1e9 if spmm_ms else None,
         "gather": {"hit_GBps": hit_bytes / (hit_ms * 1e-3) / 1e9 if hit_ms else None, "hit_bytes": hit_bytes,
