@@ -56,9 +56,8 @@ struct SpOp {
     int64_t nnz = 0;
     const int64_t *ptr = nullptr;     // device [n_out+1]
     const int32_t *idx = nullptr;     // device [nnz]   source row of each entry
-    const float *val = nullptr;       // device [nnz] or null
-    // device [nnz]: weight of each entry, val * in_scale[source] formed once (a sequential read in the kernels
-    // instead of a gather from in_scale per entry); null when every weight is 1
+    // device [nnz]: weight of each entry, edge value * in_scale[source] formed once (a sequential read in the
+    // kernels instead of a gather from in_scale per entry); null when every weight is 1
     const float *wt = nullptr;
     const float *out_scale = nullptr; // device [n_out] or null
     const float *in_scale = nullptr;  // device [n_in]  or null

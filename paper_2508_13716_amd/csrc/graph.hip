@@ -253,7 +253,6 @@ extern "C" int capgnn_graph_create(capgnn_graph **out, int64_t n_loc, int64_t n_
     f.n_out = n_loc; f.n_in = n_cols; f.nnz = nnz; f.n_long = nl_f; f.n_sub = n_loc; f.n_long_sub = nl_f;
     if ((rc = upload(g, rowptr, n_loc + 1, &f.ptr))) return fail(rc);
     if ((rc = upload(g, col, nnz, &f.idx))) return fail(rc);
-    if (edge_val && (rc = upload(g, edge_val, nnz, &f.val))) return fail(rc);
     if ((rc = upload_weights(g, nnz, col, edge_val, col_scale, &f.wt))) return fail(rc);
     if (row_scale && (rc = upload(g, row_scale, n_loc, &f.out_scale))) return fail(rc);
     if (col_scale && (rc = upload(g, col_scale, n_cols, &f.in_scale))) return fail(rc);
@@ -269,7 +268,7 @@ extern "C" int capgnn_graph_create(capgnn_graph **out, int64_t n_loc, int64_t n_
     SpOp &b = g->bwd;
     b.n_out = n_cols; b.n_in = n_loc; b.nnz = nnz; b.out_scale = f.in_scale; b.in_scale = f.out_scale;
     if (share) {
-        b.ptr = f.ptr; b.idx = f.idx; b.val = f.val; b.order = f.order; b.n_long = f.n_long;
+        b.ptr = f.ptr; b.idx = f.idx; b.order = f.order; b.n_long = f.n_long;
         b.order_sub = f.order; b.n_sub = n_loc; b.n_long_sub = f.n_long; b.max_deg = f.max_deg;
         b.giant = f.giant; b.giant_sub = f.giant;
         b.ncb = f.ncb; b.b_off = f.b_off; b.b_ew = f.b_ew; b.b_long = f.b_long; b.b_mid = f.b_mid;
@@ -291,7 +290,6 @@ extern "C" int capgnn_graph_create(capgnn_graph **out, int64_t n_loc, int64_t n_
         b.n_sub = n_loc;
         if ((rc = upload(g, colptr.data(), n_cols + 1, &b.ptr))) return fail(rc);
         if ((rc = upload(g, rowidx.data(), nnz, &b.idx))) return fail(rc);
-        if (edge_val && (rc = upload(g, cscval.data(), nnz, &b.val))) return fail(rc);
         if ((rc = upload_weights(g, nnz, rowidx.data(), edge_val ? cscval.data() : nullptr, row_scale, &b.wt))) return fail(rc);
         if ((rc = upload(g, order_b.data(), order_b.size(), &b.order))) return fail(rc);
         if ((rc = upload(g, order_bs.data(), order_bs.size(), &b.order_sub))) return fail(rc);

@@ -17,9 +17,7 @@ namespace capgnn {
 struct SpmmArgs {
     const int64_t *ptr;
     const int32_t *idx;
-    const float *val;
     const float *out_scale;
-    const float *in_scale;
     const float *wt;          // per-entry weights, or null: every weight is 1
     const int32_t *order;
     int64_t list_begin, list_end;
@@ -689,7 +687,7 @@ int launch_spmm(const SpOp &op, bool restrict_sub, const void *X, int64_t ldx, v
     const int es_out = elem_bytes(out_dtype);
     const bool vec = aligned16(X) && aligned16(Y) && (ldx * es) % 16 == 0 && (ldy * es_out) % 16 == 0 && ldx >= f_up;
     SpmmArgs a;
-    a.ptr = op.ptr; a.idx = op.idx; a.val = op.val; a.out_scale = op.out_scale; a.in_scale = op.in_scale;
+    a.ptr = op.ptr; a.idx = op.idx; a.out_scale = op.out_scale;
     a.wt = op.wt;
     a.order = restrict_sub ? op.order_sub : op.order;
     a.list_begin = 0; a.list_end = n_rows;
