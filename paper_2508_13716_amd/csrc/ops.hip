@@ -97,33 +97,46 @@ __global__ __launch_bounds__(256) void relu_mask_dbias_vec4_kernel(int64_t n, in
         const int nv = F - f < 4 ? F - f : 4;    // valid features of this thread's vector (the rest is row padding)
         for (int64_t r0 = static_cast<int64_t>(blockIdx.x) * RB_ROWS; r0 < n; r0 += static_cast<int64_t>(gridDim.x) * RB_ROWS) {
             const int64_t r1 = r0 + RB_ROWS < n ? r0 + RB_ROWS : n;
-            for (int64_t r = r0 + ty; r < r1; r += TY) {
-                const float4 gv = ld4(src, r * lds + f, src_bf16);
-                float g[4] = {gv.x, gv.y, gv.z, gv.w};
-                bool zeroed = false;
-                if (relu) {
-                    const float4 hv = ld4(H, r * ldh + f, h_bf16);
-                    const float h[4] = {hv.x, hv.y, hv.z, hv.w};
+            // four rows per trip: their loads are issued together, so a thread keeps eight vectors in flight
+            for (int64_t rb = r0 + ty; rb < r1; rb += 4 * TY) {
+                float4 gv[4], hv[4];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (!(h[j] > 0.f) && g[j] != 0.f) { g[j] = 0.f; zeroed = true; }
-                }
-                if (!in_place || zeroed) {
-                    if (nv == 4) {
-                        if (dst_bf16) {
-                            uint2 o;
-                            o.x = bf16_rne_bits(g[0]) | (bf16_rne_bits(g[1]) << 16);
-                            o.y = bf16_rne_bits(g[2]) | (bf16_rne_bits(g[3]) << 16);
-                            *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(dst) + r * ldd + f) = o;
-                        } else {
-                            *reinterpret_cast<float4 *>(reinterpret_cast<float *>(dst) + r * ldd + f) = make_float4(g[0], g[1], g[2], g[3]);
-                        }
-                    } else {
-                        for (int j = 0; j < nv; ++j) st_elem(dst, r * ldd + f + j, g[j], dst_bf16);
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t r = rb + static_cast<int64_t>(u) * TY;
+                    if (r < r1) {
+                        gv[u] = ld4(src, r * lds + f, src_bf16);
+                        if (relu) hv[u] = ld4(H, r * ldh + f, h_bf16);
                     }
                 }
 #pragma unroll
-                for (int j = 0; j < 4; ++j) s[j] += g[j];
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t r = rb + static_cast<int64_t>(u) * TY;
+                    if (r >= r1) continue;
+                    float g[4] = {gv[u].x, gv[u].y, gv[u].z, gv[u].w};
+                    bool zeroed = false;
+                    if (relu) {
+                        const float h[4] = {hv[u].x, hv[u].y, hv[u].z, hv[u].w};
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (!(h[j] > 0.f) && g[j] != 0.f) { g[j] = 0.f; zeroed = true; }
+                    }
+                    if (!in_place || zeroed) {
+                        if (nv == 4) {
+                            if (dst_bf16) {
+                                uint2 o;
+                                o.x = bf16_rne_bits(g[0]) | (bf16_rne_bits(g[1]) << 16);
+                                o.y = bf16_rne_bits(g[2]) | (bf16_rne_bits(g[3]) << 16);
+                                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(dst) + r * ldd + f) = o;
+                            } else {
+                                *reinterpret_cast<float4 *>(reinterpret_cast<float *>(dst) + r * ldd + f) = make_float4(g[0], g[1], g[2], g[3]);
+                            }
+                        } else {
+                            for (int j = 0; j < nv; ++j) st_elem(dst, r * ldd + f + j, g[j], dst_bf16);
+                        }
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) s[j] += g[j];
+                }
             }
         }
     }
