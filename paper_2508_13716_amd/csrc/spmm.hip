@@ -65,6 +65,46 @@ __device__ __forceinline__ void load_elems(const char *p, float (&x)[E]) {
     }
 }
 
+// The same elements kept as loaded (packed bf16 stay packed: half the registers while several loads are in flight)
+// and widened only when they are consumed.
+template <bool BF16, int E> struct RawVec { float v[E]; };
+template <> struct RawVec<true, 8> { uint4 v; };
+template <> struct RawVec<true, 1> { uint16_t v; };
+
+template <bool BF16, int E>
+__device__ __forceinline__ void load_raw(const char *p, RawVec<BF16, E> &r) {
+    if constexpr (BF16 && E == 8) r.v = *reinterpret_cast<const uint4 *>(p);
+    else if constexpr (BF16 && E == 1) r.v = *reinterpret_cast<const uint16_t *>(p);
+    else load_elems<BF16, E>(p, r.v);
+}
+
+template <bool BF16, int E>
+__device__ __forceinline__ void zero_raw(RawVec<BF16, E> &r) {
+    if constexpr (BF16 && E == 8) r.v = make_uint4(0u, 0u, 0u, 0u);
+    else if constexpr (BF16 && E == 1) r.v = 0;
+    else {
+#pragma unroll
+        for (int j = 0; j < E; ++j) r.v[j] = 0.f;
+    }
+}
+
+template <bool BF16, int E>
+__device__ __forceinline__ void fma_raw(float w, const RawVec<BF16, E> &r, float (&acc)[E]) {
+    if constexpr (BF16 && E == 8) {
+        const uint32_t u[4] = {r.v.x, r.v.y, r.v.z, r.v.w};
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            acc[2 * d] = fmaf(w, __uint_as_float(u[d] << 16), acc[2 * d]);
+            acc[2 * d + 1] = fmaf(w, __uint_as_float(u[d] & 0xffff0000u), acc[2 * d + 1]);
+        }
+    } else if constexpr (BF16 && E == 1) {
+        acc[0] = fmaf(w, bf16_bits_to_f32(r.v), acc[0]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < E; ++j) acc[j] = fmaf(w, r.v[j], acc[j]);
+    }
+}
+
 template <bool BF16>
 __device__ __forceinline__ float load_one(const char *p) {
     if constexpr (BF16) return bf16_bits_to_f32(*reinterpret_cast<const uint16_t *>(p));
@@ -121,7 +161,7 @@ __device__ __forceinline__ void accumulate_range(const SpmmArgs &a, int64_t e_be
         const int nsteps = (cnt + G - 1) / G;
         int s = 0;
         for (; s + U <= nsteps; s += U) {
-            float x[U][NV][E];
+            RawVec<BF16, E> x[U][NV];
             float ws[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -136,19 +176,14 @@ __device__ __forceinline__ void accumulate_range(const SpmmArgs &a, int64_t e_be
                 const char *p = xbase + static_cast<int64_t>(cj) * a.ldx_bytes;
 #pragma unroll
                 for (int v = 0; v < NV; ++v) {
-                    if (ok[v]) load_elems<BF16, E>(p + v * LPR * E * ES, x[u][v]);
-                    else {
-#pragma unroll
-                        for (int j = 0; j < E; ++j) x[u][v][j] = 0.f;
-                    }
+                    if (ok[v]) load_raw<BF16, E>(p + v * LPR * E * ES, x[u][v]);
+                    else zero_raw<BF16, E>(x[u][v]);
                 }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
-                for (int v = 0; v < NV; ++v)
-#pragma unroll
-                    for (int j = 0; j < E; ++j) acc[v][j] = fmaf(ws[u], x[u][v][j], acc[v][j]);
+                for (int v = 0; v < NV; ++v) fma_raw<BF16, E>(ws[u], x[u][v], acc[v]);
         }
         for (; s < nsteps; ++s) {
             int cj;
