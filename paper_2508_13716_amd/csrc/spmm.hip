@@ -209,11 +209,13 @@ __device__ __forceinline__ void accumulate_range(const SpmmArgs &a, int64_t e_be
     }
 }
 
+// The wave-per-row launches are bound by how many gathers the resident waves keep in flight: at least six waves per
+// SIMD are asked for (the bf16-in / fp32-out variants otherwise settle at four).
 // MODE 0: one single-wave workgroup per output row (rows of one work-list class differ in length, and a wave that
 // shares a workgroup with a longer row would hold its slot until that one ends).  MODE 1: one workgroup per row.  MODE 2: one workgroup per piece of a cut row;
 // the raw fp32 sum of the piece goes to a.part and spmm_pieces_finish_kernel completes the row.
 template <bool BF16, bool OBF16, int E, int LPR, int NV, int MODE>
-__global__ __launch_bounds__(MODE == 0 ? 64 : 256) void spmm_kernel(SpmmArgs a) {
+__global__ __launch_bounds__(MODE == 0 ? 64 : 256, (MODE == 0 && NV < 3) ? 6 : 1) void spmm_kernel(SpmmArgs a) {
     constexpr bool LONG = MODE >= 1;
     constexpr int G = 64 / LPR;
     constexpr int ES = OBF16 ? 2 : 4;   // element size of the output
