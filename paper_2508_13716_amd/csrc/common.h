@@ -85,7 +85,7 @@ constexpr int EXACT_ROW = 256;  // work lists sort rows at least this long by th
 constexpr int LONG_ROW = 2048;  // rows at least this long are reduced by a whole workgroup
 constexpr int GIANT_ROW = 16384;  // rows at least this long are cut into pieces when the caller brings scratch
 constexpr int GIANT_PIECE = 4096; // entries per piece: one workgroup each, partial sums combined in piece order
-constexpr int CB_ROWS = 16384;  // source rows per column block: 16384 x 128-byte slices = 2 MB, half an XCD's L2
+constexpr int CB_ROWS = 32768;  // source rows per column block: 32768 x 128-byte slices = 4 MB, one XCD's L2 (swept: 8192 .. 49152)
 constexpr int B_LONG_GROUP = 512; // rows with at least this many entries per source block on average: workgroup per group
 constexpr int B_MID_GROUP = 128;  // ... at least this many: wave per group
 constexpr int SLICE_BYTES = 128;  // feature bytes of one source row that one task of the blocked kernel gathers

@@ -324,7 +324,7 @@ __global__ __launch_bounds__(MODE == 0 ? 64 : 256, (MODE == 0 && NV < 3) ? 6 : 1
 // A task is (source block cb, output position p, feature slice s): it sums the entries of row order[p] whose
 // source lies in block cb, over one SLICE_BYTES-wide slice of the feature row, and stores the partial row to
 // scratch.  The grid is laid out so that the workgroups running on one L2 domain at any moment share (cb, s):
-// their gathers then address CB_ROWS * SLICE_BYTES = 2 MB, which that L2 holds.  Workgroup b runs on domain
+// their gathers then address CB_ROWS * SLICE_BYTES = 4 MB, the size of that L2.  Workgroup b runs on domain
 // b % NUM_XCD; the slices (times H interleaved shares of the rows when there are fewer slices than domains)
 // are dealt to the domains, and each domain sweeps its units block by block.  Within a (unit, block) phase the
 // positions come heaviest first in three classes: a whole workgroup per task, a wave per task, and eight
