@@ -15,14 +15,18 @@ namespace capgnn {
 // cache line gets a whole line when that costs at most a third more memory (96-byte rows at a 96-byte pitch
 // straddle two lines three times out of four; C4's 47-wide aggregation gains 8 %).  Wider rows keep the 16-byte
 // pitch: padding 400-byte rows to 512 made C3's dense products 12 % slower.
-// When the graph has a column-blocked copy, a pitch that is an even number of 128-byte lines gets one more line:
-// the blocked kernel gathers the same 128-byte slice of many rows at a time, and with an even line count those
-// slices fall on one or two of the sixteen channels of an L2 (measured on C2: 1.88 -> 1.70 ms per launch).
+// When the graph has a column-blocked copy the pitch is a whole, odd number of 128-byte lines: the blocked kernel
+// gathers the same 128-byte slice of many rows at a time; the slices then coincide with cache lines (C2's 41-wide
+// launch 0.57 -> 0.44 ms) and, with an odd line count, spread over all sixteen channels of an L2 instead of one or
+// two (C2's 256-wide launches 1.88 -> 1.70 ms).
 static int pad_ld(const capgnn_graph *g, int f, int dtype) {
     const int es = elem_bytes(dtype);
     const int bytes16 = (f * es + 15) / 16 * 16;
     int bytes = (bytes16 < 128 && (128 - bytes16) * 3 <= bytes16) ? 128 : bytes16;
-    if ((g->fwd.ncb || g->bwd.ncb) && bytes % 256 == 0) bytes += 128;
+    if (g->fwd.ncb || g->bwd.ncb) {
+        bytes = (bytes + 127) / 128 * 128;          // slices of the blocked kernel coincide with cache lines
+        if (bytes % 256 == 0) bytes += 128;
+    }
     return bytes / es;
 }
 
