@@ -401,7 +401,9 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes": bmin, "gathered_bytes_no_reuse": bgather,
                      "gather_rate_GBps": bgather / (dom["ms"] * 1e-3) / 1e9, "ms": dom["ms"],
-                     "gedges_s": part.nnz / (dom["ms"] * 1e-3) / 1e9},
+                     "gedges_s": part.nnz / (dom["ms"] * 1e-3) / 1e9,
+                     "note": "achieved = algorithmic bytes / launch time; the gather itself is served by the L2s "
+                             "(C2: L2 channels busy for all of the kernel's cycles, profiles/spmm_C2_hbm_counters.txt)"},
     }
     if args.cpu_scale is None:
         # the oracle moves about 3 GFLOP-equivalents per second per 16 cores on this kind of epoch
