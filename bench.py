@@ -209,6 +209,31 @@ def bench_zipf_requests(args):
                       "hit_fraction_closed_form": hits_expected, "lookups": res}))
 
 
+def bench_mfma_peak(args):
+    """What the matrix cores deliver with register-resident operands (fp32 and bf16 instructions); one JSON line."""
+    import torch
+    from paper_2508_13716_amd import binding as B
+    st = torch.cuda.Stream()
+    wgs, iters = 256 * 8, 4096
+    out = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
+    res = {}
+    for name, dt, peak in (("f32", B.F32, 157.3), ("bf16", B.BF16, BF16_MATRIX_PEAK_TFLOPS)):
+        B.mfma_peak(dt, wgs, iters, out, st)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        flop = 0.0
+        for _ in range(args.steps):
+            flop += B.mfma_peak(dt, wgs, iters, out, st)
+        e1.record(st)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        res[name] = {"tflops": flop / ms / 1e9, "data_sheet_tflops": peak, "frac": flop / ms / 1e9 / peak}
+    print(json.dumps({"metric": "matrix-instruction throughput, register-resident operands", "unit": "TFLOP/s", "n_gpus": 1,
+                      "steps": args.steps, "data": "synthetic", "config": {"workload": f"{wgs} workgroups x 4 waves x {4 * iters} instructions"},
+                      "measured": res}))
+
+
 def bench_reorder(args):
     """Aggregation time of one SpMM launch (forward and transposed, hidden width 256) before and after the
     vertices are stored in a locality order, on the named config's graph (--config; 'clustered' = a graph with
@@ -276,7 +301,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C2")
-    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder", "zipf_requests"],
+    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder", "zipf_requests", "mfma_peak"],
                     help="epoch (default): the headline benchmark; cache_update: throughput of the cache write path; "
                          "policy: hit-rate curves of the cache policies; reorder: SpMM before / after vertex reordering "
                          "(--config C2..C5 or clustered); zipf_requests: request-list gather under Zipf(1.1) requests")
@@ -305,6 +330,8 @@ def main():
         return bench_reorder(args)
     if args.what == "zipf_requests":
         return bench_zipf_requests(args)
+    if args.what == "mfma_peak":
+        return bench_mfma_peak(args)
     if args.what == "policy":
         return bench_policy(args)
 

@@ -299,6 +299,12 @@ int capgnn_relabel_csr(int64_t n_loc, int64_t n_halo, const int64_t *rowptr, con
  * out_f32 != 0 stores C as float even when dtype is BF16 (weight gradients, logits).
  * ---------------------------------------------------------------------------------------- */
 size_t capgnn_gemm_workspace_bytes(int trans_a, int64_t M, int64_t N, int64_t K);
+
+/* Measurement aid for the matrix-core roofline of the dense products: launches `workgroups` workgroups of 256 threads
+ * that each issue 4 * iters register-resident matrix instructions per wave (v_mfma_f32_32x32x2_f32 for CAPGNN_F32,
+ * v_mfma_f32_32x32x16_bf16 for CAPGNN_BF16) and returns in *flop (host) the floating-point operations the launch
+ * performs; the caller times it.  out: device float[workgroups * 256] (receives one value per thread). */
+int capgnn_mfma_peak(int dtype, int workgroups, int iters, float *out, double *flop, void *stream);
 int capgnn_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K,
                 const void *A, int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc,
                 int dtype, int out_f32, int accumulate, const float *bias, int relu,

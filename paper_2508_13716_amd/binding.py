@@ -91,6 +91,7 @@ SIGNATURES = {
     "capgnn_cache_lookup": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _vp]),
     "capgnn_halo_gather": (_i32, [_vp, _i32, _vp, _i64, _i32, _vp, _i64, _vp, _vp, _vp, C.POINTER(GatherStats)]),
     "capgnn_gemm_workspace_bytes": (_sz, [_i32, _i64, _i64, _i64]),
+    "capgnn_mfma_peak": (_i32, [_i32, _i32, _i32, _vp, C.POINTER(C.c_double), _vp]),
     "capgnn_gemm": (_i32, [_i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _i32, _vp, _i32,
                            _vp, _i64, _vp, _sz, _vp]),
     "capgnn_layer_order": (_i32, [_vp, C.POINTER(Layer), _i32]),
@@ -359,6 +360,13 @@ def relabel_csr(n_loc: int, n_halo: int, rowptr, col, new2old, edge_val=None):
 
 
 # --------------------------------------------------------------------------- dense, layer, loss, epoch
+def mfma_peak(dtype: int, workgroups: int, iters: int, out, stream=None) -> float:
+    """Launches the register-resident matrix-instruction loop; returns the FLOPs it performs (the caller times it)."""
+    flop = C.c_double(0.0)
+    _check(lib().capgnn_mfma_peak(dtype, workgroups, iters, _p(out), C.byref(flop), _stream(stream)))
+    return float(flop.value)
+
+
 def gemm_workspace_bytes(trans_a: int, M: int, N: int, K: int) -> int:
     return int(lib().capgnn_gemm_workspace_bytes(trans_a, M, N, K))
 

@@ -699,9 +699,50 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
     return CAPGNN_OK;
 }
 
+// Register-resident matrix-instruction loop: what the matrix cores deliver on this chip when nothing else is in
+// the way (four independent 32x32 accumulator tiles per wave, operands never reloaded).  The utilisation figures
+// of the product kernels can be read against it as well as against the data-sheet peak.
+template <bool BF16>
+__global__ __launch_bounds__(256) void mfma_peak_kernel(int iters, float *out) {
+    floatx16 acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+    const float a = 1.f + 1e-3f * threadIdx.x, b = 1.f - 1e-3f * threadIdx.x;
+    bf16x8 ha, hb;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { ha[j] = static_cast<__bf16>(a); hb[j] = static_cast<__bf16>(b); }
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if constexpr (BF16) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ha, hb, acc[t], 0, 0, 0);
+            else acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[t], 0, 0, 0);
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[t][r];
+    out[static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x] = s;     // keeps the loop alive
+}
+
 }  // namespace capgnn
 
 using namespace capgnn;
+
+extern "C" int capgnn_mfma_peak(int dtype, int workgroups, int iters, float *out, double *flop, void *stream) {
+    if ((dtype != CAPGNN_F32 && dtype != CAPGNN_BF16) || workgroups <= 0 || iters <= 0 || !out || !flop)
+        CG_FAIL(CAPGNN_EINVAL, "mfma_peak: bad argument");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == CAPGNN_BF16) hipLaunchKernelGGL(mfma_peak_kernel<true>, dim3(workgroups), dim3(256), 0, st, iters, out);
+    else hipLaunchKernelGGL(mfma_peak_kernel<false>, dim3(workgroups), dim3(256), 0, st, iters, out);
+    CG_HIP(hipGetLastError());
+    const double per_instr = dtype == CAPGNN_BF16 ? 2.0 * 32 * 32 * 16 : 2.0 * 32 * 32 * 2;
+    *flop = per_instr * 4.0 * iters * 4.0 * workgroups;     // 4 tiles per wave, 4 waves per workgroup
+    return CAPGNN_OK;
+}
 
 extern "C" size_t capgnn_gemm_workspace_bytes(int trans_a, int64_t M, int64_t N, int64_t K) {
     return gemm_ws_bytes(trans_a, M, N, K);
