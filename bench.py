@@ -309,6 +309,9 @@ def main():
     ap.add_argument("--reorder", default="none", choices=["none", "popularity", "bfs"],
                     help="store the vertices in a locality order before the graph handle is built (epoch benchmark)")
     ap.add_argument("--orders", default=None, help="comma list of 1 (aggregate first) / 2 (transform first) per layer")
+    ap.add_argument("--f32-product", default="auto", choices=["auto", "native", "split"],
+                    help="how products of fp32 operands are formed: the fp32 matrix instruction, three bf16 pieces per operand "
+                         "on the bf16 matrix cores, or (default) the library's choice by size")
     ap.add_argument("--cpu-scale", type=float, default=None,
                     help="share of the workload the oracle is timed on (0 = skip; default: sized for 10-30 s of CPU work)")
     args = ap.parse_args()
@@ -324,6 +327,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     B.lib()
+    B.set_f32_product({"auto": B.F32_PRODUCT_AUTO, "native": B.F32_PRODUCT_NATIVE, "split": B.F32_PRODUCT_SPLIT}[args.f32_product])
     if args.what == "cache_update":
         return bench_cache_update(args)
     if args.what == "reorder":
@@ -409,6 +413,7 @@ def main():
         "config": {"workload": f"{cfg.name}: {part.n_loc} local + {part.n_halo} halo vertices, {part.nnz} edges, "
                                f"{cfg.kind} dims {cfg.dims}, GPU tier {dp.cache.cap_gpu if dp.cache else 0} halo rows",
                    "orders": ["agg_first" if o == 1 else "xform_first" for o in res_orders],
+                   "f32_product": args.f32_product,
                    "spmm_launches_per_epoch": len(launches), "loss": loss, "vertex_order": args.reorder,
                    "host_tier": {0: "kernel reads pinned memory", 1: "DMA into a staging area, same epoch",
                                  2: "DMA into a staging area, one epoch ahead (pipelined)"}[dp.miss_mode] if dp.cache else None},

@@ -294,11 +294,29 @@ int capgnn_relabel_csr(int64_t n_loc, int64_t n_halo, const int64_t *rowptr, con
  * trans_a: A is stored [K x M];  trans_b: B is stored [N x K].  bias: device float[N] or NULL.
  * relu_mask: device [M x ldm] of `dtype` or NULL; when given, C[i,j] is zeroed where
  * relu_mask[i,j] <= 0 (the sigma' factor of the backward recursion).
- * ws is needed only when trans_a (reduction over the vertex dimension is split over workgroups and
- * reduced in a fixed order): capgnn_gemm_workspace_bytes().
+ * ws is required when trans_a (reduction over the vertex dimension is split over workgroups and
+ * reduced in a fixed order) and optional otherwise (room to lay the weight matrix out for the bf16
+ * matrix cores; without it a slower kernel runs): capgnn_gemm_workspace_bytes().
  * out_f32 != 0 stores C as float even when dtype is BF16 (weight gradients, logits).
  * ---------------------------------------------------------------------------------------- */
 size_t capgnn_gemm_workspace_bytes(int trans_a, int64_t M, int64_t N, int64_t K);
+
+/* How products of fp32 operands are formed (process-wide; takes effect with the next call that launches a product).
+ *   CAPGNN_F32_PRODUCT_NATIVE  the fp32 matrix instruction (v_mfma_f32_32x32x2_f32).
+ *   CAPGNN_F32_PRODUCT_SPLIT   each fp32 operand is cut, exactly, into three bf16 numbers and the six largest of the nine
+ *                              piece products are accumulated in fp32 on the bf16 matrix cores; what is dropped is
+ *                              2^-23 of a product at most, the size of the fp32 instruction's own rounding.  Needs the
+ *                              workspace of capgnn_gemm_workspace_bytes() also when !trans_a (the weight matrix is cut
+ *                              there); without it, and for trans_a && trans_b, the native instruction runs.
+ *                              Non-finite operands give NaN where the native instruction may give an infinity.
+ *   CAPGNN_F32_PRODUCT_AUTO    (default) SPLIT for products of 2^28 multiply-adds and more, except trans_a products
+ *                              with N <= 64; NATIVE otherwise.
+ * bf16 operands are not affected.  Returns CAPGNN_EINVAL for an unknown mode. */
+#define CAPGNN_F32_PRODUCT_NATIVE 0
+#define CAPGNN_F32_PRODUCT_SPLIT 1
+#define CAPGNN_F32_PRODUCT_AUTO 2
+int capgnn_set_f32_product(int mode);
+int capgnn_get_f32_product(void);
 
 /* Measurement aid for the matrix-core roofline of the dense products: launches `workgroups` workgroups of 256 threads
  * that each issue 4 * iters register-resident matrix instructions per wave (v_mfma_f32_32x32x2_f32 for CAPGNN_F32,

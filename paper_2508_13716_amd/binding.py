@@ -91,6 +91,8 @@ SIGNATURES = {
     "capgnn_cache_lookup": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _vp]),
     "capgnn_halo_gather": (_i32, [_vp, _i32, _vp, _i64, _i32, _vp, _i64, _vp, _vp, _vp, C.POINTER(GatherStats)]),
     "capgnn_gemm_workspace_bytes": (_sz, [_i32, _i64, _i64, _i64]),
+    "capgnn_set_f32_product": (_i32, [_i32]),
+    "capgnn_get_f32_product": (_i32, []),
     "capgnn_mfma_peak": (_i32, [_i32, _i32, _i32, _vp, C.POINTER(C.c_double), _vp]),
     "capgnn_gemm": (_i32, [_i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _i32, _vp, _i32,
                            _vp, _i64, _vp, _sz, _vp]),
@@ -360,6 +362,18 @@ def relabel_csr(n_loc: int, n_halo: int, rowptr, col, new2old, edge_val=None):
 
 
 # --------------------------------------------------------------------------- dense, layer, loss, epoch
+F32_PRODUCT_NATIVE, F32_PRODUCT_SPLIT, F32_PRODUCT_AUTO = 0, 1, 2
+
+
+def set_f32_product(mode: int) -> None:
+    """Chooses how products of fp32 operands are formed (fp32 matrix instruction / three-way bf16 split / by size)."""
+    _check(lib().capgnn_set_f32_product(mode))
+
+
+def get_f32_product() -> int:
+    return int(lib().capgnn_get_f32_product())
+
+
 def mfma_peak(dtype: int, workgroups: int, iters: int, out, stream=None) -> float:
     """Launches the register-resident matrix-instruction loop; returns the FLOPs it performs (the caller times it)."""
     flop = C.c_double(0.0)

@@ -11,6 +11,7 @@
 #include "common.h"
 
 #include <algorithm>
+#include <atomic>
 
 namespace capgnn {
 
@@ -128,6 +129,79 @@ __device__ __forceinline__ void store_tile(const GemmArgs &g, const floatx16 (&a
         }
 }
 
+// The same through LDS: a wave rounds 32 rows of its accumulators at a time into a private LDS area (lds, STAGE_BYTES
+// per wave) and leaves along the rows of C, 16 bytes per lane, so that a store instruction covers 4 rows x 256 bytes
+// instead of 2 x 128 and the read-modify-write of an accumulating product moves whole vectors.  fp32 results only.
+constexpr int STAGE_PITCH = 64 + 8;                         // floats per staged row (four rows further = other half of the banks)
+constexpr int STAGE_BYTES = 32 * STAGE_PITCH * 4;           // per wave
+
+__device__ __forceinline__ void store_tile_staged(const GemmArgs &g, const floatx16 (&acc)[2][2], float *lds, int64_t row0,
+                                                  int64_t col0, int lane, int bz) {
+    const int l32 = lane & 31, half = lane >> 5;
+    float *dst = g.part ? g.part + static_cast<int64_t>(bz) * g.M * g.N : reinterpret_cast<float *>(g.C);
+    const int64_t ld = g.part ? g.N : g.ldc;
+    const bool vec = (reinterpret_cast<uintptr_t>(dst) % 16 == 0) && (ld % 4 == 0);
+    const bool plain = g.part != nullptr;                   // partials take no epilogue
+    const int cg = lane & 15, rq = lane >> 4;               // the lane's column group (4 columns) and row within a quad of rows
+    const int64_t col = col0 + 4 * cg;
+    float bv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (!plain && g.bias)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (col + e < g.N) bv[e] = g.bias[col + e];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) lds[(8 * (r >> 2) + 4 * half + (r & 3)) * STAGE_PITCH + j * 32 + l32] = acc[i][j][r];
+        __builtin_amdgcn_wave_barrier();
+        if (col < g.N) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int lr = 4 * t + rq;
+                const int64_t row = row0 + i * 32 + lr;
+                if (row >= g.M) continue;
+                const float4 v4 = *reinterpret_cast<const float4 *>(&lds[lr * STAGE_PITCH + 4 * cg]);
+                float v[4] = {v4.x, v4.y, v4.z, v4.w};
+                float *out = dst + row * ld + col;
+                const bool whole = vec && col + 4 <= g.N;
+                if (!plain) {
+                    if (g.accumulate) {
+                        if (whole) {
+                            const float4 c4 = *reinterpret_cast<const float4 *>(out);
+                            v[0] += c4.x; v[1] += c4.y; v[2] += c4.z; v[3] += c4.w;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (col + e < g.N) v[e] += out[e];
+                        }
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] += bv[e];
+                        if (g.relu) v[e] = v[e] > 0.f ? v[e] : 0.f;
+                    }
+                    if (g.mask) {
+                        const float *mk = reinterpret_cast<const float *>(g.mask) + row * g.ldm + col;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < g.N && !(mk[e] > 0.f)) v[e] = 0.f;
+                    }
+                }
+                if (whole) {
+                    *reinterpret_cast<float4 *>(out) = make_float4(v[0], v[1], v[2], v[3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (col + e < g.N) out[e] = v[e];
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
 constexpr int BK = 16;
 constexpr int PAD = 4;
 
@@ -211,8 +285,13 @@ template <bool BF16, bool A_KC, bool B_KC, int BM, int BN>
 __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
     constexpr int WM = BM / 2, WN = BN / 2;
     constexpr int TM = WM / 32, TN = WN / 32;
-    __shared__ __attribute__((aligned(16))) float As[2][BK][BM + PAD];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BK][BN + PAD];
+    // operand tiles; fp32 results of full-size tiles leave through the same memory (store_tile_staged)
+    constexpr int OPERAND_FLOATS = 2 * BK * (BM + PAD) + 2 * BK * (BN + PAD);
+    constexpr bool STAGED = !BF16 && TM == 2 && TN == 2;
+    constexpr int SMEM_FLOATS = (STAGED && 4 * STAGE_BYTES / 4 > OPERAND_FLOATS) ? 4 * STAGE_BYTES / 4 : OPERAND_FLOATS;
+    __shared__ __attribute__((aligned(16))) float smem[SMEM_FLOATS];
+    float (*As)[BK][BM + PAD] = reinterpret_cast<float (*)[BK][BM + PAD]>(smem);
+    float (*Bs)[BK][BN + PAD] = reinterpret_cast<float (*)[BK][BN + PAD]>(smem + 2 * BK * (BM + PAD));
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -295,7 +374,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
         __syncthreads();
     }
 
-    store_tile<TM, TN>(g, acc, m0 + wm * WM, n0 + wn * WN, l32, half, bz);
+    if constexpr (STAGED) {
+        // the last pass through the loop ended with a barrier: every wave is done with the operands
+        store_tile_staged(g, acc, smem + wave * (STAGE_BYTES / 4), m0 + wm * WM, n0 + wn * WN, lane, bz);
+    } else {
+        store_tile<TM, TN>(g, acc, m0 + wm * WM, n0 + wn * WN, l32, half, bz);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -536,6 +620,353 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// fp32 operands on the bf16 matrix cores.  An fp32 number is the exact sum of three bf16 numbers (its 24 significant
+// bits cut into 8 + 8 + 8, with signs), so a product a * b is the sum of nine bf16 products, each exact in fp32.  The
+// three smallest (together at most 2^-23 of the product: the size of fp32's own rounding) are dropped, the other six are accumulated in
+// fp32 by v_mfma_f32_32x32x16_bf16, smallest first.  Six such instructions cover the k-range of eight
+// v_mfma_f32_32x32x2_f32 at about a fifteenth of the cost each.
+//
+// LDS holds the three pieces of both operand tiles, 32 k per step, in one buffer (the next step's operands wait in
+// registers; three workgroups share a compute unit and fill one another's barriers).  An operand stored along the
+// reduction index is cut while it is staged and kept in 16-byte units S[piece][k / 8][row] (a lane's eight k are one
+// 16-byte read, consecutive lanes read consecutive units; a plane is 32 bytes longer than a power of two so that the
+// 8-byte staging stores of 16 consecutive lanes, 2 rows x 4 units x 2 halves, cover 128 consecutive bytes of banks); the weight matrix of a plain product is
+// cut once, by split_repack_kernel, into the same units in global memory and only copied here; an operand stored across
+// the reduction index (both operands of X^T G) is transposed in registers and kept in 8-byte units
+// S[piece][k / 4][row], which makes both the staging stores (32 bytes per thread and piece) and the operand reads
+// (two 8-byte reads) run over consecutive LDS addresses.
+constexpr int SBK = 32;
+
+// x = p0 + p1 + p2 exactly, each piece the upper half of the returned word.  The first two pieces are rounded to
+// nearest (ties upwards), which bounds the second piece by 2^-8 |x| and the third by 2^-16 |x|; the remainders are
+// exact fp32 differences with at most 16 and 7 significant bits.
+__device__ __forceinline__ void split3(float x, uint32_t &p0, uint32_t &p1, uint32_t &p2) {
+    p0 = __float_as_uint(x) + 0x8000u;
+    const float r1 = x - __uint_as_float(p0 & 0xffff0000u);
+    p1 = __float_as_uint(r1) + 0x8000u;
+    const float r2 = r1 - __uint_as_float(p1 & 0xffff0000u);
+    p2 = __float_as_uint(r2);
+}
+
+// upper halves of two words, `lo`'s in the low half
+__device__ __forceinline__ uint32_t upper_halves(uint32_t hi, uint32_t lo) { return __builtin_amdgcn_perm(hi, lo, 0x07060302u); }
+
+// 16-byte units of an operand kept along the reduction index: unit (piece, u = k / 8, row)
+template <int BT>
+struct Units16 {
+    static constexpr int PLANE = BT + 2;                    // units per (piece, u) plane
+    static constexpr int BYTES = 3 * 4 * PLANE * 16;
+    static __device__ __forceinline__ int at(int piece, int u, int row) { return ((piece * 4 + u) * PLANE + row) * 16; }
+};
+
+// operand stored along the reduction index, cut while staged: a row's 32 k are eight float4 of eight threads
+template <int BT>
+struct SplitRowLoader {
+    static constexpr int NLD = BT * SBK / 4 / 256;
+    float4 r[NLD];
+    const char *pf[NLD];
+
+    __device__ __forceinline__ void fetch(const char *base, int64_t ld, int64_t t0, int64_t T, int64_t k0, int64_t k_end,
+                                          int vec, int tid) {
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const int idx = tid + 256 * q;
+            const int row = idx >> 3, kq = idx & 7;
+            const int64_t t = t0 + row, k = k0 + 4 * kq;
+            const int nv = (t < T) ? static_cast<int>(k_end - k < 4 ? k_end - k : 4) : 0;
+            r[q] = load4<false>(base, t * ld + k, nv, vec);
+        }
+    }
+
+    __device__ __forceinline__ void fast_begin(const char *base, int64_t ld, int64_t t0, int64_t k0, int tid) {
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const int idx = tid + 256 * q;
+            pf[q] = base + ((t0 + (idx >> 3)) * ld + k0 + 4 * (idx & 7)) * 4;
+        }
+    }
+
+    __device__ __forceinline__ void fetch_fast() {
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            r[q] = *reinterpret_cast<const float4 *>(pf[q]);
+            pf[q] += SBK * 4;
+        }
+    }
+
+    __device__ __forceinline__ void stash(char *s, int tid) const {
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const int idx = tid + 256 * q;
+            const int row = idx >> 3, kq = idx & 7;
+            uint32_t x[3], y[3], z[3], w[3];
+            split3(r[q].x, x[0], x[1], x[2]);
+            split3(r[q].y, y[0], y[1], y[2]);
+            split3(r[q].z, z[0], z[1], z[2]);
+            split3(r[q].w, w[0], w[1], w[2]);
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+                *reinterpret_cast<uint2 *>(s + Units16<BT>::at(p, kq >> 1, row) + 8 * (kq & 1)) =
+                    make_uint2(upper_halves(y[p], x[p]), upper_halves(w[p], z[p]));
+        }
+    }
+};
+
+// second operand already cut into units Wt[piece][k / 8][n] (n padded to whole tiles, k to whole steps): plain copies
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int BT>
+struct SplitPlaneLoader {
+    static constexpr int NLD = 3 * 4 * BT / 256;
+    u32x4 r[NLD];
+    const u32x4 *pf;                // the thread's first unit; its others lie q * stride_q further on
+    int64_t stride_q;               // in units
+
+    // ku_total: 16-byte units along k of one piece; n_pad: rows of a plane.  256 consecutive units of the LDS image
+    // (piece, u, row) are 256 / BT planes of BT rows: thread tid copies row tid % BT of planes tid / BT + q * 256 / BT.
+    __device__ __forceinline__ void begin(const uint16_t *Wt, int64_t ku_total, int64_t n_pad, int64_t t0, int64_t k0, int tid) {
+        static_assert(BT == 128 || BT == 64, "planes per pass: 2 or 4, both divide the 4 units of a piece");
+        const int pu = tid / BT, row = tid % BT;
+        pf = reinterpret_cast<const u32x4 *>(Wt) + (k0 / 8 + pu) * n_pad + t0 + row;
+        stride_q = (256 / BT) * n_pad;
+        piece_stride = (ku_total - 4) * n_pad;
+    }
+    int64_t piece_stride;           // extra distance when q crosses into the next piece
+
+    __device__ __forceinline__ void fetch(int64_t n_pad) {
+        constexpr int PPQ = 256 / BT;           // planes per pass
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) r[q] = pf[q * stride_q + ((q * PPQ) / 4) * piece_stride];
+        pf += (SBK / 8) * n_pad;
+    }
+
+    __device__ __forceinline__ void stash(char *s, int tid) const {
+        constexpr int PPQ = 256 / BT;
+        const int pu0 = tid / BT, row = tid % BT;
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const int pu = pu0 + q * PPQ;
+            *reinterpret_cast<u32x4 *>(s + Units16<BT>::at(pu >> 2, pu & 3, row)) = r[q];
+        }
+    }
+};
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// operands stored across the reduction index (both of X^T G): waves 0-1 stage the first operand's tile, waves 2-3 the
+// second's; per thread two blocks of 4 k x 4 columns (k-blocks kb and kb + 4); kept as 8-byte units (piece, k / 4, row)
+struct SplitColLoader {
+    f32x4 r[8];
+    const f32x4 *pf;                // check-free path: the thread's first vector of the next step
+    const char *base;               // this thread's operand
+    int64_t ld, t0, T;
+    char *s;                        // its LDS tile
+    int bt, kb, tq;                 // tile width; the thread's k-block and column group
+    bool idle;                      // narrow second tiles leave a wave without work
+
+    static constexpr int bytes(int bt_) { return 3 * 8 * bt_ * 8; }
+
+    __device__ __forceinline__ void init(const GemmArgs &g, int64_t m0, int64_t n0, int bm, int bn, char *As, char *Bs, int tid) {
+        const bool second = __builtin_amdgcn_readfirstlane(tid >> 7) != 0;        // uniform over the wave
+        base = second ? g.B : g.A;
+        ld = second ? g.ldb : g.lda;
+        t0 = second ? n0 : m0;
+        T = second ? g.N : g.M;
+        s = second ? Bs : As;
+        bt = second ? bn : bm;
+        const int tt = tid & 127, cpr = bt / 4;
+        kb = tt / cpr; tq = tt % cpr;
+        idle = kb >= 4;
+    }
+
+    __device__ __forceinline__ void fetch(int64_t k0, int64_t k_end, int vec) {
+        if (idle) return;
+        const int64_t t = t0 + 4 * tq;
+        const int ncol = static_cast<int>(T - t < 4 ? T - t : 4);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int64_t k = k0 + 4 * kb + 16 * (j >> 2) + (j & 3);
+            const float4 v = load4<false>(base, k * ld + t, k < k_end ? ncol : 0, vec);
+            r[j] = f32x4{v.x, v.y, v.z, v.w};
+        }
+    }
+
+    __device__ __forceinline__ void fast_begin(int64_t k0) {
+        pf = reinterpret_cast<const f32x4 *>(base + ((k0 + 4 * kb) * ld + t0 + 4 * tq) * 4);
+    }
+
+    // the check-free path runs only when rows are whole 16-byte vectors
+    __device__ __forceinline__ void fetch_fast() {
+        if (idle) return;
+        const int64_t ld4 = ld / 4;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[j] = pf[(16 * (j >> 2) + (j & 3)) * ld4];
+        pf += SBK * ld4;
+    }
+
+    __device__ __forceinline__ void stash() const {
+        if (idle) return;
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {           // one column: four consecutive k, one 8-byte unit per piece
+                uint32_t k0[3], k1[3], k2[3], k3[3];
+                split3(r[4 * blk + 0][c], k0[0], k0[1], k0[2]);
+                split3(r[4 * blk + 1][c], k1[0], k1[1], k1[2]);
+                split3(r[4 * blk + 2][c], k2[0], k2[1], k2[2]);
+                split3(r[4 * blk + 3][c], k3[0], k3[1], k3[2]);
+#pragma unroll
+                for (int p = 0; p < 3; ++p)
+                    *reinterpret_cast<uint2 *>(s + (((p * 8 + kb + 4 * blk) * bt) + 4 * tq + c) * 8) =
+                        make_uint2(upper_halves(k1[p], k0[p]), upper_halves(k3[p], k2[p]));
+            }
+    }
+};
+
+// TRANS: C = A^T B with both operands stored across the reduction index (the weight gradient); otherwise A is
+// stored along it and the second operand comes cut into units (Wt: ku_total units along k per piece, n_pad rows).
+template <bool TRANS, int BM, int BN>
+__global__ __launch_bounds__(256, 2) void gemm_split_kernel(GemmArgs g, const uint16_t *Wt, int64_t ku_total, int64_t n_pad) {
+    constexpr int WM = BM / 2, WN = BN / 2;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int A_BYTES = TRANS ? SplitColLoader::bytes(BM) : Units16<BM>::BYTES;
+    constexpr int B_BYTES = TRANS ? SplitColLoader::bytes(BN) : Units16<BN>::BYTES;
+    __shared__ __attribute__((aligned(16))) char smem[A_BYTES + B_BYTES];
+    char *As = smem, *Bs = smem + A_BYTES;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, half = lane >> 5;
+    int bx, by, bz;
+    if (!tile_coords(g, &bx, &by, &bz)) return;      // uniform over the workgroup
+    const int64_t m0 = static_cast<int64_t>(by) * BM;
+    const int64_t n0 = static_cast<int64_t>(bx) * BN;
+    const int64_t k_begin = static_cast<int64_t>(bz) * g.k_chunk;
+    const int64_t k_end = (k_begin + g.k_chunk < g.K) ? k_begin + g.k_chunk : g.K;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    SplitRowLoader<BM> la_r;
+    SplitPlaneLoader<BN> lb_p;
+    SplitColLoader lc;
+    const int64_t nk = (k_end > k_begin) ? (k_end - k_begin + SBK - 1) / SBK : 0;
+    const int64_t nk_full = (k_end > k_begin) ? (k_end - k_begin) / SBK : 0;
+    // uniform over the workgroup: every row / column of the tile exists and vector loads are allowed
+    const bool interior = TRANS ? (m0 + BM <= g.M && n0 + BN <= g.N && g.a_vec && g.b_vec) : (m0 + BM <= g.M && g.a_vec);
+    const int both_vec = g.a_vec && g.b_vec;
+    if constexpr (TRANS) lc.init(g, m0, n0, BM, BN, As, Bs, tid);
+    if (nk > 0) {
+        if constexpr (TRANS) {
+            lc.fetch(k_begin, k_end, both_vec);
+            lc.stash();
+            if (interior) lc.fast_begin(k_begin + SBK);
+        } else {
+            la_r.fetch(g.A, g.lda, m0, g.M, k_begin, k_end, g.a_vec, tid);
+            lb_p.begin(Wt, ku_total, n_pad, n0, k_begin, tid);
+            lb_p.fetch(n_pad);
+            la_r.stash(As, tid);
+            lb_p.stash(Bs, tid);
+            if (interior) la_r.fast_begin(g.A, g.lda, m0, k_begin + SBK, tid);
+        }
+    }
+    __syncthreads();
+    for (int64_t kt = 0; kt < nk; ++kt) {
+        const bool more = kt + 1 < nk;
+        if (more) {
+            const bool fast = interior && kt + 1 < nk_full;
+            if constexpr (TRANS) {
+                if (fast) lc.fetch_fast();
+                else lc.fetch(k_begin + (kt + 1) * SBK, k_end, both_vec);
+            } else {
+                if (fast) la_r.fetch_fast();
+                else la_r.fetch(g.A, g.lda, m0, g.M, k_begin + (kt + 1) * SBK, k_end, g.a_vec, tid);
+                lb_p.fetch(n_pad);
+            }
+        }
+#pragma unroll
+        for (int ks = 0; ks < SBK / 16; ++ks) {
+            bf16x8 a[3][TM], b[3][TN];
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const int row = wm * WM + i * 32 + l32;
+                    uint4 v;
+                    if constexpr (TRANS) {
+                        const uint2 v0 = *reinterpret_cast<const uint2 *>(As + ((p * 8 + 4 * ks + 2 * half) * BM + row) * 8);
+                        const uint2 v1 = *reinterpret_cast<const uint2 *>(As + ((p * 8 + 4 * ks + 2 * half + 1) * BM + row) * 8);
+                        v = make_uint4(v0.x, v0.y, v1.x, v1.y);
+                    } else {
+                        v = *reinterpret_cast<const uint4 *>(As + Units16<BM>::at(p, 2 * ks + half, row));
+                    }
+                    a[p][i] = __builtin_bit_cast(bf16x8, v);
+                }
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int row = wn * WN + j * 32 + l32;
+                    uint4 v;
+                    if constexpr (TRANS) {
+                        const uint2 v0 = *reinterpret_cast<const uint2 *>(Bs + ((p * 8 + 4 * ks + 2 * half) * BN + row) * 8);
+                        const uint2 v1 = *reinterpret_cast<const uint2 *>(Bs + ((p * 8 + 4 * ks + 2 * half + 1) * BN + row) * 8);
+                        v = make_uint4(v0.x, v0.y, v1.x, v1.y);
+                    } else {
+                        v = *reinterpret_cast<const uint4 *>(Bs + Units16<BN>::at(p, 2 * ks + half, row));
+                    }
+                    b[p][j] = __builtin_bit_cast(bf16x8, v);
+                }
+            }
+            // the six piece products, smallest first
+#define CG_PIECES(PA_, PB_)                                                                                                  \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j)                            \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[PA_][i], b[PB_][j], acc[i][j], 0, 0, 0);
+            CG_PIECES(2, 0) CG_PIECES(0, 2) CG_PIECES(1, 1) CG_PIECES(1, 0) CG_PIECES(0, 1) CG_PIECES(0, 0)
+#undef CG_PIECES
+        }
+        if (more) {
+            __syncthreads();            // every wave has read this step's operands
+            if constexpr (TRANS) {
+                lc.stash();
+            } else {
+                la_r.stash(As, tid);
+                lb_p.stash(Bs, tid);
+            }
+            __syncthreads();
+        }
+    }
+    if constexpr (TM == 2 && TN == 2) {
+        static_assert(4 * STAGE_BYTES <= A_BYTES + B_BYTES, "the staged output must fit the operand buffers");
+        __syncthreads();                    // every wave is done with the operands
+        store_tile_staged(g, acc, reinterpret_cast<float *>(smem + wave * STAGE_BYTES), m0 + wm * WM, n0 + wn * WN, lane, bz);
+    } else {
+        store_tile<TM, TN>(g, acc, m0 + wm * WM, n0 + wn * WN, l32, half, bz);
+    }
+}
+
+// Cuts the (small) second operand of a plain product into bf16 pieces laid out in 16-byte units
+// Wt[piece][k / 8][n][k % 8], n_pad rows, ku_total units along k, zero beyond N and K.  kc: the source is [n][k]
+// (pitch ldw), else [k][n].
+__global__ __launch_bounds__(256) void split_repack_kernel(const float *W, int64_t ldw, int kc, int64_t K, int64_t N,
+                                                           uint16_t *Wt, int64_t n_pad, int64_t ku_total) {
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t plane = ku_total * n_pad * 8;
+    if (t >= plane) return;
+    const int64_t ku = t / (n_pad * 8), n = (t / 8) % n_pad, k = 8 * ku + (t % 8);
+    const float x = (n < N && k < K) ? (kc ? W[n * ldw + k] : W[k * ldw + n]) : 0.f;
+    uint32_t p0, p1, p2;
+    split3(x, p0, p1, p2);
+    Wt[t] = static_cast<uint16_t>(p0 >> 16);
+    Wt[plane + t] = static_cast<uint16_t>(p1 >> 16);
+    Wt[2 * plane + t] = static_cast<uint16_t>(p2 >> 16);
+}
+
 // Lays the (small) second operand of a product out as Wt[n][k], k contiguous, rows padded to 16 bytes, for the
 // bf16 kernel.  kc: the source already is [n][k] (pitch ldw), else it is [k][n].
 __global__ __launch_bounds__(256) void repack_bf16_kernel(const uint16_t *W, int64_t ldw, int kc, int64_t K, int64_t N,
@@ -598,14 +1029,35 @@ static size_t transposed_b_bytes(int64_t N, int64_t K) {
     return align_up(static_cast<size_t>(N) * ((K + 7) / 8 * 8) * sizeof(uint16_t), 256);
 }
 
+// the three bf16 planes of an fp32 weight matrix: rows padded to whole tiles, k to whole steps
+static int64_t split_rows(int64_t N) { return (N + 127) / 128 * 128; }
+static int64_t split_ld(int64_t K) { return (K + SBK - 1) / SBK * SBK; }
+static size_t split_b_bytes(int64_t N, int64_t K) {
+    return align_up(static_cast<size_t>(3) * split_rows(N) * split_ld(K) * sizeof(uint16_t), 256);
+}
+
 size_t gemm_ws_bytes(int trans_a, int64_t M, int64_t N, int64_t K) {
     int bm, bn;
     tile_for(N, &bm, &bn);
     // the larger split of the two kernels (they step through K in 16s and 32s)
     const int s = std::max(choose_split(trans_a, M, N, K, bm, bn, BK), choose_split(trans_a, M, N, K, bm, bn, HBK));
     size_t b = s > 1 ? align_up(static_cast<size_t>(s) * M * N * sizeof(float), 256) : 0;
-    if (!trans_a) b = std::max(b, transposed_b_bytes(N, K));    // room to lay a bf16 weight out for the bf16 kernel
+    // room to lay a weight matrix out for the bf16 kernel (bf16 operands) or as its three planes (fp32 operands)
+    if (!trans_a) b = std::max(b, std::max(transposed_b_bytes(N, K), split_b_bytes(N, K)));
     return b;
+}
+
+// how products of fp32 operands are formed (capgnn_set_f32_product)
+static std::atomic<int> f32_product_mode{CAPGNN_F32_PRODUCT_AUTO};
+// AUTO: smaller products stay on the fp32 instruction, and so do weight gradients at most 64 columns wide (half of
+// the threads that stage their operands would idle; measured slower)
+constexpr int64_t SPLIT_MIN_MACS = int64_t(1) << 28;
+
+template <bool TRANS>
+static void launch_split_tiles(const GemmArgs &g, int bn, dim3 grid, const uint16_t *Wt, int64_t ku_total, int64_t n_pad,
+                               hipStream_t st) {
+    if (bn == 64) hipLaunchKernelGGL((gemm_split_kernel<TRANS, 128, 64>), grid, dim3(256), 0, st, g, Wt, ku_total, n_pad);
+    else hipLaunchKernelGGL((gemm_split_kernel<TRANS, 128, 128>), grid, dim3(256), 0, st, g, Wt, ku_total, n_pad);
 }
 
 template <bool BF16, bool A_KC, bool B_KC>
@@ -639,7 +1091,14 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
     const bool repack_b = dtype == CAPGNN_BF16 && !trans_a && ws && ws_bytes >= transposed_b_bytes(N, K);
     const bool half_path = dtype == CAPGNN_BF16 && aligned16(A) && (lda * 2) % 16 == 0 &&
                            (repack_b || (aligned16(B) && (ldb * 2) % 16 == 0));
-    const int bk = half_path ? HBK : BK;
+    // fp32 operands as three bf16 pieces each (see gemm_split_kernel)
+    const int mode = f32_product_mode.load(std::memory_order_relaxed);
+    const bool split_path = dtype == CAPGNN_F32 && mode != CAPGNN_F32_PRODUCT_NATIVE && !(trans_a && trans_b) &&
+                            (mode == CAPGNN_F32_PRODUCT_SPLIT ||
+                             (M * N >= SPLIT_MIN_MACS / (K > 0 ? K : 1) && !(trans_a && N <= 64))) &&
+                            (trans_a || (ws && ws_bytes >= split_b_bytes(N, K)));
+    const int bk = (half_path || split_path) ? HBK : BK;
+    static_assert(SBK == HBK, "the two bf16 kernels step through K alike");
     const int S = choose_split(trans_a, M, N, K, bm, bn, bk);
     GemmArgs g;
     g.M = M; g.N = N; g.K = K;
@@ -669,7 +1128,17 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
     g.c_staged = half_path && g.out_bf16 && !g.part && !g.mask && !g.accumulate && aligned16(C) && (ldc * 2) % 16 == 0;
     dim3 grid(static_cast<unsigned>(n_wg), 1, 1);
     bool akc = !trans_a, bkc = trans_b != 0;
-    if (half_path) {
+    if (split_path) {
+        if (trans_a) {
+            launch_split_tiles<true>(g, bn, grid, nullptr, 0, 0, stream);
+        } else {
+            const int64_t n_pad = split_rows(N), ku_total = split_ld(K) / 8;
+            hipLaunchKernelGGL(split_repack_kernel, dim3(static_cast<unsigned>((ku_total * n_pad * 8 + 255) / 256)), dim3(256), 0,
+                               stream, static_cast<const float *>(B), ldb, bkc ? 1 : 0, K, N, static_cast<uint16_t *>(ws), n_pad,
+                               ku_total);
+            launch_split_tiles<false>(g, bn, grid, static_cast<const uint16_t *>(ws), ku_total, n_pad, stream);
+        }
+    } else if (half_path) {
         if (repack_b) {
             const int64_t ldt = (K + 7) / 8 * 8;
             hipLaunchKernelGGL(repack_bf16_kernel, dim3(static_cast<unsigned>((N * ldt + 255) / 256)), dim3(256), 0, stream,
@@ -743,6 +1212,15 @@ extern "C" int capgnn_mfma_peak(int dtype, int workgroups, int iters, float *out
     *flop = per_instr * 4.0 * iters * 4.0 * workgroups;     // 4 tiles per wave, 4 waves per workgroup
     return CAPGNN_OK;
 }
+
+extern "C" int capgnn_set_f32_product(int mode) {
+    if (mode != CAPGNN_F32_PRODUCT_NATIVE && mode != CAPGNN_F32_PRODUCT_SPLIT && mode != CAPGNN_F32_PRODUCT_AUTO)
+        CG_FAIL(CAPGNN_EINVAL, "set_f32_product: unknown mode %d", mode);
+    f32_product_mode.store(mode, std::memory_order_relaxed);
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_get_f32_product(void) { return f32_product_mode.load(std::memory_order_relaxed); }
 
 extern "C" size_t capgnn_gemm_workspace_bytes(int trans_a, int64_t M, int64_t N, int64_t K) {
     return gemm_ws_bytes(trans_a, M, N, K);
