@@ -12,6 +12,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <type_traits>
 
 namespace capgnn {
 
@@ -638,19 +639,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 // (two 8-byte reads) run over consecutive LDS addresses.
 constexpr int SBK = 32;
 
-// x = p0 + p1 + p2 exactly, each piece the upper half of the returned word.  The first two pieces are rounded to
-// nearest (ties upwards), which bounds the second piece by 2^-8 |x| and the third by 2^-16 |x|; the remainders are
-// exact fp32 differences with at most 16 and 7 significant bits.
-__device__ __forceinline__ void split3(float x, uint32_t &p0, uint32_t &p1, uint32_t &p2) {
-    p0 = __float_as_uint(x) + 0x8000u;
-    const float r1 = x - __uint_as_float(p0 & 0xffff0000u);
-    p1 = __float_as_uint(r1) + 0x8000u;
-    const float r2 = r1 - __uint_as_float(p1 & 0xffff0000u);
-    p2 = __float_as_uint(r2);
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// two fp32 numbers rounded to bf16 (nearest even), the first in the low half: one v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t bf16_pair(float x0, float x1) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2{x0, x1}), bf16x2));
 }
 
-// upper halves of two words, `lo`'s in the low half
-__device__ __forceinline__ uint32_t upper_halves(uint32_t hi, uint32_t lo) { return __builtin_amdgcn_perm(hi, lo, 0x07060302u); }
+// x = piece 0 + piece 1 + piece 2 exactly, for two numbers at once; p[i] holds piece i of x0 in its low half and of
+// x1 in its high half.  Rounding to nearest bounds the second piece by 2^-8 |x| and the third by 2^-16 |x|; the
+// remainders are exact fp32 differences with at most 16 and 8 significant bits.
+__device__ __forceinline__ void split3_pair(float x0, float x1, uint32_t (&p)[3]) {
+    p[0] = bf16_pair(x0, x1);
+    const float r0 = x0 - __uint_as_float(p[0] << 16), r1 = x1 - __uint_as_float(p[0] & 0xffff0000u);
+    p[1] = bf16_pair(r0, r1);
+    const float s0 = r0 - __uint_as_float(p[1] << 16), s1 = r1 - __uint_as_float(p[1] & 0xffff0000u);
+    p[2] = bf16_pair(s0, s1);
+}
 
 // 16-byte units of an operand kept along the reduction index: unit (piece, u = k / 8, row)
 template <int BT>
@@ -695,20 +701,27 @@ struct SplitRowLoader {
         }
     }
 
-    __device__ __forceinline__ void stash(char *s, int tid) const {
+    uint2 pk[NLD][3];               // the pieces of r, ready for LDS
+
+    __device__ __forceinline__ void cut() {
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            uint32_t lo[3], hi[3];
+            split3_pair(r[q].x, r[q].y, lo);
+            split3_pair(r[q].z, r[q].w, hi);
+#pragma unroll
+            for (int p = 0; p < 3; ++p) pk[q][p] = make_uint2(lo[p], hi[p]);
+        }
+    }
+
+    __device__ __forceinline__ void put(char *s, int tid) const {
 #pragma unroll
         for (int q = 0; q < NLD; ++q) {
             const int idx = tid + 256 * q;
             const int row = idx >> 3, kq = idx & 7;
-            uint32_t x[3], y[3], z[3], w[3];
-            split3(r[q].x, x[0], x[1], x[2]);
-            split3(r[q].y, y[0], y[1], y[2]);
-            split3(r[q].z, z[0], z[1], z[2]);
-            split3(r[q].w, w[0], w[1], w[2]);
 #pragma unroll
             for (int p = 0; p < 3; ++p)
-                *reinterpret_cast<uint2 *>(s + Units16<BT>::at(p, kq >> 1, row) + 8 * (kq & 1)) =
-                    make_uint2(upper_halves(y[p], x[p]), upper_halves(w[p], z[p]));
+                *reinterpret_cast<uint2 *>(s + Units16<BT>::at(p, kq >> 1, row) + 8 * (kq & 1)) = pk[q][p];
         }
     }
 };
@@ -805,21 +818,31 @@ struct SplitColLoader {
         pf += SBK * ld4;
     }
 
-    __device__ __forceinline__ void stash() const {
+    uint2 pk[2][4][3];              // the pieces of r, ready for LDS: [k-block][column][piece], four k each
+
+    __device__ __forceinline__ void cut() {
         if (idle) return;
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {           // one column: four consecutive k, one 8-byte unit per piece
-                uint32_t k0[3], k1[3], k2[3], k3[3];
-                split3(r[4 * blk + 0][c], k0[0], k0[1], k0[2]);
-                split3(r[4 * blk + 1][c], k1[0], k1[1], k1[2]);
-                split3(r[4 * blk + 2][c], k2[0], k2[1], k2[2]);
-                split3(r[4 * blk + 3][c], k3[0], k3[1], k3[2]);
+            for (int c = 0; c < 4; ++c) {
+                uint32_t lo[3], hi[3];
+                split3_pair(r[4 * blk + 0][c], r[4 * blk + 1][c], lo);
+                split3_pair(r[4 * blk + 2][c], r[4 * blk + 3][c], hi);
 #pragma unroll
-                for (int p = 0; p < 3; ++p)
-                    *reinterpret_cast<uint2 *>(s + (((p * 8 + kb + 4 * blk) * bt) + 4 * tq + c) * 8) =
-                        make_uint2(upper_halves(k1[p], k0[p]), upper_halves(k3[p], k2[p]));
+                for (int p = 0; p < 3; ++p) pk[blk][c][p] = make_uint2(lo[p], hi[p]);
+            }
+    }
+
+    __device__ __forceinline__ void put() const {
+        if (idle) return;
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                char *dst = s + (((p * 8 + kb + 4 * blk) * bt) + 4 * tq) * 8;      // the thread's four columns: 32 bytes
+                *reinterpret_cast<uint4 *>(dst) = make_uint4(pk[blk][0][p].x, pk[blk][0][p].y, pk[blk][1][p].x, pk[blk][1][p].y);
+                *reinterpret_cast<uint4 *>(dst + 16) = make_uint4(pk[blk][2][p].x, pk[blk][2][p].y, pk[blk][3][p].x, pk[blk][3][p].y);
             }
     }
 };
@@ -866,33 +889,29 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(GemmArgs g, const ui
     if (nk > 0) {
         if constexpr (TRANS) {
             lc.fetch(k_begin, k_end, both_vec);
-            lc.stash();
+            lc.cut();
+            lc.put();
             if (interior) lc.fast_begin(k_begin + SBK);
         } else {
             la_r.fetch(g.A, g.lda, m0, g.M, k_begin, k_end, g.a_vec, tid);
             lb_p.begin(Wt, ku_total, n_pad, n0, k_begin, tid);
             lb_p.fetch(n_pad);
-            la_r.stash(As, tid);
+            la_r.cut();
+            la_r.put(As, tid);
             lb_p.stash(Bs, tid);
             if (interior) la_r.fast_begin(g.A, g.lda, m0, k_begin + SBK, tid);
         }
     }
     __syncthreads();
-    for (int64_t kt = 0; kt < nk; ++kt) {
-        const bool more = kt + 1 < nk;
-        if (more) {
-            const bool fast = interior && kt + 1 < nk_full;
-            if constexpr (TRANS) {
-                if (fast) lc.fetch_fast();
-                else lc.fetch(k_begin + (kt + 1) * SBK, k_end, both_vec);
-            } else {
-                if (fast) la_r.fetch_fast();
-                else la_r.fetch(g.A, g.lda, m0, g.M, k_begin + (kt + 1) * SBK, k_end, g.a_vec, tid);
-                lb_p.fetch(n_pad);
-            }
-        }
+    // the products of one step (32 k) out of LDS; CUT: the operands of the next step, which wait in registers, are
+    // cut into their pieces between the matrix instructions of the second half (about five vector instructions fit
+    // behind each matrix instruction's issue)
+    auto products = [&](auto cut_tag) {
+        constexpr bool CUT = decltype(cut_tag)::value;
 #pragma unroll
         for (int ks = 0; ks < SBK / 16; ++ks) {
+            // nothing of the second half moves into the first: the loads of the next operands get that long to arrive
+            if (CUT && ks == SBK / 16 - 1) __builtin_amdgcn_sched_barrier(0);
             bf16x8 a[3][TM], b[3][TN];
 #pragma unroll
             for (int p = 0; p < 3; ++p) {
@@ -923,24 +942,47 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(GemmArgs g, const ui
                     b[p][j] = __builtin_bit_cast(bf16x8, v);
                 }
             }
+            if (CUT && ks == SBK / 16 - 1) la_r.cut();
             // the six piece products, smallest first
 #define CG_PIECES(PA_, PB_)                                                                                                  \
     _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j)                            \
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[PA_][i], b[PB_][j], acc[i][j], 0, 0, 0);
             CG_PIECES(2, 0) CG_PIECES(0, 2) CG_PIECES(1, 1) CG_PIECES(1, 0) CG_PIECES(0, 1) CG_PIECES(0, 0)
 #undef CG_PIECES
-        }
-        if (more) {
-            __syncthreads();            // every wave has read this step's operands
-            if constexpr (TRANS) {
-                lc.stash();
-            } else {
-                la_r.stash(As, tid);
-                lb_p.stash(Bs, tid);
+            if (CUT && ks == SBK / 16 - 1) {
+#pragma unroll
+                for (int t = 0; t < 6 * TM * TN; ++t) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one matrix instruction
+                    __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);      // vector instructions behind it
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __syncthreads();
         }
+    };
+    for (int64_t kt = 0; kt + 1 < nk; ++kt) {
+        const bool fast = interior && kt + 1 < nk_full;
+        if constexpr (TRANS) {
+            if (fast) lc.fetch_fast();
+            else lc.fetch(k_begin + (kt + 1) * SBK, k_end, both_vec);
+        } else {
+            if (fast) la_r.fetch_fast();
+            else la_r.fetch(g.A, g.lda, m0, g.M, k_begin + (kt + 1) * SBK, k_end, g.a_vec, tid);
+            lb_p.fetch(n_pad);
+        }
+        // (measured: cutting between the matrix instructions pays for the plain product, 4 %; the weight gradient, with
+        // twice the cutting per thread, lost 9 % that way and cuts after its products)
+        products(std::integral_constant<bool, !TRANS>{});
+        __syncthreads();            // every wave has read this step's operands
+        if constexpr (TRANS) {
+            lc.cut();
+            lc.put();
+        } else {
+            la_r.put(As, tid);
+            lb_p.stash(Bs, tid);
+        }
+        __syncthreads();
     }
+    if (nk > 0) products(std::false_type{});
     if constexpr (TM == 2 && TN == 2) {
         static_assert(4 * STAGE_BYTES <= A_BYTES + B_BYTES, "the staged output must fit the operand buffers");
         __syncthreads();                    // every wave is done with the operands
@@ -960,11 +1002,11 @@ __global__ __launch_bounds__(256) void split_repack_kernel(const float *W, int64
     if (t >= plane) return;
     const int64_t ku = t / (n_pad * 8), n = (t / 8) % n_pad, k = 8 * ku + (t % 8);
     const float x = (n < N && k < K) ? (kc ? W[n * ldw + k] : W[k * ldw + n]) : 0.f;
-    uint32_t p0, p1, p2;
-    split3(x, p0, p1, p2);
-    Wt[t] = static_cast<uint16_t>(p0 >> 16);
-    Wt[plane + t] = static_cast<uint16_t>(p1 >> 16);
-    Wt[2 * plane + t] = static_cast<uint16_t>(p2 >> 16);
+    uint32_t p[3];
+    split3_pair(x, 0.f, p);
+    Wt[t] = static_cast<uint16_t>(p[0]);
+    Wt[plane + t] = static_cast<uint16_t>(p[1]);
+    Wt[2 * plane + t] = static_cast<uint16_t>(p[2]);
 }
 
 // Lays the (small) second operand of a product out as Wt[n][k], k contiguous, rows padded to 16 bytes, for the
