@@ -49,18 +49,27 @@ def spmm_min_bytes(part, F, n_out, n_in_touched, es):
     return part.nnz * 4 + (n_out + 1) * 8 + n_in_touched * F * es + n_out * F * es
 
 
-def gemm_report(cfg, part, orders, kernels):
-    """FLOP rate of the first layer's forward transform against the matrix-core peak of its operand type."""
+def gemm_report(cfg, part, orders, kernels, f32_product):
+    """FLOP rate of the first layer's forward transform, and the work it gives the matrix cores against their peak:
+    the fp32 instruction does the product's own FLOPs (peak 157.3 TFLOP/s); the split form does six bf16 piece
+    products per fp32 product (peak 2500 TFLOP/s); bf16 operands run on the bf16 cores as they are."""
     rec = [k for k in kernels if k["kind"] == "gemm" and k["layer"] == 0 and not k["backward"]]
     if not rec:
         return None
     rows = part.n_loc if orders[0] == 1 else part.n_cols
     mult = 2 if cfg.kind == "sage" else 1                    # GraphSAGE adds the self transform over the local rows
     flops = 2.0 * rows * cfg.dims[0] * cfg.dims[1] + (mult - 1) * 2.0 * part.n_loc * cfg.dims[0] * cfg.dims[1]
-    peak = FP32_MATRIX_PEAK_TFLOPS if cfg.dtype == "f32" else BF16_MATRIX_PEAK_TFLOPS
     tf = flops / (rec[0]["ms"] * 1e-3) / 1e12
+    split = cfg.dtype == "f32" and (f32_product == "split" or
+                                    (f32_product == "auto" and rows * cfg.dims[0] * cfg.dims[1] >= 1 << 28))
+    if cfg.dtype != "f32":
+        form, peak, work = "bf16 matrix instruction", BF16_MATRIX_PEAK_TFLOPS, tf
+    elif split:
+        form, peak, work = "three bf16 pieces per operand, six piece products", BF16_MATRIX_PEAK_TFLOPS, 6.0 * tf
+    else:
+        form, peak, work = "fp32 matrix instruction", FP32_MATRIX_PEAK_TFLOPS, tf
     return {"kernel": "transform of layer 0 (forward)", "gflop": flops / 1e9, "ms": rec[0]["ms"], "tflops": tf,
-            "peak_tflops": peak, "frac_of_matrix_peak": tf / peak,
+            "product_form": form, "matrix_core_tflops": work, "peak_tflops": peak, "frac_of_matrix_peak": work / peak,
             "note": "matrix-core busy cycles of the same kernels: profiles/gemm_C2_C4_mfma_counters.txt"}
 
 
@@ -234,6 +243,63 @@ def bench_mfma_peak(args):
                       "measured": res}))
 
 
+def bench_products(args):
+    """The dense products of a configuration's layers, alone, operands resident, in both forms of the fp32 product
+    (fp32 matrix instruction / three bf16 pieces): time, rate, and distance from an fp64 product of the same operands."""
+    import torch
+    from paper_2508_13716_amd import binding as B, synth
+    cfg = synth.CONFIGS[args.config]
+    if cfg.dtype != "f32":
+        print("bench.py --what products: the two product forms exist for fp32 configurations (C1, C2, C3)", file=sys.stderr)
+        sys.exit(2)
+    n_cols, n_loc = cfg.n_loc + cfg.n_halo, cfg.n_loc
+
+    def pad(n):                                             # rows of whole, odd numbers of 128-byte lines
+        b = (n * 4 + 127) // 128 * 128
+        return (b + 128 if b % 256 == 0 else b) // 4
+
+    def run(ta, tb, M, N, K, mode):
+        sa, sb = ((K, M) if ta else (M, K)), ((N, K) if tb else (K, N))
+        lda, ldb, ldc = pad(sa[1]), (pad(sb[1]) if ta else sb[1]), pad(N)
+        g = torch.Generator(device="cuda").manual_seed(M + 3 * N + 7 * K)
+        A = torch.randn((sa[0], lda), device="cuda", generator=g)
+        Bm = torch.randn((sb[0], ldb), device="cuda", generator=g)
+        Cd = torch.empty((M, ldc), device="cuda")
+        wsb = B.gemm_workspace_bytes(ta, M, N, K)
+        ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+        B.set_f32_product(mode)
+        st = torch.cuda.Stream()
+        call = lambda: B.gemm(ta, tb, M, N, K, A, lda, Bm, ldb, Cd, ldc, B.F32, out_f32=1, ws=ws, ws_bytes=wsb, stream=st)
+        for _ in range(args.warmup):
+            call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(args.steps):
+            call()
+        e1.record(st)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        Ad, Bd = A[:, :sa[1]].double(), Bm[:, :sb[1]].double()
+        ref = (Ad.T if ta else Ad) @ (Bd.T if tb else Bd)
+        err = float((Cd[:, :N].double() - ref).abs().max() / ref.abs().max())
+        return {"ms": ms, "tflops": 2e-9 * M * N * K / ms, "err": err}
+
+    out = []
+    for l in range(len(cfg.dims) - 1):
+        fi, fo = cfg.dims[l], cfg.dims[l + 1]
+        for name, ta, tb, M, N, K in ((f"layer {l}: X W", 0, 0, n_cols, fo, fi), (f"layer {l}: X^T dT", 1, 0, fi, fo, n_cols),
+                                      (f"layer {l}: dT W^T", 0, 1, n_loc, fi, fo)):
+            out.append({"product": name, "M": M, "N": N, "K": K, "trans_a": ta, "trans_b": tb,
+                        "fp32_instruction": run(ta, tb, M, N, K, B.F32_PRODUCT_NATIVE),
+                        "three_bf16_pieces": run(ta, tb, M, N, K, B.F32_PRODUCT_SPLIT)})
+    B.set_f32_product(B.F32_PRODUCT_AUTO)
+    print(json.dumps({"metric": "dense products alone, both forms of the fp32 product", "unit": "ms / TFLOP/s / max error over max |result|",
+                      "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
+                      "config": {"workload": f"{args.config}: {n_loc} local + {cfg.n_halo} halo rows, dims {list(cfg.dims)}"},
+                      "products": out}))
+
+
 def bench_reorder(args):
     """Aggregation time of one SpMM launch (forward and transposed, hidden width 256) before and after the
     vertices are stored in a locality order, on the named config's graph (--config; 'clustered' = a graph with
@@ -301,7 +367,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C2")
-    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder", "zipf_requests", "mfma_peak"],
+    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder", "zipf_requests", "mfma_peak", "products"],
                     help="epoch (default): the headline benchmark; cache_update: throughput of the cache write path; "
                          "policy: hit-rate curves of the cache policies; reorder: SpMM before / after vertex reordering "
                          "(--config C2..C5 or clustered); zipf_requests: request-list gather under Zipf(1.1) requests")
@@ -336,6 +402,8 @@ def main():
         return bench_zipf_requests(args)
     if args.what == "mfma_peak":
         return bench_mfma_peak(args)
+    if args.what == "products":
+        return bench_products(args)
     if args.what == "policy":
         return bench_policy(args)
 
@@ -427,7 +495,7 @@ def main():
                    "staged_scatter_GBps": 2 * miss_bytes / (staged_ms * 1e-3) / 1e9 if staged_ms else None,
                    "miss_host_link_GBps": miss_bytes / (miss_ms * 1e-3) / 1e9 if miss_ms else None,
                    "miss_bytes": miss_bytes},
-        "gemm": gemm_report(cfg, part, res_orders, kernels),
+        "gemm": gemm_report(cfg, part, res_orders, kernels, args.f32_product),
         "kernels": kernels[:12],
         "roofline": {"kernel": f"{dom['kind']} layer {dom['layer']} F={F}", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
