@@ -358,7 +358,9 @@ int capgnn_layer_fwd(const capgnn_graph *g, const capgnn_layer *l, const void *X
                      void *H, int64_t ldh, void *saved, void *ws, size_t ws_bytes, void *stream);
 
 /* Backward of the same layer.  H is the forward output (its sign pattern is sigma').  dH: device
- * [n_loc x lddh], gradient w.r.t. H; it is overwritten with dZ = dH * 1[H > 0] for ReLU layers.
+ * [n_loc x lddh], gradient w.r.t. H; it is overwritten with dZ = dH * 1[H > 0] for ReLU layers, and its
+ * contents afterwards are unspecified (a GCN layer of an operator without edge values leaves dZ with each row
+ * multiplied by the row's normalisation scale, the form its transposed aggregation reads).
  * dW, dW_self: device float [f_in x f_out] (dense); dbias: device float[f_out]; any may be NULL.
  * dX: device [n_rows_dx x lddx] or NULL; n_rows_dx = n_cols when need_halo_grad, else n_loc
  * (gradient w.r.t. the halo rows is computed only on request; it is never sent anywhere). */

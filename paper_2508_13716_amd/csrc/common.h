@@ -59,6 +59,9 @@ struct SpOp {
     // device [nnz]: weight of each entry, edge value * in_scale[source] formed once (a sequential read in the
     // kernels instead of a gather from in_scale per entry); null when every weight is 1
     const float *wt = nullptr;
+    // no edge values: the weight of an entry is in_scale[source] alone, so a caller that multiplies row s of the
+    // operand by in_scale[s] first may ask for the unweighted sum (SpmmEpilogue::operand_scaled)
+    bool weights_by_source = false;
     const float *out_scale = nullptr; // device [n_out] or null
     const float *in_scale = nullptr;  // device [n_in]  or null
     // work lists: output rows by entry count, descending; rows shorter than EXACT_ROW only by power-of-two class,
@@ -76,6 +79,9 @@ struct SpOp {
     int ncb = 0;                      // 0: no blocked copy
     const uint32_t *b_off = nullptr;  // device [ncb*n_out + 1]
     const int2 *b_ew = nullptr;       // device [nnz]  {source row, bits of the float weight val * in_scale[source]}
+    // the same entries without their weights, 4 bytes each (operators without edge values): read instead of b_ew when
+    // every weight is 1, or when the caller has multiplied the operand rows by in_scale beforehand
+    const int32_t *b_src = nullptr;   // device [nnz] or null
     // positions [0, b_long) hold rows whose groups are long enough for a whole workgroup, [b_long, b_mid) for
     // one wave per group, the rest are walked eight rows per wave (`order` is descending in entry count)
     int64_t b_long = 0, b_mid = 0;
@@ -142,6 +148,7 @@ struct SpmmEpilogue {
     int relu = 0;
     int accumulate = 0;            // add the previous contents of Y
     int out_f32 = 0;               // store Y as float although X is bf16
+    int operand_scaled = 0;        // row s of X already carries in_scale[s] (only for operators with weights_by_source)
     void *ws = nullptr;            // scratch for the column-blocked kernel or for cut rows (spmm_ws_bytes), may be null
     size_t ws_bytes = 0;
 };
@@ -154,7 +161,7 @@ int launch_spmm(const SpOp &op, bool restrict_sub, const void *X, int64_t ldx, v
 int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
                 const void *B, int64_t ldb, void *C, int64_t ldc, int dtype, int out_f32, int accumulate,
                 const float *bias, int relu, const void *relu_mask, int64_t ldm, void *ws, size_t ws_bytes,
-                hipStream_t stream);
+                hipStream_t stream, const float *row_scale = nullptr);   // row_scale: C[i,:] *= row_scale[i] at the very end (fp32 C)
 size_t gemm_ws_bytes(int trans_a, int64_t M, int64_t N, int64_t K);
 
 // dZ = dH * 1[H > 0] in place (when relu) and dbias[f] = sum_i dZ[i,f] (when dbias), fixed summation order.
@@ -163,7 +170,7 @@ size_t gemm_ws_bytes(int trans_a, int64_t M, int64_t N, int64_t K);
 size_t relu_bias_ws_bytes(int64_t n, int F);
 int launch_relu_mask_dbias(int64_t n, int F, const void *src, int64_t lds, int src_dtype, void *dH, int64_t lddh,
                            const void *H, int64_t ldh, int dtype, int h_dtype, int relu, float *dbias, void *ws,
-                           size_t ws_bytes, hipStream_t stream);
+                           size_t ws_bytes, hipStream_t stream, const float *row_scale = nullptr);
 int launch_sgd(float *W, const float *dW, int64_t n, float lr, hipStream_t stream);
 
 uint64_t hash_gid(uint64_t x);

@@ -31,6 +31,7 @@ struct GemmArgs {
     const char *mask; int64_t ldm; int mask_bf16;
     int gx, gy, S;                  // tiles along N, along M, reduction splits
     int c_staged;                   // bf16 kernel: write C through LDS in 16-byte pieces (no mask / accumulate / split)
+    const float *rscale;            // C[i,:] *= rscale[i] after everything else (fp32 C), or null
 };
 
 // Tile of a workgroup in the one-dimensional grid.  Workgroup b runs on L2 domain b % NUM_XCD; the order is
@@ -124,6 +125,7 @@ __device__ __forceinline__ void store_tile(const GemmArgs &g, const floatx16 (&a
                                                  : reinterpret_cast<const float *>(g.mask)[row * g.ldm + col];
                     if (!(mv > 0.f)) v = 0.f;
                 }
+                if (g.rscale) v *= g.rscale[row];
                 if (g.out_bf16) reinterpret_cast<uint16_t *>(g.C)[row * g.ldc + col] = static_cast<uint16_t>(f32_to_bf16_rne(v));
                 else reinterpret_cast<float *>(g.C)[row * g.ldc + col] = v;
             }
@@ -188,6 +190,11 @@ __device__ __forceinline__ void store_tile_staged(const GemmArgs &g, const float
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
                             if (col + e < g.N && !(mk[e] > 0.f)) v[e] = 0.f;
+                    }
+                    if (g.rscale) {
+                        const float rs = g.rscale[row];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] *= rs;
                     }
                 }
                 if (whole) {
@@ -1047,6 +1054,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmArgs g, int S) {
                                      : reinterpret_cast<const float *>(g.mask)[row * g.ldm + col];
         if (!(mv > 0.f)) v = 0.f;
     }
+    if (g.rscale) v *= g.rscale[row];
     if (g.out_bf16) reinterpret_cast<uint16_t *>(g.C)[row * g.ldc + col] = static_cast<uint16_t>(f32_to_bf16_rne(v));
     else reinterpret_cast<float *>(g.C)[row * g.ldc + col] = v;
 }
@@ -1117,7 +1125,7 @@ static void launch_bf16_tiles(const GemmArgs &g, int bn, dim3 grid, hipStream_t 
 int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
                 const void *B, int64_t ldb, void *C, int64_t ldc, int dtype, int out_f32, int accumulate,
                 const float *bias, int relu, const void *relu_mask, int64_t ldm, void *ws, size_t ws_bytes,
-                hipStream_t stream) {
+                hipStream_t stream, const float *row_scale) {
     if (dtype != CAPGNN_F32 && dtype != CAPGNN_BF16) CG_FAIL(CAPGNN_EINVAL, "gemm: unknown dtype %d", dtype);
     if (M < 0 || N < 0 || K < 0) CG_FAIL(CAPGNN_EINVAL, "gemm: negative size");
     if (M == 0 || N == 0) return CAPGNN_OK;
@@ -1155,6 +1163,7 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
     g.out_bf16 = (dtype == CAPGNN_BF16 && !out_f32);
     g.accumulate = accumulate; g.relu = relu; g.bias = bias;
     g.mask = static_cast<const char *>(relu_mask); g.ldm = ldm; g.mask_bf16 = (dtype == CAPGNN_BF16);
+    g.rscale = row_scale;
     if (S > 1) {
         const size_t need = static_cast<size_t>(S) * M * N * sizeof(float);
         if (!ws || ws_bytes < need) CG_FAIL(CAPGNN_ENOMEM, "gemm: workspace of %zu bytes needed, %zu given", need, ws_bytes);
@@ -1167,7 +1176,7 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
     if (n_wg >= (int64_t(1) << 31) || gx >= (int64_t(1) << 24) || gy >= (int64_t(1) << 30))
         CG_FAIL(CAPGNN_EINVAL, "gemm: %lld x %lld tiles exceed the grid", (long long)gy, (long long)gx);
     g.gx = static_cast<int>(gx); g.gy = static_cast<int>(gy); g.S = S;
-    g.c_staged = half_path && g.out_bf16 && !g.part && !g.mask && !g.accumulate && aligned16(C) && (ldc * 2) % 16 == 0;
+    g.c_staged = half_path && g.out_bf16 && !g.part && !g.mask && !g.accumulate && !g.rscale && aligned16(C) && (ldc * 2) % 16 == 0;
     dim3 grid(static_cast<unsigned>(n_wg), 1, 1);
     bool akc = !trans_a, bkc = trans_b != 0;
     if (split_path) {

@@ -97,6 +97,7 @@ struct BlockedHost {
     int64_t n_long = 0, n_mid = 0;
     std::vector<uint32_t> off;
     std::vector<int2> ew;
+    std::vector<int32_t> src;         // ew[].x alone, for operators without edge values
 };
 
 static int32_t float_bits(float f) {
@@ -141,12 +142,17 @@ static bool build_blocked(const int64_t *ptr, const int32_t *idx, const float *v
         std::sort(out->ew.begin() + out->off[t], out->ew.begin() + out->off[t + 1], [&](const int2 &x, const int2 &y) {
             return refs[x.x] != refs[y.x] ? refs[x.x] > refs[y.x] : x.x < y.x;
         });
+    if (!val) {
+        out->src.resize(nnz);
+        for (int64_t q = 0; q < nnz; ++q) out->src[q] = out->ew[q].x;
+    }
     return true;
 }
 
 static int upload_blocked(capgnn_graph *g, const BlockedHost &bh, SpOp *op) {
     CG_TRY(upload(g, bh.off.data(), bh.off.size(), &op->b_off));
     CG_TRY(upload(g, bh.ew.data(), bh.ew.size(), &op->b_ew));
+    if (!bh.src.empty()) CG_TRY(upload(g, bh.src.data(), bh.src.size(), &op->b_src));
     op->ncb = bh.ncb;
     op->b_long = bh.n_long;
     op->b_mid = bh.n_mid;
@@ -263,6 +269,7 @@ extern "C" int capgnn_graph_create(capgnn_graph **out, int64_t n_loc, int64_t n_
     if ((rc = upload(g, rowptr, n_loc + 1, &f.ptr))) return fail(rc);
     if ((rc = upload(g, col, nnz, &f.idx))) return fail(rc);
     if ((rc = upload_weights(g, nnz, col, edge_val, col_scale, &f.wt))) return fail(rc);
+    f.weights_by_source = !edge_val && col_scale;
     if (row_scale && (rc = upload(g, row_scale, n_loc, &f.out_scale))) return fail(rc);
     if (col_scale && (rc = upload(g, col_scale, n_cols, &f.in_scale))) return fail(rc);
     if ((rc = upload(g, order_f.data(), order_f.size(), &f.order))) return fail(rc);
@@ -276,11 +283,12 @@ extern "C" int capgnn_graph_create(capgnn_graph **out, int64_t n_loc, int64_t n_
 
     SpOp &b = g->bwd;
     b.n_out = n_cols; b.n_in = n_loc; b.nnz = nnz; b.out_scale = f.in_scale; b.in_scale = f.out_scale;
+    b.weights_by_source = !edge_val && row_scale;
     if (share) {
         b.ptr = f.ptr; b.idx = f.idx; b.order = f.order; b.n_long = f.n_long;
         b.order_sub = f.order; b.n_sub = n_loc; b.n_long_sub = f.n_long; b.max_deg = f.max_deg;
         b.giant = f.giant; b.giant_sub = f.giant;
-        b.ncb = f.ncb; b.b_off = f.b_off; b.b_ew = f.b_ew; b.b_long = f.b_long; b.b_mid = f.b_mid;
+        b.ncb = f.ncb; b.b_off = f.b_off; b.b_ew = f.b_ew; b.b_src = f.b_src; b.b_long = f.b_long; b.b_mid = f.b_mid;
         const bool same_scales = (!row_scale && !col_scale) ||
                                  (row_scale && col_scale && std::memcmp(row_scale, col_scale, n_loc * sizeof(float)) == 0);
         b.wt = f.wt;

@@ -157,7 +157,10 @@ static int layer_fwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
                            sage ? 1 : 0, l->bias, relu, nullptr, 0, gws, gwb, st));
         return CAPGNN_OK;
     }
-    // XFORM_FIRST
+    // XFORM_FIRST.  When an entry's weight depends on its source alone (no edge values), the product's epilogue
+    // multiplies row s of T by that weight and the aggregation sums unweighted: its entry list is half as long to read.
+    // fp32 only: a bf16 T would round the scaled rows a second time.
+    const bool pre = dt == CAPGNN_F32 && g->fwd.weights_by_source;
     const int64_t ldt = pad_ld(g, l->f_out, dt);
     const size_t need = fwd_ws_bytes(g, l, order);
     if (!ws || ws_bytes < need) CG_FAIL(CAPGNN_ENOMEM, "layer_fwd: workspace of %zu bytes needed, %zu given", need, ws_bytes);
@@ -166,7 +169,7 @@ static int layer_fwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
         Scope s(CAPGNN_K_GEMM, li, 0, st);
         void *gws = static_cast<char *>(ws) + fwd_t_bytes(g, l, order);
         CG_TRY(launch_gemm(0, 0, g->n_cols, l->f_out, l->f_in, X, ldx, l->W, l->f_out, ws, ldt, dt, 0, 0, nullptr, 0,
-                           nullptr, 0, gws, fwd_g_bytes(g, l), st));
+                           nullptr, 0, gws, fwd_g_bytes(g, l), st, pre ? g->fwd.in_scale : nullptr));
         if (sage)
             CG_TRY(launch_gemm(0, 0, g->n_loc, l->f_out, l->f_in, X, ldx, l->W_self, l->f_out, H, ldh, dt, l->out_f32, 0,
                                nullptr, 0, nullptr, 0, gws, fwd_g_bytes(g, l), st));
@@ -174,6 +177,7 @@ static int layer_fwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
     Scope s(CAPGNN_K_SPMM_FWD, li, 0, st);
     SpmmEpilogue ep;
     ep.bias = l->bias; ep.relu = relu; ep.accumulate = sage ? 1 : 0; ep.out_f32 = l->out_f32;
+    ep.operand_scaled = pre;
     ep.ws = static_cast<char *>(ws) + fwd_t_bytes(g, l, order) + fwd_g_bytes(g, l);
     ep.ws_bytes = ws_bytes - fwd_t_bytes(g, l, order) - fwd_g_bytes(g, l);
     CG_TRY(launch_spmm(g->fwd, false, ws, ldt, H, ldh, l->f_out, dt, ep, st));
@@ -207,13 +211,18 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
     sp_ep.ws = w;
     sp_ep.ws_bytes = ws_bytes - static_cast<size_t>(w - static_cast<char *>(ws));
 
+    // The transposed aggregation weighs an entry by the scale of its (local) source row alone when the operator has no
+    // edge values: the rows it gathers are multiplied by that scale where they are produced (dZ below when it is
+    // gathered itself and nothing else reads it; dH W^T in the other order) and it sums unweighted.  fp32 only.
+    const bool pre_b = dt == CAPGNN_F32 && g->bwd.weights_by_source;
+    const bool scale_dz = pre_b && order == CAPGNN_XFORM_FIRST && !sage && (dW || dX);
     {   // dZ = dH * sigma'(Z) in place; dbias = column sums of dZ
         Scope s(CAPGNN_K_ELEMENTWISE, li, 1, st);
         const int h_dt = (l->out_f32 ? CAPGNN_F32 : dt);
         // dH32: the same gradient before it was rounded to the storage type (the loss gradient of a bf16 model);
         // the bias gradient is then summed from it and dH is (re)written as its masked, rounded copy
         CG_TRY(launch_relu_mask_dbias(g->n_loc, l->f_out, dH32, lddh32, CAPGNN_F32, dH, lddh, H, ldh, dt, h_dt, relu, dbias,
-                                      ws_rb, rb, st));
+                                      ws_rb, rb, st, scale_dz ? g->bwd.in_scale : nullptr));
     }
     if (order == CAPGNN_AGG_FIRST) {
         if (!saved) CG_FAIL(CAPGNN_EINVAL, "layer_bwd: saved is NULL");
@@ -226,11 +235,12 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
                 CG_TRY(launch_gemm(1, 0, l->f_in, l->f_out, g->n_loc, X, ldx, dH, lddh, dW_self, l->f_out, dt, 1, 0,
                                    nullptr, 0, nullptr, 0, ws_gemm, gw, st));
             if (dX) CG_TRY(launch_gemm(0, 1, g->n_loc, l->f_in, l->f_out, dH, lddh, l->W, l->f_out, tmp, ldm, dt, 0, 0,
-                                       nullptr, 0, nullptr, 0, ws_gemm, gw, st));
+                                       nullptr, 0, nullptr, 0, ws_gemm, gw, st, pre_b ? g->bwd.in_scale : nullptr));
         }
         if (dX) {
             {
                 Scope s(CAPGNN_K_SPMM_BWD, li, 1, st);
+                sp_ep.operand_scaled = pre_b;
                 CG_TRY(launch_spmm(g->bwd, !need_halo_grad, tmp, ldm, dX, lddx, l->f_in, dt, sp_ep, st));
             }
             if (sage) {
@@ -246,6 +256,7 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
     if (dW || dX) {
         Scope s(CAPGNN_K_SPMM_BWD, li, 1, st);
         const bool sub = !dW && !need_halo_grad;
+        sp_ep.operand_scaled = scale_dz;
         CG_TRY(launch_spmm(g->bwd, sub, dH, lddh, tmp, ldt, l->f_out, dt, sp_ep, st));
     }
     Scope s(CAPGNN_K_GEMM, li, 1, st);

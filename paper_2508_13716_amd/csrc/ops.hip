@@ -32,7 +32,7 @@ constexpr int RB_MAX_BLOCKS = 1024;   // workgroups (= partial rows); each walks
 __global__ __launch_bounds__(256) void relu_mask_dbias_kernel(int64_t n, int F, const char *src, int64_t lds,
                                                               int src_bf16, char *dst, int64_t ldd, int dst_bf16,
                                                               const char *H, int64_t ldh, int h_bf16, int relu,
-                                                              float *partial) {
+                                                              float *partial, const float *rscale) {
     __shared__ float red[256];
     const int tx = threadIdx.x, ty = threadIdx.y, TX = blockDim.x, TY = blockDim.y;
     const bool in_place = src == dst;
@@ -49,8 +49,9 @@ __global__ __launch_bounds__(256) void relu_mask_dbias_kernel(int64_t n, int F, 
                         const float h = ld_elem(H, r * ldh + f, h_bf16);
                         if (!(h > 0.f)) { g = 0.f; zeroed = true; }
                     }
-                    if (!in_place || zeroed) st_elem(dst, r * ldd + f, g, dst_bf16);
                     s += g;
+                    if (rscale) g *= rscale[r];         // the stored copy carries the row's scale, the column sums do not
+                    if (!in_place || zeroed || rscale) st_elem(dst, r * ldd + f, g, dst_bf16);
                 }
             }
         }
@@ -87,7 +88,7 @@ __device__ __forceinline__ uint32_t bf16_rne_bits(float v) {
 __global__ __launch_bounds__(256) void relu_mask_dbias_vec4_kernel(int64_t n, int F, const char *src, int64_t lds,
                                                                    int src_bf16, char *dst, int64_t ldd, int dst_bf16,
                                                                    const char *H, int64_t ldh, int h_bf16, int relu,
-                                                                   float *partial) {
+                                                                   float *partial, const float *rscale) {
     __shared__ float red[256][4];
     const int tx = threadIdx.x, ty = threadIdx.y, TX = blockDim.x, TY = blockDim.y;
     const bool in_place = src == dst;
@@ -120,7 +121,14 @@ __global__ __launch_bounds__(256) void relu_mask_dbias_vec4_kernel(int64_t n, in
                         for (int j = 0; j < 4; ++j)
                             if (!(h[j] > 0.f) && g[j] != 0.f) { g[j] = 0.f; zeroed = true; }
                     }
-                    if (!in_place || zeroed) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) s[j] += g[j];
+                    if (rscale) {                       // the stored copy carries the row's scale, the column sums do not
+                        const float rs = rscale[r];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) g[j] *= rs;
+                    }
+                    if (!in_place || zeroed || rscale) {
                         if (nv == 4) {
                             if (dst_bf16) {
                                 uint2 o;
@@ -134,8 +142,6 @@ __global__ __launch_bounds__(256) void relu_mask_dbias_vec4_kernel(int64_t n, in
                             for (int j = 0; j < nv; ++j) st_elem(dst, r * ldd + f + j, g[j], dst_bf16);
                         }
                     }
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) s[j] += g[j];
                 }
             }
         }
@@ -180,7 +186,7 @@ size_t relu_bias_ws_bytes(int64_t n, int F) {
 
 int launch_relu_mask_dbias(int64_t n, int F, const void *src, int64_t lds, int src_dtype, void *dH, int64_t lddh,
                            const void *H, int64_t ldh, int dtype, int h_dtype, int relu, float *dbias, void *ws,
-                           size_t ws_bytes, hipStream_t stream) {
+                           size_t ws_bytes, hipStream_t stream, const float *row_scale) {
     if (F <= 0) return CAPGNN_OK;
     if (n <= 0) {   // no rows: the bias gradient is zero (summing zero partial blocks)
         if (dbias) {
@@ -192,7 +198,7 @@ int launch_relu_mask_dbias(int64_t n, int F, const void *src, int64_t lds, int s
     }
     if (!src) { src = dH; lds = lddh; src_dtype = dtype; }
     const bool converting = src != dH;
-    if (!relu && !dbias && !converting) return CAPGNN_OK;
+    if (!relu && !dbias && !converting && !row_scale) return CAPGNN_OK;
     if (!dH || (relu && !H)) CG_FAIL(CAPGNN_EINVAL, "relu_mask_dbias: NULL operand");
     if (lddh < F || lds < F || (relu && ldh < F)) CG_FAIL(CAPGNN_EINVAL, "relu_mask_dbias: leading dimension smaller than F");
     const int64_t nb = rb_blocks(n);
@@ -208,7 +214,7 @@ int launch_relu_mask_dbias(int64_t n, int F, const void *src, int64_t lds, int s
         hipLaunchKernelGGL(relu_mask_dbias_vec4_kernel, dim3(static_cast<unsigned>(nb)), block, 0, stream, n, F,
                            static_cast<const char *>(src), lds, src_dtype == CAPGNN_BF16 ? 1 : 0, static_cast<char *>(dH), lddh,
                            dtype == CAPGNN_BF16 ? 1 : 0, static_cast<const char *>(H), ldh, h_dtype == CAPGNN_BF16 ? 1 : 0,
-                           relu, dbias ? static_cast<float *>(ws) : nullptr);
+                           relu, dbias ? static_cast<float *>(ws) : nullptr, row_scale);
         CG_HIP(hipGetLastError());
         if (dbias) {
             hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 31) / 32), dim3(256), 0, stream, nb, F,
@@ -223,7 +229,7 @@ int launch_relu_mask_dbias(int64_t n, int F, const void *src, int64_t lds, int s
     hipLaunchKernelGGL(relu_mask_dbias_kernel, dim3(static_cast<unsigned>(nb)), block, 0, stream, n, F,
                        static_cast<const char *>(src), lds, src_dtype == CAPGNN_BF16 ? 1 : 0, static_cast<char *>(dH), lddh,
                        dtype == CAPGNN_BF16 ? 1 : 0, static_cast<const char *>(H), ldh, h_dtype == CAPGNN_BF16 ? 1 : 0,
-                       relu, dbias ? static_cast<float *>(ws) : nullptr);
+                       relu, dbias ? static_cast<float *>(ws) : nullptr, row_scale);
     CG_HIP(hipGetLastError());
     if (dbias) {
         hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 31) / 32), dim3(256), 0, stream, nb, F,

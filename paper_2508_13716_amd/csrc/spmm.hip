@@ -333,6 +333,7 @@ __global__ __launch_bounds__(MODE == 0 ? 64 : 256, (MODE == 0 && NV < 3) ? 6 : 1
 struct SpmmBlockedArgs {
     const uint32_t *off;         // [ncb*n_out + 1]
     const int2 *ew;              // [nnz] {source row, weight bits}
+    const int32_t *src;          // [nnz] source row alone: read instead of ew (every weight taken as 1) when not null
     int64_t n_out, n_long, n_mid;
     int ncb, H;                  // source blocks, row shares per slice
     int64_t RG_long, RG_mid, RG; // workgroups per (unit, block): long class, medium class, all
@@ -342,6 +343,11 @@ struct SpmmBlockedArgs {
     float *part;                 // [ncb*n_out][ldp] partial rows
     int64_t ldp;
 };
+
+// entry i: {source row, weight bits}; from the 4-byte list when the weights are not needed (uniform over the launch)
+__device__ __forceinline__ int2 blocked_entry(const SpmmBlockedArgs &b, uint32_t i) {
+    return b.src ? make_int2(b.src[i], 0x3f800000) : b.ew[i];
+}
 
 constexpr int B_LPR = SLICE_BYTES / 16;      // lanes that cover one slice with 16-byte loads
 constexpr int B_GROUPS = 64 / B_LPR;         // entries (or rows) a wave works on at the same time
@@ -373,12 +379,12 @@ __device__ __forceinline__ void blocked_row_accumulate(const SpmmBlockedArgs &b,
                                                        const char *xbase, bool ok, float (&acc)[E]) {
     const int grp = lane / B_LPR;
     int2 pr = make_int2(0, 0);
-    if (e0 + lane < e1) pr = b.ew[e0 + lane];
+    if (e0 + lane < e1) pr = blocked_entry(b, e0 + lane);
     for (uint32_t c0 = e0; c0 < e1; c0 += 64) {
         const int coff = static_cast<int>(__umul24(static_cast<uint32_t>(pr.x), b.ld16));   // 16-byte units
         const int wbits = pr.y;                                                               // 0 beyond the end
         pr = make_int2(0, 0);
-        if (c0 + 64 + lane < e1) pr = b.ew[c0 + 64 + lane];      // next chunk's entries are on their way early
+        if (c0 + 64 + lane < e1) pr = blocked_entry(b, c0 + 64 + lane);      // next chunk's entries are on their way early
         const int cnt = static_cast<int>(e1 - c0 < 64u ? e1 - c0 : 64u);
         float xk[B_GROUPS][E], wk[B_GROUPS];
 #pragma unroll
@@ -493,14 +499,14 @@ __global__ __launch_bounds__(256) void spmm_blocked_kernel(SpmmBlockedArgs b) {
 #pragma unroll
         for (int j = 0; j < E; ++j) acc[j] = 0.f;
         int2 pr = make_int2(0, 0);
-        if (e + l < e1) pr = b.ew[e + l];
+        if (e + l < e1) pr = blocked_entry(b, e + l);
         while (__any(e < e1)) {
             const int coff = static_cast<int>(__umul24(static_cast<uint32_t>(pr.x), b.ld16));   // in 16-byte units
             const int wbits = pr.y;
             const int n = e < e1 ? static_cast<int>(e1 - e) : 0;    // entries this group still has (may exceed 8)
             e += B_LPR;
             pr = make_int2(0, 0);
-            if (e + l < e1) pr = b.ew[e + l];                       // next trip's entries are on their way early
+            if (e + l < e1) pr = blocked_entry(b, e + l);                       // next trip's entries are on their way early
             float xk[B_LPR][E], wk[B_LPR];
 #pragma unroll
             for (int k = 0; k < B_LPR; ++k) {
@@ -623,7 +629,7 @@ size_t spmm_ws_bytes(const SpOp &op, int F, int dtype) {
 template <bool BF16, bool OBF16>
 static int launch_blocked(const SpOp &op, const BlockedGeom &g, const SpmmArgs &a, float *part, hipStream_t st) {
     SpmmBlockedArgs b;
-    b.off = op.b_off; b.ew = op.b_ew; b.n_out = op.n_out; b.n_long = op.b_long; b.n_mid = op.b_mid;
+    b.off = op.b_off; b.ew = op.b_ew; b.src = (a.wt == nullptr) ? op.b_src : nullptr; b.n_out = op.n_out; b.n_long = op.b_long; b.n_mid = op.b_mid;
     b.ncb = op.ncb; b.H = g.H; b.RG_long = g.RG_long; b.RG_mid = g.RG_mid; b.RG = g.RG;
     b.X = a.X; b.ld16 = static_cast<uint32_t>(a.ldx_bytes >> 4); b.F_lim = a.F_lim;
     b.part = part; b.ldp = g.ldp;
@@ -726,6 +732,10 @@ int launch_spmm(const SpOp &op, bool restrict_sub, const void *X, int64_t ldx, v
     SpmmArgs a;
     a.ptr = op.ptr; a.idx = op.idx; a.out_scale = op.out_scale;
     a.wt = op.wt;
+    if (ep.operand_scaled) {
+        if (!op.weights_by_source) CG_FAIL(CAPGNN_EINVAL, "spmm: operand_scaled asks for an operator whose weights depend on the source alone");
+        a.wt = nullptr;             // the rows of X carry the weights
+    }
     a.order = restrict_sub ? op.order_sub : op.order;
     a.list_begin = 0; a.list_end = n_rows;
     a.X = static_cast<const char *>(X); a.ldx_bytes = ldx * es;
