@@ -79,9 +79,9 @@ struct SpOp {
     int ncb = 0;                      // 0: no blocked copy
     const uint32_t *b_off = nullptr;  // device [ncb*n_out + 1]
     const int2 *b_ew = nullptr;       // device [nnz]  {source row, bits of the float weight val * in_scale[source]}
-    // the same entries without their weights, 4 bytes each (operators without edge values): read instead of b_ew when
+    // the same entries without their weights, as 16-bit row numbers inside the block (operators without edge values): read instead of b_ew when
     // every weight is 1, or when the caller has multiplied the operand rows by in_scale beforehand
-    const int32_t *b_src = nullptr;   // device [nnz] or null
+    const uint16_t *b_src = nullptr;  // device [nnz] or null: source row - cb * CB_ROWS (2 bytes per entry)
     // positions [0, b_long) hold rows whose groups are long enough for a whole workgroup, [b_long, b_mid) for
     // one wave per group, the rest are walked eight rows per wave (`order` is descending in entry count)
     int64_t b_long = 0, b_mid = 0;

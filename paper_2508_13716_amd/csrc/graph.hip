@@ -97,7 +97,7 @@ struct BlockedHost {
     int64_t n_long = 0, n_mid = 0;
     std::vector<uint32_t> off;
     std::vector<int2> ew;
-    std::vector<int32_t> src;         // ew[].x alone, for operators without edge values
+    std::vector<uint16_t> src;        // ew[].x % CB_ROWS alone, for operators without edge values
 };
 
 static int32_t float_bits(float f) {
@@ -144,7 +144,8 @@ static bool build_blocked(const int64_t *ptr, const int32_t *idx, const float *v
         });
     if (!val) {
         out->src.resize(nnz);
-        for (int64_t q = 0; q < nnz; ++q) out->src[q] = out->ew[q].x;
+        static_assert(CB_ROWS <= 65536, "block-local row numbers are stored in 16 bits");
+        for (int64_t q = 0; q < nnz; ++q) out->src[q] = static_cast<uint16_t>(out->ew[q].x % CB_ROWS);
     }
     return true;
 }

@@ -333,7 +333,7 @@ __global__ __launch_bounds__(MODE == 0 ? 64 : 256, (MODE == 0 && NV < 3) ? 6 : 1
 struct SpmmBlockedArgs {
     const uint32_t *off;         // [ncb*n_out + 1]
     const int2 *ew;              // [nnz] {source row, weight bits}
-    const int32_t *src;          // [nnz] source row alone: read instead of ew (every weight taken as 1) when not null
+    const uint16_t *src;         // [nnz] source row inside its block: read instead of ew (every weight taken as 1) when not null
     int64_t n_out, n_long, n_mid;
     int ncb, H;                  // source blocks, row shares per slice
     int64_t RG_long, RG_mid, RG; // workgroups per (unit, block): long class, medium class, all
@@ -344,9 +344,10 @@ struct SpmmBlockedArgs {
     int64_t ldp;
 };
 
-// entry i: {source row, weight bits}; from the 4-byte list when the weights are not needed (uniform over the launch)
-__device__ __forceinline__ int2 blocked_entry(const SpmmBlockedArgs &b, uint32_t i) {
-    return b.src ? make_int2(b.src[i], 0x3f800000) : b.ew[i];
+// entry i of block cb: {source row, weight bits}; from the 2-byte list when the weights are not needed (uniform over
+// the launch)
+__device__ __forceinline__ int2 blocked_entry(const SpmmBlockedArgs &b, int cb, uint32_t i) {
+    return b.src ? make_int2(cb * CB_ROWS + b.src[i], 0x3f800000) : b.ew[i];
 }
 
 constexpr int B_LPR = SLICE_BYTES / 16;      // lanes that cover one slice with 16-byte loads
@@ -375,16 +376,16 @@ __device__ __forceinline__ int group_bcast(int v, int k) {
 // entries g, g+8, ... of the chunk, so up to eight 16-byte-per-lane feature loads are in flight per wave.
 // On return every lane of group g holds the sum over that group's entries; the caller adds the groups.
 template <bool BF16, int E>
-__device__ __forceinline__ void blocked_row_accumulate(const SpmmBlockedArgs &b, uint32_t e0, uint32_t e1, int lane,
+__device__ __forceinline__ void blocked_row_accumulate(const SpmmBlockedArgs &b, int cb, uint32_t e0, uint32_t e1, int lane,
                                                        const char *xbase, bool ok, float (&acc)[E]) {
     const int grp = lane / B_LPR;
     int2 pr = make_int2(0, 0);
-    if (e0 + lane < e1) pr = blocked_entry(b, e0 + lane);
+    if (e0 + lane < e1) pr = blocked_entry(b, cb, e0 + lane);
     for (uint32_t c0 = e0; c0 < e1; c0 += 64) {
         const int coff = static_cast<int>(__umul24(static_cast<uint32_t>(pr.x), b.ld16));   // 16-byte units
         const int wbits = pr.y;                                                               // 0 beyond the end
         pr = make_int2(0, 0);
-        if (c0 + 64 + lane < e1) pr = blocked_entry(b, c0 + 64 + lane);      // next chunk's entries are on their way early
+        if (c0 + 64 + lane < e1) pr = blocked_entry(b, cb, c0 + 64 + lane);      // next chunk's entries are on their way early
         const int cnt = static_cast<int>(e1 - c0 < 64u ? e1 - c0 : 64u);
         float xk[B_GROUPS][E], wk[B_GROUPS];
 #pragma unroll
@@ -452,7 +453,7 @@ __global__ __launch_bounds__(256) void spmm_blocked_kernel(SpmmBlockedArgs b) {
         float acc[E];
 #pragma unroll
         for (int j = 0; j < E; ++j) acc[j] = 0.f;
-        blocked_row_accumulate<BF16, E>(b, w0, w1, lane, xbase, ok, acc);
+        blocked_row_accumulate<BF16, E>(b, cb, w0, w1, lane, xbase, ok, acc);
         add_groups<E>(acc);
         if (wave > 0 && lane < B_LPR) {
 #pragma unroll
@@ -480,7 +481,7 @@ __global__ __launch_bounds__(256) void spmm_blocked_kernel(SpmmBlockedArgs b) {
             float acc[E];
 #pragma unroll
             for (int j = 0; j < E; ++j) acc[j] = 0.f;
-            blocked_row_accumulate<BF16, E>(b, e0, e1, lane, xbase, ok, acc);
+            blocked_row_accumulate<BF16, E>(b, cb, e0, e1, lane, xbase, ok, acc);
             add_groups<E>(acc);
             if (lane < B_LPR) store_elems<false, E>(reinterpret_cast<char *>(b.part + (tbase + p) * b.ldp + elem0), acc);
         }
@@ -499,14 +500,14 @@ __global__ __launch_bounds__(256) void spmm_blocked_kernel(SpmmBlockedArgs b) {
 #pragma unroll
         for (int j = 0; j < E; ++j) acc[j] = 0.f;
         int2 pr = make_int2(0, 0);
-        if (e + l < e1) pr = blocked_entry(b, e + l);
+        if (e + l < e1) pr = blocked_entry(b, cb, e + l);
         while (__any(e < e1)) {
             const int coff = static_cast<int>(__umul24(static_cast<uint32_t>(pr.x), b.ld16));   // in 16-byte units
             const int wbits = pr.y;
             const int n = e < e1 ? static_cast<int>(e1 - e) : 0;    // entries this group still has (may exceed 8)
             e += B_LPR;
             pr = make_int2(0, 0);
-            if (e + l < e1) pr = blocked_entry(b, e + l);                       // next trip's entries are on their way early
+            if (e + l < e1) pr = blocked_entry(b, cb, e + l);                       // next trip's entries are on their way early
             float xk[B_LPR][E], wk[B_LPR];
 #pragma unroll
             for (int k = 0; k < B_LPR; ++k) {
