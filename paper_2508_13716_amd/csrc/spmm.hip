@@ -354,6 +354,8 @@ constexpr int B_LPR = SLICE_BYTES / 16;      // lanes that cover one slice with 
 constexpr int B_GROUPS = 64 / B_LPR;         // entries (or rows) a wave works on at the same time
 constexpr int B_MID_PER_WAVE = 4;            // consecutive medium positions one wave handles
 constexpr int B_SHORT_PER_GROUP = 2;         // consecutive short positions one lane group handles
+// entries per trip of a lane group when the entries carry no weights (bf16 rows widen to twice the registers)
+template <bool BF16> constexpr int B_SHORT_DEPTH = BF16 ? 8 : 16;
 constexpr int B_MID_PER_WG = 4 * B_MID_PER_WAVE;
 constexpr int B_SHORT_PER_WG = 4 * B_GROUPS * B_SHORT_PER_GROUP;
 static_assert(B_LPR == 8, "lane-group shuffles below assume 8-lane groups");
@@ -375,10 +377,45 @@ __device__ __forceinline__ int group_bcast(int v, int k) {
 // All 64 lanes work on ONE row: entries [e0, e1) are read 64 at a time (coalesced), lane group g then takes
 // entries g, g+8, ... of the chunk, so up to eight 16-byte-per-lane feature loads are in flight per wave.
 // On return every lane of group g holds the sum over that group's entries; the caller adds the groups.
-template <bool BF16, int E>
+template <bool BF16, bool WEIGHTED, int E>
 __device__ __forceinline__ void blocked_row_accumulate(const SpmmBlockedArgs &b, int cb, uint32_t e0, uint32_t e1, int lane,
                                                        const char *xbase, bool ok, float (&acc)[E]) {
     const int grp = lane / B_LPR;
+    if constexpr (!WEIGHTED) {
+        // bare row numbers: NC chunks of 64 entries per trip (NC * 8 feature loads in flight per lane), plain sums
+        // (NC = 2 costs a wave per SIMD in registers and 2 % of the launch: measured)
+        constexpr int NC = 1;
+        const int rowbase = cb * CB_ROWS;
+        int cur[NC];
+#pragma unroll
+        for (int q = 0; q < NC; ++q) cur[q] = (e0 + 64 * q + lane < e1) ? rowbase + b.src[e0 + 64 * q + lane] : 0;
+        for (uint32_t c0 = e0; c0 < e1; c0 += 64 * NC) {
+            int coff[NC];
+#pragma unroll
+            for (int q = 0; q < NC; ++q) coff[q] = static_cast<int>(__umul24(static_cast<uint32_t>(cur[q]), b.ld16));
+#pragma unroll
+            for (int q = 0; q < NC; ++q)
+                cur[q] = (c0 + 64 * (NC + q) + lane < e1) ? rowbase + b.src[c0 + 64 * (NC + q) + lane] : 0;
+            const int cnt = static_cast<int>(e1 - c0 < 64u * NC ? e1 - c0 : 64u * NC);
+            float xk[NC * B_GROUPS][E];
+#pragma unroll
+            for (int k = 0; k < NC * B_GROUPS; ++k) {
+                const int src = (k % B_GROUPS) * B_GROUPS + grp;             // lane that holds the entry, in chunk k / B_GROUPS
+                const uint32_t ck = static_cast<uint32_t>(__shfl(coff[k / B_GROUPS], src));
+                if ((k / B_GROUPS) * 64 + src < cnt && ok) {
+                    load_elems<BF16, E>(xbase + (static_cast<uint64_t>(ck) << 4), xk[k]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < E; ++j) xk[k][j] = 0.f;
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < NC * B_GROUPS; ++k)
+#pragma unroll
+                for (int j = 0; j < E; ++j) acc[j] += xk[k][j];
+        }
+        return;
+    }
     int2 pr = make_int2(0, 0);
     if (e0 + lane < e1) pr = blocked_entry(b, cb, e0 + lane);
     for (uint32_t c0 = e0; c0 < e1; c0 += 64) {
@@ -419,7 +456,8 @@ __device__ __forceinline__ void add_groups(float (&acc)[E]) {
         for (int j = 0; j < E; ++j) acc[j] += __shfl_xor(acc[j], off);
 }
 
-template <bool BF16>
+// WEIGHTED: entries come with their weights (b.ew); otherwise as bare block-local row numbers (b.src), every weight 1.
+template <bool BF16, bool WEIGHTED>
 __global__ __launch_bounds__(256) void spmm_blocked_kernel(SpmmBlockedArgs b) {
     constexpr int E = BF16 ? 8 : 4;
     constexpr int ES = BF16 ? 2 : 4;
@@ -453,7 +491,7 @@ __global__ __launch_bounds__(256) void spmm_blocked_kernel(SpmmBlockedArgs b) {
         float acc[E];
 #pragma unroll
         for (int j = 0; j < E; ++j) acc[j] = 0.f;
-        blocked_row_accumulate<BF16, E>(b, cb, w0, w1, lane, xbase, ok, acc);
+        blocked_row_accumulate<BF16, WEIGHTED, E>(b, cb, w0, w1, lane, xbase, ok, acc);
         add_groups<E>(acc);
         if (wave > 0 && lane < B_LPR) {
 #pragma unroll
@@ -481,7 +519,7 @@ __global__ __launch_bounds__(256) void spmm_blocked_kernel(SpmmBlockedArgs b) {
             float acc[E];
 #pragma unroll
             for (int j = 0; j < E; ++j) acc[j] = 0.f;
-            blocked_row_accumulate<BF16, E>(b, cb, e0, e1, lane, xbase, ok, acc);
+            blocked_row_accumulate<BF16, WEIGHTED, E>(b, cb, e0, e1, lane, xbase, ok, acc);
             add_groups<E>(acc);
             if (lane < B_LPR) store_elems<false, E>(reinterpret_cast<char *>(b.part + (tbase + p) * b.ldp + elem0), acc);
         }
@@ -499,6 +537,41 @@ __global__ __launch_bounds__(256) void spmm_blocked_kernel(SpmmBlockedArgs b) {
         float acc[E];
 #pragma unroll
         for (int j = 0; j < E; ++j) acc[j] = 0.f;
+        if constexpr (!WEIGHTED) {
+            // bare row numbers, B_SHORT_DEPTH entries per trip: each lane fetches an eighth of them, the group exchanges
+            // them and every lane has that many feature loads in flight; the sums need no multiply
+            constexpr int NQ = B_SHORT_DEPTH<BF16> / B_LPR;
+            const int rowbase = cb * CB_ROWS;
+            int cur[NQ];
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) cur[q] = (e + q * B_LPR + l < e1) ? rowbase + b.src[e + q * B_LPR + l] : 0;
+            while (__any(e < e1)) {
+                const int n = e < e1 ? static_cast<int>(e1 - e) : 0;    // entries this group still has (may exceed a trip)
+                int coff[NQ];
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) coff[q] = static_cast<int>(__umul24(static_cast<uint32_t>(cur[q]), b.ld16));
+                e += B_SHORT_DEPTH<BF16>;
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) cur[q] = (e + q * B_LPR + l < e1) ? rowbase + b.src[e + q * B_LPR + l] : 0;
+                float xk[B_SHORT_DEPTH<BF16>][E];
+#pragma unroll
+                for (int k = 0; k < B_SHORT_DEPTH<BF16>; ++k) {
+                    const uint32_t ck = static_cast<uint32_t>(group_bcast(coff[k / B_LPR], k % B_LPR));
+                    if (k < n && ok) {
+                        load_elems<BF16, E>(xbase + (static_cast<uint64_t>(ck) << 4), xk[k]);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < E; ++j) xk[k][j] = 0.f;
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < B_SHORT_DEPTH<BF16>; ++k)
+#pragma unroll
+                    for (int j = 0; j < E; ++j) acc[j] += xk[k][j];
+            }
+            if (any_entry) store_elems<false, E>(reinterpret_cast<char *>(b.part + (tbase + p) * b.ldp + elem0), acc);
+            continue;
+        }
         int2 pr = make_int2(0, 0);
         if (e + l < e1) pr = blocked_entry(b, cb, e + l);
         while (__any(e < e1)) {
@@ -634,7 +707,8 @@ static int launch_blocked(const SpOp &op, const BlockedGeom &g, const SpmmArgs &
     b.ncb = op.ncb; b.H = g.H; b.RG_long = g.RG_long; b.RG_mid = g.RG_mid; b.RG = g.RG;
     b.X = a.X; b.ld16 = static_cast<uint32_t>(a.ldx_bytes >> 4); b.F_lim = a.F_lim;
     b.part = part; b.ldp = g.ldp;
-    hipLaunchKernelGGL((spmm_blocked_kernel<BF16>), dim3(static_cast<unsigned>(g.grid)), dim3(256), 0, st, b);
+    if (b.src) hipLaunchKernelGGL((spmm_blocked_kernel<BF16, false>), dim3(static_cast<unsigned>(g.grid)), dim3(256), 0, st, b);
+    else hipLaunchKernelGGL((spmm_blocked_kernel<BF16, true>), dim3(static_cast<unsigned>(g.grid)), dim3(256), 0, st, b);
     CG_HIP(hipGetLastError());
     SpmmReduceArgs r;
     r.off = op.b_off; r.order = op.order; r.out_scale = op.out_scale; r.part = part; r.ldp = g.ldp; r.n_out = op.n_out;
