@@ -631,19 +631,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 // ---------------------------------------------------------------------------------------------------
 // fp32 operands on the bf16 matrix cores.  An fp32 number is the exact sum of three bf16 numbers (its 24 significant
 // bits cut into 8 + 8 + 8, with signs), so a product a * b is the sum of nine bf16 products, each exact in fp32.  The
-// three smallest (together at most 2^-23 of the product: the size of fp32's own rounding) are dropped, the other six are accumulated in
-// fp32 by v_mfma_f32_32x32x16_bf16, smallest first.  Six such instructions cover the k-range of eight
-// v_mfma_f32_32x32x2_f32 at about a fifteenth of the cost each.
+// three smallest (together at most 2^-23 of the product: the size of fp32's own rounding) are dropped, the other six
+// are accumulated in fp32 by v_mfma_f32_32x32x16_bf16, smallest first.  Six such instructions cover the k-range of
+// eight v_mfma_f32_32x32x2_f32 at about a fifteenth of the cost each.
 //
 // LDS holds the three pieces of both operand tiles, 32 k per step, in one buffer (the next step's operands wait in
-// registers; three workgroups share a compute unit and fill one another's barriers).  An operand stored along the
+// registers; two workgroups share a compute unit and fill one another's barriers).  An operand stored along the
 // reduction index is cut while it is staged and kept in 16-byte units S[piece][k / 8][row] (a lane's eight k are one
 // 16-byte read, consecutive lanes read consecutive units; a plane is 32 bytes longer than a power of two so that the
-// 8-byte staging stores of 16 consecutive lanes, 2 rows x 4 units x 2 halves, cover 128 consecutive bytes of banks); the weight matrix of a plain product is
-// cut once, by split_repack_kernel, into the same units in global memory and only copied here; an operand stored across
-// the reduction index (both operands of X^T G) is transposed in registers and kept in 8-byte units
-// S[piece][k / 4][row], which makes both the staging stores (32 bytes per thread and piece) and the operand reads
-// (two 8-byte reads) run over consecutive LDS addresses.
+// 8-byte staging stores of 16 consecutive lanes, 2 rows x 4 units x 2 halves, cover 128 consecutive bytes of banks);
+// the weight matrix of a plain product is cut once, by split_repack_kernel, into the same units in global memory and
+// only copied here; an operand stored across the reduction index (both operands of X^T G) is transposed in registers
+// and kept in 8-byte units S[piece][k / 4][row], which makes both the staging stores (32 bytes per thread and piece)
+// and the operand reads (two 8-byte reads) run over consecutive LDS addresses.
 constexpr int SBK = 32;
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
