@@ -159,6 +159,88 @@ __global__ __launch_bounds__(256) void relu_mask_dbias_vec4_kernel(int64_t n, in
     }
 }
 
+// The same for bf16 data on all three sides with eight consecutive features per thread (16-byte accesses): the wide
+// bf16 layers are bound by this kernel's memory traffic, and 8-byte accesses leave half of the load path idle.
+// blockDim = (TX, 256/TX), TX = ceil(F/8) rounded up to a power of two (F <= 2048); rows start on 16-byte boundaries.
+__global__ __launch_bounds__(256) void relu_mask_dbias_bf16x8_kernel(int64_t n, int F, const char *src, int64_t lds, char *dst,
+                                                                     int64_t ldd, const char *H, int64_t ldh, int relu,
+                                                                     float *partial, const float *rscale) {
+    __shared__ float red[256][8];
+    const int tx = threadIdx.x, ty = threadIdx.y, TX = blockDim.x, TY = blockDim.y;
+    const bool in_place = src == dst;
+    const int f = 8 * tx;
+    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (f < F) {
+        const int nv = F - f < 8 ? F - f : 8;    // valid features of this thread's vector (the rest is row padding)
+        for (int64_t r0 = static_cast<int64_t>(blockIdx.x) * RB_ROWS; r0 < n; r0 += static_cast<int64_t>(gridDim.x) * RB_ROWS) {
+            const int64_t r1 = r0 + RB_ROWS < n ? r0 + RB_ROWS : n;
+            for (int64_t rb = r0 + ty; rb < r1; rb += 4 * TY) {
+                uint4 gv[4], hv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t r = rb + static_cast<int64_t>(u) * TY;
+                    if (r < r1) {
+                        gv[u] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(src) + r * lds + f);
+                        if (relu) hv[u] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(H) + r * ldh + f);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t r = rb + static_cast<int64_t>(u) * TY;
+                    if (r >= r1) continue;
+                    const uint32_t gw[4] = {gv[u].x, gv[u].y, gv[u].z, gv[u].w};
+                    float g[8];
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        g[2 * d] = __uint_as_float(gw[d] << 16);
+                        g[2 * d + 1] = __uint_as_float(gw[d] & 0xffff0000u);
+                    }
+                    bool zeroed = false;
+                    if (relu) {
+                        const uint32_t hw[4] = {hv[u].x, hv[u].y, hv[u].z, hv[u].w};
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            const float h0 = __uint_as_float(hw[d] << 16), h1 = __uint_as_float(hw[d] & 0xffff0000u);
+                            if (!(h0 > 0.f) && g[2 * d] != 0.f) { g[2 * d] = 0.f; zeroed = true; }
+                            if (!(h1 > 0.f) && g[2 * d + 1] != 0.f) { g[2 * d + 1] = 0.f; zeroed = true; }
+                        }
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) s[j] += g[j];
+                    if (rscale) {                       // the stored copy carries the row's scale, the column sums do not
+                        const float rs = rscale[r];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) g[j] *= rs;
+                    }
+                    if (!in_place || zeroed || rscale) {
+                        if (nv == 8) {
+                            uint4 o;
+                            o.x = bf16_rne_bits(g[0]) | (bf16_rne_bits(g[1]) << 16);
+                            o.y = bf16_rne_bits(g[2]) | (bf16_rne_bits(g[3]) << 16);
+                            o.z = bf16_rne_bits(g[4]) | (bf16_rne_bits(g[5]) << 16);
+                            o.w = bf16_rne_bits(g[6]) | (bf16_rne_bits(g[7]) << 16);
+                            *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(dst) + r * ldd + f) = o;
+                        } else {
+                            for (int j = 0; j < nv; ++j) st_elem(dst, r * ldd + f + j, g[j], 1);
+                        }
+                    }
+                }
+            }
+        }
+    }
+    if (!partial) return;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) red[ty * TX + tx][j] = s[j];
+    __syncthreads();
+    if (ty == 0 && f < F) {
+        for (int j = 0; j < 8 && f + j < F; ++j) {
+            float t = 0.f;
+            for (int y = 0; y < TY; ++y) t += red[y * TX + tx][j];
+            partial[static_cast<int64_t>(blockIdx.x) * F + f + j] = t;
+        }
+    }
+}
+
 // dbias[f] = sum_b partial[b][f]: 32 features x 8 strided groups per workgroup, doubles, fixed order
 __global__ __launch_bounds__(256) void dbias_final_kernel(int64_t nblocks, int F, const float *partial, float *dbias) {
     __shared__ double red[8][32];
@@ -207,6 +289,22 @@ int launch_relu_mask_dbias(int64_t n, int F, const void *src, int64_t lds, int s
     const int ses = elem_bytes(src_dtype), des = elem_bytes(dtype), hes = elem_bytes(h_dtype);
     const bool vec = F <= 1024 && aligned16(src) && aligned16(dH) && (lds * ses) % 16 == 0 && (lddh * des) % 16 == 0 &&
                      (!relu || (aligned16(H) && (ldh * hes) % 16 == 0));
+    const bool all_bf16 = src_dtype == CAPGNN_BF16 && dtype == CAPGNN_BF16 && (!relu || h_dtype == CAPGNN_BF16);
+    if (vec && all_bf16 && F >= 64 && F <= 2048) {
+        int TX = 1;
+        while (TX < (F + 7) / 8) TX <<= 1;
+        dim3 block(TX, 256 / TX);
+        hipLaunchKernelGGL(relu_mask_dbias_bf16x8_kernel, dim3(static_cast<unsigned>(nb)), block, 0, stream, n, F,
+                           static_cast<const char *>(src), lds, static_cast<char *>(dH), lddh, static_cast<const char *>(H), ldh,
+                           relu, dbias ? static_cast<float *>(ws) : nullptr, row_scale);
+        CG_HIP(hipGetLastError());
+        if (dbias) {
+            hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 31) / 32), dim3(256), 0, stream, nb, F,
+                               static_cast<const float *>(ws), dbias);
+            CG_HIP(hipGetLastError());
+        }
+        return CAPGNN_OK;
+    }
     if (vec) {
         int TX = 1;
         while (TX < (F + 3) / 4) TX <<= 1;
