@@ -471,6 +471,23 @@ def test_gemm_f32_split_product(env, ta, tb):
         B.set_f32_product(B.F32_PRODUCT_AUTO)
 
 
+def test_mfma_peak_loop_runs_and_counts_its_work(env):
+    """The register-resident matrix-instruction loop: the reported work is 4 tiles x 4 waves x iterations x workgroups x
+    the instruction's 2 * 32 * 32 * k FLOPs, and every thread writes a finite, positive checksum (its operands are
+    positive)."""
+    torch, B = env["torch"], env["B"]
+    wgs, iters = 8, 16
+    out = torch.full((wgs * 256,), -1.0, dtype=torch.float32, device="cuda")
+    for dt, k in ((B.F32, 2), (B.BF16, 16)):
+        flop = B.mfma_peak(dt, wgs, iters, out)
+        torch.cuda.synchronize()
+        assert flop == 2.0 * 32 * 32 * k * 4 * iters * 4 * wgs
+        got = out.cpu().numpy()
+        assert np.isfinite(got).all() and (got > 0).all()
+    with pytest.raises(B.CapgnnError):
+        B.mfma_peak(B.F32, 0, iters, out)
+
+
 def test_gemm_relu_mask_epilogue(env):
     torch, B, H, O, orc = env["torch"], env["B"], env["H"], env["O"], env["orc"]
     rng = np.random.default_rng(3)
