@@ -73,6 +73,37 @@ def gemm_report(cfg, part, orders, kernels, f32_product):
             "note": "matrix-core busy cycles of the same kernels: profiles/gemm_C2_C4_mfma_counters.txt"}
 
 
+def f32_product_check(cfg):
+    """Both forms of the fp32 product on one product of the first layer's shape (4096 rows): the largest deviation from an
+    fp64 product of the same operands, relative to the largest result.  Untimed; shows in the benchmark line itself
+    that the form the library chooses is as close to the exact product as the fp32 matrix instruction."""
+    import torch
+    from paper_2508_13716_amd import binding as B
+    if cfg.dtype != "f32":
+        return None
+    M, K, N = 4096, cfg.dims[0], cfg.dims[1]
+    lda = (K + 3) // 4 * 4
+    gen = torch.Generator(device="cuda").manual_seed(1)
+    A = torch.randn((M, lda), device="cuda", generator=gen)
+    W = torch.randn((K, N), device="cuda", generator=gen)
+    ref = A[:, :K].double() @ W.double()
+    wsb = B.gemm_workspace_bytes(0, M, N, K)
+    ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+    out = {}
+    before = B.get_f32_product()
+    try:
+        for name, mode in (("fp32_instruction", B.F32_PRODUCT_NATIVE), ("three_bf16_pieces", B.F32_PRODUCT_SPLIT)):
+            Cd = torch.empty((M, N), device="cuda")
+            B.set_f32_product(mode)
+            B.gemm(0, 0, M, N, K, A, lda, W, N, Cd, N, B.F32, out_f32=1, ws=ws, ws_bytes=wsb, stream=torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            out[name] = float((Cd.double() - ref).abs().max() / ref.abs().max())
+    finally:
+        B.set_f32_product(before)
+    out["product"] = f"{M} x {N} x {K}, standard normal operands"
+    return out
+
+
 def cpu_baseline(cfg, scale, full_prob):
     """The oracle as it stands, timed on the host cores: on the same partition when scale >= 1, else on a
     scaled-down partition of the same shape (same average degree, widths and cache fraction)."""
@@ -496,6 +527,7 @@ def main():
                    "miss_host_link_GBps": miss_bytes / (miss_ms * 1e-3) / 1e9 if miss_ms else None,
                    "miss_bytes": miss_bytes},
         "gemm": gemm_report(cfg, part, res_orders, kernels, args.f32_product),
+        "f32_product_max_rel_err": f32_product_check(cfg),
         "kernels": kernels[:12],
         "roofline": {"kernel": f"{dom['kind']} layer {dom['layer']} F={F}", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
