@@ -92,8 +92,8 @@ constexpr int LONG_ROW = 2048;  // rows at least this long are reduced by a whol
 constexpr int GIANT_ROW = 16384;  // rows at least this long are cut into pieces when the caller brings scratch
 constexpr int GIANT_PIECE = 4096; // entries per piece: one workgroup each, partial sums combined in piece order
 constexpr int CB_ROWS = 32768;  // source rows per column block: 32768 x 128-byte slices = 4 MB, one XCD's L2 (swept: 8192 .. 49152)
-constexpr int B_LONG_GROUP = 512; // rows with at least this many entries per source block on average: workgroup per group
-constexpr int B_MID_GROUP = 128;  // ... at least this many: wave per group
+constexpr int B_LONG_GROUP = 1024; // rows with at least this many entries per source block on average: workgroup per group (swept 256 .. 4096)
+constexpr int B_MID_GROUP = 256;  // ... at least this many: wave per group (swept 64 .. 1024; the eight-rows-per-wave class below is the fastest)
 constexpr int SLICE_BYTES = 128;  // feature bytes of one source row that one task of the blocked kernel gathers
 constexpr int NUM_XCD = 8;        // L2 domains of the chip; workgroup b is dispatched to domain b % NUM_XCD
 
