@@ -40,11 +40,13 @@ def adversarial_graphs():
     return gs
 
 
-def run_spmm(env, part, F, ld, dtype, with_vals, seed, blocked=False):
+def run_spmm(env, part, F, ld, dtype, with_vals, seed, blocked=False, unit_weights=False):
     torch, B, H, O, orc = env["torch"], env["B"], env["H"], env["O"], env["orc"]
     rng = np.random.default_rng(seed)
     r = rng.uniform(0.5, 1.5, part.n_loc).astype(np.float32)
     c = rng.uniform(0.5, 1.5, part.n_cols).astype(np.float32)
+    if unit_weights:       # every entry weighs 1 in both directions: the kernels read bare source rows
+        r, c = np.ones_like(r), np.ones_like(c)
     v = rng.uniform(-1, 1, part.nnz).astype(np.float32) if with_vals else None
     X = rng.standard_normal((part.n_cols, F)).astype(np.float32)
     dY = rng.standard_normal((part.n_loc, F)).astype(np.float32)
@@ -114,6 +116,21 @@ def test_spmm_column_blocked(env, shape):
                                (256, 264, "bf16", False)]:
         say(f"spmm blocked {part.name} F={F} ld={ld} {dtype}")
         run_spmm(env, part, F, ld, dtype, vals, seed=F, blocked=True)
+
+
+@pytest.mark.parametrize("shape", ["wide", "tall"])
+def test_spmm_column_blocked_unit_weights(env, shape):
+    """The same operators with every weight equal to 1 (no edge values, scales of 1): the blocked kernel then reads
+    its entries as 2-byte row numbers inside the source block, exchanges no weights between lanes and adds instead of
+    multiplying.  Widths span one partial slice, several slices and a ragged last slice, both storage types."""
+    if shape == "wide":
+        part = synth.make_partition("blk-wide-1", 2500, 38000, 330000, seed=31, max_deg=9000, halo_edge_frac=0.9)
+    else:
+        part = synth.make_partition("blk-tall-1", 37000, 2000, 2600000, seed=32, max_deg=4000, halo_edge_frac=0.2)
+    for F, ld, dtype in [(32, 32, "f32"), (41, 44, "f32"), (256, 256, "f32"), (602, 604, "f32"), (64, 64, "bf16"),
+                         (200, 200, "bf16")]:
+        say(f"spmm blocked, unit weights {part.name} F={F} ld={ld} {dtype}")
+        run_spmm(env, part, F, ld, dtype, False, seed=F, blocked=True, unit_weights=True)
 
 
 def test_spmm_rows_cut_into_pieces(env):
