@@ -148,11 +148,20 @@ def test_epoch_after_vertex_update_and_staleness_bound(env, miss_mode):
     dp.close()
 
 
+@pytest.mark.parametrize("graph", ["small", "blocked"])
 @pytest.mark.parametrize("kind", ["gcn", "sage"])
 @pytest.mark.parametrize("order", ["agg", "xform"])
-def test_layer_fwd_bwd_with_halo_gradient(env, kind, order):
+def test_layer_fwd_bwd_with_halo_gradient(env, kind, order, graph):
+    """One layer, both association orders, with and without the halo part of the input gradient.  "blocked": a
+    dense-degree partition whose operator gets the column-blocked copy in both directions, so the aggregations run the
+    blocked kernels, on rows that the producing kernels have multiplied by the per-source weights (GCN) or with unit
+    weights (mean aggregator)."""
     torch, B, H, O, orc = env["torch"], env["B"], env["H"], env["O"], env["orc"]
-    part = synth.make_partition("layer", 900, 700, 12000, seed=41, max_deg=2500, self_loops=(kind == "gcn"))
+    if graph == "small":
+        part = synth.make_partition("layer", 900, 700, 12000, seed=41, max_deg=2500, self_loops=(kind == "gcn"))
+    else:
+        part = synth.make_partition("layer-blk", 37000, 36000, 5200000, seed=43, max_deg=4000, halo_edge_frac=0.5,
+                                    self_loops=(kind == "gcn"))
     fi, fo = 50, 36
     rng = np.random.default_rng(7)
     X = rng.standard_normal((part.n_cols, fi)).astype(np.float32)
