@@ -241,19 +241,28 @@ __global__ __launch_bounds__(256) void relu_mask_dbias_bf16x8_kernel(int64_t n, 
     }
 }
 
-// dbias[f] = sum_b partial[b][f]: 32 features x 8 strided groups per workgroup, doubles, fixed order
-__global__ __launch_bounds__(256) void dbias_final_kernel(int64_t nblocks, int F, const float *partial, float *dbias) {
-    __shared__ double red[8][32];
+// dbias[f] = sum_b partial[b][f]: 32 features x 32 strided groups per workgroup, doubles, fixed order
+constexpr int DBF_GROUPS = 32;
+__global__ __launch_bounds__(1024) void dbias_final_kernel(int64_t nblocks, int F, const float *partial, float *dbias) {
+    __shared__ double red[DBF_GROUPS][32];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const int f = blockIdx.x * 32 + tx;
     double s = 0.0;
-    if (f < F)
-        for (int64_t b = ty; b < nblocks; b += 8) s += static_cast<double>(partial[b * F + f]);
+    if (f < F) {
+        int64_t b = ty;
+        for (; b + 3 * DBF_GROUPS < nblocks; b += 4 * DBF_GROUPS) {      // four loads in flight
+            const float v0 = partial[b * F + f], v1 = partial[(b + DBF_GROUPS) * F + f];
+            const float v2 = partial[(b + 2 * DBF_GROUPS) * F + f], v3 = partial[(b + 3 * DBF_GROUPS) * F + f];
+            s += static_cast<double>(v0); s += static_cast<double>(v1);
+            s += static_cast<double>(v2); s += static_cast<double>(v3);
+        }
+        for (; b < nblocks; b += DBF_GROUPS) s += static_cast<double>(partial[b * F + f]);
+    }
     red[ty][tx] = s;
     __syncthreads();
     if (ty == 0 && f < F) {
         double t = 0.0;
-        for (int y = 0; y < 8; ++y) t += red[y][tx];
+        for (int y = 0; y < DBF_GROUPS; ++y) t += red[y][tx];
         dbias[f] = static_cast<float>(t);
     }
 }
@@ -272,7 +281,7 @@ int launch_relu_mask_dbias(int64_t n, int F, const void *src, int64_t lds, int s
     if (F <= 0) return CAPGNN_OK;
     if (n <= 0) {   // no rows: the bias gradient is zero (summing zero partial blocks)
         if (dbias) {
-            hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 31) / 32), dim3(256), 0, stream, int64_t(0), F,
+            hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 31) / 32), dim3(32 * DBF_GROUPS), 0, stream, int64_t(0), F,
                                static_cast<const float *>(nullptr), dbias);
             CG_HIP(hipGetLastError());
         }
@@ -299,7 +308,7 @@ int launch_relu_mask_dbias(int64_t n, int F, const void *src, int64_t lds, int s
                            relu, dbias ? static_cast<float *>(ws) : nullptr, row_scale);
         CG_HIP(hipGetLastError());
         if (dbias) {
-            hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 31) / 32), dim3(256), 0, stream, nb, F,
+            hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 31) / 32), dim3(32 * DBF_GROUPS), 0, stream, nb, F,
                                static_cast<const float *>(ws), dbias);
             CG_HIP(hipGetLastError());
         }
@@ -315,7 +324,7 @@ int launch_relu_mask_dbias(int64_t n, int F, const void *src, int64_t lds, int s
                            relu, dbias ? static_cast<float *>(ws) : nullptr, row_scale);
         CG_HIP(hipGetLastError());
         if (dbias) {
-            hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 31) / 32), dim3(256), 0, stream, nb, F,
+            hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 31) / 32), dim3(32 * DBF_GROUPS), 0, stream, nb, F,
                                static_cast<const float *>(ws), dbias);
             CG_HIP(hipGetLastError());
         }
@@ -330,7 +339,7 @@ int launch_relu_mask_dbias(int64_t n, int F, const void *src, int64_t lds, int s
                        relu, dbias ? static_cast<float *>(ws) : nullptr, row_scale);
     CG_HIP(hipGetLastError());
     if (dbias) {
-        hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 31) / 32), dim3(256), 0, stream, nb, F,
+        hipLaunchKernelGGL(dbias_final_kernel, dim3((F + 31) / 32), dim3(32 * DBF_GROUPS), 0, stream, nb, F,
                            static_cast<const float *>(ws), dbias);
         CG_HIP(hipGetLastError());
     }
@@ -482,6 +491,69 @@ __global__ __launch_bounds__(64) void loss_final_kernel(int parts, const double 
     loss_out[0] = static_cast<float>(c / norm);
 }
 
+// Up to LOSS_SMALL_N rows: one workgroup does a whole reduction (16-byte loads, fixed order), which saves the second
+// launch of the two-level form; these kernels run for a few microseconds either way.
+constexpr int64_t LOSS_SMALL_N = int64_t(1) << 18;
+
+__device__ __forceinline__ int nonzero_bytes(uint32_t w) {
+    return ((w & 0xffu) != 0) + ((w & 0xff00u) != 0) + ((w & 0xff0000u) != 0) + ((w & 0xff000000u) != 0);
+}
+
+// norm_out[0] = max(number of masked rows, 1) * times; mask must start on a 16-byte boundary
+__global__ __launch_bounds__(1024) void count_small_kernel(int64_t n, const uint8_t *mask, float times, float *norm_out) {
+    __shared__ double red[1024];
+    const int64_t n16 = n / 16;
+    const uint4 *m4 = reinterpret_cast<const uint4 *>(mask);
+    int cnt = 0;
+    for (int64_t i = threadIdx.x; i < n16; i += 1024) {
+        const uint4 v = m4[i];
+        cnt += nonzero_bytes(v.x) + nonzero_bytes(v.y) + nonzero_bytes(v.z) + nonzero_bytes(v.w);
+    }
+    for (int64_t i = n16 * 16 + threadIdx.x; i < n; i += 1024) cnt += mask[i] ? 1 : 0;
+    const double c = block_sum_1024(static_cast<double>(cnt), red);
+    if (threadIdx.x == 0) norm_out[0] = (c > 0.0 ? static_cast<float>(c) : 1.f) * times;
+}
+
+// loss_out[0] = sum(row_loss) / norm; row_loss must start on a 16-byte boundary
+__global__ __launch_bounds__(1024) void loss_small_kernel(int64_t n, const float *row_loss, float norm_val, const float *norm_dev,
+                                                          float *loss_out) {
+    __shared__ double red[1024];
+    const int64_t n4 = n / 4;
+    const float4 *r4 = reinterpret_cast<const float4 *>(row_loss);
+    double c = 0.0;
+    for (int64_t i = threadIdx.x; i < n4; i += 1024) {
+        const float4 v = r4[i];
+        c += static_cast<double>(v.x); c += static_cast<double>(v.y); c += static_cast<double>(v.z); c += static_cast<double>(v.w);
+    }
+    for (int64_t i = n4 * 4 + threadIdx.x; i < n; i += 1024) c += static_cast<double>(row_loss[i]);
+    c = block_sum_1024(c, red);
+    if (threadIdx.x == 0) {
+        const double norm = norm_dev ? static_cast<double>(norm_dev[0]) : static_cast<double>(norm_val);
+        loss_out[0] = static_cast<float>(c / norm);
+    }
+}
+
+// the two reductions around a loss kernel: the normaliser from the mask, and the loss from the per-row terms
+static void launch_mask_count(int64_t n, const uint8_t *mask, float times, double *part, int parts, float *norm_dev,
+                              hipStream_t st) {
+    if (n <= LOSS_SMALL_N && reinterpret_cast<uintptr_t>(mask) % 16 == 0) {
+        hipLaunchKernelGGL(count_small_kernel, dim3(1), dim3(1024), 0, st, n, mask, times, norm_dev);
+        return;
+    }
+    hipLaunchKernelGGL(count_mask_kernel, dim3(parts), dim3(1024), 0, st, n, mask, part);
+    hipLaunchKernelGGL(count_final_kernel, dim3(1), dim3(64), 0, st, parts, part, times, norm_dev);
+}
+
+static void launch_loss_sum(int64_t n, const float *row_loss, double *part, int parts, float norm_val, const float *norm_dev,
+                            float *loss_dev, hipStream_t st) {
+    if (n <= LOSS_SMALL_N && reinterpret_cast<uintptr_t>(row_loss) % 16 == 0) {
+        hipLaunchKernelGGL(loss_small_kernel, dim3(1), dim3(1024), 0, st, n, row_loss, norm_val, norm_dev, loss_dev);
+        return;
+    }
+    hipLaunchKernelGGL(loss_partial_kernel, dim3(parts), dim3(1024), 0, st, n, row_loss, part);
+    hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(64), 0, st, parts, part, norm_val, norm_dev, loss_dev);
+}
+
 }  // namespace capgnn
 
 using namespace capgnn;
@@ -508,16 +580,14 @@ extern "C" int capgnn_sigmoid_bce(int64_t n, int C, const float *Z, int64_t ldz,
     else if (!mask) norm_val = static_cast<float>(n) * static_cast<float>(C);
     else {   // masked rows x classes
         norm_dev = static_cast<float *>(ws);
-        hipLaunchKernelGGL(count_mask_kernel, dim3(parts), dim3(1024), 0, st, n, mask, part);
-        hipLaunchKernelGGL(count_final_kernel, dim3(1), dim3(64), 0, st, parts, part, static_cast<float>(C), norm_dev);
+        launch_mask_count(n, mask, static_cast<float>(C), part, parts, norm_dev, st);
     }
     float *row_loss = reinterpret_cast<float *>(static_cast<char *>(ws) + LOSS_HEADER);
     const int lpr = loss_lanes_per_row_host(C);
     const int64_t rows_per_block = 4 * (64 / lpr);
     hipLaunchKernelGGL(sigmoid_bce_kernel, dim3(static_cast<unsigned>((n + rows_per_block - 1) / rows_per_block)), dim3(256), 0, st, n, C, lpr, Z, ldz, targets,
                        ldt, mask, norm_val, norm_dev, row_loss, static_cast<char *>(dZ), lddz, dz_dtype == CAPGNN_BF16 ? 1 : 0);
-    hipLaunchKernelGGL(loss_partial_kernel, dim3(parts), dim3(1024), 0, st, n, row_loss, part);
-    hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(64), 0, st, parts, part, norm_val, norm_dev, loss_dev);
+    launch_loss_sum(n, row_loss, part, parts, norm_val, norm_dev, loss_dev, st);
     CG_HIP(hipGetLastError());
     return CAPGNN_OK;
 }
@@ -541,16 +611,14 @@ extern "C" int capgnn_softmax_ce(int64_t n, int C, const float *Z, int64_t ldz, 
     else if (!mask) norm_val = static_cast<float>(n);
     else {
         norm_dev = scratch;
-        hipLaunchKernelGGL(count_mask_kernel, dim3(parts), dim3(1024), 0, st, n, mask, part);
-        hipLaunchKernelGGL(count_final_kernel, dim3(1), dim3(64), 0, st, parts, part, 1.f, norm_dev);
+        launch_mask_count(n, mask, 1.f, part, parts, norm_dev, st);
     }
     float *row_loss = reinterpret_cast<float *>(static_cast<char *>(ws) + LOSS_HEADER);
     const int lpr = loss_lanes_per_row_host(C);
     const int64_t rows_per_block = 4 * (64 / lpr);
     hipLaunchKernelGGL(softmax_ce_kernel, dim3(static_cast<unsigned>((n + rows_per_block - 1) / rows_per_block)), dim3(256), 0, st, n, C, lpr, Z, ldz,
                        labels, mask, norm_val, norm_dev, row_loss, static_cast<char *>(dZ), lddz, dz_dtype == CAPGNN_BF16 ? 1 : 0);
-    hipLaunchKernelGGL(loss_partial_kernel, dim3(parts), dim3(1024), 0, st, n, row_loss, part);
-    hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(64), 0, st, parts, part, norm_val, norm_dev, loss_dev);
+    launch_loss_sum(n, row_loss, part, parts, norm_val, norm_dev, loss_dev, st);
     CG_HIP(hipGetLastError());
     return CAPGNN_OK;
 }
