@@ -128,8 +128,9 @@ class DeviceProblem:
                 self.cache.fill(l, prob.tables[l])
             self.cache.set_miss_mode(miss_mode)
 
-        per16 = 16 // self.es
-        self.ld0 = synth.pad_to(cfg.dims[0], per16)
+        # input rows start on cache-line boundaries: a 32-float step of a product then reads one line per row, and the
+        # halo gather writes whole lines
+        self.ld0 = synth.pad_to(cfg.dims[0], 128 // self.es)
         self.X0 = padded_matrix(prob.X0, self.ld0, rows=part.n_cols)
 
         self.W, self.W_self, self.bias = [], [], []
