@@ -95,15 +95,30 @@ __device__ __forceinline__ void zero_row(char *d, int row_bytes, int l, int lpr,
 // is a single load wide (the copy is latency-bound otherwise: index, row, store are three dependent round trips).
 constexpr int SCATTER_ROWS = 4;
 
-__global__ __launch_bounds__(256) void scatter_tier_kernel(const char *table, int64_t pitch, const int32_t *dst_list,
-                                                           int64_t n, char *out, int64_t out_pitch, int row_bytes,
-                                                           int lpr, int vec16, int es) {
+// One tier's rows and where they go; `blocks` workgroups of the launch work on it.
+struct TierRows {
+    const char *table;
+    const int32_t *dst_list;
+    int64_t n;
+    unsigned blocks;
+};
+
+// One launch serves up to two tiers of the same layer (same pitch and row geometry): workgroups [0, a.blocks) take
+// tier a, the rest tier b.
+__global__ __launch_bounds__(256) void scatter_tier_kernel(TierRows a, TierRows b, int64_t pitch, char *out,
+                                                           int64_t out_pitch, int row_bytes, int lpr, int vec16, int es) {
+    const bool second = blockIdx.x >= a.blocks;            // uniform over the workgroup
+    const char *table = second ? b.table : a.table;
+    const int32_t *dst_list = second ? b.dst_list : a.dst_list;
+    const int64_t n = second ? b.n : a.n;
+    const unsigned blocks = second ? b.blocks : a.blocks;
+    const unsigned bx = second ? blockIdx.x - a.blocks : blockIdx.x;
     const int lane = threadIdx.x & 63;
     const int l = lane % lpr;
     const int rows_per_wave = 64 / lpr;
-    const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int64_t wave = static_cast<int64_t>(bx) * 4 + (threadIdx.x >> 6);
     const int64_t per_wave = static_cast<int64_t>(rows_per_wave) * SCATTER_ROWS;
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * 4 * per_wave;   // a capped grid walks the list in strides
+    const int64_t stride = static_cast<int64_t>(blocks) * 4 * per_wave;   // a capped grid walks the list in strides
     for (int64_t base = wave * per_wave; base < n; base += stride) {
         const int64_t k0 = base + lane / lpr;
         const char *src[SCATTER_ROWS];
@@ -353,8 +368,32 @@ int gather_all_hits(const capgnn_cache *c, int layer, void *out, int64_t ld, hip
     CopyGeom g;
     const char *tab = c->gpu_tier + c->gpu_off[layer];
     CG_TRY(copy_geom(c, layer, out, ld, tab, &g));
-    hipLaunchKernelGGL(scatter_tier_kernel, dim3(scatter_blocks_for(c->cap_gpu, g.lpr)), dim3(256), 0, st, tab, c->pitch[layer],
-                       c->gpu_list_d, c->cap_gpu, static_cast<char *>(out), g.out_pitch, g.row_bytes, g.lpr, g.vec16, g.es);
+    const TierRows a{tab, c->gpu_list_d, c->cap_gpu, scatter_blocks_for(c->cap_gpu, g.lpr)}, none{nullptr, nullptr, 0, 0};
+    hipLaunchKernelGGL(scatter_tier_kernel, dim3(a.blocks), dim3(256), 0, st, a, none, c->pitch[layer],
+                       static_cast<char *>(out), g.out_pitch, g.row_bytes, g.lpr, g.vec16, g.es);
+    CG_HIP(hipGetLastError());
+    return CAPGNN_OK;
+}
+
+// Both device-resident sources of one layer's halo rows in one launch: the GPU tier and the staged copy of the host
+// tier (the caller has made `st` wait for that copy).
+int gather_hits_and_staged(const capgnn_cache *c, int layer, void *out, int64_t ld, void *staging, hipStream_t st) {
+    if (c->cap_gpu == 0) return scatter_staged(c, layer, out, ld, staging, st);
+    if (c->n_host == 0) return gather_all_hits(c, layer, out, ld, st);
+    if (!staging) CG_FAIL(CAPGNN_EINVAL, "halo_gather: staging area is NULL");
+    const char *tab = c->gpu_tier + c->gpu_off[layer];
+    const char *stab = static_cast<const char *>(staging) + c->host_off[layer];
+    CopyGeom g, gs;
+    CG_TRY(copy_geom(c, layer, out, ld, tab, &g));
+    CG_TRY(copy_geom(c, layer, out, ld, stab, &gs));
+    if (g.vec16 != gs.vec16 || g.lpr != gs.lpr) {       // differently aligned sources: one launch each
+        CG_TRY(gather_all_hits(c, layer, out, ld, st));
+        return scatter_staged(c, layer, out, ld, staging, st);
+    }
+    const TierRows a{tab, c->gpu_list_d, c->cap_gpu, scatter_blocks_for(c->cap_gpu, g.lpr)};
+    const TierRows b{stab, c->host_list_d, c->n_host, scatter_blocks_for(c->n_host, g.lpr)};
+    hipLaunchKernelGGL(scatter_tier_kernel, dim3(a.blocks + b.blocks), dim3(256), 0, st, a, b, c->pitch[layer],
+                       static_cast<char *>(out), g.out_pitch, g.row_bytes, g.lpr, g.vec16, g.es);
     CG_HIP(hipGetLastError());
     return CAPGNN_OK;
 }
@@ -376,8 +415,9 @@ static int scatter_host_rows(const capgnn_cache *c, int layer, const char *tab, 
     // requests in flight and leaves the compute units to the kernels of the main stream.
     unsigned blocks = scatter_blocks_for(c->n_host, g.lpr);
     if (pinned && blocks > HOST_READ_BLOCKS) blocks = HOST_READ_BLOCKS;
-    hipLaunchKernelGGL(scatter_tier_kernel, dim3(blocks), dim3(256), 0, st, tab, c->pitch[layer],
-                       c->host_list_d, c->n_host, static_cast<char *>(out), g.out_pitch, g.row_bytes, g.lpr, g.vec16, g.es);
+    const TierRows a{tab, c->host_list_d, c->n_host, blocks}, none{nullptr, nullptr, 0, 0};
+    hipLaunchKernelGGL(scatter_tier_kernel, dim3(blocks), dim3(256), 0, st, a, none, c->pitch[layer],
+                       static_cast<char *>(out), g.out_pitch, g.row_bytes, g.lpr, g.vec16, g.es);
     CG_HIP(hipGetLastError());
     return CAPGNN_OK;
 }

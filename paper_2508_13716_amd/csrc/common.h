@@ -181,5 +181,6 @@ int gather_all_misses(const capgnn_cache *c, int layer, void *out, int64_t ld, v
 // the two halves of the staged path: DMA of the layer's host tier into the staging area, scatter from there
 int stage_misses(const capgnn_cache *c, int layer, void *staging, hipStream_t st);
 int scatter_staged(const capgnn_cache *c, int layer, void *out, int64_t ld, void *staging, hipStream_t st);
+int gather_hits_and_staged(const capgnn_cache *c, int layer, void *out, int64_t ld, void *staging, hipStream_t st);
 
 }  // namespace capgnn

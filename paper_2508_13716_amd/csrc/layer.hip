@@ -472,22 +472,23 @@ static int epoch_impl(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer
         char *X = Xl(l);
         char *halo = halo_rows(l);
         if (c) {
-            {
-                Scope s(CAPGNN_K_GATHER_HIT, l, 0, st);
-                CG_TRY(gather_all_hits(c, l, halo, p.ldx[l], st));
-            }
             if (pipelined) {
+                // the staged rows landed while the previous epoch ran: both device-resident sources in one launch
                 CG_HIP(hipStreamWaitEvent(st, c->ev_layer[l], 0));
                 {
-                    Scope s(CAPGNN_K_GATHER_STAGED, l, 0, st);   // a device copy, like the GPU tier's
-                    CG_TRY(scatter_staged(c, l, halo, p.ldx[l], staging, st));
+                    Scope s(CAPGNN_K_GATHER_HIT, l, 0, st);
+                    CG_TRY(gather_hits_and_staged(c, l, halo, p.ldx[l], staging, st));
                 }
                 CG_HIP(hipEventRecord(c->ev_consumed[l], st));
                 CG_HIP(hipStreamWaitEvent(side, c->ev_consumed[l], 0));
                 Scope s(CAPGNN_K_GATHER_MISS, l, 0, side);     // the next epoch's rows of this layer
                 CG_TRY(stage_misses(c, l, staging, side));
                 CG_HIP(hipEventRecord(c->ev_layer[l], side));
-            } else if (has_miss) {
+            } else {
+                Scope s(CAPGNN_K_GATHER_HIT, l, 0, st);
+                CG_TRY(gather_all_hits(c, l, halo, p.ldx[l], st));
+            }
+            if (!pipelined && has_miss) {
                 if (side != st) {
                     if (g_rec.on) {
                         // the recorder's stop event of this layer's transfer doubles as the join point
