@@ -786,6 +786,8 @@ struct SplitColLoader {
     bool idle;                      // narrow second tiles leave a wave without work
 
     static constexpr int bytes(int bt_) { return 3 * 8 * bt_ * 8; }
+    // where column `row` of a tile sits inside its (piece, k / 4) plane, in 8-byte units (see put())
+    static __device__ __forceinline__ int col_slot(int row) { return row ^ ((row >> 3) & 2); }
 
     __device__ __forceinline__ void init(const GemmArgs &g, int64_t m0, int64_t n0, int bm, int bn, char *As, char *Bs, int tid) {
         const bool second = __builtin_amdgcn_readfirstlane(tid >> 7) != 0;        // uniform over the wave
@@ -847,9 +849,12 @@ struct SplitColLoader {
         for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
             for (int p = 0; p < 3; ++p) {
-                char *dst = s + (((p * 8 + kb + 4 * blk) * bt) + 4 * tq) * 8;      // the thread's four columns: 32 bytes
-                *reinterpret_cast<uint4 *>(dst) = make_uint4(pk[blk][0][p].x, pk[blk][0][p].y, pk[blk][1][p].x, pk[blk][1][p].y);
-                *reinterpret_cast<uint4 *>(dst + 16) = make_uint4(pk[blk][2][p].x, pk[blk][2][p].y, pk[blk][3][p].x, pk[blk][3][p].y);
+                // the thread's four columns: 32 bytes.  Eight neighbouring lanes write 16 bytes each, 32 bytes apart: every
+                // second group of four swaps its two halves (col_slot below), so that one store covers all the banks.
+                char *dst = s + (((p * 8 + kb + 4 * blk) * bt) + 4 * tq) * 8;
+                const int sw = ((tq >> 2) & 1) * 16;
+                *reinterpret_cast<uint4 *>(dst + sw) = make_uint4(pk[blk][0][p].x, pk[blk][0][p].y, pk[blk][1][p].x, pk[blk][1][p].y);
+                *reinterpret_cast<uint4 *>(dst + 16 - sw) = make_uint4(pk[blk][2][p].x, pk[blk][2][p].y, pk[blk][3][p].x, pk[blk][3][p].y);
             }
     }
 };
@@ -927,8 +932,9 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(GemmArgs g, const ui
                     const int row = wm * WM + i * 32 + l32;
                     uint4 v;
                     if constexpr (TRANS) {
-                        const uint2 v0 = *reinterpret_cast<const uint2 *>(As + ((p * 8 + 4 * ks + 2 * half) * BM + row) * 8);
-                        const uint2 v1 = *reinterpret_cast<const uint2 *>(As + ((p * 8 + 4 * ks + 2 * half + 1) * BM + row) * 8);
+                        const int slot = SplitColLoader::col_slot(row);
+                        const uint2 v0 = *reinterpret_cast<const uint2 *>(As + ((p * 8 + 4 * ks + 2 * half) * BM + slot) * 8);
+                        const uint2 v1 = *reinterpret_cast<const uint2 *>(As + ((p * 8 + 4 * ks + 2 * half + 1) * BM + slot) * 8);
                         v = make_uint4(v0.x, v0.y, v1.x, v1.y);
                     } else {
                         v = *reinterpret_cast<const uint4 *>(As + Units16<BM>::at(p, 2 * ks + half, row));
@@ -940,8 +946,9 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(GemmArgs g, const ui
                     const int row = wn * WN + j * 32 + l32;
                     uint4 v;
                     if constexpr (TRANS) {
-                        const uint2 v0 = *reinterpret_cast<const uint2 *>(Bs + ((p * 8 + 4 * ks + 2 * half) * BN + row) * 8);
-                        const uint2 v1 = *reinterpret_cast<const uint2 *>(Bs + ((p * 8 + 4 * ks + 2 * half + 1) * BN + row) * 8);
+                        const int slot = SplitColLoader::col_slot(row);
+                        const uint2 v0 = *reinterpret_cast<const uint2 *>(Bs + ((p * 8 + 4 * ks + 2 * half) * BN + slot) * 8);
+                        const uint2 v1 = *reinterpret_cast<const uint2 *>(Bs + ((p * 8 + 4 * ks + 2 * half + 1) * BN + slot) * 8);
                         v = make_uint4(v0.x, v0.y, v1.x, v1.y);
                     } else {
                         v = *reinterpret_cast<const uint4 *>(Bs + Units16<BN>::at(p, 2 * ks + half, row));
