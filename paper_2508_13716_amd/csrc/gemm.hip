@@ -1006,6 +1006,147 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(GemmArgs g, const ui
     }
 }
 
+// The weight gradient once more, with eight waves on a 128 x 128 tile (2 x 4, each a 64 x 32 part): half the staging
+// and half the accumulators per thread, so that four waves share a SIMD and one wave's cutting and LDS traffic run
+// beside another's matrix instructions.  Same LDS image as gemm_split_kernel<true, ...>.
+struct SplitColLoader8 {
+    f32x4 r[4];                     // one block of 4 k x 4 columns per thread
+    const f32x4 *pf;
+    const char *base;
+    int64_t ld, t0, T;
+    char *s;
+    int kb, tq;                     // the thread's k-block (0..7) and column group (0..31)
+    uint2 pk[4][3];                 // [column][piece], four k each
+
+    __device__ __forceinline__ void init(const GemmArgs &g, int64_t m0, int64_t n0, char *As, char *Bs, int tid) {
+        const bool second = __builtin_amdgcn_readfirstlane(tid >> 8) != 0;        // uniform over the wave
+        base = second ? g.B : g.A;
+        ld = second ? g.ldb : g.lda;
+        t0 = second ? n0 : m0;
+        T = second ? g.N : g.M;
+        s = second ? Bs : As;
+        const int tt = tid & 255;
+        kb = tt >> 5; tq = tt & 31;
+    }
+
+    __device__ __forceinline__ void fetch(int64_t k0, int64_t k_end, int vec) {
+        const int64_t t = t0 + 4 * tq;
+        const int ncol = static_cast<int>(T - t < 4 ? (T - t > 0 ? T - t : 0) : 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t k = k0 + 4 * kb + j;
+            const float4 v = load4<false>(base, k * ld + t, k < k_end ? ncol : 0, vec);
+            r[j] = f32x4{v.x, v.y, v.z, v.w};
+        }
+    }
+
+    __device__ __forceinline__ void fast_begin(int64_t k0) {
+        pf = reinterpret_cast<const f32x4 *>(base + ((k0 + 4 * kb) * ld + t0 + 4 * tq) * 4);
+    }
+
+    __device__ __forceinline__ void fetch_fast() {
+        const int64_t ld4 = ld / 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r[j] = pf[j * ld4];
+        pf += SBK * ld4;
+    }
+
+    __device__ __forceinline__ void cut() {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            uint32_t lo[3], hi[3];
+            split3_pair(r[0][c], r[1][c], lo);
+            split3_pair(r[2][c], r[3][c], hi);
+#pragma unroll
+            for (int p = 0; p < 3; ++p) pk[c][p] = make_uint2(lo[p], hi[p]);
+        }
+    }
+
+    __device__ __forceinline__ void put() const {
+        const int sw = ((tq >> 2) & 1) * 16;       // see SplitColLoader::put
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            char *dst = s + (((p * 8 + kb) * 128) + 4 * tq) * 8;
+            *reinterpret_cast<uint4 *>(dst + sw) = make_uint4(pk[0][p].x, pk[0][p].y, pk[1][p].x, pk[1][p].y);
+            *reinterpret_cast<uint4 *>(dst + 16 - sw) = make_uint4(pk[2][p].x, pk[2][p].y, pk[3][p].x, pk[3][p].y);
+        }
+    }
+};
+
+__global__ __launch_bounds__(512, 2) void gemm_split_trans8_kernel(GemmArgs g) {
+    constexpr int BM = 128, BN = 128, WM = 64, WN = 32, TM = 2;
+    constexpr int A_BYTES = SplitColLoader::bytes(BM), B_BYTES = SplitColLoader::bytes(BN);
+    __shared__ __attribute__((aligned(16))) char smem[A_BYTES + B_BYTES];
+    char *As = smem, *Bs = smem + A_BYTES;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    const int l32 = lane & 31, half = lane >> 5;
+    int bx, by, bz;
+    if (!tile_coords(g, &bx, &by, &bz)) return;      // uniform over the workgroup
+    const int64_t m0 = static_cast<int64_t>(by) * BM;
+    const int64_t n0 = static_cast<int64_t>(bx) * BN;
+    const int64_t k_begin = static_cast<int64_t>(bz) * g.k_chunk;
+    const int64_t k_end = (k_begin + g.k_chunk < g.K) ? k_begin + g.k_chunk : g.K;
+
+    floatx16 acc[TM][1];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][0][r] = 0.f;
+
+    SplitColLoader8 lc;
+    const int64_t nk = (k_end > k_begin) ? (k_end - k_begin + SBK - 1) / SBK : 0;
+    const int64_t nk_full = (k_end > k_begin) ? (k_end - k_begin) / SBK : 0;
+    const bool interior = m0 + BM <= g.M && n0 + BN <= g.N && g.a_vec && g.b_vec;
+    const int both_vec = g.a_vec && g.b_vec;
+    lc.init(g, m0, n0, As, Bs, tid);
+    if (nk > 0) {
+        lc.fetch(k_begin, k_end, both_vec);
+        lc.cut();
+        lc.put();
+        if (interior) lc.fast_begin(k_begin + SBK);
+    }
+    __syncthreads();
+    const int slot_b = SplitColLoader::col_slot(wn * WN + l32);
+    auto products = [&]() {
+#pragma unroll
+        for (int ks = 0; ks < SBK / 16; ++ks) {
+            bf16x8 a[3][TM], b[3];
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const int slot = SplitColLoader::col_slot(wm * WM + i * 32 + l32);
+                    const uint2 v0 = *reinterpret_cast<const uint2 *>(As + ((p * 8 + 4 * ks + 2 * half) * BM + slot) * 8);
+                    const uint2 v1 = *reinterpret_cast<const uint2 *>(As + ((p * 8 + 4 * ks + 2 * half + 1) * BM + slot) * 8);
+                    a[p][i] = __builtin_bit_cast(bf16x8, make_uint4(v0.x, v0.y, v1.x, v1.y));
+                }
+                const uint2 w0 = *reinterpret_cast<const uint2 *>(Bs + ((p * 8 + 4 * ks + 2 * half) * BN + slot_b) * 8);
+                const uint2 w1 = *reinterpret_cast<const uint2 *>(Bs + ((p * 8 + 4 * ks + 2 * half + 1) * BN + slot_b) * 8);
+                b[p] = __builtin_bit_cast(bf16x8, make_uint4(w0.x, w0.y, w1.x, w1.y));
+            }
+            // the six piece products, smallest first
+#define CG_PIECES8(PA_, PB_)                                                                                                 \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                                           \
+        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[PA_][i], b[PB_], acc[i][0], 0, 0, 0);
+            CG_PIECES8(2, 0) CG_PIECES8(0, 2) CG_PIECES8(1, 1) CG_PIECES8(1, 0) CG_PIECES8(0, 1) CG_PIECES8(0, 0)
+#undef CG_PIECES8
+        }
+    };
+    for (int64_t kt = 0; kt + 1 < nk; ++kt) {
+        if (interior && kt + 1 < nk_full) lc.fetch_fast();
+        else lc.fetch(k_begin + (kt + 1) * SBK, k_end, both_vec);
+        products();
+        __syncthreads();            // every wave has read this step's operands
+        lc.cut();
+        lc.put();
+        __syncthreads();
+    }
+    if (nk > 0) products();
+    store_tile<TM, 1>(g, acc, m0 + wm * WM, n0 + wn * WN, l32, half, bz);
+}
+
 // Cuts the (small) second operand of a plain product into bf16 pieces laid out in 16-byte units
 // Wt[piece][k / 8][n][k % 8], n_pad rows, ku_total units along k, zero beyond N and K.  kc: the source is [n][k]
 // (pitch ldw), else [k][n].
@@ -1187,7 +1328,9 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
     dim3 grid(static_cast<unsigned>(n_wg), 1, 1);
     bool akc = !trans_a, bkc = trans_b != 0;
     if (split_path) {
-        if (trans_a) {
+        if (trans_a && bn == 128) {
+            hipLaunchKernelGGL(gemm_split_trans8_kernel, grid, dim3(512), 0, stream, g);
+        } else if (trans_a) {
             launch_split_tiles<true>(g, bn, grid, nullptr, 0, 0, stream);
         } else {
             const int64_t n_pad = split_rows(N), ku_total = split_ld(K) / 8;
