@@ -135,17 +135,23 @@ __device__ __forceinline__ void store_tile(const GemmArgs &g, const floatx16 (&a
 // The same through LDS: a wave rounds 32 rows of its accumulators at a time into a private LDS area (lds, STAGE_BYTES
 // per wave) and leaves along the rows of C, 16 bytes per lane, so that a store instruction covers 4 rows x 256 bytes
 // instead of 2 x 128 and the read-modify-write of an accumulating product moves whole vectors.  fp32 results only.
-constexpr int STAGE_PITCH = 64 + 8;                         // floats per staged row (four rows further = other half of the banks)
-constexpr int STAGE_BYTES = 32 * STAGE_PITCH * 4;           // per wave
+template <int TN> constexpr int STAGE_PITCH_T = TN * 32 + 8;  // floats per staged row (four rows further = other half of the banks)
+template <int TN> constexpr int STAGE_BYTES_T = 32 * STAGE_PITCH_T<TN> * 4;   // per wave
+constexpr int STAGE_BYTES = STAGE_BYTES_T<2>;
 
-__device__ __forceinline__ void store_tile_staged(const GemmArgs &g, const floatx16 (&acc)[2][2], float *lds, int64_t row0,
+// TN: 32-column accumulator tiles side by side in the wave's part (2 or 1)
+template <int TN>
+__device__ __forceinline__ void store_tile_staged(const GemmArgs &g, const floatx16 (&acc)[2][TN], float *lds, int64_t row0,
                                                   int64_t col0, int lane, int bz) {
+    constexpr int STAGE_PITCH = STAGE_PITCH_T<TN>;
+    constexpr int CGS = TN * 8;                              // groups of four columns in a row
+    constexpr int RPP = 64 / CGS;                            // rows per pass of the wave
     const int l32 = lane & 31, half = lane >> 5;
     float *dst = g.part ? g.part + static_cast<int64_t>(bz) * g.M * g.N : reinterpret_cast<float *>(g.C);
     const int64_t ld = g.part ? g.N : g.ldc;
     const bool vec = (reinterpret_cast<uintptr_t>(dst) % 16 == 0) && (ld % 4 == 0);
     const bool plain = g.part != nullptr;                   // partials take no epilogue
-    const int cg = lane & 15, rq = lane >> 4;               // the lane's column group (4 columns) and row within a quad of rows
+    const int cg = lane % CGS, rq = lane / CGS;             // the lane's column group (4 columns) and row within a pass
     const int64_t col = col0 + 4 * cg;
     float bv[4] = {0.f, 0.f, 0.f, 0.f};
     if (!plain && g.bias)
@@ -155,14 +161,14 @@ __device__ __forceinline__ void store_tile_staged(const GemmArgs &g, const float
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) lds[(8 * (r >> 2) + 4 * half + (r & 3)) * STAGE_PITCH + j * 32 + l32] = acc[i][j][r];
         __builtin_amdgcn_wave_barrier();
         if (col < g.N) {
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const int lr = 4 * t + rq;
+            for (int t = 0; t < 32 / RPP; ++t) {
+                const int lr = RPP * t + rq;
                 const int64_t row = row0 + i * 32 + lr;
                 if (row >= g.M) continue;
                 const float4 v4 = *reinterpret_cast<const float4 *>(&lds[lr * STAGE_PITCH + 4 * cg]);
@@ -674,9 +680,9 @@ struct Units16 {
 };
 
 // operand stored along the reduction index, cut while staged: a row's 32 k are eight float4 of eight threads
-template <int BT>
+template <int BT, int NT = 256>
 struct SplitRowLoader {
-    static constexpr int NLD = BT * SBK / 4 / 256;
+    static constexpr int NLD = BT * SBK / 4 / NT;
     float4 r[NLD];
     const char *pf[NLD];
 
@@ -684,7 +690,7 @@ struct SplitRowLoader {
                                           int vec, int tid) {
 #pragma unroll
         for (int q = 0; q < NLD; ++q) {
-            const int idx = tid + 256 * q;
+            const int idx = tid + NT * q;
             const int row = idx >> 3, kq = idx & 7;
             const int64_t t = t0 + row, k = k0 + 4 * kq;
             const int nv = (t < T) ? static_cast<int>(k_end - k < 4 ? k_end - k : 4) : 0;
@@ -695,7 +701,7 @@ struct SplitRowLoader {
     __device__ __forceinline__ void fast_begin(const char *base, int64_t ld, int64_t t0, int64_t k0, int tid) {
 #pragma unroll
         for (int q = 0; q < NLD; ++q) {
-            const int idx = tid + 256 * q;
+            const int idx = tid + NT * q;
             pf[q] = base + ((t0 + (idx >> 3)) * ld + k0 + 4 * (idx & 7)) * 4;
         }
     }
@@ -724,7 +730,7 @@ struct SplitRowLoader {
     __device__ __forceinline__ void put(char *s, int tid) const {
 #pragma unroll
         for (int q = 0; q < NLD; ++q) {
-            const int idx = tid + 256 * q;
+            const int idx = tid + NT * q;
             const int row = idx >> 3, kq = idx & 7;
 #pragma unroll
             for (int p = 0; p < 3; ++p)
@@ -736,33 +742,33 @@ struct SplitRowLoader {
 // second operand already cut into units Wt[piece][k / 8][n] (n padded to whole tiles, k to whole steps): plain copies
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-template <int BT>
+template <int BT, int NT = 256>
 struct SplitPlaneLoader {
-    static constexpr int NLD = 3 * 4 * BT / 256;
+    static constexpr int NLD = 3 * 4 * BT / NT;
     u32x4 r[NLD];
     const u32x4 *pf;                // the thread's first unit; its others lie q * stride_q further on
     int64_t stride_q;               // in units
 
-    // ku_total: 16-byte units along k of one piece; n_pad: rows of a plane.  256 consecutive units of the LDS image
-    // (piece, u, row) are 256 / BT planes of BT rows: thread tid copies row tid % BT of planes tid / BT + q * 256 / BT.
+    // ku_total: 16-byte units along k of one piece; n_pad: rows of a plane.  NT consecutive units of the LDS image
+    // (piece, u, row) are NT / BT planes of BT rows: thread tid copies row tid % BT of planes tid / BT + q * NT / BT.
     __device__ __forceinline__ void begin(const uint16_t *Wt, int64_t ku_total, int64_t n_pad, int64_t t0, int64_t k0, int tid) {
-        static_assert(BT == 128 || BT == 64, "planes per pass: 2 or 4, both divide the 4 units of a piece");
+        static_assert((BT == 128 || BT == 64) && (NT / BT == 2 || NT / BT == 4), "planes per pass: 2 or 4, both divide the 4 units of a piece");
         const int pu = tid / BT, row = tid % BT;
         pf = reinterpret_cast<const u32x4 *>(Wt) + (k0 / 8 + pu) * n_pad + t0 + row;
-        stride_q = (256 / BT) * n_pad;
+        stride_q = (NT / BT) * n_pad;
         piece_stride = (ku_total - 4) * n_pad;
     }
     int64_t piece_stride;           // extra distance when q crosses into the next piece
 
     __device__ __forceinline__ void fetch(int64_t n_pad) {
-        constexpr int PPQ = 256 / BT;           // planes per pass
+        constexpr int PPQ = NT / BT;           // planes per pass
 #pragma unroll
         for (int q = 0; q < NLD; ++q) r[q] = pf[q * stride_q + ((q * PPQ) / 4) * piece_stride];
         pf += (SBK / 8) * n_pad;
     }
 
     __device__ __forceinline__ void stash(char *s, int tid) const {
-        constexpr int PPQ = 256 / BT;
+        constexpr int PPQ = NT / BT;
         const int pu0 = tid / BT, row = tid % BT;
 #pragma unroll
         for (int q = 0; q < NLD; ++q) {
@@ -861,9 +867,13 @@ struct SplitColLoader {
 
 // TRANS: C = A^T B with both operands stored across the reduction index (the weight gradient); otherwise A is
 // stored along it and the second operand comes cut into units (Wt: ku_total units along k per piece, n_pad rows).
-template <bool TRANS, int BM, int BN>
-__global__ __launch_bounds__(256, 2) void gemm_split_kernel(GemmArgs g, const uint16_t *Wt, int64_t ku_total, int64_t n_pad) {
-    constexpr int WM = BM / 2, WN = BN / 2;
+// NW waves: four (2 x 2) or, for the plain product on a 128 x 128 tile, eight (2 x 4, each a 64 x 32 part: half the
+// staging and half the accumulators per thread, four waves per SIMD).
+template <bool TRANS, int BM, int BN, int NW = 4>
+__global__ __launch_bounds__(NW * 64, 2) void gemm_split_kernel(GemmArgs g, const uint16_t *Wt, int64_t ku_total, int64_t n_pad) {
+    static_assert(NW == 4 || (NW == 8 && !TRANS && BN == 128), "eight waves: plain product, 128 columns");
+    constexpr int NT = NW * 64;
+    constexpr int WM = BM / 2, WN = BN / (NW / 2);
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int A_BYTES = TRANS ? SplitColLoader::bytes(BM) : Units16<BM>::BYTES;
     constexpr int B_BYTES = TRANS ? SplitColLoader::bytes(BN) : Units16<BN>::BYTES;
@@ -872,7 +882,7 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(GemmArgs g, const ui
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / (NW / 2), wn = wave % (NW / 2);
     const int l32 = lane & 31, half = lane >> 5;
     int bx, by, bz;
     if (!tile_coords(g, &bx, &by, &bz)) return;      // uniform over the workgroup
@@ -889,8 +899,8 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(GemmArgs g, const ui
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    SplitRowLoader<BM> la_r;
-    SplitPlaneLoader<BN> lb_p;
+    SplitRowLoader<BM, NT> la_r;
+    SplitPlaneLoader<BN, NT> lb_p;
     SplitColLoader lc;
     const int64_t nk = (k_end > k_begin) ? (k_end - k_begin + SBK - 1) / SBK : 0;
     const int64_t nk_full = (k_end > k_begin) ? (k_end - k_begin) / SBK : 0;
@@ -997,10 +1007,10 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(GemmArgs g, const ui
         __syncthreads();
     }
     if (nk > 0) products(std::false_type{});
-    if constexpr (TM == 2 && TN == 2) {
-        static_assert(4 * STAGE_BYTES <= A_BYTES + B_BYTES, "the staged output must fit the operand buffers");
+    if constexpr (TM == 2 && (TN == 2 || TN == 1)) {
+        static_assert(NW * STAGE_BYTES_T<TN> <= A_BYTES + B_BYTES, "the staged output must fit the operand buffers");
         __syncthreads();                    // every wave is done with the operands
-        store_tile_staged(g, acc, reinterpret_cast<float *>(smem + wave * STAGE_BYTES), m0 + wm * WM, n0 + wn * WN, lane, bz);
+        store_tile_staged<TN>(g, acc, reinterpret_cast<float *>(smem + wave * STAGE_BYTES_T<TN>), m0 + wm * WM, n0 + wn * WN, lane, bz);
     } else {
         store_tile<TM, TN>(g, acc, m0 + wm * WM, n0 + wn * WN, l32, half, bz);
     }
@@ -1251,11 +1261,16 @@ static std::atomic<int> f32_product_mode{CAPGNN_F32_PRODUCT_AUTO};
 // the threads that stage their operands would idle; measured slower)
 constexpr int64_t SPLIT_MIN_MACS = int64_t(1) << 28;
 
-template <bool TRANS>
-static void launch_split_tiles(const GemmArgs &g, int bn, dim3 grid, const uint16_t *Wt, int64_t ku_total, int64_t n_pad,
-                               hipStream_t st) {
-    if (bn == 64) hipLaunchKernelGGL((gemm_split_kernel<TRANS, 128, 64>), grid, dim3(256), 0, st, g, Wt, ku_total, n_pad);
-    else hipLaunchKernelGGL((gemm_split_kernel<TRANS, 128, 128>), grid, dim3(256), 0, st, g, Wt, ku_total, n_pad);
+// tiles 64 columns wide keep four waves; 128-column tiles run eight (both forms of the product)
+static void launch_split_tiles(bool trans, const GemmArgs &g, int bn, dim3 grid, const uint16_t *Wt, int64_t ku_total,
+                               int64_t n_pad, hipStream_t st) {
+    if (trans) {
+        if (bn == 64) hipLaunchKernelGGL((gemm_split_kernel<true, 128, 64>), grid, dim3(256), 0, st, g, Wt, ku_total, n_pad);
+        else hipLaunchKernelGGL(gemm_split_trans8_kernel, grid, dim3(512), 0, st, g);
+    } else {
+        if (bn == 64) hipLaunchKernelGGL((gemm_split_kernel<false, 128, 64>), grid, dim3(256), 0, st, g, Wt, ku_total, n_pad);
+        else hipLaunchKernelGGL((gemm_split_kernel<false, 128, 128, 8>), grid, dim3(512), 0, st, g, Wt, ku_total, n_pad);
+    }
 }
 
 template <bool BF16, bool A_KC, bool B_KC>
@@ -1328,16 +1343,14 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
     dim3 grid(static_cast<unsigned>(n_wg), 1, 1);
     bool akc = !trans_a, bkc = trans_b != 0;
     if (split_path) {
-        if (trans_a && bn == 128) {
-            hipLaunchKernelGGL(gemm_split_trans8_kernel, grid, dim3(512), 0, stream, g);
-        } else if (trans_a) {
-            launch_split_tiles<true>(g, bn, grid, nullptr, 0, 0, stream);
+        if (trans_a) {
+            launch_split_tiles(true, g, bn, grid, nullptr, 0, 0, stream);
         } else {
             const int64_t n_pad = split_rows(N), ku_total = split_ld(K) / 8;
             hipLaunchKernelGGL(split_repack_kernel, dim3(static_cast<unsigned>((ku_total * n_pad * 8 + 255) / 256)), dim3(256), 0,
                                stream, static_cast<const float *>(B), ldb, bkc ? 1 : 0, K, N, static_cast<uint16_t *>(ws), n_pad,
                                ku_total);
-            launch_split_tiles<false>(g, bn, grid, static_cast<const uint16_t *>(ws), ku_total, n_pad, stream);
+            launch_split_tiles(false, g, bn, grid, static_cast<const uint16_t *>(ws), ku_total, n_pad, stream);
         }
     } else if (half_path) {
         if (repack_b) {
