@@ -780,103 +780,26 @@ struct SplitPlaneLoader {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// operands stored across the reduction index (both of X^T G): waves 0-1 stage the first operand's tile, waves 2-3 the
-// second's; per thread two blocks of 4 k x 4 columns (k-blocks kb and kb + 4); kept as 8-byte units (piece, k / 4, row)
-struct SplitColLoader {
-    f32x4 r[8];
-    const f32x4 *pf;                // check-free path: the thread's first vector of the next step
-    const char *base;               // this thread's operand
-    int64_t ld, t0, T;
-    char *s;                        // its LDS tile
-    int bt, kb, tq;                 // tile width; the thread's k-block and column group
-    bool idle;                      // narrow second tiles leave a wave without work
-
-    static constexpr int bytes(int bt_) { return 3 * 8 * bt_ * 8; }
-    // where column `row` of a tile sits inside its (piece, k / 4) plane, in 8-byte units (see put())
-    static __device__ __forceinline__ int col_slot(int row) { return row ^ ((row >> 3) & 2); }
-
-    __device__ __forceinline__ void init(const GemmArgs &g, int64_t m0, int64_t n0, int bm, int bn, char *As, char *Bs, int tid) {
-        const bool second = __builtin_amdgcn_readfirstlane(tid >> 7) != 0;        // uniform over the wave
-        base = second ? g.B : g.A;
-        ld = second ? g.ldb : g.lda;
-        t0 = second ? n0 : m0;
-        T = second ? g.N : g.M;
-        s = second ? Bs : As;
-        bt = second ? bn : bm;
-        const int tt = tid & 127, cpr = bt / 4;
-        kb = tt / cpr; tq = tt % cpr;
-        idle = kb >= 4;
-    }
-
-    __device__ __forceinline__ void fetch(int64_t k0, int64_t k_end, int vec) {
-        if (idle) return;
-        const int64_t t = t0 + 4 * tq;
-        const int ncol = static_cast<int>(T - t < 4 ? T - t : 4);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int64_t k = k0 + 4 * kb + 16 * (j >> 2) + (j & 3);
-            const float4 v = load4<false>(base, k * ld + t, k < k_end ? ncol : 0, vec);
-            r[j] = f32x4{v.x, v.y, v.z, v.w};
-        }
-    }
-
-    __device__ __forceinline__ void fast_begin(int64_t k0) {
-        pf = reinterpret_cast<const f32x4 *>(base + ((k0 + 4 * kb) * ld + t0 + 4 * tq) * 4);
-    }
-
-    // the check-free path runs only when rows are whole 16-byte vectors
-    __device__ __forceinline__ void fetch_fast() {
-        if (idle) return;
-        const int64_t ld4 = ld / 4;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) r[j] = pf[(16 * (j >> 2) + (j & 3)) * ld4];
-        pf += SBK * ld4;
-    }
-
-    uint2 pk[2][4][3];              // the pieces of r, ready for LDS: [k-block][column][piece], four k each
-
-    __device__ __forceinline__ void cut() {
-        if (idle) return;
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                uint32_t lo[3], hi[3];
-                split3_pair(r[4 * blk + 0][c], r[4 * blk + 1][c], lo);
-                split3_pair(r[4 * blk + 2][c], r[4 * blk + 3][c], hi);
-#pragma unroll
-                for (int p = 0; p < 3; ++p) pk[blk][c][p] = make_uint2(lo[p], hi[p]);
-            }
-    }
-
-    __device__ __forceinline__ void put() const {
-        if (idle) return;
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-            for (int p = 0; p < 3; ++p) {
-                // the thread's four columns: 32 bytes.  Eight neighbouring lanes write 16 bytes each, 32 bytes apart: every
-                // second group of four swaps its two halves (col_slot below), so that one store covers all the banks.
-                char *dst = s + (((p * 8 + kb + 4 * blk) * bt) + 4 * tq) * 8;
-                const int sw = ((tq >> 2) & 1) * 16;
-                *reinterpret_cast<uint4 *>(dst + sw) = make_uint4(pk[blk][0][p].x, pk[blk][0][p].y, pk[blk][1][p].x, pk[blk][1][p].y);
-                *reinterpret_cast<uint4 *>(dst + 16 - sw) = make_uint4(pk[blk][2][p].x, pk[blk][2][p].y, pk[blk][3][p].x, pk[blk][3][p].y);
-            }
-    }
+// LDS image of an operand stored across the reduction index (both of X^T G): 8-byte units (piece, k / 4, column), a
+// plane of bt columns per (piece, k / 4).  A staging thread holds four neighbouring columns (32 bytes) and stores them
+// as two 16-byte halves; eight neighbouring lanes are 32 bytes apart, so every second group of four lanes swaps its
+// halves and one store covers all the banks.  col_slot() is where a column ends up.
+struct ColUnits8 {
+    static constexpr int bytes(int bt) { return 3 * 8 * bt * 8; }
+    static __device__ __forceinline__ int col_slot(int col) { return col ^ ((col >> 3) & 2); }
 };
 
-// TRANS: C = A^T B with both operands stored across the reduction index (the weight gradient); otherwise A is
-// stored along it and the second operand comes cut into units (Wt: ku_total units along k per piece, n_pad rows).
-// NW waves: four (2 x 2) or, for the plain product on a 128 x 128 tile, eight (2 x 4, each a 64 x 32 part: half the
-// staging and half the accumulators per thread, four waves per SIMD).
-template <bool TRANS, int BM, int BN, int NW = 4>
+// C = A B (or A B^T) with A stored along the reduction index; the second operand comes cut into units (Wt: ku_total
+// units along k per piece, n_pad rows).  NW waves: four (2 x 2) or, on a 128 x 128 tile, eight (2 x 4, each a 64 x 32
+// part: half the staging and half the accumulators per thread, four waves per SIMD).
+template <int BM, int BN, int NW = 4>
 __global__ __launch_bounds__(NW * 64, 2) void gemm_split_kernel(GemmArgs g, const uint16_t *Wt, int64_t ku_total, int64_t n_pad) {
-    static_assert(NW == 4 || (NW == 8 && !TRANS && BN == 128), "eight waves: plain product, 128 columns");
+    static_assert(NW == 4 || (NW == 8 && BN == 128), "eight waves: 128 columns");
     constexpr int NT = NW * 64;
     constexpr int WM = BM / 2, WN = BN / (NW / 2);
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int A_BYTES = TRANS ? SplitColLoader::bytes(BM) : Units16<BM>::BYTES;
-    constexpr int B_BYTES = TRANS ? SplitColLoader::bytes(BN) : Units16<BN>::BYTES;
+    constexpr int A_BYTES = Units16<BM>::BYTES;
+    constexpr int B_BYTES = Units16<BN>::BYTES;
     __shared__ __attribute__((aligned(16))) char smem[A_BYTES + B_BYTES];
     char *As = smem, *Bs = smem + A_BYTES;
 
@@ -901,33 +824,23 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_split_kernel(GemmArgs g, cons
 
     SplitRowLoader<BM, NT> la_r;
     SplitPlaneLoader<BN, NT> lb_p;
-    SplitColLoader lc;
     const int64_t nk = (k_end > k_begin) ? (k_end - k_begin + SBK - 1) / SBK : 0;
     const int64_t nk_full = (k_end > k_begin) ? (k_end - k_begin) / SBK : 0;
-    // uniform over the workgroup: every row / column of the tile exists and vector loads are allowed
-    const bool interior = TRANS ? (m0 + BM <= g.M && n0 + BN <= g.N && g.a_vec && g.b_vec) : (m0 + BM <= g.M && g.a_vec);
-    const int both_vec = g.a_vec && g.b_vec;
-    if constexpr (TRANS) lc.init(g, m0, n0, BM, BN, As, Bs, tid);
+    // uniform over the workgroup: every row of the tile exists and vector loads are allowed
+    const bool interior = m0 + BM <= g.M && g.a_vec;
     if (nk > 0) {
-        if constexpr (TRANS) {
-            lc.fetch(k_begin, k_end, both_vec);
-            lc.cut();
-            lc.put();
-            if (interior) lc.fast_begin(k_begin + SBK);
-        } else {
-            la_r.fetch(g.A, g.lda, m0, g.M, k_begin, k_end, g.a_vec, tid);
-            lb_p.begin(Wt, ku_total, n_pad, n0, k_begin, tid);
-            lb_p.fetch(n_pad);
-            la_r.cut();
-            la_r.put(As, tid);
-            lb_p.stash(Bs, tid);
-            if (interior) la_r.fast_begin(g.A, g.lda, m0, k_begin + SBK, tid);
-        }
+        la_r.fetch(g.A, g.lda, m0, g.M, k_begin, k_end, g.a_vec, tid);
+        lb_p.begin(Wt, ku_total, n_pad, n0, k_begin, tid);
+        lb_p.fetch(n_pad);
+        la_r.cut();
+        la_r.put(As, tid);
+        lb_p.stash(Bs, tid);
+        if (interior) la_r.fast_begin(g.A, g.lda, m0, k_begin + SBK, tid);
     }
     __syncthreads();
-    // the products of one step (32 k) out of LDS; CUT: the operands of the next step, which wait in registers, are
-    // cut into their pieces between the matrix instructions of the second half (about five vector instructions fit
-    // behind each matrix instruction's issue)
+    // the products of one step (32 k) out of LDS; CUT: the first operand of the next step, which waits in registers, is
+    // cut into its pieces between the matrix instructions of the second half (about five vector instructions fit
+    // behind each matrix instruction's issue; measured: 4 %)
     auto products = [&](auto cut_tag) {
         constexpr bool CUT = decltype(cut_tag)::value;
 #pragma unroll
@@ -940,30 +853,12 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_split_kernel(GemmArgs g, cons
 #pragma unroll
                 for (int i = 0; i < TM; ++i) {
                     const int row = wm * WM + i * 32 + l32;
-                    uint4 v;
-                    if constexpr (TRANS) {
-                        const int slot = SplitColLoader::col_slot(row);
-                        const uint2 v0 = *reinterpret_cast<const uint2 *>(As + ((p * 8 + 4 * ks + 2 * half) * BM + slot) * 8);
-                        const uint2 v1 = *reinterpret_cast<const uint2 *>(As + ((p * 8 + 4 * ks + 2 * half + 1) * BM + slot) * 8);
-                        v = make_uint4(v0.x, v0.y, v1.x, v1.y);
-                    } else {
-                        v = *reinterpret_cast<const uint4 *>(As + Units16<BM>::at(p, 2 * ks + half, row));
-                    }
-                    a[p][i] = __builtin_bit_cast(bf16x8, v);
+                    a[p][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(As + Units16<BM>::at(p, 2 * ks + half, row)));
                 }
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const int row = wn * WN + j * 32 + l32;
-                    uint4 v;
-                    if constexpr (TRANS) {
-                        const int slot = SplitColLoader::col_slot(row);
-                        const uint2 v0 = *reinterpret_cast<const uint2 *>(Bs + ((p * 8 + 4 * ks + 2 * half) * BN + slot) * 8);
-                        const uint2 v1 = *reinterpret_cast<const uint2 *>(Bs + ((p * 8 + 4 * ks + 2 * half + 1) * BN + slot) * 8);
-                        v = make_uint4(v0.x, v0.y, v1.x, v1.y);
-                    } else {
-                        v = *reinterpret_cast<const uint4 *>(Bs + Units16<BN>::at(p, 2 * ks + half, row));
-                    }
-                    b[p][j] = __builtin_bit_cast(bf16x8, v);
+                    b[p][j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(Bs + Units16<BN>::at(p, 2 * ks + half, row)));
                 }
             }
             if (CUT && ks == SBK / 16 - 1) la_r.cut();
@@ -984,26 +879,13 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_split_kernel(GemmArgs g, cons
         }
     };
     for (int64_t kt = 0; kt + 1 < nk; ++kt) {
-        const bool fast = interior && kt + 1 < nk_full;
-        if constexpr (TRANS) {
-            if (fast) lc.fetch_fast();
-            else lc.fetch(k_begin + (kt + 1) * SBK, k_end, both_vec);
-        } else {
-            if (fast) la_r.fetch_fast();
-            else la_r.fetch(g.A, g.lda, m0, g.M, k_begin + (kt + 1) * SBK, k_end, g.a_vec, tid);
-            lb_p.fetch(n_pad);
-        }
-        // (measured: cutting between the matrix instructions pays for the plain product, 4 %; the weight gradient, with
-        // twice the cutting per thread, lost 9 % that way and cuts after its products)
-        products(std::integral_constant<bool, !TRANS>{});
+        if (interior && kt + 1 < nk_full) la_r.fetch_fast();
+        else la_r.fetch(g.A, g.lda, m0, g.M, k_begin + (kt + 1) * SBK, k_end, g.a_vec, tid);
+        lb_p.fetch(n_pad);
+        products(std::true_type{});
         __syncthreads();            // every wave has read this step's operands
-        if constexpr (TRANS) {
-            lc.cut();
-            lc.put();
-        } else {
-            la_r.put(As, tid);
-            lb_p.stash(Bs, tid);
-        }
+        la_r.put(As, tid);
+        lb_p.stash(Bs, tid);
         __syncthreads();
     }
     if (nk > 0) products(std::false_type{});
@@ -1016,32 +898,38 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_split_kernel(GemmArgs g, cons
     }
 }
 
-// The weight gradient once more, with eight waves on a 128 x 128 tile (2 x 4, each a 64 x 32 part): half the staging
-// and half the accumulators per thread, so that four waves share a SIMD and one wave's cutting and LDS traffic run
-// beside another's matrix instructions.  Same LDS image as gemm_split_kernel<true, ...>.
-struct SplitColLoader8 {
+// The weight gradient with eight waves on a 128 x BN tile (BN = 128: 2 x 4 waves, each a 64 x 32 part; BN = 64: 4 x 2,
+// each 32 x 32): half the staging and at most half the accumulators per thread of the four-wave form, so that four
+// waves share a SIMD and one wave's cutting and LDS traffic run beside another's matrix instructions.  Waves 0-3 stage
+// the first operand's tile, waves 4-7 the second's; LDS image as in gemm_split_kernel<true, ...>: 8-byte units
+// (piece, k / 4, column), columns placed by ColUnits8::col_slot.
+struct SplitColLoader {
     f32x4 r[4];                     // one block of 4 k x 4 columns per thread
     const f32x4 *pf;
     const char *base;
     int64_t ld, t0, T;
     char *s;
-    int kb, tq;                     // the thread's k-block (0..7) and column group (0..31)
+    int bt, kb, tq;                 // tile width; the thread's k-block and column group
+    bool idle;                      // a 64-column second tile leaves half of its waves without work
     uint2 pk[4][3];                 // [column][piece], four k each
 
-    __device__ __forceinline__ void init(const GemmArgs &g, int64_t m0, int64_t n0, char *As, char *Bs, int tid) {
+    __device__ __forceinline__ void init(const GemmArgs &g, int64_t m0, int64_t n0, int bm, int bn, char *As, char *Bs, int tid) {
         const bool second = __builtin_amdgcn_readfirstlane(tid >> 8) != 0;        // uniform over the wave
         base = second ? g.B : g.A;
         ld = second ? g.ldb : g.lda;
         t0 = second ? n0 : m0;
         T = second ? g.N : g.M;
         s = second ? Bs : As;
-        const int tt = tid & 255;
-        kb = tt >> 5; tq = tt & 31;
+        bt = second ? bn : bm;
+        const int tt = tid & 255, cpr = bt / 4;
+        kb = tt / cpr; tq = tt % cpr;
+        idle = kb >= 8;
     }
 
     __device__ __forceinline__ void fetch(int64_t k0, int64_t k_end, int vec) {
+        if (idle) return;
         const int64_t t = t0 + 4 * tq;
-        const int ncol = static_cast<int>(T - t < 4 ? (T - t > 0 ? T - t : 0) : 4);
+        const int ncol = static_cast<int>(T - t < 4 ? T - t : 4);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int64_t k = k0 + 4 * kb + j;
@@ -1054,7 +942,9 @@ struct SplitColLoader8 {
         pf = reinterpret_cast<const f32x4 *>(base + ((k0 + 4 * kb) * ld + t0 + 4 * tq) * 4);
     }
 
+    // the check-free path runs only when rows are whole 16-byte vectors
     __device__ __forceinline__ void fetch_fast() {
+        if (idle) return;
         const int64_t ld4 = ld / 4;
 #pragma unroll
         for (int j = 0; j < 4; ++j) r[j] = pf[j * ld4];
@@ -1062,6 +952,7 @@ struct SplitColLoader8 {
     }
 
     __device__ __forceinline__ void cut() {
+        if (idle) return;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             uint32_t lo[3], hi[3];
@@ -1073,24 +964,29 @@ struct SplitColLoader8 {
     }
 
     __device__ __forceinline__ void put() const {
-        const int sw = ((tq >> 2) & 1) * 16;       // see SplitColLoader::put
+        if (idle) return;
+        const int sw = ((tq >> 2) & 1) * 16;       // see ColUnits8
 #pragma unroll
         for (int p = 0; p < 3; ++p) {
-            char *dst = s + (((p * 8 + kb) * 128) + 4 * tq) * 8;
+            char *dst = s + (((p * 8 + kb) * bt) + 4 * tq) * 8;
             *reinterpret_cast<uint4 *>(dst + sw) = make_uint4(pk[0][p].x, pk[0][p].y, pk[1][p].x, pk[1][p].y);
             *reinterpret_cast<uint4 *>(dst + 16 - sw) = make_uint4(pk[2][p].x, pk[2][p].y, pk[3][p].x, pk[3][p].y);
         }
     }
 };
 
-__global__ __launch_bounds__(512, 2) void gemm_split_trans8_kernel(GemmArgs g) {
-    constexpr int BM = 128, BN = 128, WM = 64, WN = 32, TM = 2;
-    constexpr int A_BYTES = SplitColLoader::bytes(BM), B_BYTES = SplitColLoader::bytes(BN);
+template <int BN>
+__global__ __launch_bounds__(512, 2) void gemm_split_trans_kernel(GemmArgs g) {
+    static_assert(BN == 128 || BN == 64, "tile widths");
+    constexpr int BM = 128;
+    constexpr int WAVES_N = BN / 32, WAVES_M = 8 / WAVES_N;     // every wave one 32-column strip
+    constexpr int WM = BM / WAVES_M, WN = 32, TM = WM / 32;
+    constexpr int A_BYTES = ColUnits8::bytes(BM), B_BYTES = ColUnits8::bytes(BN);
     __shared__ __attribute__((aligned(16))) char smem[A_BYTES + B_BYTES];
     char *As = smem, *Bs = smem + A_BYTES;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int l32 = lane & 31, half = lane >> 5;
     int bx, by, bz;
     if (!tile_coords(g, &bx, &by, &bz)) return;      // uniform over the workgroup
@@ -1105,12 +1001,13 @@ __global__ __launch_bounds__(512, 2) void gemm_split_trans8_kernel(GemmArgs g) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][0][r] = 0.f;
 
-    SplitColLoader8 lc;
+    SplitColLoader lc;
     const int64_t nk = (k_end > k_begin) ? (k_end - k_begin + SBK - 1) / SBK : 0;
     const int64_t nk_full = (k_end > k_begin) ? (k_end - k_begin) / SBK : 0;
+    // uniform over the workgroup: every row / column of the tile exists and vector loads are allowed
     const bool interior = m0 + BM <= g.M && n0 + BN <= g.N && g.a_vec && g.b_vec;
     const int both_vec = g.a_vec && g.b_vec;
-    lc.init(g, m0, n0, As, Bs, tid);
+    lc.init(g, m0, n0, BM, BN, As, Bs, tid);
     if (nk > 0) {
         lc.fetch(k_begin, k_end, both_vec);
         lc.cut();
@@ -1118,7 +1015,7 @@ __global__ __launch_bounds__(512, 2) void gemm_split_trans8_kernel(GemmArgs g) {
         if (interior) lc.fast_begin(k_begin + SBK);
     }
     __syncthreads();
-    const int slot_b = SplitColLoader::col_slot(wn * WN + l32);
+    const int slot_b = ColUnits8::col_slot(wn * WN + l32);
     auto products = [&]() {
 #pragma unroll
         for (int ks = 0; ks < SBK / 16; ++ks) {
@@ -1127,7 +1024,7 @@ __global__ __launch_bounds__(512, 2) void gemm_split_trans8_kernel(GemmArgs g) {
             for (int p = 0; p < 3; ++p) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i) {
-                    const int slot = SplitColLoader::col_slot(wm * WM + i * 32 + l32);
+                    const int slot = ColUnits8::col_slot(wm * WM + i * 32 + l32);
                     const uint2 v0 = *reinterpret_cast<const uint2 *>(As + ((p * 8 + 4 * ks + 2 * half) * BM + slot) * 8);
                     const uint2 v1 = *reinterpret_cast<const uint2 *>(As + ((p * 8 + 4 * ks + 2 * half + 1) * BM + slot) * 8);
                     a[p][i] = __builtin_bit_cast(bf16x8, make_uint4(v0.x, v0.y, v1.x, v1.y));
@@ -1137,11 +1034,11 @@ __global__ __launch_bounds__(512, 2) void gemm_split_trans8_kernel(GemmArgs g) {
                 b[p] = __builtin_bit_cast(bf16x8, make_uint4(w0.x, w0.y, w1.x, w1.y));
             }
             // the six piece products, smallest first
-#define CG_PIECES8(PA_, PB_)                                                                                                 \
+#define CG_PIECES_T(PA_, PB_)                                                                                                 \
     _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                                           \
         acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[PA_][i], b[PB_], acc[i][0], 0, 0, 0);
-            CG_PIECES8(2, 0) CG_PIECES8(0, 2) CG_PIECES8(1, 1) CG_PIECES8(1, 0) CG_PIECES8(0, 1) CG_PIECES8(0, 0)
-#undef CG_PIECES8
+            CG_PIECES_T(2, 0) CG_PIECES_T(0, 2) CG_PIECES_T(1, 1) CG_PIECES_T(1, 0) CG_PIECES_T(0, 1) CG_PIECES_T(0, 0)
+#undef CG_PIECES_T
         }
     };
     for (int64_t kt = 0; kt + 1 < nk; ++kt) {
@@ -1265,11 +1162,11 @@ constexpr int64_t SPLIT_MIN_MACS = int64_t(1) << 28;
 static void launch_split_tiles(bool trans, const GemmArgs &g, int bn, dim3 grid, const uint16_t *Wt, int64_t ku_total,
                                int64_t n_pad, hipStream_t st) {
     if (trans) {
-        if (bn == 64) hipLaunchKernelGGL((gemm_split_kernel<true, 128, 64>), grid, dim3(256), 0, st, g, Wt, ku_total, n_pad);
-        else hipLaunchKernelGGL(gemm_split_trans8_kernel, grid, dim3(512), 0, st, g);
+        if (bn == 64) hipLaunchKernelGGL(gemm_split_trans_kernel<64>, grid, dim3(512), 0, st, g);
+        else hipLaunchKernelGGL(gemm_split_trans_kernel<128>, grid, dim3(512), 0, st, g);
     } else {
-        if (bn == 64) hipLaunchKernelGGL((gemm_split_kernel<false, 128, 64>), grid, dim3(256), 0, st, g, Wt, ku_total, n_pad);
-        else hipLaunchKernelGGL((gemm_split_kernel<false, 128, 128, 8>), grid, dim3(512), 0, st, g, Wt, ku_total, n_pad);
+        if (bn == 64) hipLaunchKernelGGL((gemm_split_kernel<128, 64>), grid, dim3(256), 0, st, g, Wt, ku_total, n_pad);
+        else hipLaunchKernelGGL((gemm_split_kernel<128, 128, 8>), grid, dim3(512), 0, st, g, Wt, ku_total, n_pad);
     }
 }
 
