@@ -64,6 +64,25 @@ def test_epoch_config1_matches_oracle(env, orders, miss_mode):
     dp.close()
 
 
+@pytest.mark.parametrize("cache_frac", [0.0, 1.0])
+def test_epoch_pipelined_with_one_tier_empty(env, cache_frac):
+    """Pipelined mode scatters the GPU tier's rows and the staged host rows of a layer in one launch; with either tier
+    empty the same call must serve the other one alone."""
+    H, O, B = env["H"], env["O"], env["B"]
+    import copy
+    cfg = copy.deepcopy(synth.CONFIGS["C1"])
+    cfg.cache_frac = cache_frac
+    prob = H.make_problem(cfg, mask_frac=0.5)
+    assert prob.cap_gpu == (0 if cache_frac == 0.0 else prob.part.n_halo)
+    dp = H.DeviceProblem(prob, miss_mode=B.MISS_PIPELINED)
+    ref = O.oracle_epoch(prob)
+    for rep in range(3):
+        say(f"pipelined epoch, cache_frac={cache_frac} rep={rep}")
+        loss, _ = dp.run_epoch()
+        compare_epoch(env, prob, dp, ref, loss, TOL["f32"], f"C1 pipelined cache_frac={cache_frac} rep={rep}")
+    dp.close()
+
+
 @pytest.mark.parametrize("name,scale", [("C2", 0.02), ("C3", 0.01), ("C4", 0.002), ("C5", 0.004)])
 def test_epoch_scaled_configs_match_oracle(env, name, scale):
     B, H, O = env["B"], env["H"], env["O"]
