@@ -793,7 +793,7 @@ struct ColUnits8 {
 // units along k per piece, n_pad rows).  NW waves: four (2 x 2) or, on a 128 x 128 tile, eight (2 x 4, each a 64 x 32
 // part: half the staging and half the accumulators per thread, four waves per SIMD).
 template <int BM, int BN, int NW = 4>
-__global__ __launch_bounds__(NW * 64, 2) void gemm_split_kernel(GemmArgs g, const uint16_t *Wt, int64_t ku_total, int64_t n_pad) {
+__global__ __launch_bounds__(NW * 64, NW / 2) void gemm_split_kernel(GemmArgs g, const uint16_t *Wt, int64_t ku_total, int64_t n_pad) {
     static_assert(NW == 4 || (NW == 8 && BN == 128), "eight waves: 128 columns");
     constexpr int NT = NW * 64;
     constexpr int WM = BM / 2, WN = BN / (NW / 2);
@@ -976,7 +976,8 @@ struct SplitColLoader {
 };
 
 template <int BN>
-__global__ __launch_bounds__(512, 2) void gemm_split_trans_kernel(GemmArgs g) {
+// (second launch bound: waves per SIMD; two workgroups of eight waves per compute unit need four)
+__global__ __launch_bounds__(512, BN == 128 ? 4 : 2) void gemm_split_trans_kernel(GemmArgs g) {
     static_assert(BN == 128 || BN == 64, "tile widths");
     constexpr int BM = 128;
     constexpr int WAVES_N = BN / 32, WAVES_M = 8 / WAVES_N;     // every wave one 32-column strip
