@@ -9,6 +9,8 @@
  * Every floating-point routine works in double precision and sums each output element
  * sequentially in the order stated; OpenMP is used only across independent output
  * elements (rows, or feature columns), so results do not depend on the thread count.
+ * The dense products of the combination step are not in this file: they are numpy's float64
+ * matrix product, a library primitive, called from oracle.py.
  *
  * What each routine follows in the paper (arxiv 2508.13716):
  *   orc_placement     JACA, "Vertex Importance": cache the highest-priority halo vertices
@@ -27,7 +29,6 @@
  *   orc_spmm_fwd      aggregation step of Eq. 1; A-hat * H in the GCN rule of Lemma 2's proof.
  *   orc_spmm_bwd      the transposed product the chain rule of that rule needs
  *                     (Lemma 3's recursion, operands put in conformable order).
- *   orc_matmul        combination step: the dense transform by W, and its gradients.
  *   orc_softmax_ce    evaluation setup: cross-entropy loss for single-label tasks.
  */
 #include <math.h>
@@ -293,33 +294,6 @@ void orc_spmm_bwd(int64_t n_loc, int64_t n_cols, const int64_t *rowptr, const in
         }
         for (int64_t j = 0; j < n_cols; ++j)
             for (int64_t f = f0; f < f1; ++f) dX[j * F + f] *= c[j];
-    }
-}
-
-/* ---------------------------------------------------------------- dense products */
-/* C[M,N] (+)= op(A) op(B), reduction length K, every C[i,j] summed over k = 0..K-1 in order.
- * ta: A is stored [K,M] (use A^T);  tb: B is stored [N,K] (use B^T).  All row-major, dense. */
-void orc_matmul(int ta, int tb, int64_t M, int64_t N, int64_t K,
-                const double *A, const double *B, double *C, int accumulate)
-{
-#pragma omp parallel for schedule(static)
-    for (int64_t i = 0; i < M; ++i) {
-        double *c = C + i * N;
-        if (!accumulate) for (int64_t j = 0; j < N; ++j) c[j] = 0.0;
-        if (!tb) {
-            for (int64_t k = 0; k < K; ++k) {
-                double a = ta ? A[k * M + i] : A[i * K + k];
-                const double *b = B + k * N;
-                for (int64_t j = 0; j < N; ++j) c[j] += a * b[j];
-            }
-        } else {
-            for (int64_t j = 0; j < N; ++j) {
-                const double *b = B + j * K;
-                double s = 0.0;
-                for (int64_t k = 0; k < K; ++k) s += (ta ? A[k * M + i] : A[i * K + k]) * b[k];
-                c[j] += s;
-            }
-        }
     }
 }
 

@@ -35,6 +35,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "capgnn_oracle.c")
 _SO = os.path.join(_HERE, "libcapgnn_oracle.so")
 _lib_handle = None
+_blas_limit = None
 
 
 def build(force: bool = False) -> str:
@@ -67,7 +68,6 @@ def _lib():
         L.orc_mean_scales.argtypes = [i64, i64, p, p, p]
         L.orc_spmm_fwd.argtypes = [i64, p, p, p, p, p, p, i64, p]
         L.orc_spmm_bwd.argtypes = [i64, i64, p, p, p, p, p, p, i64, p]
-        L.orc_matmul.argtypes = [C.c_int, C.c_int, i64, i64, i64, p, p, p, C.c_int]
         L.orc_softmax_ce.argtypes = [i64, i64, p, p, p, C.c_double, p]
         L.orc_softmax_ce.restype = C.c_double
         _lib_handle = L
@@ -87,7 +87,11 @@ def max_threads() -> int:
 
 
 def set_threads(n: int) -> None:
+    """Threads of the C loops (OpenMP) and of numpy's matrix product (its BLAS thread pool)."""
+    global _blas_limit
     _lib().orc_set_threads(int(n))
+    from threadpoolctl import threadpool_limits
+    _blas_limit = threadpool_limits(limits=int(n), user_api="blas")
 
 
 # ------------------------------------------------------------------ cache side
@@ -325,14 +329,11 @@ def spmm_bwd(g: Graph, dY) -> np.ndarray:
 
 
 def matmul(A, B, ta: bool = False, tb: bool = False) -> np.ndarray:
+    """op(A) op(B) in float64, op = transpose when ta / tb: the dense product of the combination step (Eq. 1's
+    COMBINE; Z = (A_hat H) W in the forward rule of Lemma 2's proof) and of its chain rule.  A library primitive:
+    numpy's matrix product."""
     A, B = _f64(A), _f64(B)
-    M = A.shape[1] if ta else A.shape[0]
-    K = A.shape[0] if ta else A.shape[1]
-    N = B.shape[0] if tb else B.shape[1]
-    assert (B.shape[1] if tb else B.shape[0]) == K
-    out = np.zeros((M, N), np.float64)
-    _lib().orc_matmul(int(ta), int(tb), M, N, K, _ptr(A), _ptr(B), _ptr(out), 0)
-    return out
+    return np.ascontiguousarray(np.matmul(A.T if ta else A, B.T if tb else B))
 
 
 def softmax_ce(Z, y, mask=None, norm: float = 0.0):
@@ -410,21 +411,16 @@ def layer_fwd(g: Graph, l: Layer, X):
     return H, {"M": M, "Z": Z}
 
 
-def layer_bwd(g: Graph, l: Layer, X, saved, dH, need_dx: bool = True, relu_on=None):
-    """Chain rule of layer_fwd.  Returns dict(dW, dW_self, db, dX) with dX over all n_cols rows.
-
-    relu_on: optional boolean [n_loc, f_out] that replaces the decision 1[Z > 0].  The decision is an
-    integer taken from a floating-point value; a caller comparing against an fp32 implementation passes
-    that implementation's decisions for the elements whose Z is zero within fp32 rounding, so that both
-    sides differentiate the same piecewise-linear function."""
+def layer_bwd(g: Graph, l: Layer, X, saved, dH, need_dx: bool = True):
+    """Chain rule of layer_fwd.  Returns dict(dW, dW_self, db, dX, dZ) with dX over all n_cols rows.  The factor
+    sigma'(Z) of the backward recursion is decided here, from this side's own fp64 Z, and by nothing else."""
     X = _f64(X)
     dH = _f64(dH)
     if l.act == "relu":
-        on = (saved["Z"] > 0.0) if relu_on is None else np.asarray(relu_on, bool)   # sigma'(0) = 0
-        dZ = dH * on
+        dZ = dH * (saved["Z"] > 0.0)                     # sigma'(0) = 0
     else:
         dZ = dH
-    out = {"db": dZ.sum(axis=0), "dW": matmul(saved["M"], dZ, ta=True), "dW_self": None, "dX": None}
+    out = {"db": dZ.sum(axis=0), "dW": matmul(saved["M"], dZ, ta=True), "dW_self": None, "dX": None, "dZ": dZ}
     if l.kind == "sage":
         out["dW_self"] = matmul(X[: g.n_loc], dZ, ta=True)
     if need_dx:
@@ -438,13 +434,14 @@ def layer_bwd(g: Graph, l: Layer, X, saved, dH, need_dx: bool = True, relu_on=No
 
 def epoch(g: Graph, layers: List[Layer], X0_local, halo_tables: Sequence[Optional[np.ndarray]],
           labels, mask=None, loss_norm: float = 0.0, lr: float = 0.0, halo_grad: bool = False,
-          relu_on: Optional[Sequence] = None, loss_kind: str = "ce"):
+          loss_kind: str = "ce"):
     """One full-batch forward + backward over the partition.
 
     halo_tables[l] is the logical [n_halo, f_in(l)] cache table feeding layer l (None when the
-    partition has no halo).  relu_on[l], when given, overrides layer l's backward decision 1[Z > 0]
-    (see layer_bwd).  loss_kind "ce": labels are class indices (single-label tasks); "bce": labels is the
-    [n_loc, classes] 0/1 target matrix (multi-label tasks).  Returns dict(loss, logits, dW, dW_self, db, dX_halo, hidden, new_W ...).
+    partition has no halo).  loss_kind "ce": labels are class indices (single-label tasks); "bce": labels is the
+    [n_loc, classes] 0/1 target matrix (multi-label tasks).  Returns dict(loss, logits, dW, dW_self, db, dX_halo,
+    new_W ...) and the intermediate quantities of every layer l: X[l] its input [local rows; halo rows], M[l] the
+    aggregated input, hidden[l] = Z_l, dH[l] the loss gradient with respect to its output, dZ[l] = dH[l] (.) sigma'(Z_l).
     """
     n_halo = g.n_cols - g.n_loc
     ids = np.arange(n_halo, dtype=np.int64)
@@ -463,12 +460,13 @@ def epoch(g: Graph, layers: List[Layer], X0_local, halo_tables: Sequence[Optiona
     logits = H
     loss, dH = (softmax_ce if loss_kind == "ce" else sigmoid_bce)(logits, labels, mask, loss_norm)
     res = {"loss": loss, "logits": logits, "dW": [None] * len(layers), "dW_self": [None] * len(layers),
-           "db": [None] * len(layers), "dX_halo": [None] * len(layers), "hidden": [s["Z"] for s in saves]}
+           "db": [None] * len(layers), "dX_halo": [None] * len(layers), "hidden": [s["Z"] for s in saves],
+           "X": Xs, "M": [s["M"] for s in saves], "dH": [None] * len(layers), "dZ": [None] * len(layers)}
     for li in range(len(layers) - 1, -1, -1):
         need_dx = li > 0 or halo_grad
-        b = layer_bwd(g, layers[li], Xs[li], saves[li], dH, need_dx=need_dx,
-                      relu_on=None if relu_on is None else relu_on[li])
-        res["dW"][li], res["dW_self"][li], res["db"][li] = b["dW"], b["dW_self"], b["db"]
+        res["dH"][li] = dH
+        b = layer_bwd(g, layers[li], Xs[li], saves[li], dH, need_dx=need_dx)
+        res["dW"][li], res["dW_self"][li], res["db"][li], res["dZ"][li] = b["dW"], b["dW_self"], b["db"], b["dZ"]
         if b["dX"] is not None:
             res["dX_halo"][li] = b["dX"][g.n_loc:]
             dH = b["dX"][: g.n_loc]

@@ -1,7 +1,9 @@
 """Per-kernel parity of the HIP library against the CPU oracle (needs an MI355X).
 
 fp32 results must agree within 1e-4, bf16 within 2e-2, in the norm-wise metric
-max|gpu - ref| / max|ref|; cache lookup and gather must agree bit for bit.
+max|gpu - ref| / max|ref| and, for the aggregations, also element by element:
+|gpu - ref| <= tol (|ref| + rms of the element's own row), so that the rows of hub vertices cannot vouch
+for short rows; cache lookup and gather must agree bit for bit.
 """
 import numpy as np
 import pytest
@@ -74,8 +76,10 @@ def run_spmm(env, part, F, ld, dtype, with_vals, seed, blocked=False, unit_weigh
     dXref = orc.spmm_bwd(og, O.widen(dYs))
     Y, dX = O.widen(H.dev_to_np(Yd)), O.widen(H.dev_to_np(dXd))
     tol = TOL_BF16 if dtype == "bf16" else TOL_F32
-    assert O.normwise(Y[:, :F], Yref) <= tol, (part.name, F, ld, dtype)
-    assert O.normwise(dX[:, :F], dXref) <= tol, (part.name, F, ld, dtype)
+    errs = (O.normwise(Y[:, :F], Yref), O.elementwise(Y[:, :F], Yref, by_row=True),
+            O.normwise(dX[:, :F], dXref), O.elementwise(dX[:, :F], dXref, by_row=True))
+    say(f"   fwd {errs[0]:.2e} norm-wise, {errs[1]:.2e} element-wise by row; transposed {errs[2]:.2e}, {errs[3]:.2e}")
+    assert max(errs) <= tol, (part.name, F, ld, dtype, errs)
     assert (Y[:, F:] == 7.0).all() and (dX[:, F:] == 7.0).all(), "padding columns were written"
     g.close()
 

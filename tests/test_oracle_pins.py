@@ -149,12 +149,22 @@ def test_spmm_bwd_vs_dense_transpose(orc):
 
 # ----------------------------------------------------------------------------- dense product, loss
 @pytest.mark.parametrize("ta,tb", list(itertools.product([False, True], repeat=2)))
-def test_matmul_vs_numpy(orc, ta, tb):
+def test_matmul_vs_triple_loop(orc, ta, tb):
+    """The dense product of the combination step against its definition, C[i,j] = sum_k A[i,k] B[k,j], written out
+    as three loops here (the oracle's routine is a library call; an operand taken transposed must be read so)."""
     rng = np.random.default_rng(3)
     A = rng.standard_normal((9, 13))          # logical [M=9, K=13]
     B = rng.standard_normal((13, 5))
+    want = np.zeros((9, 5))
+    for i in range(9):
+        for j in range(5):
+            s = 0.0
+            for k in range(13):
+                s += A[i, k] * B[k, j]
+            want[i, j] = s
     out = orc.matmul(A.T.copy() if ta else A, B.T.copy() if tb else B, ta=ta, tb=tb)
-    np.testing.assert_allclose(out, A @ B, rtol=1e-13, atol=1e-14)
+    assert out.shape == (9, 5) and out.flags.c_contiguous
+    np.testing.assert_allclose(out, want, rtol=1e-13, atol=1e-14)
 
 
 def test_loss_closed_forms(orc):

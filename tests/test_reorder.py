@@ -59,7 +59,7 @@ def test_epoch_on_relabelled_partition_matches_oracle_and_the_original(orc, name
     import torch
     from paper_2508_13716_amd import binding as B, harness as H
     from tests import oracle_side as O
-    from tests.test_gpu_epoch import compare_epoch, TOL
+    from tests.gpu_compare import compare_epoch, TOL
     env = dict(torch=torch, B=B, H=H, O=O, orc=orc)
     cfg = synth.CONFIGS[name] if scale == 1.0 else synth.CONFIGS[name].scaled(scale)
     prob = H.make_problem(cfg, mask_frac=0.5)

@@ -62,7 +62,7 @@ def test_epoch_with_multilabel_loss_and_gin_layers(orc, kind, dtype):
     import torch
     from paper_2508_13716_amd import binding as B, harness as H
     from tests import oracle_side as O
-    from tests.test_gpu_epoch import compare_epoch, TOL
+    from tests.gpu_compare import compare_epoch, TOL
     env = dict(torch=torch, B=B, H=H, O=O, orc=orc)
     cfg = synth.Config(f"ML-{kind}-{dtype}", kind, 3000, 2500, 45_000, [96, 64, 24], dtype, 0.4, max_deg=400,
                        seed=synth.BASE_SEED * 10 + 8, extra={"loss": "bce", "gin_eps": 0.1})
