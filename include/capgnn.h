@@ -358,7 +358,9 @@ int capgnn_layer_fwd(const capgnn_graph *g, const capgnn_layer *l, const void *X
                      void *H, int64_t ldh, void *saved, void *ws, size_t ws_bytes, void *stream);
 
 /* Backward of the same layer.  H is the forward output (its sign pattern is sigma').  dH: device
- * [n_loc x lddh], gradient w.r.t. H; it is overwritten with dZ = dH * 1[H > 0] for ReLU layers, and its
+ * [n_loc x lddh], gradient w.r.t. H, of the type H is stored in (float for a BF16 layer with out_f32: the loss
+ * gradient is consumed unrounded - it is summed over all vertices, and values that cluster as closely as
+ * (softmax - onehot) / n would all be rounded the same way); it is overwritten with dZ = dH * 1[H > 0] for ReLU layers, and its
  * contents afterwards are unspecified (a GCN layer of an operator without edge values leaves dZ with each row
  * multiplied by the row's normalisation scale, the form its transposed aggregation reads).
  * dW, dW_self: device float [f_in x f_out] (dense); dbias: device float[f_out]; any may be NULL.

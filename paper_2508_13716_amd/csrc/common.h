@@ -148,6 +148,7 @@ struct SpmmEpilogue {
     int relu = 0;
     int accumulate = 0;            // add the previous contents of Y
     int out_f32 = 0;               // store Y as float although X is bf16
+    int out_bf16 = 0;              // store Y as bf16 although X is float (the loss gradient of a bf16 model is gathered unrounded)
     int operand_scaled = 0;        // row s of X already carries in_scale[s] (only for operators with weights_by_source)
     void *ws = nullptr;            // scratch for the column-blocked kernel or for cut rows (spmm_ws_bytes), may be null
     size_t ws_bytes = 0;

@@ -115,6 +115,16 @@ static size_t fwd_ws_bytes(const capgnn_graph *g, const capgnn_layer *l, int ord
            spmm_ws_bytes(g->fwd, order == CAPGNN_AGG_FIRST ? l->f_in : l->f_out, l->dtype);
 }
 
+// A bf16 layer that stores its output as float (the layer that feeds the loss) also takes its output gradient as
+// float: the loss gradient's values cluster around (p - 1) / n and p / n, so rounding them to bf16 before they are
+// summed over millions of vertices shifts every term the same way (measured on the 2.45 M-vertex configuration: 2 % of
+// the last weight gradient, against 0.02 % when only the aggregated gradient is rounded).  The transposed aggregation
+// reads the float rows and rounds its result once; the dense products that need a bf16 operand read this copy.
+static size_t grad_copy_bytes(const capgnn_graph *g, const capgnn_layer *l) {
+    if (!(l->dtype == CAPGNN_BF16 && l->out_f32)) return 0;
+    return align_up(static_cast<size_t>(g->n_loc) * pad_ld(g, l->f_out, CAPGNN_BF16) * sizeof(uint16_t), 256);
+}
+
 static size_t bwd_ws_bytes(const capgnn_graph *g, const capgnn_layer *l, int order) {
     const int es = elem_bytes(l->dtype);
     size_t b = relu_bias_ws_bytes(g->n_loc, l->f_out);
@@ -124,6 +134,7 @@ static size_t bwd_ws_bytes(const capgnn_graph *g, const capgnn_layer *l, int ord
     if (order == CAPGNN_AGG_FIRST) b += align_up(static_cast<size_t>(g->n_loc) * pad_ld(g, l->f_in, l->dtype) * es, 256);
     else b += align_up(static_cast<size_t>(g->n_cols) * pad_ld(g, l->f_out, l->dtype) * es, 256);
     b += spmm_ws_bytes(g->bwd, order == CAPGNN_AGG_FIRST ? l->f_in : l->f_out, l->dtype);
+    b += grad_copy_bytes(g, l);
     return b;
 }
 
@@ -187,7 +198,7 @@ static int layer_fwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
 static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int order, int li, const void *X, int64_t ldx,
                           const void *H, int64_t ldh, const void *saved, void *dH, int64_t lddh, float *dW,
                           float *dW_self, float *dbias, void *dX, int64_t lddx, int need_halo_grad, void *ws,
-                          size_t ws_bytes, hipStream_t st, const float *dH32 = nullptr, int64_t lddh32 = 0) {
+                          size_t ws_bytes, hipStream_t st) {
     const int dt = l->dtype;
     const bool sage = l->kind == CAPGNN_SAGE_MEAN;
     const int relu = l->act == CAPGNN_ACT_RELU;
@@ -207,6 +218,16 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
     void *tmp = w;   // dM (AGG_FIRST) or dT (XFORM_FIRST)
     w += order == CAPGNN_AGG_FIRST ? align_up(static_cast<size_t>(g->n_loc) * pad_ld(g, l->f_in, dt) * elem_bytes(dt), 256)
                                    : align_up(static_cast<size_t>(g->n_cols) * pad_ld(g, l->f_out, dt) * elem_bytes(dt), 256);
+    // float output gradient of a bf16 layer (see grad_copy_bytes): dZ stays float for the transposed aggregation; the
+    // dense products read its rounded copy
+    const bool f32grad = dt == CAPGNN_BF16 && l->out_f32;
+    void *dHb = dH;                 // the gradient as the dense products read it (storage type of the layer)
+    int64_t lddhb = lddh;
+    if (f32grad) {
+        dHb = w;
+        lddhb = pad_ld(g, l->f_out, CAPGNN_BF16);
+        w += grad_copy_bytes(g, l);
+    }
     SpmmEpilogue sp_ep;   // scratch of the transposed aggregation
     sp_ep.ws = w;
     sp_ep.ws_bytes = ws_bytes - static_cast<size_t>(w - static_cast<char *>(ws));
@@ -216,25 +237,33 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
     // gathered itself and nothing else reads it; dH W^T in the other order) and it sums unweighted.  fp32 only.
     const bool pre_b = dt == CAPGNN_F32 && g->bwd.weights_by_source;
     const bool scale_dz = pre_b && order == CAPGNN_XFORM_FIRST && !sage && (dW || dX);
+    const bool need_copy = f32grad && (order == CAPGNN_AGG_FIRST || sage);
     {   // dZ = dH * sigma'(Z) in place; dbias = column sums of dZ
         Scope s(CAPGNN_K_ELEMENTWISE, li, 1, st);
         const int h_dt = (l->out_f32 ? CAPGNN_F32 : dt);
-        // dH32: the same gradient before it was rounded to the storage type (the loss gradient of a bf16 model);
-        // the bias gradient is then summed from it and dH is (re)written as its masked, rounded copy
-        CG_TRY(launch_relu_mask_dbias(g->n_loc, l->f_out, dH32, lddh32, CAPGNN_F32, dH, lddh, H, ldh, dt, h_dt, relu, dbias,
-                                      ws_rb, rb, st, scale_dz ? g->bwd.in_scale : nullptr));
+        if (f32grad) {
+            // mask and bias gradient in float, in place; then the rounded copy where a dense product needs one
+            CG_TRY(launch_relu_mask_dbias(g->n_loc, l->f_out, nullptr, 0, CAPGNN_F32, dH, lddh, H, ldh, CAPGNN_F32, h_dt, relu,
+                                          dbias, ws_rb, rb, st, nullptr));
+            if (need_copy)
+                CG_TRY(launch_relu_mask_dbias(g->n_loc, l->f_out, dH, lddh, CAPGNN_F32, dHb, lddhb, nullptr, 0, CAPGNN_BF16,
+                                              h_dt, 0, nullptr, ws_rb, rb, st, nullptr));
+        } else {
+            CG_TRY(launch_relu_mask_dbias(g->n_loc, l->f_out, nullptr, 0, dt, dH, lddh, H, ldh, dt, h_dt, relu, dbias,
+                                          ws_rb, rb, st, scale_dz ? g->bwd.in_scale : nullptr));
+        }
     }
     if (order == CAPGNN_AGG_FIRST) {
         if (!saved) CG_FAIL(CAPGNN_EINVAL, "layer_bwd: saved is NULL");
         const int64_t ldm = pad_ld(g, l->f_in, dt);
         {
             Scope s(CAPGNN_K_GEMM, li, 1, st);
-            if (dW) CG_TRY(launch_gemm(1, 0, l->f_in, l->f_out, g->n_loc, saved, ldm, dH, lddh, dW, l->f_out, dt, 1, 0,
+            if (dW) CG_TRY(launch_gemm(1, 0, l->f_in, l->f_out, g->n_loc, saved, ldm, dHb, lddhb, dW, l->f_out, dt, 1, 0,
                                        nullptr, 0, nullptr, 0, ws_gemm, gw, st));
             if (sage && dW_self)
-                CG_TRY(launch_gemm(1, 0, l->f_in, l->f_out, g->n_loc, X, ldx, dH, lddh, dW_self, l->f_out, dt, 1, 0,
+                CG_TRY(launch_gemm(1, 0, l->f_in, l->f_out, g->n_loc, X, ldx, dHb, lddhb, dW_self, l->f_out, dt, 1, 0,
                                    nullptr, 0, nullptr, 0, ws_gemm, gw, st));
-            if (dX) CG_TRY(launch_gemm(0, 1, g->n_loc, l->f_in, l->f_out, dH, lddh, l->W, l->f_out, tmp, ldm, dt, 0, 0,
+            if (dX) CG_TRY(launch_gemm(0, 1, g->n_loc, l->f_in, l->f_out, dHb, lddhb, l->W, l->f_out, tmp, ldm, dt, 0, 0,
                                        nullptr, 0, nullptr, 0, ws_gemm, gw, st, pre_b ? g->bwd.in_scale : nullptr));
         }
         if (dX) {
@@ -245,7 +274,7 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
             }
             if (sage) {
                 Scope s(CAPGNN_K_GEMM, li, 1, st);
-                CG_TRY(launch_gemm(0, 1, g->n_loc, l->f_in, l->f_out, dH, lddh, l->W_self, l->f_out, dX, lddx, dt, 0, 1,
+                CG_TRY(launch_gemm(0, 1, g->n_loc, l->f_in, l->f_out, dHb, lddhb, l->W_self, l->f_out, dX, lddx, dt, 0, 1,
                                    nullptr, 0, nullptr, 0, ws_gemm, gw, st));
             }
         }
@@ -257,20 +286,21 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
         Scope s(CAPGNN_K_SPMM_BWD, li, 1, st);
         const bool sub = !dW && !need_halo_grad;
         sp_ep.operand_scaled = scale_dz;
-        CG_TRY(launch_spmm(g->bwd, sub, dH, lddh, tmp, ldt, l->f_out, dt, sp_ep, st));
+        sp_ep.out_bf16 = f32grad;       // float rows in, one rounding on the way out
+        CG_TRY(launch_spmm(g->bwd, sub, dH, lddh, tmp, ldt, l->f_out, f32grad ? CAPGNN_F32 : dt, sp_ep, st));
     }
     Scope s(CAPGNN_K_GEMM, li, 1, st);
     if (dW) CG_TRY(launch_gemm(1, 0, l->f_in, l->f_out, g->n_cols, X, ldx, tmp, ldt, dW, l->f_out, dt, 1, 0, nullptr, 0,
                                nullptr, 0, ws_gemm, gw, st));
     if (sage && dW_self)
-        CG_TRY(launch_gemm(1, 0, l->f_in, l->f_out, g->n_loc, X, ldx, dH, lddh, dW_self, l->f_out, dt, 1, 0, nullptr, 0,
+        CG_TRY(launch_gemm(1, 0, l->f_in, l->f_out, g->n_loc, X, ldx, dHb, lddhb, dW_self, l->f_out, dt, 1, 0, nullptr, 0,
                            nullptr, 0, ws_gemm, gw, st));
     if (dX) {
         const int64_t rows = need_halo_grad ? g->n_cols : g->n_loc;
         CG_TRY(launch_gemm(0, 1, rows, l->f_in, l->f_out, tmp, ldt, l->W, l->f_out, dX, lddx, dt, 0, 0, nullptr, 0,
                            nullptr, 0, ws_gemm, gw, st));
         if (sage)
-            CG_TRY(launch_gemm(0, 1, g->n_loc, l->f_in, l->f_out, dH, lddh, l->W_self, l->f_out, dX, lddx, dt, 0, 1,
+            CG_TRY(launch_gemm(0, 1, g->n_loc, l->f_in, l->f_out, dHb, lddhb, l->W_self, l->f_out, dX, lddx, dt, 0, 1,
                                nullptr, 0, nullptr, 0, ws_gemm, gw, st));
     }
     return CAPGNN_OK;
@@ -304,7 +334,7 @@ static int plan_epoch(const capgnn_graph *g, const capgnn_cache *c, const capgnn
     }
     p->ldz = pad_ld(g, layers[L - 1].f_out, CAPGNN_F32);
     p->logits_off = take(static_cast<size_t>(g->n_loc) * p->ldz * sizeof(float));
-    // a bf16 model keeps the loss gradient in float as well: the last layer's bias gradient is summed from it
+    // a bf16 model keeps the loss gradient in float: the last layer's backward pass reads it unrounded
     if (layers[0].dtype == CAPGNN_BF16) p->dz32_off = take(static_cast<size_t>(g->n_loc) * p->ldz * sizeof(float));
     p->ld_grad = max_w;
     p->grad_off[0] = take(static_cast<size_t>(g->n_loc) * max_w * sizeof(float));
@@ -531,10 +561,12 @@ static int epoch_impl(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer
         const void *Hl = last ? static_cast<const void *>(Z) : static_cast<const void *>(Xl(l + 1));
         const int64_t ldh = last ? ldz : p.ldx[l + 1];
         void *dX = l > 0 ? static_cast<void *>(w + p.grad_off[cur ^ 1]) : nullptr;
+        // the last layer of a bf16 model takes the loss gradient as float (its output is float as well)
+        const bool f32grad = last && dt == CAPGNN_BF16;
         CG_TRY(layer_bwd_impl(g, &layers[l], p.order[l], l, Xl(l), p.ldx[l], Hl, ldh, w + p.saved_off[l],
-                              w + p.grad_off[cur], p.ld_grad, dW[l], dW_self ? dW_self[l] : nullptr, dbias[l], dX,
-                              p.ld_grad, 0, w + p.layer_ws_off, p.layer_ws_bytes, st,
-                              (last && dt == CAPGNN_BF16) ? reinterpret_cast<const float *>(w + p.dz32_off) : nullptr, ldz));
+                              f32grad ? static_cast<void *>(w + p.dz32_off) : static_cast<void *>(w + p.grad_off[cur]),
+                              f32grad ? ldz : p.ld_grad, dW[l], dW_self ? dW_self[l] : nullptr, dbias[l], dX,
+                              p.ld_grad, 0, w + p.layer_ws_off, p.layer_ws_bytes, st));
         cur ^= 1;
     }
     if (lr != 0.f) {

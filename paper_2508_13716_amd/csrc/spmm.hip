@@ -131,7 +131,13 @@ __device__ __forceinline__ void store_elems(char *p, const float (&x)[E]) {
         v.z = f32_to_bf16_bits(x[4]) | (f32_to_bf16_bits(x[5]) << 16);
         v.w = f32_to_bf16_bits(x[6]) | (f32_to_bf16_bits(x[7]) << 16);
         *reinterpret_cast<uint4 *>(p) = v;
+    } else if constexpr (BF16 && E == 4) {      // float operand, bf16 result: four elements per lane
+        uint2 v;
+        v.x = f32_to_bf16_bits(x[0]) | (f32_to_bf16_bits(x[1]) << 16);
+        v.y = f32_to_bf16_bits(x[2]) | (f32_to_bf16_bits(x[3]) << 16);
+        *reinterpret_cast<uint2 *>(p) = v;
     } else {
+        static_assert(E == 1, "unsupported element packing");
         store_one<BF16>(p, x[0]);
     }
 }
@@ -792,7 +798,8 @@ static int dispatch(const SpmmArgs &a, bool vec, const GiantList *gl, int64_t n_
 
 int launch_spmm(const SpOp &op, bool restrict_sub, const void *X, int64_t ldx, void *Y, int64_t ldy, int F,
                 int dtype, const SpmmEpilogue &ep, hipStream_t stream) {
-    const int out_dtype = (ep.out_f32 || dtype == CAPGNN_F32) ? CAPGNN_F32 : CAPGNN_BF16;
+    int out_dtype = (ep.out_f32 || dtype == CAPGNN_F32) ? CAPGNN_F32 : CAPGNN_BF16;
+    if (ep.out_bf16 && dtype == CAPGNN_F32) out_dtype = CAPGNN_BF16;     // float operand, rounded once on the way out
     if (dtype != CAPGNN_F32 && dtype != CAPGNN_BF16) CG_FAIL(CAPGNN_EINVAL, "spmm: unknown dtype %d", dtype);
     if (F <= 0 || F > (1 << 20)) CG_FAIL(CAPGNN_EINVAL, "spmm: F=%d out of range", F);
     if (ldx < F || ldy < F) CG_FAIL(CAPGNN_EINVAL, "spmm: leading dimension smaller than F");
@@ -825,6 +832,7 @@ int launch_spmm(const SpOp &op, bool restrict_sub, const void *X, int64_t ldx, v
         const bool off_ok = (a.ldx_bytes >> 4) < (int64_t(1) << 24) && op.n_in * (a.ldx_bytes >> 4) < (int64_t(1) << 32);
         if (bg.ok && off_ok && ep.ws_bytes >= bg.ws && (reinterpret_cast<uintptr_t>(ep.ws) & 15u) == 0) {
             float *part = static_cast<float *>(ep.ws);
+            if (dtype == CAPGNN_F32 && out_dtype == CAPGNN_BF16) return launch_blocked<false, true>(op, bg, a, part, stream);
             if (dtype == CAPGNN_F32) return launch_blocked<false, false>(op, bg, a, part, stream);
             if (out_dtype == CAPGNN_BF16) return launch_blocked<true, true>(op, bg, a, part, stream);
             return launch_blocked<true, false>(op, bg, a, part, stream);
@@ -838,6 +846,7 @@ int launch_spmm(const SpOp &op, bool restrict_sub, const void *X, int64_t ldx, v
     if (gl.n_rows > 0 && ep.ws && (reinterpret_cast<uintptr_t>(ep.ws) & 15u) == 0 &&
         ep.ws_bytes >= static_cast<size_t>(gl.n_pieces) * a.ldp * sizeof(float))
         cut = &gl;
+    if (dtype == CAPGNN_F32 && out_dtype == CAPGNN_BF16) return dispatch<false, true>(a, vec, cut, n_long, n_rows, stream);
     if (dtype == CAPGNN_F32) return dispatch<false, false>(a, vec, cut, n_long, n_rows, stream);
     if (out_dtype == CAPGNN_BF16) return dispatch<true, true>(a, vec, cut, n_long, n_rows, stream);
     return dispatch<true, false>(a, vec, cut, n_long, n_rows, stream);

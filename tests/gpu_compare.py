@@ -128,7 +128,7 @@ def teacher_forced_layers(env, prob, dp, ref, tol, tag, need_halo=False):
             assert np.array_equal(O.widen(Hs) > 0.0, Z > 0.0)          # rounding keeps the oracle's decisions
         Xd = H.padded_matrix(_to_storage(ref["X"][l], dt), ldx)
         Hd_oracle = H.padded_matrix(Hs, ldh)
-        dHd = H.padded_matrix(_to_storage(ref["dH"][l], dt), ldh if not out_f32 else synth.pad_to(p.f_out, per16))
+        dHd = H.padded_matrix(_to_storage(ref["dH"][l], "f32" if out_f32 else dt), ldh)   # the gradient has the type of H
         lddh = dHd.shape[1]
         Hd = torch.zeros_like(Hd_oracle)
         saved = torch.empty(max(B.layer_saved_bytes(dp.graph, ly), 256), dtype=torch.uint8, device="cuda")
