@@ -382,6 +382,18 @@ int capgnn_softmax_ce(int64_t n, int C, const float *Z, int64_t ldz, const int32
                       const uint8_t *mask, double loss_norm, float *loss_dev, void *dZ, int64_t lddz,
                       int dz_dtype, void *ws, size_t ws_bytes, void *stream);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): capgnn_softmax_ce without the workspace arguments.  Its scratch is a device array built into the
+ * library, sized for n <= CAPGNN_LOSS_STATIC_MAX_ROWS (4 MiB + 8 KiB per GPU, held until the process ends); more rows
+ * return CAPGNN_ENOMEM and touch nothing.  The call allocates nothing and frees nothing, on the host or the device.
+ * It runs on the CURRENT device, which must be the device of `stream`, Z, labels, mask, loss_dev and dZ.  All calls on
+ * one GPU share that GPU's array: calls that may overlap in time on one GPU (different streams, or different
+ * threads) race on it; calls on one stream are ordered and safe.  Results are those of capgnn_softmax_ce bit for bit. */
+#define CAPGNN_LOSS_STATIC_MAX_ROWS (1 << 20)
+int capgnn_softmax_ce_static(int64_t n, int C, const float *Z, int64_t ldz, const int32_t *labels,
+                             const uint8_t *mask, double loss_norm, float *loss_dev, void *dZ, int64_t lddz,
+                             int dz_dtype, void *stream);
+
 /* Masked binary cross-entropy on logits (evaluation setup: binary cross-entropy for multi-label tasks) and its
  * gradient: loss = (1/norm) sum_{mask} sum_k ( max(z,0) - z*y + log(1 + exp(-|z|)) ), which equals
  * -[y log s(z) + (1-y) log(1 - s(z))] with s the logistic function; dZ = (s(Z) - Y)/norm, zero in unmasked rows.

@@ -104,6 +104,7 @@ SIGNATURES = {
                                 _i32, _vp, _sz, _vp]),
     "capgnn_loss_workspace_bytes": (_sz, [_i64]),
     "capgnn_softmax_ce": (_i32, [_i64, _i32, _vp, _i64, _vp, _vp, C.c_double, _vp, _vp, _i64, _i32, _vp, _sz, _vp]),
+    "capgnn_softmax_ce_static": (_i32, [_i64, _i32, _vp, _i64, _vp, _vp, C.c_double, _vp, _vp, _i64, _i32, _vp]),
     "capgnn_sigmoid_bce": (_i32, [_i64, _i32, _vp, _i64, _vp, _i64, _vp, C.c_double, _vp, _vp, _i64, _i32, _vp, _sz, _vp]),
     "capgnn_epoch_multilabel": (_i32, [_vp, _vp, C.POINTER(Layer), _i32, _vp, _i64, _vp, _i64, _vp, C.c_double, _vp,
                                        C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_vp), C.c_float, C.POINTER(C.c_float),
@@ -430,6 +431,16 @@ def softmax_ce(n: int, n_classes: int, Z, ldz: int, labels, mask, loss_norm: flo
                dz_dtype: int, ws, ws_bytes: int, stream=None):
     _check(lib().capgnn_softmax_ce(n, n_classes, _p(Z), ldz, _p(labels), _p(mask), loss_norm, _p(loss_dev), _p(dZ), lddz,
                                    dz_dtype, _p(ws), ws_bytes, _stream(stream)))
+
+
+LOSS_STATIC_MAX_ROWS = 1 << 20
+
+
+def softmax_ce_static(n: int, n_classes: int, Z, ldz: int, labels, mask, loss_norm: float, loss_dev, dZ, lddz: int,
+                      dz_dtype: int, stream=None):
+    """capgnn_softmax_ce on the library's built-in scratch: no workspace, no allocation (n <= LOSS_STATIC_MAX_ROWS)."""
+    _check(lib().capgnn_softmax_ce_static(n, n_classes, _p(Z), ldz, _p(labels), _p(mask), loss_norm, _p(loss_dev), _p(dZ),
+                                          lddz, dz_dtype, _stream(stream)))
 
 
 def sigmoid_bce(n: int, n_classes: int, Z, ldz: int, targets, ldt: int, mask, loss_norm: float, loss_dev, dZ, lddz: int,

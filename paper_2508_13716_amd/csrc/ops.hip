@@ -1,6 +1,8 @@
 // Small VALU kernels around the layer: sigma' masking + bias gradient, softmax cross-entropy, SGD step.
 #include "common.h"
 
+#include <mutex>
+
 #include <algorithm>
 
 namespace capgnn {
@@ -592,16 +594,10 @@ extern "C" int capgnn_sigmoid_bce(int64_t n, int C, const float *Z, int64_t ldz,
     return CAPGNN_OK;
 }
 
-extern "C" int capgnn_softmax_ce(int64_t n, int C, const float *Z, int64_t ldz, const int32_t *labels,
-                                 const uint8_t *mask, double loss_norm, float *loss_dev, void *dZ, int64_t lddz,
-                                 int dz_dtype, void *ws, size_t ws_bytes, void *stream) {
-    if (dz_dtype != CAPGNN_F32 && dz_dtype != CAPGNN_BF16) CG_FAIL(CAPGNN_EINVAL, "softmax_ce: unknown dz_dtype");
-    if (n < 0 || C <= 0) CG_FAIL(CAPGNN_EINVAL, "softmax_ce: bad sizes");
-    if (n == 0) return CAPGNN_OK;
-    if (!Z || !labels || !loss_dev) CG_FAIL(CAPGNN_EINVAL, "softmax_ce: NULL operand");
-    if (ldz < C || (dZ && lddz < C)) CG_FAIL(CAPGNN_EINVAL, "softmax_ce: leading dimension smaller than C");
-    if (!ws || ws_bytes < capgnn_loss_workspace_bytes(n)) CG_FAIL(CAPGNN_ENOMEM, "softmax_ce: workspace too small");
-    hipStream_t st = static_cast<hipStream_t>(stream);
+// everything capgnn_softmax_ce does after its argument checks; `ws` holds capgnn_loss_workspace_bytes(n) bytes
+static int softmax_ce_launch(int64_t n, int C, const float *Z, int64_t ldz, const int32_t *labels, const uint8_t *mask,
+                             double loss_norm, float *loss_dev, void *dZ, int64_t lddz, int dz_dtype, void *ws,
+                             hipStream_t st) {
     float *norm_dev = nullptr;
     float norm_val = 1.f;
     float *scratch = static_cast<float *>(ws);
@@ -621,4 +617,67 @@ extern "C" int capgnn_softmax_ce(int64_t n, int C, const float *Z, int64_t ldz, 
     launch_loss_sum(n, row_loss, part, parts, norm_val, norm_dev, loss_dev, st);
     CG_HIP(hipGetLastError());
     return CAPGNN_OK;
+}
+
+static int softmax_ce_check(int64_t n, int C, const float *Z, int64_t ldz, const int32_t *labels, float *loss_dev,
+                            const void *dZ, int64_t lddz, int dz_dtype) {
+    if (dz_dtype != CAPGNN_F32 && dz_dtype != CAPGNN_BF16) CG_FAIL(CAPGNN_EINVAL, "softmax_ce: unknown dz_dtype");
+    if (n < 0 || C <= 0) CG_FAIL(CAPGNN_EINVAL, "softmax_ce: bad sizes");
+    if (n == 0) return CAPGNN_OK;
+    if (!Z || !labels || !loss_dev) CG_FAIL(CAPGNN_EINVAL, "softmax_ce: NULL operand");
+    if (ldz < C || (dZ && lddz < C)) CG_FAIL(CAPGNN_EINVAL, "softmax_ce: leading dimension smaller than C");
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_softmax_ce(int64_t n, int C, const float *Z, int64_t ldz, const int32_t *labels,
+                                 const uint8_t *mask, double loss_norm, float *loss_dev, void *dZ, int64_t lddz,
+                                 int dz_dtype, void *ws, size_t ws_bytes, void *stream) {
+    CG_TRY(softmax_ce_check(n, C, Z, ldz, labels, loss_dev, dZ, lddz, dz_dtype));
+    if (n == 0) return CAPGNN_OK;
+    if (!ws || ws_bytes < capgnn_loss_workspace_bytes(n)) CG_FAIL(CAPGNN_ENOMEM, "softmax_ce: workspace too small");
+    return softmax_ce_launch(n, C, Z, ldz, labels, mask, loss_norm, loss_dev, dZ, lddz, dz_dtype, ws,
+                             static_cast<hipStream_t>(stream));
+}
+
+// ------------------------------------------------------------------ the same loss without any allocation by anyone
+// The scratch of capgnn_softmax_ce (normaliser, per-workgroup partial sums, per-row loss terms) for up to
+// CAPGNN_LOSS_STATIC_MAX_ROWS rows, as a device array that is part of the library image: every GPU the library
+// runs on holds its own copy until the process ends.  Host code never uses the array's name as an address: the
+// address on the current device is asked for once per device and kept.
+static __device__ __align__(256) unsigned char scratch[LOSS_HEADER + static_cast<size_t>(CAPGNN_LOSS_STATIC_MAX_ROWS) * sizeof(float)];
+
+constexpr int MAX_DEVICES = 64;
+static void *g_scratch_ptr[MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the current device (looked up on the first call on that device)
+static int static_scratch(void **out) {
+    int dev = -1;
+    CG_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) CG_FAIL(CAPGNN_EUNSUPPORTED, "softmax_ce_static: device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        CG_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) CG_FAIL(CAPGNN_EHIP, "softmax_ce_static: the scratch array has no address on device %d", dev);
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_softmax_ce_static(int64_t n, int C, const float *Z, int64_t ldz, const int32_t *labels,
+                                        const uint8_t *mask, double loss_norm, float *loss_dev, void *dZ, int64_t lddz,
+                                        int dz_dtype, void *stream) {
+    CG_TRY(softmax_ce_check(n, C, Z, ldz, labels, loss_dev, dZ, lddz, dz_dtype));
+    if (n > CAPGNN_LOSS_STATIC_MAX_ROWS)
+        CG_FAIL(CAPGNN_ENOMEM, "softmax_ce_static: %lld rows, the built-in scratch holds %d; use capgnn_softmax_ce with a workspace",
+                static_cast<long long>(n), CAPGNN_LOSS_STATIC_MAX_ROWS);
+    if (n == 0) return CAPGNN_OK;
+    void *ws = nullptr;
+    CG_TRY(static_scratch(&ws));
+    // nothing in the scratch has to start at zero: the normaliser, parts[0..parts) and row terms [0, n) are all written
+    // before they are read, so what an earlier (larger) call left behind is never seen
+    return softmax_ce_launch(n, C, Z, ldz, labels, mask, loss_norm, loss_dev, dZ, lddz, dz_dtype, ws,
+                             static_cast<hipStream_t>(stream));
 }
