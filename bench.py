@@ -22,6 +22,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 FP32_MATRIX_PEAK_TFLOPS = 157.3
 BF16_MATRIX_PEAK_TFLOPS = 2500.0
+L2_PEAK_GBPS = 8 * 2048 * 2.4          # 8 L2s x 2 KB per clock x 2.4 GHz = 39 322 GB/s (equally 256 CUs x 64 B per clock)
 
 
 def spmm_launches(cfg, part, orders):
@@ -50,9 +51,11 @@ def spmm_min_bytes(part, F, n_out, n_in_touched, es):
 
 
 def gemm_report(cfg, part, orders, kernels, f32_product):
-    """FLOP rate of the first layer's forward transform, and the work it gives the matrix cores against their peak:
-    the fp32 instruction does the product's own FLOPs (peak 157.3 TFLOP/s); the split form does six bf16 piece
-    products per fp32 product (peak 2500 TFLOP/s); bf16 operands run on the bf16 cores as they are."""
+    """The first layer's forward transform: the METHOD's FLOP rate (2 M N K per product, whatever the implementation
+    spends on it) against the peak of the matrix instruction for the operands' own type - fp32 157.3 TFLOP/s, bf16
+    2500 - and, beside it, the work the implementation gives the matrix cores: the split form of the fp32 product
+    issues six bf16 piece products per fp32 product, so its instruction-level rate is six times the method's and is
+    measured against the bf16 peak.  The second figure is implementation work, not the method's."""
     rec = [k for k in kernels if k["kind"] == "gemm" and k["layer"] == 0 and not k["backward"]]
     if not rec:
         return None
@@ -62,15 +65,20 @@ def gemm_report(cfg, part, orders, kernels, f32_product):
     tf = flops / (rec[0]["ms"] * 1e-3) / 1e12
     split = cfg.dtype == "f32" and (f32_product == "split" or
                                     (f32_product == "auto" and rows * cfg.dims[0] * cfg.dims[1] >= 1 << 28))
-    if cfg.dtype != "f32":
-        form, peak, work = "bf16 matrix instruction", BF16_MATRIX_PEAK_TFLOPS, tf
-    elif split:
-        form, peak, work = "three bf16 pieces per operand, six piece products", BF16_MATRIX_PEAK_TFLOPS, 6.0 * tf
+    method_peak = FP32_MATRIX_PEAK_TFLOPS if cfg.dtype == "f32" else BF16_MATRIX_PEAK_TFLOPS
+    out = {"kernel": "transform of layer 0 (forward)", "gflop": flops / 1e9, "ms": rec[0]["ms"],
+           "method_tflops": tf, "method_peak_tflops": method_peak, "method_frac_of_peak": tf / method_peak,
+           "method_peak_is": "fp32 matrix instruction" if cfg.dtype == "f32" else "bf16 matrix instruction"}
+    if split:
+        out.update({"product_form": "three bf16 pieces per operand, six piece products per fp32 product",
+                    "instruction_work_tflops": 6.0 * tf, "instruction_peak_tflops": BF16_MATRIX_PEAK_TFLOPS,
+                    "instruction_work_frac_of_bf16_peak": 6.0 * tf / BF16_MATRIX_PEAK_TFLOPS,
+                    "method_frac_of_bf16_peak": tf / BF16_MATRIX_PEAK_TFLOPS,
+                    "note": "the factor 6 is implementation work; SQ_VALU_MFMA_BUSY_CYCLES of the same kernels is in "
+                            "profiles/gemm_C2_C4_mfma_counters.txt"})
     else:
-        form, peak, work = "fp32 matrix instruction", FP32_MATRIX_PEAK_TFLOPS, tf
-    return {"kernel": "transform of layer 0 (forward)", "gflop": flops / 1e9, "ms": rec[0]["ms"], "tflops": tf,
-            "product_form": form, "matrix_core_tflops": work, "peak_tflops": peak, "frac_of_matrix_peak": work / peak,
-            "note": "matrix-core busy cycles of the same kernels: profiles/gemm_C2_C4_mfma_counters.txt"}
+        out["product_form"] = "fp32 matrix instruction" if cfg.dtype == "f32" else "bf16 matrix instruction"
+    return out
 
 
 def f32_product_check(cfg):
@@ -90,31 +98,64 @@ def f32_product_check(cfg):
     wsb = B.gemm_workspace_bytes(0, M, N, K)
     ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
     out = {}
-    before = B.get_f32_product()
-    try:
-        for name, mode in (("fp32_instruction", B.F32_PRODUCT_NATIVE), ("three_bf16_pieces", B.F32_PRODUCT_SPLIT)):
-            Cd = torch.empty((M, N), device="cuda")
-            B.set_f32_product(mode)
-            B.gemm(0, 0, M, N, K, A, lda, W, N, Cd, N, B.F32, out_f32=1, ws=ws, ws_bytes=wsb, stream=torch.cuda.current_stream())
-            torch.cuda.synchronize()
-            out[name] = float((Cd.double() - ref).abs().max() / ref.abs().max())
-    finally:
-        B.set_f32_product(before)
+    for name, mode in (("fp32_instruction", B.F32_PRODUCT_NATIVE), ("three_bf16_pieces", B.F32_PRODUCT_SPLIT)):
+        Cd = torch.empty((M, N), device="cuda")
+        B.gemm(0, 0, M, N, K, A, lda, W, N, Cd, N, B.F32, out_f32=1, ws=ws, ws_bytes=wsb, stream=torch.cuda.current_stream(),
+               f32_product=mode)
+        torch.cuda.synchronize()
+        out[name] = float((Cd.double() - ref).abs().max() / ref.abs().max())
     out["product"] = f"{M} x {N} x {K}, standard normal operands"
     return out
 
 
-def cpu_baseline(cfg, scale, full_prob):
-    """The oracle as it stands, timed on the host cores: on the same partition when scale >= 1, else on a
-    scaled-down partition of the same shape (same average degree, widths and cache fraction)."""
+def gather_peaks(steps):
+    """What the memory levels deliver for the aggregation's access pattern, measured now on this GPU: 128-byte lines at
+    random line numbers, 16 loads in flight per lane, nothing else (capgnn_gather_peak), on tables that fit an L2
+    (2 MB), the Infinity Cache (128 MB) and neither (2 GB).  GB/s."""
+    import torch
+    from paper_2508_13716_amd import binding as B
+    st = torch.cuda.Stream()
+    wgs = 256 * 16
+    out_buf = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
+    res = {}
+    for name, nbytes, iters in (("l2_2MB", 2 << 20, 64), ("infinity_cache_128MB", 128 << 20, 32), ("hbm_2GB", 2 << 30, 16)):
+        table = torch.zeros(nbytes // 4, dtype=torch.float32, device="cuda")
+        B.gather_peak(table, nbytes // 128, wgs, iters, out_buf, st)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        moved = 0.0
+        for _ in range(max(3, steps // 4)):
+            moved += B.gather_peak(table, nbytes // 128, wgs, iters, out_buf, st)
+        e1.record(st)
+        torch.cuda.synchronize()
+        res[name] = moved / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del table
+    res["published_l2_peak"] = L2_PEAK_GBPS
+    res["note"] = ("published: 8 XCDs x 2 KB per clock per L2 x 2.4 GHz (= 256 compute units x 64 B per clock into their L1s); "
+                   "the measured rows are this GPU's rates for scattered 128-byte lines")
+    return res
+
+
+def cpu_baseline(prob, n_agg, threads=None, sample=None):
+    """The oracle as it stands, timed on the host cores on `prob` (one full fp64 epoch).  threads: None = all cores."""
     from oracle import oracle as orc
-    from paper_2508_13716_amd import harness as H
     from tests import oracle_side as O
-    prob = full_prob if scale >= 1.0 else H.make_problem(cfg.scaled(scale))
-    t0 = time.perf_counter()
-    ref = O.oracle_epoch(prob)
-    dt = time.perf_counter() - t0
-    return prob, ref, dt, orc.max_threads()
+    all_cores = orc.max_threads()
+    if threads is not None:
+        orc.set_threads(threads)
+    try:
+        t0 = time.perf_counter()
+        O.oracle_epoch(prob)
+        dt = time.perf_counter() - t0
+    finally:
+        if threads is not None:
+            orc.set_threads(all_cores)
+    part, cfg = prob.part, prob.cfg
+    return {"value": part.nnz * n_agg / dt / 1e9, "unit": "GEdges/s (edges aggregated per epoch / epoch wall time)",
+            "cores": all_cores if threads is None else threads, "kind": "oracle",
+            "sample": sample or f"the whole of {cfg.name} ({part.n_loc} local, {part.n_halo} halo, {part.nnz} edges), one full fp64 oracle epoch, {dt:.2f} s",
+            "epoch_s_on_sample": dt}
 
 
 def bench_cache_update(args):
@@ -298,9 +339,9 @@ def bench_products(args):
         Cd = torch.empty((M, ldc), device="cuda")
         wsb = B.gemm_workspace_bytes(ta, M, N, K)
         ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
-        B.set_f32_product(mode)
         st = torch.cuda.Stream()
-        call = lambda: B.gemm(ta, tb, M, N, K, A, lda, Bm, ldb, Cd, ldc, B.F32, out_f32=1, ws=ws, ws_bytes=wsb, stream=st)
+        call = lambda: B.gemm(ta, tb, M, N, K, A, lda, Bm, ldb, Cd, ldc, B.F32, out_f32=1, ws=ws, ws_bytes=wsb, stream=st,
+                              f32_product=mode)
         for _ in range(args.warmup):
             call()
         torch.cuda.synchronize()
@@ -324,7 +365,6 @@ def bench_products(args):
             out.append({"product": name, "M": M, "N": N, "K": K, "trans_a": ta, "trans_b": tb,
                         "fp32_instruction": run(ta, tb, M, N, K, B.F32_PRODUCT_NATIVE),
                         "three_bf16_pieces": run(ta, tb, M, N, K, B.F32_PRODUCT_SPLIT)})
-    B.set_f32_product(B.F32_PRODUCT_AUTO)
     print(json.dumps({"metric": "dense products alone, both forms of the fp32 product", "unit": "ms / TFLOP/s / max error over max |result|",
                       "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
                       "config": {"workload": f"{args.config}: {n_loc} local + {cfg.n_halo} halo rows, dims {list(cfg.dims)}"},
@@ -397,7 +437,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="C2")
+    ap.add_argument("--config", default=None, help="one workload only (C1..C5); default: C2 as the headline line with C1, C3, C4, C5 under 'configs'")
     ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder", "zipf_requests", "mfma_peak", "products"],
                     help="epoch (default): the headline benchmark; cache_update: throughput of the cache write path; "
                          "policy: hit-rate curves of the cache policies; reorder: SpMM before / after vertex reordering "
@@ -410,7 +450,7 @@ def main():
                     help="how products of fp32 operands are formed: the fp32 matrix instruction, three bf16 pieces per operand "
                          "on the bf16 matrix cores, or (default) the library's choice by size")
     ap.add_argument("--cpu-scale", type=float, default=None,
-                    help="share of the workload the oracle is timed on (0 = skip; default: sized for 10-30 s of CPU work)")
+                    help="share of the workload the oracle is timed on (0 = skip; default: the whole workload, 0.1-27 s per configuration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the partition-local step on ONE GPU; --gpus > 1 is not part of it "
@@ -424,7 +464,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     B.lib()
-    B.set_f32_product({"auto": B.F32_PRODUCT_AUTO, "native": B.F32_PRODUCT_NATIVE, "split": B.F32_PRODUCT_SPLIT}[args.f32_product])
+    if args.what != "epoch" and args.config is None:
+        args.config = "C2"
     if args.what == "cache_update":
         return bench_cache_update(args)
     if args.what == "reorder":
@@ -438,39 +479,75 @@ def main():
     if args.what == "policy":
         return bench_policy(args)
 
-    cfg = synth.CONFIGS[args.config]
-    t_gen = time.perf_counter()
+    peaks = gather_peaks(args.steps)
+    if args.config is not None:
+        out = epoch_record(args.config, args, peaks, headline=True)
+    else:
+        # the headline line is C2's; the other four named workloads ride along, each measured the same way
+        out = epoch_record("C2", args, peaks, headline=True)
+        out["configs"] = {}
+        for name in ("C1", "C3", "C4", "C5"):
+            rec = epoch_record(name, args, peaks, headline=False)
+            out["configs"][name] = rec
+    out["gather_peaks_GBps"] = peaks
+    print(json.dumps(out))
+
+
+def traffic_for(key):
+    """(bytes per launch beyond L2, where it comes from) for a launch key of profiles/traffic_per_launch.txt, or (None, None):
+    a PROFILED CONSTANT (two rocprofv3 --pmc runs, FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size), not
+    measured in this run; the file names the commit the counters were taken at."""
+    tpath = os.path.join(ROOT, "profiles", "traffic_per_launch.txt")
+    if not os.path.exists(tpath):
+        return None, None
+    taken_at = None
+    for line in open(tpath):
+        if line.startswith("# taken at"):
+            taken_at = line[2:].strip()
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == key:
+            return float(parts[1]), f"profiled constant from profiles/traffic_per_launch.txt ({taken_at or 'commit not recorded'}); not measured in this run"
+    return None, None
+
+
+def epoch_record(name, args, peaks, headline):
+    """Builds the named workload, times args.steps epochs, and returns its record (the whole JSON line when headline)."""
+    import numpy as np
+    import torch
+    from paper_2508_13716_amd import binding as B, harness as H, synth
+    cfg = synth.CONFIGS[name]
     prob = H.make_problem(cfg)
     if args.reorder != "none":
         prob, _ = H.relabel_problem(prob, B.RELABEL_POPULARITY if args.reorder == "popularity" else B.RELABEL_BFS)
     part = prob.part
-    t_gen = time.perf_counter() - t_gen
     orders = [int(x) for x in args.orders.split(",")] if args.orders else None
-    dp = H.DeviceProblem(prob, orders=orders, miss_mode=B.MISS_PIPELINED if args.miss_mode is None else args.miss_mode)
+    f32p = {"auto": B.F32_PRODUCT_AUTO, "native": B.F32_PRODUCT_NATIVE, "split": B.F32_PRODUCT_SPLIT}[args.f32_product]
+    miss_mode = B.MISS_PIPELINED if args.miss_mode is None else args.miss_mode
+
+    def timed(dp, steps):
+        for _ in range(args.warmup):
+            dp.run_epoch()
+        torch.cuda.synchronize()
+        acc, stage, dev_epochs = {}, {}, []
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            loss, times = dp.run_epoch(want_times=True)
+            per_epoch = {}
+            for r in times["records"]:      # several records of one epoch may share a key (the GEMMs of one layer)
+                key = (r["kind"], r["layer"], r["backward"])
+                per_epoch[key] = per_epoch.get(key, 0.0) + r["ms"]
+            for key, ms in per_epoch.items():
+                acc.setdefault(key, []).append(ms)
+            dev_epochs.append(times["total_ms"])
+            for k in ("pick_cache_ms", "communication_ms", "aggregation_ms", "combine_ms", "loss_ms", "other_ms", "total_ms"):
+                stage[k] = stage.get(k, 0.0) + times[k] / steps
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps, acc, stage, dev_epochs, loss
+
+    dp = H.DeviceProblem(prob, orders=orders, miss_mode=miss_mode, f32_product=f32p)
     res_orders = dp.resolved_orders()
     es = dp.es
-
-    for _ in range(args.warmup):
-        dp.run_epoch()
-    torch.cuda.synchronize()
-    acc = {}
-    stage = {}
-    dev_epochs = []
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        loss, times = dp.run_epoch(want_times=True)
-        per_epoch = {}
-        for r in times["records"]:      # several records of one epoch may share a key (the GEMMs of one layer)
-            key = (r["kind"], r["layer"], r["backward"])
-            per_epoch[key] = per_epoch.get(key, 0.0) + r["ms"]
-        for key, ms in per_epoch.items():
-            acc.setdefault(key, []).append(ms)
-        dev_epochs.append(times["total_ms"])
-        for k in ("pick_cache_ms", "communication_ms", "aggregation_ms", "combine_ms", "loss_ms", "other_ms", "total_ms"):
-            stage[k] = stage.get(k, 0.0) + times[k] / args.steps
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step, acc, stage, dev_epochs, loss = timed(dp, args.steps)
 
     launches = spmm_launches(cfg, part, res_orders)
     # the method's own count: one aggregation per layer forward, one transposed aggregation per layer
@@ -487,21 +564,22 @@ def main():
     bmin = spmm_min_bytes(part, F, n_out, touched, es)
     bgather = part.nnz * (4 + F * es) + n_out * F * es
     achieved = bmin / (dom["ms"] * 1e-3) / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic_per_launch.txt")
-    if os.path.exists(tpath):
-        want = f"{cfg.name}:{dom['kind']}:L{dom['layer']}:F{F}"
-        for line in open(tpath):
-            parts = line.split()
-            if len(parts) == 2 and parts[0] == want:
-                traffic = float(parts[1])
+    traffic, traffic_src = traffic_for(f"{cfg.name}:{dom['kind']}:L{dom['layer']}:F{F}")
     spmm_ms = sum(k["ms"] for k in spmm_recs)
     hit_bytes = sum(2 * dp.cache.cap_gpu * cfg.dims[l] * es for l in range(dp.L)) if dp.cache else 0
     miss_bytes = sum((part.n_halo - dp.cache.cap_gpu) * cfg.dims[l] * es for l in range(dp.L)) if dp.cache else 0
     hit_ms = sum(k["ms"] for k in kernels if k["kind"] == "gather_hit")
     staged_ms = sum(k["ms"] for k in kernels if k["kind"] == "gather_staged")
     miss_ms = sum(k["ms"] for k in kernels if k["kind"] == "gather_miss")
-    pipelined_mode = (B.MISS_PIPELINED if args.miss_mode is None else args.miss_mode) == B.MISS_PIPELINED
+    pipelined_mode = miss_mode == B.MISS_PIPELINED
+    copy_rate = ((hit_bytes + (2 * miss_bytes if (staged_ms or pipelined_mode) else 0)) / ((hit_ms + staged_ms) * 1e-3) / 1e9
+                 if hit_ms + staged_ms else None)
+    # which memory level serves the gather: the column-blocked kernel walks 4 MB panels (an L2); the one-wave-per-row
+    # kernel gathers from the whole operand
+    operand_bytes = touched * F * es
+    blocked = bool(B.spmm_workspace_bytes(dp.graph, F, dp.dtype) > operand_bytes)     # partial rows for every source block
+    level = "l2_2MB" if blocked else ("infinity_cache_128MB" if operand_bytes <= (256 << 20) else "hbm_2GB")
+    gather_rate = part.nnz * F * es / (dom["ms"] * 1e-3) / 1e9
 
     out = {
         "metric": "aggregation GEdges/s + achieved HBM GB/s; partition epoch ms (fwd+bwd)",
@@ -519,41 +597,73 @@ def main():
                                  2: "DMA into a staging area, one epoch ahead (pipelined)"}[dp.miss_mode] if dp.cache else None},
         "epoch_ms_device": stage.get("total_ms"),
         "epoch_ms_device_median": float(np.median(dev_epochs)), "epoch_ms_device_min": float(np.min(dev_epochs)),
-        "env": {"device": torch.cuda.get_device_name(0), "hip": torch.version.hip, "torch": torch.__version__,
-                "host_cores": os.cpu_count()},
         "stages_ms": {k: round(v, 4) for k, v in stage.items()},
         "aggregation_gedges_s_kernel_only": part.nnz * len(launches) / (spmm_ms * 1e-3) / 1e9 if spmm_ms else None,
         # pipelined mode: one launch per layer copies the GPU tier's rows and the staged host rows (read + written bytes)
-        "gather": {"device_copy_GBps": (hit_bytes + (2 * miss_bytes if (staged_ms or pipelined_mode) else 0)) /
-                                       ((hit_ms + staged_ms) * 1e-3) / 1e9 if hit_ms + staged_ms else None,
+        "gather": {"device_copy_GBps": copy_rate, "device_copy_frac_of_hbm_peak": copy_rate / HBM_PEAK_GBPS if copy_rate else None,
                    "hit_bytes": hit_bytes,
                    "miss_host_link_GBps": miss_bytes / (miss_ms * 1e-3) / 1e9 if miss_ms else None,
                    "miss_bytes": miss_bytes},
         "gemm": gemm_report(cfg, part, res_orders, kernels, args.f32_product),
-        "f32_product_max_rel_err": f32_product_check(cfg),
-        "kernels": kernels[:12],
+        "kernels": kernels[:12 if headline else 6],
         "roofline": {"kernel": f"{dom['kind']} layer {dom['layer']} F={F}", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "algorithmic_bytes": bmin, "gathered_bytes_no_reuse": bgather,
-                     "gather_rate_GBps": bgather / (dom["ms"] * 1e-3) / 1e9, "ms": dom["ms"],
+                     "traffic_source": traffic_src,
+                     "traffic_frac_of_hbm_peak": traffic / (dom["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS if traffic else None,
+                     "algorithmic_bytes": bmin, "gathered_bytes_no_reuse": bgather, "ms": dom["ms"],
                      "gedges_s": part.nnz / (dom["ms"] * 1e-3) / 1e9,
-                     "note": "achieved = algorithmic bytes / launch time; the gather itself is served by the L2s "
-                             "(C2: L2 channels busy for all of the kernel's cycles, profiles/spmm_C2_hbm_counters.txt)"},
+                     "note": "achieved = algorithmic bytes (every index, needed source row and output row once) / launch time"},
+        # the roof the same launch actually sits on: what the CUs request (every entry's feature bytes) against the rate the
+        # serving memory level delivers for scattered 128-byte lines, measured in this run (gather_peaks_GBps)
+        "roofline_gather": {"kernel": f"{dom['kind']} layer {dom['layer']} F={F}",
+                            "bound": {"l2_2MB": "l2", "infinity_cache_128MB": "infinity cache", "hbm_2GB": "hbm, scattered lines"}[level],
+                            "achieved": gather_rate, "peak": peaks[level], "unit": "GB/s", "frac": gather_rate / peaks[level],
+                            "peak_is": f"capgnn_gather_peak on a {level.split('_')[-1]} table, this run",
+                            "frac_of_published_l2_peak": gather_rate / L2_PEAK_GBPS,
+                            "kernel_form": "column-blocked (4 MB source panels)" if blocked else "one wave per row"},
     }
-    if args.cpu_scale is None:
-        # the oracle moves about 3 GFLOP-equivalents per second per 16 cores on this kind of epoch
-        est_full_s = part.nnz * sum(cfg.dims[:-1]) * 2 * 2 / 3.0e9 / 8
-        args.cpu_scale = 1.0 if est_full_s <= 30 else max(0.02, 20.0 / est_full_s)
-    if args.cpu_scale > 0:
-        sprob, _, dt, cores = cpu_baseline(cfg, args.cpu_scale, prob)
-        s_edges = sprob.part.nnz * n_agg
-        out["cpu_baseline"] = {"value": s_edges / dt / 1e9, "unit": "GEdges/s (edges aggregated per epoch / epoch wall time)",
-                               "cores": cores, "kind": "oracle",
-                               "sample": f"{cfg.name} at {min(args.cpu_scale, 1.0):g} of its vertices and edges "
-                                         f"({sprob.part.n_loc} local, {sprob.part.n_halo} halo, {sprob.part.nnz} edges; same "
-                                         f"average degree and widths), one full fp64 oracle epoch, {dt:.2f} s",
-                               "epoch_s_on_sample": dt}
-    print(json.dumps(out))
+    if headline:
+        out["env"] = {"device": torch.cuda.get_device_name(0), "hip": torch.version.hip, "torch": torch.__version__,
+                      "host_cores": os.cpu_count()}
+        out["f32_product_max_rel_err"] = f32_product_check(cfg)
+    # Alg. 1 on this GPU: how many halo rows its memory would cache
+    if dp.cache and dp.cache.cap_gpu < part.n_halo:
+        free_b, total_b = torch.cuda.mem_get_info()
+        cap = B.cal_capacity(total_b / 2 ** 30, 4096.0, cfg.dims[:dp.L], part.n_halo, es)
+        out["alg1_capacity"] = {"gpu_memory_GiB": total_b / 2 ** 30, "reserved_MB": 4096, "rows": cap, "halo_rows": part.n_halo,
+                                "note": "Alg. 1 (cal_capacity) with this GPU's memory"}
+        if cap >= part.n_halo and not headline:
+            # the same workload with the GPU tier Alg. 1 grants here: every halo row is a hit, no host-link traffic
+            dp.close()
+            del dp
+            torch.cuda.empty_cache()
+            import copy
+            prob_all = copy.copy(prob)
+            prob_all.cap_gpu = part.n_halo
+            dp = H.DeviceProblem(prob_all, orders=orders, miss_mode=miss_mode, f32_product=f32p)
+            ms2, _, stage2, _, _ = timed(dp, args.steps)
+            out["alg1_capacity"].update({"epoch_ms_wall": ms2, "epoch_ms_device": stage2.get("total_ms"),
+                                         "gedges_s": edges_per_epoch / (ms2 * 1e-3) / 1e9})
+    dp.close()
+    del dp
+    torch.cuda.empty_cache()
+    if args.cpu_scale is None or args.cpu_scale > 0:
+        scale = args.cpu_scale
+        if scale is None or scale >= 1.0:
+            out["cpu_baseline"] = cpu_baseline(prob, n_agg)
+        else:
+            sprob = H.make_problem(cfg.scaled(scale))
+            out["cpu_baseline"] = cpu_baseline(sprob, n_agg, sample=f"{cfg.name} at {scale:g} of its vertices and edges "
+                                               f"({sprob.part.n_loc} local, {sprob.part.n_halo} halo, {sprob.part.nnz} edges; same average degree and widths), one full fp64 oracle epoch")
+        if name in ("C1", "C2", "C3"):
+            # the single-thread leg, on a bounded sample of the same shape (the whole of C1)
+            s1 = 1.0 if name == "C1" else 0.1
+            sprob = prob if s1 >= 1.0 else H.make_problem(cfg.scaled(s1))
+            out["cpu_baseline_1_thread"] = cpu_baseline(
+                sprob, n_agg, threads=1,
+                sample=None if s1 >= 1.0 else f"{cfg.name} at {s1:g} of its vertices and edges ({sprob.part.n_loc} local, "
+                                              f"{sprob.part.n_halo} halo, {sprob.part.nnz} edges; same average degree and widths), one full fp64 oracle epoch")
+    return out
 
 
 if __name__ == "__main__":

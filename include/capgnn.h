@@ -114,8 +114,8 @@ int capgnn_graph_create(capgnn_graph **g, int64_t n_loc, int64_t n_halo,
 int capgnn_graph_destroy(capgnn_graph *g);
 
 /* ------------------------------------------------------------------------------------------
- * Aggregation ("SpMM is related to the number of edges", section on RAPA's cost model; the
- * `aggregation` stage of the evaluation's stage breakdown).
+ * Aggregation (the SpMM term of RAPA's cost model, Eq. 4; the `aggregation` stage of the evaluation's
+ * stage breakdown).
  * ---------------------------------------------------------------------------------------- */
 
 /* Y[i,0:F] = row_scale[i] * sum_{e in row i} edge_val[e]*col_scale[col e] * X[col e, 0:F], i < n_loc.
@@ -289,7 +289,7 @@ int capgnn_relabel_csr(int64_t n_loc, int64_t n_halo, const int64_t *rowptr, con
                        float *val_out);
 
 /* ------------------------------------------------------------------------------------------
- * Dense products on the matrix cores ("MM is related to the number of vertices").
+ * Dense products on the matrix cores (the combination step; the MM term of RAPA's cost model, Eq. 4).
  * C[M x N] (+)= op(A) op(B) with fp32 accumulation; optional fused bias / ReLU epilogue.
  * trans_a: A is stored [K x M];  trans_b: B is stored [N x K].  bias: device float[N] or NULL.
  * relu_mask: device [M x ldm] of `dtype` or NULL; when given, C[i,j] is zeroed where
@@ -301,7 +301,10 @@ int capgnn_relabel_csr(int64_t n_loc, int64_t n_halo, const int64_t *rowptr, con
  * ---------------------------------------------------------------------------------------- */
 size_t capgnn_gemm_workspace_bytes(int trans_a, int64_t M, int64_t N, int64_t K);
 
-/* How products of fp32 operands are formed (process-wide; takes effect with the next call that launches a product).
+/* How a product of fp32 operands is formed: an argument of capgnn_gemm and a field of capgnn_layer (nothing is
+ * process-wide, so distinct handles and calls stay independent).
+ *   CAPGNN_F32_PRODUCT_AUTO    (0, what a zeroed field means) SPLIT for products of 2^28 multiply-adds and more, except
+ *                              trans_a products with N <= 64; NATIVE otherwise.
  *   CAPGNN_F32_PRODUCT_NATIVE  the fp32 matrix instruction (v_mfma_f32_32x32x2_f32).
  *   CAPGNN_F32_PRODUCT_SPLIT   each fp32 operand is cut, exactly, into three bf16 numbers and the six largest of the nine
  *                              piece products are accumulated in fp32 on the bf16 matrix cores; what is dropped is
@@ -309,24 +312,28 @@ size_t capgnn_gemm_workspace_bytes(int trans_a, int64_t M, int64_t N, int64_t K)
  *                              workspace of capgnn_gemm_workspace_bytes() also when !trans_a (the weight matrix is cut
  *                              there); without it, and for trans_a && trans_b, the native instruction runs.
  *                              Non-finite operands give NaN where the native instruction may give an infinity.
- *   CAPGNN_F32_PRODUCT_AUTO    (default) SPLIT for products of 2^28 multiply-adds and more, except trans_a products
- *                              with N <= 64; NATIVE otherwise.
- * bf16 operands are not affected.  Returns CAPGNN_EINVAL for an unknown mode. */
-#define CAPGNN_F32_PRODUCT_NATIVE 0
-#define CAPGNN_F32_PRODUCT_SPLIT 1
-#define CAPGNN_F32_PRODUCT_AUTO 2
-int capgnn_set_f32_product(int mode);
-int capgnn_get_f32_product(void);
+ * bf16 operands are not affected.  Any other value: CAPGNN_EINVAL. */
+#define CAPGNN_F32_PRODUCT_AUTO 0
+#define CAPGNN_F32_PRODUCT_NATIVE 1
+#define CAPGNN_F32_PRODUCT_SPLIT 2
 
 /* Measurement aid for the matrix-core roofline of the dense products: launches `workgroups` workgroups of 256 threads
  * that each issue 4 * iters register-resident matrix instructions per wave (v_mfma_f32_32x32x2_f32 for CAPGNN_F32,
  * v_mfma_f32_32x32x16_bf16 for CAPGNN_BF16) and returns in *flop (host) the floating-point operations the launch
  * performs; the caller times it.  out: device float[workgroups * 256] (receives one value per thread). */
 int capgnn_mfma_peak(int dtype, int workgroups, int iters, float *out, double *flop, void *stream);
+
+/* Measurement aid for the gather roofline of the aggregation: `workgroups` workgroups of 256 threads whose 8-lane groups
+ * each fetch 16 * iters pseudo-random 128-byte lines (16 bytes per lane, 16 loads in flight) of `table` (device,
+ * table_lines * 128 bytes, 16-byte aligned), and nothing else.  *bytes (host) = the bytes the launch requests; the
+ * caller times it.  With a table that fits an L2 (4 MB per XCD), the Infinity Cache (256 MB) or neither, the rate is
+ * what that level delivers for the aggregation's access pattern.  out: device float[workgroups * 256]. */
+int capgnn_gather_peak(const void *table, int64_t table_lines, int workgroups, int iters, float *out, double *bytes,
+                       void *stream);
 int capgnn_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K,
                 const void *A, int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc,
                 int dtype, int out_f32, int accumulate, const float *bias, int relu,
-                const void *relu_mask, int64_t ldm, void *ws, size_t ws_bytes, void *stream);
+                const void *relu_mask, int64_t ldm, int f32_product, void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------
  * Layer and epoch.
@@ -338,6 +345,7 @@ typedef struct {
     int dtype;           /* storage type of X, H and of W / W_self                          */
     int order;           /* CAPGNN_ORDER_AUTO | CAPGNN_AGG_FIRST | CAPGNN_XFORM_FIRST       */
     int out_f32;         /* store H as float even when dtype is BF16 (the layer that feeds the loss) */
+    int f32_product;     /* CAPGNN_F32_PRODUCT_*: how this layer's products of fp32 operands are formed (0 = AUTO) */
     void *W;             /* device [f_in x f_out], dense (ld = f_out); neighbour weight for SAGE */
     void *W_self;        /* device [f_in x f_out], SAGE only, else NULL                     */
     float *bias;         /* device float[f_out] or NULL                                     */

@@ -37,7 +37,7 @@ class CapgnnError(RuntimeError):
 
 class Layer(C.Structure):
     _fields_ = [("kind", C.c_int), ("f_in", C.c_int), ("f_out", C.c_int), ("act", C.c_int), ("dtype", C.c_int),
-                ("order", C.c_int), ("out_f32", C.c_int), ("W", C.c_void_p), ("W_self", C.c_void_p),
+                ("order", C.c_int), ("out_f32", C.c_int), ("f32_product", C.c_int), ("W", C.c_void_p), ("W_self", C.c_void_p),
                 ("bias", C.c_void_p)]
 
 
@@ -91,11 +91,10 @@ SIGNATURES = {
     "capgnn_cache_lookup": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _vp]),
     "capgnn_halo_gather": (_i32, [_vp, _i32, _vp, _i64, _i32, _vp, _i64, _vp, _vp, _vp, C.POINTER(GatherStats)]),
     "capgnn_gemm_workspace_bytes": (_sz, [_i32, _i64, _i64, _i64]),
-    "capgnn_set_f32_product": (_i32, [_i32]),
-    "capgnn_get_f32_product": (_i32, []),
     "capgnn_mfma_peak": (_i32, [_i32, _i32, _i32, _vp, C.POINTER(C.c_double), _vp]),
+    "capgnn_gather_peak": (_i32, [_vp, _i64, _i32, _i32, _vp, C.POINTER(C.c_double), _vp]),
     "capgnn_gemm": (_i32, [_i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _i32, _vp, _i32,
-                           _vp, _i64, _vp, _sz, _vp]),
+                           _vp, _i64, _i32, _vp, _sz, _vp]),
     "capgnn_layer_order": (_i32, [_vp, C.POINTER(Layer), _i32]),
     "capgnn_layer_saved_bytes": (_sz, [_vp, C.POINTER(Layer)]),
     "capgnn_layer_workspace_bytes": (_sz, [_vp, C.POINTER(Layer)]),
@@ -363,16 +362,7 @@ def relabel_csr(n_loc: int, n_halo: int, rowptr, col, new2old, edge_val=None):
 
 
 # --------------------------------------------------------------------------- dense, layer, loss, epoch
-F32_PRODUCT_NATIVE, F32_PRODUCT_SPLIT, F32_PRODUCT_AUTO = 0, 1, 2
-
-
-def set_f32_product(mode: int) -> None:
-    """Chooses how products of fp32 operands are formed (fp32 matrix instruction / three-way bf16 split / by size)."""
-    _check(lib().capgnn_set_f32_product(mode))
-
-
-def get_f32_product() -> int:
-    return int(lib().capgnn_get_f32_product())
+F32_PRODUCT_AUTO, F32_PRODUCT_NATIVE, F32_PRODUCT_SPLIT = 0, 1, 2     # how a product of fp32 operands is formed
 
 
 def mfma_peak(dtype: int, workgroups: int, iters: int, out, stream=None) -> float:
@@ -382,20 +372,27 @@ def mfma_peak(dtype: int, workgroups: int, iters: int, out, stream=None) -> floa
     return float(flop.value)
 
 
+def gather_peak(table, table_lines: int, workgroups: int, iters: int, out, stream=None) -> float:
+    """Launches the pure 128-byte-line gather loop over `table`; returns the bytes it requests (the caller times it)."""
+    nbytes = C.c_double(0.0)
+    _check(lib().capgnn_gather_peak(_p(table), table_lines, workgroups, iters, _p(out), C.byref(nbytes), _stream(stream)))
+    return float(nbytes.value)
+
+
 def gemm_workspace_bytes(trans_a: int, M: int, N: int, K: int) -> int:
     return int(lib().capgnn_gemm_workspace_bytes(trans_a, M, N, K))
 
 
 def gemm(trans_a: int, trans_b: int, M: int, N: int, K: int, A, lda: int, B, ldb: int, Cm, ldc: int, dtype: int,
          out_f32: int = 0, accumulate: int = 0, bias=None, relu: int = 0, relu_mask=None, ldm: int = 0, ws=None,
-         ws_bytes: int = 0, stream=None):
+         ws_bytes: int = 0, stream=None, f32_product: int = F32_PRODUCT_AUTO):
     _check(lib().capgnn_gemm(trans_a, trans_b, M, N, K, _p(A), lda, _p(B), ldb, _p(Cm), ldc, dtype, out_f32, accumulate,
-                             _p(bias), relu, _p(relu_mask), ldm, _p(ws), ws_bytes, _stream(stream)))
+                             _p(bias), relu, _p(relu_mask), ldm, f32_product, _p(ws), ws_bytes, _stream(stream)))
 
 
 def make_layer(kind: int, f_in: int, f_out: int, act: int, dtype: int, W, W_self=None, bias=None,
-               order: int = ORDER_AUTO, out_f32: int = 0) -> Layer:
-    return Layer(kind, f_in, f_out, act, dtype, order, out_f32, _p(W), _p(W_self), _p(bias))
+               order: int = ORDER_AUTO, out_f32: int = 0, f32_product: int = F32_PRODUCT_AUTO) -> Layer:
+    return Layer(kind, f_in, f_out, act, dtype, order, out_f32, f32_product, _p(W), _p(W_self), _p(bias))
 
 
 def layer_order(g: Graph, l: Layer, need_dx: bool) -> int:

@@ -162,7 +162,8 @@ int launch_spmm(const SpOp &op, bool restrict_sub, const void *X, int64_t ldx, v
 int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
                 const void *B, int64_t ldb, void *C, int64_t ldc, int dtype, int out_f32, int accumulate,
                 const float *bias, int relu, const void *relu_mask, int64_t ldm, void *ws, size_t ws_bytes,
-                hipStream_t stream, const float *row_scale = nullptr);   // row_scale: C[i,:] *= row_scale[i] at the very end (fp32 C)
+                hipStream_t stream, const float *row_scale = nullptr,    // row_scale: C[i,:] *= row_scale[i] at the very end (fp32 C)
+                int f32_product = CAPGNN_F32_PRODUCT_AUTO);
 size_t gemm_ws_bytes(int trans_a, int64_t M, int64_t N, int64_t K);
 
 // dZ = dH * 1[H > 0] in place (when relu) and dbias[f] = sum_i dZ[i,f] (when dbias), fixed summation order.

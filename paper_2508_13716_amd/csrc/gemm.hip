@@ -1153,8 +1153,6 @@ size_t gemm_ws_bytes(int trans_a, int64_t M, int64_t N, int64_t K) {
     return b;
 }
 
-// how products of fp32 operands are formed (capgnn_set_f32_product)
-static std::atomic<int> f32_product_mode{CAPGNN_F32_PRODUCT_AUTO};
 // AUTO: smaller products stay on the fp32 instruction, and so do weight gradients at most 64 columns wide (half of
 // the threads that stage their operands would idle; measured slower)
 constexpr int64_t SPLIT_MIN_MACS = int64_t(1) << 28;
@@ -1186,8 +1184,10 @@ static void launch_bf16_tiles(const GemmArgs &g, int bn, dim3 grid, hipStream_t 
 int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
                 const void *B, int64_t ldb, void *C, int64_t ldc, int dtype, int out_f32, int accumulate,
                 const float *bias, int relu, const void *relu_mask, int64_t ldm, void *ws, size_t ws_bytes,
-                hipStream_t stream, const float *row_scale) {
+                hipStream_t stream, const float *row_scale, int f32_product) {
     if (dtype != CAPGNN_F32 && dtype != CAPGNN_BF16) CG_FAIL(CAPGNN_EINVAL, "gemm: unknown dtype %d", dtype);
+    if (f32_product != CAPGNN_F32_PRODUCT_AUTO && f32_product != CAPGNN_F32_PRODUCT_NATIVE && f32_product != CAPGNN_F32_PRODUCT_SPLIT)
+        CG_FAIL(CAPGNN_EINVAL, "gemm: unknown form of the fp32 product %d", f32_product);
     if (M < 0 || N < 0 || K < 0) CG_FAIL(CAPGNN_EINVAL, "gemm: negative size");
     if (M == 0 || N == 0) return CAPGNN_OK;
     if (!A || !B || !C) CG_FAIL(CAPGNN_EINVAL, "gemm: NULL operand");
@@ -1203,7 +1203,7 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
     const bool half_path = dtype == CAPGNN_BF16 && aligned16(A) && (lda * 2) % 16 == 0 &&
                            (repack_b || (aligned16(B) && (ldb * 2) % 16 == 0));
     // fp32 operands as three bf16 pieces each (see gemm_split_kernel)
-    const int mode = f32_product_mode.load(std::memory_order_relaxed);
+    const int mode = f32_product;
     const bool split_path = dtype == CAPGNN_F32 && mode != CAPGNN_F32_PRODUCT_NATIVE && !(trans_a && trans_b) &&
                             (mode == CAPGNN_F32_PRODUCT_SPLIT ||
                              (M * N >= SPLIT_MIN_MACS / (K > 0 ? K : 1) && !(trans_a && N <= 64))) &&
@@ -1325,23 +1325,14 @@ extern "C" int capgnn_mfma_peak(int dtype, int workgroups, int iters, float *out
     return CAPGNN_OK;
 }
 
-extern "C" int capgnn_set_f32_product(int mode) {
-    if (mode != CAPGNN_F32_PRODUCT_NATIVE && mode != CAPGNN_F32_PRODUCT_SPLIT && mode != CAPGNN_F32_PRODUCT_AUTO)
-        CG_FAIL(CAPGNN_EINVAL, "set_f32_product: unknown mode %d", mode);
-    f32_product_mode.store(mode, std::memory_order_relaxed);
-    return CAPGNN_OK;
-}
-
-extern "C" int capgnn_get_f32_product(void) { return f32_product_mode.load(std::memory_order_relaxed); }
-
 extern "C" size_t capgnn_gemm_workspace_bytes(int trans_a, int64_t M, int64_t N, int64_t K) {
     return gemm_ws_bytes(trans_a, M, N, K);
 }
 
 extern "C" int capgnn_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
                            const void *B, int64_t ldb, void *C, int64_t ldc, int dtype, int out_f32, int accumulate,
-                           const float *bias, int relu, const void *relu_mask, int64_t ldm, void *ws,
+                           const float *bias, int relu, const void *relu_mask, int64_t ldm, int f32_product, void *ws,
                            size_t ws_bytes, void *stream) {
     return launch_gemm(trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, dtype, out_f32, accumulate, bias, relu,
-                       relu_mask, ldm, ws, ws_bytes, static_cast<hipStream_t>(stream));
+                       relu_mask, ldm, ws, ws_bytes, static_cast<hipStream_t>(stream), nullptr, f32_product);
 }

@@ -162,10 +162,10 @@ static int layer_fwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
         const size_t gwb = gws ? fwd_g_bytes(g, l) : 0;
         if (sage) {
             CG_TRY(launch_gemm(0, 0, g->n_loc, l->f_out, l->f_in, X, ldx, l->W_self, l->f_out, H, ldh, dt, l->out_f32, 0,
-                               nullptr, 0, nullptr, 0, gws, gwb, st));
+                               nullptr, 0, nullptr, 0, gws, gwb, st, nullptr, l->f32_product));
         }
         CG_TRY(launch_gemm(0, 0, g->n_loc, l->f_out, l->f_in, saved, ldm, l->W, l->f_out, H, ldh, dt, l->out_f32,
-                           sage ? 1 : 0, l->bias, relu, nullptr, 0, gws, gwb, st));
+                           sage ? 1 : 0, l->bias, relu, nullptr, 0, gws, gwb, st, nullptr, l->f32_product));
         return CAPGNN_OK;
     }
     // XFORM_FIRST.  When an entry's weight depends on its source alone (no edge values), the product's epilogue
@@ -180,10 +180,10 @@ static int layer_fwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
         Scope s(CAPGNN_K_GEMM, li, 0, st);
         void *gws = static_cast<char *>(ws) + fwd_t_bytes(g, l, order);
         CG_TRY(launch_gemm(0, 0, g->n_cols, l->f_out, l->f_in, X, ldx, l->W, l->f_out, ws, ldt, dt, 0, 0, nullptr, 0,
-                           nullptr, 0, gws, fwd_g_bytes(g, l), st, pre ? g->fwd.in_scale : nullptr));
+                           nullptr, 0, gws, fwd_g_bytes(g, l), st, pre ? g->fwd.in_scale : nullptr, l->f32_product));
         if (sage)
             CG_TRY(launch_gemm(0, 0, g->n_loc, l->f_out, l->f_in, X, ldx, l->W_self, l->f_out, H, ldh, dt, l->out_f32, 0,
-                               nullptr, 0, nullptr, 0, gws, fwd_g_bytes(g, l), st));
+                               nullptr, 0, nullptr, 0, gws, fwd_g_bytes(g, l), st, nullptr, l->f32_product));
     }
     Scope s(CAPGNN_K_SPMM_FWD, li, 0, st);
     SpmmEpilogue ep;
@@ -259,12 +259,12 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
         {
             Scope s(CAPGNN_K_GEMM, li, 1, st);
             if (dW) CG_TRY(launch_gemm(1, 0, l->f_in, l->f_out, g->n_loc, saved, ldm, dHb, lddhb, dW, l->f_out, dt, 1, 0,
-                                       nullptr, 0, nullptr, 0, ws_gemm, gw, st));
+                                       nullptr, 0, nullptr, 0, ws_gemm, gw, st, nullptr, l->f32_product));
             if (sage && dW_self)
                 CG_TRY(launch_gemm(1, 0, l->f_in, l->f_out, g->n_loc, X, ldx, dHb, lddhb, dW_self, l->f_out, dt, 1, 0,
-                                   nullptr, 0, nullptr, 0, ws_gemm, gw, st));
+                                   nullptr, 0, nullptr, 0, ws_gemm, gw, st, nullptr, l->f32_product));
             if (dX) CG_TRY(launch_gemm(0, 1, g->n_loc, l->f_in, l->f_out, dHb, lddhb, l->W, l->f_out, tmp, ldm, dt, 0, 0,
-                                       nullptr, 0, nullptr, 0, ws_gemm, gw, st, pre_b ? g->bwd.in_scale : nullptr));
+                                       nullptr, 0, nullptr, 0, ws_gemm, gw, st, pre_b ? g->bwd.in_scale : nullptr, l->f32_product));
         }
         if (dX) {
             {
@@ -275,7 +275,7 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
             if (sage) {
                 Scope s(CAPGNN_K_GEMM, li, 1, st);
                 CG_TRY(launch_gemm(0, 1, g->n_loc, l->f_in, l->f_out, dHb, lddhb, l->W_self, l->f_out, dX, lddx, dt, 0, 1,
-                                   nullptr, 0, nullptr, 0, ws_gemm, gw, st));
+                                   nullptr, 0, nullptr, 0, ws_gemm, gw, st, nullptr, l->f32_product));
             }
         }
         return CAPGNN_OK;
@@ -291,17 +291,17 @@ static int layer_bwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
     }
     Scope s(CAPGNN_K_GEMM, li, 1, st);
     if (dW) CG_TRY(launch_gemm(1, 0, l->f_in, l->f_out, g->n_cols, X, ldx, tmp, ldt, dW, l->f_out, dt, 1, 0, nullptr, 0,
-                               nullptr, 0, ws_gemm, gw, st));
+                               nullptr, 0, ws_gemm, gw, st, nullptr, l->f32_product));
     if (sage && dW_self)
         CG_TRY(launch_gemm(1, 0, l->f_in, l->f_out, g->n_loc, X, ldx, dHb, lddhb, dW_self, l->f_out, dt, 1, 0, nullptr, 0,
-                           nullptr, 0, ws_gemm, gw, st));
+                           nullptr, 0, ws_gemm, gw, st, nullptr, l->f32_product));
     if (dX) {
         const int64_t rows = need_halo_grad ? g->n_cols : g->n_loc;
         CG_TRY(launch_gemm(0, 1, rows, l->f_in, l->f_out, tmp, ldt, l->W, l->f_out, dX, lddx, dt, 0, 0, nullptr, 0,
-                           nullptr, 0, ws_gemm, gw, st));
+                           nullptr, 0, ws_gemm, gw, st, nullptr, l->f32_product));
         if (sage)
             CG_TRY(launch_gemm(0, 1, g->n_loc, l->f_in, l->f_out, dHb, lddhb, l->W_self, l->f_out, dX, lddx, dt, 0, 1,
-                               nullptr, 0, nullptr, 0, ws_gemm, gw, st));
+                               nullptr, 0, nullptr, 0, ws_gemm, gw, st, nullptr, l->f32_product));
     }
     return CAPGNN_OK;
 }

@@ -99,7 +99,7 @@ class DeviceProblem:
     """Library handles + device buffers for one Problem."""
 
     def __init__(self, prob: Problem, orders: Optional[List[int]] = None, miss_mode: int = B.MISS_STAGED,
-                 map_kind: int = B.MAP_DIRECT, use_side_stream: bool = True):
+                 map_kind: int = B.MAP_DIRECT, use_side_stream: bool = True, f32_product: int = B.F32_PRODUCT_AUTO):
         torch = _torch()
         self.prob = prob
         self.miss_mode = miss_mode
@@ -151,7 +151,8 @@ class DeviceProblem:
             order = B.ORDER_AUTO if orders is None else orders[l]
             self.layers.append(B.make_layer(B.SAGE_MEAN if p.kind == "sage" else B.GCN, p.f_in, p.f_out,
                                             B.ACT_RELU if p.act == "relu" else B.ACT_NONE, self.dtype, W, Ws, b, order,
-                                            out_f32=1 if (l == L - 1 and self.dtype == B.BF16) else 0))
+                                            out_f32=1 if (l == L - 1 and self.dtype == B.BF16) else 0,
+                                            f32_product=f32_product))
         self.labels = torch.from_numpy(prob.labels).cuda()
         self.mask = torch.from_numpy(prob.mask).cuda()
         self.targets = None if prob.targets is None else torch.from_numpy(np.ascontiguousarray(prob.targets)).cuda()

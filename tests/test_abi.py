@@ -49,14 +49,3 @@ def test_host_only_entry_points_work_without_a_gpu():
     assert (c == 1).all()
     with pytest.raises(B.CapgnnError):
         B.cal_capacity(1, 0, [0], 10)
-    # the process-wide choice of how fp32 products are formed: default, round trip, unknown mode
-    assert B.get_f32_product() == B.F32_PRODUCT_AUTO
-    try:
-        for mode in (B.F32_PRODUCT_NATIVE, B.F32_PRODUCT_SPLIT, B.F32_PRODUCT_AUTO):
-            B.set_f32_product(mode)
-            assert B.get_f32_product() == mode
-        with pytest.raises(B.CapgnnError):
-            B.set_f32_product(7)
-        assert B.get_f32_product() == B.F32_PRODUCT_AUTO
-    finally:
-        B.set_f32_product(B.F32_PRODUCT_AUTO)

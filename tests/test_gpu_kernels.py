@@ -449,47 +449,45 @@ def test_gemm_f32_split_product(env, ta, tb):
         wsb = B.gemm_workspace_bytes(ta, M, N, K)
         ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
         Cd = torch.full((M, ldc), 2.0, dtype=torch.float32, device="cuda")
-        B.set_f32_product(mode)
-        B.gemm(ta, tb, M, N, K, Ad, lda, Bd, ldb, Cd, ldc, B.F32, out_f32=1, ws=ws, ws_bytes=wsb)
+        B.gemm(ta, tb, M, N, K, Ad, lda, Bd, ldb, Cd, ldc, B.F32, out_f32=1, ws=ws, ws_bytes=wsb, f32_product=mode)
         torch.cuda.synchronize()
         got = Cd.cpu().numpy()
         assert (got[:, N:] == 2.0).all()
         return got[:, :N]
 
-    try:
-        assert B.get_f32_product() == B.F32_PRODUCT_AUTO
-        for (M, N, K) in [(1, 1, 1), (130, 41, 602), (257, 256, 100), (300, 130, 1000), (602, 256, 5000), (64, 200, 33)]:
-            shapeA, shapeB = ((K, M) if ta else (M, K)), ((N, K) if tb else (K, N))
-            for which in ("select_b", "select_a", "random"):
-                say(f"gemm f32 split ta={ta} tb={tb} M={M} N={N} K={K} {which}")
-                full = lambda shape: (rng.integers(1 << 23, 1 << 24, shape) * rng.choice([-1.0, 1.0], shape)
-                                      * 2.0 ** rng.integers(-20, 20, shape)).astype(np.float32)
-                if which == "select_b":              # B[k_j, j] = +-2^e, zero elsewhere
-                    A = full(shapeA)
-                    sel = np.zeros((K, N), np.float32)
-                    sel[rng.integers(0, K, N), np.arange(N)] = rng.choice([-1.0, 1.0], N) * 2.0 ** rng.integers(-8, 8, N)
-                    Bm = np.ascontiguousarray(sel.T) if tb else sel
-                elif which == "select_a":            # A[i, k_i] = +-2^e (op(A) is M x K)
-                    Bm = full(shapeB)
-                    sel = np.zeros((M, K), np.float32)
-                    sel[np.arange(M), rng.integers(0, K, M)] = rng.choice([-1.0, 1.0], M) * 2.0 ** rng.integers(-8, 8, M)
-                    A = np.ascontiguousarray(sel.T) if ta else sel
-                else:
-                    A = rng.standard_normal(shapeA).astype(np.float32)
-                    Bm = rng.standard_normal(shapeB).astype(np.float32)
-                ref = orc.matmul(A, Bm, ta=bool(ta), tb=bool(tb))
-                for pad in (0, 3):
-                    got = run(B.F32_PRODUCT_SPLIT, A, Bm, M, N, K, pad)
-                    if which != "random":
-                        assert np.array_equal(got.astype(np.float64), ref)
-                        continue
-                    nat = run(B.F32_PRODUCT_NATIVE, A, Bm, M, N, K, pad)
-                    e_split, e_nat = O.normwise(got, ref), O.normwise(nat, ref)
-                    say(f"   normwise error: split {e_split:.3e}, fp32 instruction {e_nat:.3e}")
-                    assert e_split <= TOL_F32 and e_nat <= TOL_F32
-                    assert e_split <= 4.0 * e_nat + 2.0 ** -23
-    finally:
-        B.set_f32_product(B.F32_PRODUCT_AUTO)
+    for (M, N, K) in [(1, 1, 1), (130, 41, 602), (257, 256, 100), (300, 130, 1000), (602, 256, 5000), (64, 200, 33)]:
+        shapeA, shapeB = ((K, M) if ta else (M, K)), ((N, K) if tb else (K, N))
+        for which in ("select_b", "select_a", "random"):
+            say(f"gemm f32 split ta={ta} tb={tb} M={M} N={N} K={K} {which}")
+            full = lambda shape: (rng.integers(1 << 23, 1 << 24, shape) * rng.choice([-1.0, 1.0], shape)
+                                  * 2.0 ** rng.integers(-20, 20, shape)).astype(np.float32)
+            if which == "select_b":              # B[k_j, j] = +-2^e, zero elsewhere
+                A = full(shapeA)
+                sel = np.zeros((K, N), np.float32)
+                sel[rng.integers(0, K, N), np.arange(N)] = rng.choice([-1.0, 1.0], N) * 2.0 ** rng.integers(-8, 8, N)
+                Bm = np.ascontiguousarray(sel.T) if tb else sel
+            elif which == "select_a":            # A[i, k_i] = +-2^e (op(A) is M x K)
+                Bm = full(shapeB)
+                sel = np.zeros((M, K), np.float32)
+                sel[np.arange(M), rng.integers(0, K, M)] = rng.choice([-1.0, 1.0], M) * 2.0 ** rng.integers(-8, 8, M)
+                A = np.ascontiguousarray(sel.T) if ta else sel
+            else:
+                A = rng.standard_normal(shapeA).astype(np.float32)
+                Bm = rng.standard_normal(shapeB).astype(np.float32)
+            ref = orc.matmul(A, Bm, ta=bool(ta), tb=bool(tb))
+            for pad in (0, 3):
+                got = run(B.F32_PRODUCT_SPLIT, A, Bm, M, N, K, pad)
+                if which != "random":
+                    assert np.array_equal(got.astype(np.float64), ref)
+                    continue
+                nat = run(B.F32_PRODUCT_NATIVE, A, Bm, M, N, K, pad)
+                e_split, e_nat = O.normwise(got, ref), O.normwise(nat, ref)
+                say(f"   normwise error: split {e_split:.3e}, fp32 instruction {e_nat:.3e}")
+                assert e_split <= TOL_F32 and e_nat <= TOL_F32
+                assert e_split <= 4.0 * e_nat + 2.0 ** -23
+    one = torch.zeros(1, device="cuda")
+    with pytest.raises(B.CapgnnError):          # an unknown form is an argument error
+        B.gemm(0, 0, 1, 1, 1, one, 1, one, 1, one, 1, B.F32, f32_product=7)
 
 
 def test_mfma_peak_loop_runs_and_counts_its_work(env):
