@@ -244,6 +244,60 @@ int capgnn_overlap_ratio(const int64_t *halo_ids, int64_t n_ids, int64_t n_verti
 int capgnn_influence_score(const capgnn_graph *g, const float *inv_sqrt_din, const float *inv_sqrt_dout,
                            const float *count, float *S, void *stream);
 
+/* ------------------------------------------------------------------------------------------
+ * RAPA's subgraph adjustment (section "Resource-Aware Partitioning Algorithm": cost model Eq. 3-5, Alg. 2
+ * do_partition, Alg. 3 adjust_subgraph).  Host code; the ranking it consumes is capgnn_influence_score's (Eq. 6).
+ * ---------------------------------------------------------------------------------------- */
+
+/* One GPU as the cost model sees it: the measured cost (time) of the reference SpMM and MM and of the reference
+ * transfer host-to-device, device-to-host and device-to-device (the paper measures them on a 11585 x 11585 matrix;
+ * any unit, only the ratio to the largest value among the GPUs enters), and the memory available, in bytes. */
+typedef struct {
+    double t_spmm, t_mm;
+    double f_h2d, f_d2h, f_idt;
+    double mem_bytes;
+} capgnn_rapa_device;
+
+typedef struct {
+    double alpha;        /* Eq. 4: weight of the SpMM term (edges) against the MM term (inner vertices), in [0,1] */
+    double epsilon;      /* Alg. 2 stops when the standard deviation of the costs is below it                      */
+    double m_vertex, m_edge, m_feat;  /* Eq. 5: bytes per vertex, per edge, per feature element                    */
+    int64_t f_dim;       /* Eq. 5: feature width (the feature term counts f_dim elements for every vertex)          */
+    double beta;         /* Eq. 5: bytes reserved for gradients and the like                                        */
+    int max_sweeps;      /* safety bound on the sweeps of Alg. 2 (> 0)                                              */
+} capgnn_rapa_params;
+
+/* Edges of a partition graph by the kind of their source: *e_inner = entries whose column is a local vertex,
+ * halo_edges[k] = entries whose column is halo vertex k (all of them outer edges).  Host arrays. */
+int capgnn_halo_edge_counts(int64_t n_loc, int64_t n_halo, const int64_t *rowptr, const int32_t *col,
+                            int64_t *e_inner, int64_t *halo_edges);
+
+/* Alg. 2 around Alg. 3.  Subgraph i (on GPU i) has n_inner[i] inner vertices, e_inner[i] edges between them, and the
+ * halo vertices halo_ptr[i] .. halo_ptr[i+1]-1 of the flat arrays halo_edges (edges of that halo vertex in the
+ * subgraph) and score (its influence score S_k, Eq. 6, as computed by capgnn_influence_score).
+ * lambda_i = alpha |E_all| t_spmm/tmax + (1-alpha) |V_inner| t_mm/tmax
+ *          + |E_outer| ((f_h2d/fmax + f_d2h/fmax)(1 - 1/P) + f_idt/fmax / P)                     (Eq. 3, Eq. 4)
+ * Every sweep (Alg. 3) visits the GPUs from the weakest on (largest alpha t_spmm/tmax + (1-alpha) t_mm/tmax, ties by
+ * index).  A subgraph whose cost is at most the mean of all costs and whose memory suffices (Eq. 5) is marked done
+ * (r_i = 1).  Otherwise its halo vertices are taken in ascending score order (ties by index; a vertex is considered
+ * once over all sweeps) and removed with all their edges while the estimated cost exceeds the mean, stopping early once
+ * it is at most halfway between the old cost and the mean and the memory suffices; if nothing was removed, r_i = 1.
+ * The sweeps end (Alg. 2) when the standard deviation of the costs is below epsilon, when r = 1, or after max_sweeps.
+ * Outputs (host): keep[halo_ptr[P]] = 1 for the halo vertices that stay; lambda_out[P]; r_out[P] (last sweep);
+ * *sweeps_out; *sigma_out (after the last sweep); any of the last four may be NULL.
+ * Costs are formed in double precision exactly as written above (no fused operations).  Errors: CAPGNN_EINVAL. */
+int capgnn_rapa_adjust(int n_parts, const int64_t *n_inner, const int64_t *e_inner, const int64_t *halo_ptr,
+                       const int64_t *halo_edges, const float *score, const capgnn_rapa_device *dev,
+                       const capgnn_rapa_params *prm, uint8_t *keep, double *lambda_out, int32_t *r_out,
+                       int *sweeps_out, double *sigma_out);
+
+/* The subgraph without the halo vertices that keep[] drops ("Remove V_rem and E_rem from G_i", Alg. 3): their entries
+ * disappear, the halo vertices that stay are renumbered in their old order.  rowptr_out: host int64[n_loc+1]; col_out:
+ * host int32[nnz] (the first rowptr_out[n_loc] are written); new_index: host int64[n_halo], the new halo-local index
+ * of each old halo vertex, -1 if dropped (the caller moves its halo attributes and cache rows alike). */
+int capgnn_prune_halo(int64_t n_loc, int64_t n_halo, const int64_t *rowptr, const int32_t *col, const uint8_t *keep,
+                      int64_t *rowptr_out, int32_t *col_out, int64_t *new_index);
+
 #define CAPGNN_POLICY_JACA      0  /* static contents, highest overlap ratio first (ties: ascending vertex id) */
 #define CAPGNN_POLICY_JACA_LOW  1  /* the same with the lowest overlap ratio first (the evaluation's counter-test) */
 #define CAPGNN_POLICY_FIFO      2

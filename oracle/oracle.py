@@ -476,3 +476,150 @@ def epoch(g: Graph, layers: List[Layer], X0_local, halo_tables: Sequence[Optiona
                              for i, l in enumerate(layers)]
         res["new_bias"] = [None if l.bias is None else l.bias - lr * res["db"][i] for i, l in enumerate(layers)]
     return res
+
+
+# ------------------------------------------------------------------ RAPA: cost model and subgraph adjustment
+@dataclass
+class RapaDevice:
+    """Measured costs of one GPU on the reference operations (section "Communication and Computation Modeling"): the
+    time of the reference SpMM and MM, and of the reference transfer host-to-device, device-to-host and between
+    devices.  Only the ratios to the largest value among the GPUs enter the cost (reading: F and t are measured costs,
+    so that the slowest GPU has ratio 1), and the memory available on the GPU in bytes."""
+    t_spmm: float
+    t_mm: float
+    f_h2d: float
+    f_d2h: float
+    f_idt: float
+    mem_bytes: float
+
+
+@dataclass
+class RapaParams:
+    alpha: float            # weight between the SpMM term (edges) and the MM term (inner vertices) of Eq. 4
+    epsilon: float          # stop when the standard deviation of the costs falls below it
+    m_vertex: float = 8.0   # bytes to store one vertex
+    m_edge: float = 12.0    # bytes to store one edge
+    m_feat: float = 4.0     # bytes of one feature element
+    f_dim: int = 0          # feature width
+    beta: float = 100.0 * 2 ** 20   # memory reserved for gradients and the like (the evaluation uses 100 MB)
+    max_sweeps: int = 1000
+
+
+def rapa_cost(n_inner: int, e_all: int, e_outer: int, i: int, devs: Sequence[RapaDevice], prm: RapaParams) -> float:
+    """lambda_i = T_comp + T_comm of subgraph i on GPU i (Eq. 3 and Eq. 4):
+    T_comm = |E_outer| ((F_h2d/Fmax_h2d + F_d2h/Fmax_d2h)(1 - 1/P) + F_idt/Fmax_idt / P),
+    T_comp = alpha |E_all| t_spmm/tmax_spmm + (1 - alpha) |V_inner| t_mm/tmax_mm."""
+    P = len(devs)
+    d = devs[i]
+    mx = lambda name: max(getattr(x, name) for x in devs)
+    t_comm = e_outer * ((d.f_h2d / mx("f_h2d") + d.f_d2h / mx("f_d2h")) * (1.0 - 1.0 / P) + d.f_idt / mx("f_idt") * (1.0 / P))
+    t_comp = prm.alpha * e_all * (d.t_spmm / mx("t_spmm")) + (1.0 - prm.alpha) * n_inner * (d.t_mm / mx("t_mm"))
+    return t_comp + t_comm
+
+
+def rapa_memory_ok(n_vertices: int, n_edges: int, dev: RapaDevice, prm: RapaParams) -> bool:
+    """The memory constraint of Eq. 5 (reading: the feature term counts f_dim elements for every vertex)."""
+    need = n_vertices * prm.m_vertex + n_edges * prm.m_edge + n_vertices * prm.f_dim * prm.m_feat + prm.beta
+    return dev.mem_bytes >= need
+
+
+def rapa_do_partition(n_inner: Sequence[int], e_inner: Sequence[int], halo_edges: Sequence[np.ndarray],
+                      scores: Sequence[np.ndarray], devs: Sequence[RapaDevice], prm: RapaParams):
+    """Alg. 2 (do_partition) around Alg. 3 (adjust_subgraph), step by step.
+
+    Subgraph i has n_inner[i] inner vertices, e_inner[i] edges between inner vertices, and halo vertices k with
+    halo_edges[i][k] edges each (all of them outer edges); scores[i][k] is the influence score S_k (Eq. 6).
+    Every sweep visits the GPUs from the weakest on (largest alpha t_spmm/tmax + (1 - alpha) t_mm/tmax, ties by
+    index): a subgraph whose cost is at most the mean cost and whose memory suffices is marked done (r_i = 1);
+    otherwise its halo vertices are taken in ascending score order (ties by index) and removed one by one, with all
+    their edges, while the estimated cost exceeds the mean, stopping early once it is at most halfway between the old
+    cost and the mean and the memory suffices; a subgraph from which nothing was removed is marked done.  The sweeps
+    end when the standard deviation of the costs is below epsilon or every subgraph is marked done.
+    Returns dict(keep: per-subgraph boolean arrays, lam: final costs, r: last status vector, sweeps, sigma: the
+    standard deviation after every sweep, removed_order: per subgraph the halo vertices in the order of removal)."""
+    P = len(devs)
+    keep = [np.ones(len(h), bool) for h in halo_edges]
+    cnt = [np.asarray(h, np.int64) for h in halo_edges]
+    order = [sorted(range(len(cnt[i])), key=lambda k: (float(scores[i][k]), k)) for i in range(P)]
+    nxt = [0] * P
+    removed_order = [[] for _ in range(P)]
+    mx_s, mx_m = max(d.t_spmm for d in devs), max(d.t_mm for d in devs)
+    weakest_first = sorted(range(P), key=lambda i: (-(prm.alpha * devs[i].t_spmm / mx_s + (1.0 - prm.alpha) * devs[i].t_mm / mx_m), i))
+
+    def stats(i):
+        e_outer = int(cnt[i][keep[i]].sum())
+        return n_inner[i], e_inner[i] + e_outer, e_outer, n_inner[i] + int(keep[i].sum())
+
+    def lam(i):
+        ni, ea, eo, _ = stats(i)
+        return rapa_cost(ni, ea, eo, i, devs, prm)
+
+    def mem_ok(i):
+        _, ea, _, nv = stats(i)
+        return rapa_memory_ok(nv, ea, devs[i], prm)
+
+    sigma, sweeps, r = [], 0, [0] * P
+    while True:
+        r = [0] * P
+        for i in weakest_first:                                   # ---- adjust_subgraph
+            lam_i = lam(i)
+            lam_bar = sum(lam(j) for j in range(P)) / P
+            if lam_i <= lam_bar and mem_ok(i):
+                r[i] = 1
+                continue
+            removed_now = 0
+            lam_hat = lam_i
+            while lam_hat > lam_bar and nxt[i] < len(order[i]):
+                k = order[i][nxt[i]]
+                nxt[i] += 1
+                keep[i][k] = False
+                removed_order[i].append(k)
+                removed_now += 1
+                lam_hat = lam(i)
+                if lam_hat <= 0.5 * (lam_i + lam_bar) and mem_ok(i):
+                    break
+            if removed_now == 0:
+                r[i] = 1
+        sweeps += 1                                               # ---- do_partition
+        lams = [lam(i) for i in range(P)]
+        mean = sum(lams) / P
+        sigma.append(float(np.sqrt(sum((x - mean) ** 2 for x in lams) / P)))
+        if sigma[-1] < prm.epsilon or all(r) or sweeps >= prm.max_sweeps:
+            break
+    return {"keep": keep, "lam": [lam(i) for i in range(P)], "r": r, "sweeps": sweeps, "sigma": sigma,
+            "removed_order": removed_order}
+
+
+def halo_edge_counts(n_loc: int, n_halo: int, rowptr, col):
+    """(edges between inner vertices, edges per halo vertex) of a partition graph."""
+    col = np.asarray(col, np.int64)
+    e_inner = int((col < n_loc).sum())
+    cnt = np.zeros(n_halo, np.int64)
+    for c in col[col >= n_loc]:
+        cnt[c - n_loc] += 1
+    return e_inner, cnt
+
+
+def prune_halo(n_loc: int, n_halo: int, rowptr, col, keep):
+    """The subgraph after the halo vertices with keep[k] == False are removed with all their edges ("Remove V_rem and
+    E_rem from G_i"): the kept halo vertices are renumbered in their old order.  Returns (rowptr, col, new_index) with
+    new_index[k] = the new halo-local index of old halo vertex k, -1 if removed."""
+    rowptr = np.asarray(rowptr, np.int64)
+    col = np.asarray(col, np.int64)
+    keep = np.asarray(keep, bool)
+    new_index = np.full(n_halo, -1, np.int64)
+    q = 0
+    for k in range(n_halo):
+        if keep[k]:
+            new_index[k] = q
+            q += 1
+    new_ptr, new_col = [0], []
+    for i in range(n_loc):
+        for e in range(rowptr[i], rowptr[i + 1]):
+            c = col[e]
+            if c < n_loc:
+                new_col.append(c)
+            elif keep[c - n_loc]:
+                new_col.append(n_loc + new_index[c - n_loc])
+        new_ptr.append(len(new_col))
+    return np.array(new_ptr, np.int64), np.array(new_col, np.int32), new_index

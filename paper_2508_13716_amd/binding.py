@@ -41,6 +41,16 @@ class Layer(C.Structure):
                 ("bias", C.c_void_p)]
 
 
+class RapaDevice(C.Structure):
+    _fields_ = [("t_spmm", C.c_double), ("t_mm", C.c_double), ("f_h2d", C.c_double), ("f_d2h", C.c_double),
+                ("f_idt", C.c_double), ("mem_bytes", C.c_double)]
+
+
+class RapaParams(C.Structure):
+    _fields_ = [("alpha", C.c_double), ("epsilon", C.c_double), ("m_vertex", C.c_double), ("m_edge", C.c_double),
+                ("m_feat", C.c_double), ("f_dim", C.c_int64), ("beta", C.c_double), ("max_sweeps", C.c_int)]
+
+
 class GatherStats(C.Structure):
     _fields_ = [("hits", C.c_int64), ("misses", C.c_int64), ("absent", C.c_int64)]
 
@@ -82,6 +92,10 @@ SIGNATURES = {
     "capgnn_overlap_ratio": (_i32, [_vp, _i64, _i64, _vp, _vp]),
     "capgnn_influence_score": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp]),
     "capgnn_policy_simulate": (_i32, [_i32, _vp, _vp, _i32, _i64, _i64, _i32, _i32, _vp]),
+    "capgnn_halo_edge_counts": (_i32, [_i64, _i64, _vp, _vp, C.POINTER(_i64), _vp]),
+    "capgnn_rapa_adjust": (_i32, [_i32, _vp, _vp, _vp, _vp, _vp, C.POINTER(RapaDevice), C.POINTER(RapaParams), _vp, _vp, _vp,
+                                  C.POINTER(_i32), C.POINTER(C.c_double)]),
+    "capgnn_prune_halo": (_i32, [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp]),
     "capgnn_locality_order": (_i32, [_i32, _i64, _i64, _vp, _vp, _vp]),
     "capgnn_relabel_csr": (_i32, [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "capgnn_cache_update": (_i32, [_vp, _i32, _vp, _i64, _i32, _vp, _i64, _i64, _vp, _vp]),
@@ -335,6 +349,47 @@ def policy_simulate(halo_sets, policy: int, cap_local: int, cap_global: int, epo
     out = np.zeros(3, np.int64)
     _check(lib().capgnn_policy_simulate(len(halo_sets), _p(ptr), _p(ids), policy, cap_local, cap_global, epochs, warmup, _p(out)))
     return int(out[0]), int(out[1]), int(out[2])
+
+
+def halo_edge_counts(n_loc: int, n_halo: int, rowptr, col):
+    """(edges between inner vertices, int64 array of edges per halo vertex) of a partition graph."""
+    rowptr = np.ascontiguousarray(rowptr, np.int64)
+    col = np.ascontiguousarray(col, np.int32)
+    e_inner = C.c_int64(0)
+    cnt = np.zeros(n_halo, np.int64)
+    _check(lib().capgnn_halo_edge_counts(n_loc, n_halo, _p(rowptr), _p(col), C.byref(e_inner), _p(cnt)))
+    return int(e_inner.value), cnt
+
+
+def rapa_adjust(n_inner, e_inner, halo_edges: Sequence[np.ndarray], scores: Sequence[np.ndarray], devices: Sequence[RapaDevice],
+                params: RapaParams):
+    """Alg. 2 / Alg. 3 on P subgraphs.  Returns dict(keep: per-subgraph uint8 arrays, lam, r, sweeps, sigma)."""
+    P = len(devices)
+    ni = np.ascontiguousarray(n_inner, np.int64)
+    ei = np.ascontiguousarray(e_inner, np.int64)
+    ptr = np.zeros(P + 1, np.int64)
+    np.cumsum([len(h) for h in halo_edges], out=ptr[1:])
+    he = np.ascontiguousarray(np.concatenate([np.asarray(h, np.int64) for h in halo_edges]) if ptr[-1] else np.zeros(0, np.int64))
+    sc = np.ascontiguousarray(np.concatenate([np.asarray(x, np.float32) for x in scores]) if ptr[-1] else np.zeros(0, np.float32))
+    keep = np.zeros(int(ptr[-1]), np.uint8)
+    lam = np.zeros(P, np.float64)
+    r = np.zeros(P, np.int32)
+    sweeps, sigma = C.c_int(0), C.c_double(0.0)
+    devs = (RapaDevice * P)(*devices)
+    _check(lib().capgnn_rapa_adjust(P, _p(ni), _p(ei), _p(ptr), _p(he), _p(sc), devs, C.byref(params), _p(keep), _p(lam), _p(r),
+                                    C.byref(sweeps), C.byref(sigma)))
+    return {"keep": [keep[ptr[i]:ptr[i + 1]].copy() for i in range(P)], "lam": lam, "r": r.tolist(), "sweeps": int(sweeps.value),
+            "sigma": float(sigma.value)}
+
+
+def prune_halo(n_loc: int, n_halo: int, rowptr, col, keep):
+    """(rowptr, col, new_index) of the subgraph without the halo vertices keep[] drops."""
+    rowptr = np.ascontiguousarray(rowptr, np.int64)
+    col = np.ascontiguousarray(col, np.int32)
+    keep = np.ascontiguousarray(keep, np.uint8)
+    rp, cl, ni = np.zeros_like(rowptr), np.zeros_like(col), np.zeros(n_halo, np.int64)
+    _check(lib().capgnn_prune_halo(n_loc, n_halo, _p(rowptr), _p(col), _p(keep), _p(rp), _p(cl), _p(ni)))
+    return rp, cl[: int(rp[-1])].copy(), ni
 
 
 RELABEL_POPULARITY, RELABEL_BFS = 0, 1

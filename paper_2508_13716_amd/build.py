@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 SO = os.path.join(HERE, "libcapgnn.so")
-SOURCES = ["graph.hip", "spmm.hip", "gemm.hip", "cache.hip", "ops.hip", "layer.hip", "policy.hip", "reorder.hip"]
+SOURCES = ["graph.hip", "spmm.hip", "gemm.hip", "cache.hip", "ops.hip", "layer.hip", "policy.hip", "reorder.hip", "rapa.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]

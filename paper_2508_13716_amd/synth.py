@@ -261,6 +261,52 @@ def hand_partition(n_loc: int, n_halo: int, edges, *, seed: int = 7, self_loops:
     return Partition(name, n_loc, n_halo, rowptr, col, gid, prio, degree, self_loops, False)
 
 
+def make_partitioned_graph(n: int, nnz: int, n_parts: int, *, seed: int, shares: Optional[List[float]] = None,
+                           gamma: float = 2.1, max_deg: Optional[int] = None):
+    """One power-law graph cut into n_parts subgraphs by a random vertex assignment (part p with probability
+    shares[p]; equal shares when omitted), each returned as a Partition: rows = the part's vertices in ascending
+    global id, columns = those vertices followed by the part's halo vertices (sources of cut edges, ascending
+    global id).  halo_gid = global vertex id, halo_prio = the number of subgraphs whose halo set holds the vertex
+    (its repetition count), halo_degree = its in-degree in the whole graph.  Returns (list of Partition, dict with
+    part: part id of every vertex, in_degree: in-degree of every vertex in the whole graph)."""
+    alpha = 1.0 / (gamma - 1.0)
+    rng = rng_for(seed, 8)
+    md = max_deg if max_deg is not None else max(8, min(n // 4, int(40 * nnz / max(n, 1))))
+    law = _calibrated(n, alpha, nnz, md)
+    dst = law.draw(rng, rng.permutation(n), nnz)
+    src = law.draw(rng, rng.permutation(n), nnz)
+    ok = dst != src
+    key = np.unique(dst[ok].astype(np.int64) * np.int64(n) + src[ok].astype(np.int64))      # dedupe, sort by (dst, src)
+    dst, src = key // np.int64(n), key % np.int64(n)
+    p = np.full(n_parts, 1.0 / n_parts) if shares is None else np.asarray(shares, np.float64) / np.sum(shares)
+    part = rng.choice(n_parts, size=n, p=p).astype(np.int64)
+    in_degree = np.bincount(dst, minlength=n).astype(np.int64)
+    halo_sets = []
+    for i in range(n_parts):
+        sel = (part[dst] == i) & (part[src] != i)
+        halo_sets.append(np.unique(src[sel]))
+    repeat = np.zeros(n, np.int64)
+    for h in halo_sets:
+        repeat[h] += 1
+    parts = []
+    for i in range(n_parts):
+        loc = np.nonzero(part == i)[0].astype(np.int64)
+        halo = halo_sets[i]
+        lut = np.full(n, -1, np.int64)
+        lut[loc] = np.arange(len(loc))
+        lut[halo] = len(loc) + np.arange(len(halo))
+        sel = part[dst] == i
+        rows, cols = lut[dst[sel]], lut[src[sel]]
+        assert (rows >= 0).all() and (rows < len(loc)).all() and (cols >= 0).all()
+        order = np.lexsort((cols, rows))
+        rows, cols = rows[order], cols[order]
+        rowptr = np.zeros(len(loc) + 1, np.int64)
+        np.cumsum(np.bincount(rows, minlength=len(loc)), out=rowptr[1:])
+        parts.append(Partition(f"part{i}of{n_parts}", len(loc), len(halo), rowptr, cols.astype(np.int32), halo.astype(np.int64),
+                               repeat[halo], np.maximum(in_degree[halo], 1), False, False))
+    return parts, {"part": part, "in_degree": in_degree}
+
+
 # --------------------------------------------------------------------------- tensors
 def pad_to(f: int, mult: int) -> int:
     return (f + mult - 1) // mult * mult

@@ -670,3 +670,102 @@ def test_zipf_hit_fraction_closed_form(orc):
     req = rng.choice(N, size=400_000, p=p)
     hit = float((tier[req] == 0).mean())
     assert abs(hit - harm(k, s) / harm(N, s)) < 5e-3
+
+
+# ----------------------------------------------------------------------------- RAPA: Alg. 2 / Alg. 3
+def _two_gpu_example(orc, epsilon):
+    devs = [orc.RapaDevice(2.0, 2.0, 1.0, 1.0, 1.0, 1e18), orc.RapaDevice(1.0, 1.0, 1.0, 1.0, 1.0, 1e18)]
+    prm = orc.RapaParams(alpha=0.5, epsilon=epsilon)
+    return orc.rapa_do_partition([10, 10], [20, 20], [np.array([3, 1, 2, 4]), np.array([2, 2])],
+                                 [np.array([0.5, 0.1, 0.3, 0.9]), np.array([0.2, 0.4])], devs, prm)
+
+
+def test_rapa_hand_trace_golden(orc):
+    """The two-GPU example traced by hand in tests/golden/rapa_hand_trace.txt: costs (Eq. 3-4), the halfway rule and the
+    removal order of adjust_subgraph (Alg. 3), and both stopping conditions of do_partition (Alg. 2)."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "rapa_hand_trace.txt")) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for eps, sweeps, l0, l1, sig, order0, keep1 in rows:
+        res = _two_gpu_example(orc, float(eps))
+        assert res["sweeps"] == int(sweeps)
+        np.testing.assert_allclose(res["lam"], [float(l0), float(l1)], rtol=1e-14)
+        np.testing.assert_allclose(res["sigma"], [float(x) for x in sig.split(",")], rtol=1e-14)
+        assert res["removed_order"][0] == [int(x) for x in order0.split(",")]
+        assert res["keep"][1].tolist() == [bool(int(x)) for x in keep1.split(",")] and res["removed_order"][1] == []
+        assert res["keep"][0].sum() == 4 - len(order0.split(","))
+    assert _two_gpu_example(orc, 0.1)["r"] == [1, 1] and _two_gpu_example(orc, 1.0)["r"] == [0, 1]
+
+
+def test_rapa_cost_model_closed_forms(orc):
+    """Eq. 3 / Eq. 4 term by term: one GPU has no peers (only the inter-device term is left, with weight 1/P = 1);
+    equal GPUs have all ratios 1; alpha = 1 and alpha = 0 isolate the SpMM and the MM term; the memory constraint
+    switches exactly at its bound."""
+    one = [orc.RapaDevice(3.0, 5.0, 7.0, 11.0, 13.0, 1e9)]
+    p = orc.RapaParams(alpha=0.25, epsilon=0.0)
+    assert orc.rapa_cost(10, 100, 40, 0, one, p) == 0.25 * 100 + 0.75 * 10 + 40 * 1.0
+    two = [orc.RapaDevice(1.0, 4.0, 2.0, 2.0, 6.0, 1e9), orc.RapaDevice(2.0, 2.0, 1.0, 4.0, 3.0, 1e9)]
+    assert orc.rapa_cost(0, 100, 0, 0, two, orc.RapaParams(1.0, 0.0)) == 100 * 0.5          # SpMM term, ratio 1/2
+    assert orc.rapa_cost(7, 100, 0, 1, two, orc.RapaParams(0.0, 0.0)) == 7 * 0.5            # MM term, ratio 2/4
+    # outer edges only: GPU 0: (2/2 + 2/4) * 1/2 + 6/6 * 1/2 = 1.25 per edge
+    assert orc.rapa_cost(0, 8, 8, 0, two, orc.RapaParams(0.0, 0.0)) == 8 * 1.25
+    prm = orc.RapaParams(0.5, 0.0, m_vertex=8, m_edge=12, m_feat=4, f_dim=10, beta=100)
+    need = 5 * 8 + 20 * 12 + 5 * 10 * 4 + 100
+    assert orc.rapa_memory_ok(5, 20, orc.RapaDevice(1, 1, 1, 1, 1, need), prm)
+    assert not orc.rapa_memory_ok(5, 20, orc.RapaDevice(1, 1, 1, 1, 1, need - 1), prm)
+
+
+def test_rapa_invariants_on_random_instances(orc):
+    """Properties the two listings fix, on random instances: what is removed from a subgraph is a prefix of its
+    ascending-score order (ties by index); a subgraph that starts at or below the mean with ample memory is never
+    touched in the first sweep; costs never rise; the loop ends with sigma < epsilon or r = 1; nothing can be pruned
+    from subgraphs without halo vertices (r = 1 after one sweep); with too little memory for a cheap subgraph nothing
+    is removed from it either (the listing only prunes while the cost exceeds the mean)."""
+    rng = np.random.default_rng(17)
+    for trial in range(30):
+        P = int(rng.integers(2, 6))
+        n_inner = rng.integers(50, 500, P).tolist()
+        e_inner = rng.integers(100, 5000, P).tolist()
+        halo_edges = [rng.integers(1, 30, int(rng.integers(0, 200))) for _ in range(P)]
+        scores = [np.round(rng.random(len(h)), 2) for h in halo_edges]                     # rounded: ties do occur
+        devs = [orc.RapaDevice(*rng.uniform(0.5, 2.0, 5).tolist(), 1e18) for _ in range(P)]
+        prm = orc.RapaParams(alpha=float(rng.uniform(0.1, 0.9)), epsilon=float(rng.uniform(0.0, 50.0)))
+        lam0 = [orc.rapa_cost(n_inner[i], e_inner[i] + int(halo_edges[i].sum()), int(halo_edges[i].sum()), i, devs, prm)
+                for i in range(P)]
+        res = orc.rapa_do_partition(n_inner, e_inner, halo_edges, scores, devs, prm)
+        assert res["sigma"][-1] < prm.epsilon or all(res["r"])
+        for i in range(P):
+            want = sorted(range(len(halo_edges[i])), key=lambda k: (scores[i][k], k))
+            assert res["removed_order"][i] == want[: len(res["removed_order"][i])]
+            assert set(np.nonzero(~res["keep"][i])[0].tolist()) == set(res["removed_order"][i])
+            assert res["lam"][i] <= lam0[i] * (1 + 1e-12)
+    # no halo vertex anywhere: one sweep, everything marked done, nothing changes
+    devs = [orc.RapaDevice(1, 1, 1, 1, 1, 1e18), orc.RapaDevice(2, 2, 1, 1, 1, 1e18)]
+    res = orc.rapa_do_partition([10, 30], [50, 90], [np.zeros(0, np.int64)] * 2, [np.zeros(0)] * 2, devs, orc.RapaParams(0.5, 0.0))
+    assert res["sweeps"] == 1 and res["r"] == [1, 1]
+    # the cheap subgraph is short of memory: the listing's loop does not run for it (its cost is below the mean)
+    devs = [orc.RapaDevice(1, 1, 1, 1, 1, 1e18), orc.RapaDevice(1, 1, 1, 1, 1, 10.0)]
+    res = orc.rapa_do_partition([100, 10], [1000, 10], [np.array([5, 5]), np.array([1, 1])], [np.array([0.1, 0.2])] * 2, devs,
+                                orc.RapaParams(0.5, 1e9))
+    assert res["keep"][1].all() and res["sweeps"] == 1
+
+
+def test_prune_halo_and_edge_counts_vs_bruteforce(orc):
+    part = synth.make_partition("prune", 40, 25, 400, seed=3, max_deg=30, self_loops=False)
+    e_inner, cnt = orc.halo_edge_counts(part.n_loc, part.n_halo, part.rowptr, part.col)
+    assert e_inner + cnt.sum() == part.nnz and np.array_equal(cnt, part.halo_prio)
+    rng = np.random.default_rng(1)
+    keep = rng.random(part.n_halo) < 0.5
+    rp, cl, new_index = orc.prune_halo(part.n_loc, part.n_halo, part.rowptr, part.col, keep)
+    # edge set brute force: (row, old column) pairs that survive, mapped to new numbers
+    kept_old = [k for k in range(part.n_halo) if keep[k]]
+    assert [new_index[k] for k in kept_old] == list(range(len(kept_old))) and (new_index[~keep] == -1).all()
+    want = []
+    for i in range(part.n_loc):
+        for e in range(part.rowptr[i], part.rowptr[i + 1]):
+            c = int(part.col[e])
+            if c < part.n_loc:
+                want.append((i, c))
+            elif keep[c - part.n_loc]:
+                want.append((i, part.n_loc + kept_old.index(c - part.n_loc)))
+    got = [(i, int(cl[e])) for i in range(part.n_loc) for e in range(rp[i], rp[i + 1])]
+    assert got == want and rp[-1] == len(want) == part.nnz - cnt[~keep].sum()
