@@ -108,7 +108,7 @@ def f32_product_check(cfg):
     return out
 
 
-def gather_peaks(steps):
+def gather_peaks(steps, sweep=False):
     """What the memory levels deliver for the aggregation's access pattern, measured now on this GPU: 128-byte lines at
     random line numbers, 16 loads in flight per lane, nothing else (capgnn_gather_peak), on tables that fit an L2
     (2 MB), the Infinity Cache (128 MB) and neither (2 GB).  GB/s."""
@@ -118,7 +118,11 @@ def gather_peaks(steps):
     wgs = 256 * 16
     out_buf = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
     res = {}
-    for name, nbytes, iters in (("l2_2MB", 2 << 20, 64), ("infinity_cache_128MB", 128 << 20, 32), ("hbm_2GB", 2 << 30, 16)):
+    sizes = [("l2_2MB", 2 << 20, 64), ("infinity_cache_128MB", 128 << 20, 32), ("hbm_2GB", 2 << 30, 16)]
+    if sweep:
+        sizes = [(f"{b >> 10}KB", b, 64 if b <= (4 << 20) else 24) for b in (16 << 10, 256 << 10, 1 << 20, 2 << 20, 4 << 20, 8 << 20, 32 << 20,
+                                                                              128 << 20, 512 << 20, 2 << 30)]
+    for name, nbytes, iters in sizes:
         table = torch.zeros(nbytes // 4, dtype=torch.float32, device="cuda")
         B.gather_peak(table, nbytes // 128, wgs, iters, out_buf, st)
         torch.cuda.synchronize()
@@ -438,7 +442,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default=None, help="one workload only (C1..C5); default: C2 as the headline line with C1, C3, C4, C5 under 'configs'")
-    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder", "zipf_requests", "mfma_peak", "products"],
+    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder", "zipf_requests", "mfma_peak", "products", "gather_peak"],
                     help="epoch (default): the headline benchmark; cache_update: throughput of the cache write path; "
                          "policy: hit-rate curves of the cache policies; reorder: SpMM before / after vertex reordering "
                          "(--config C2..C5 or clustered); zipf_requests: request-list gather under Zipf(1.1) requests")
@@ -474,6 +478,10 @@ def main():
         return bench_zipf_requests(args)
     if args.what == "mfma_peak":
         return bench_mfma_peak(args)
+    if args.what == "gather_peak":
+        print(json.dumps({"metric": "scattered 128-byte-line gather rate by table size", "unit": "GB/s", "n_gpus": 1,
+                          "data": "synthetic", "measured": gather_peaks(args.steps, sweep=True)}))
+        return
     if args.what == "products":
         return bench_products(args)
     if args.what == "policy":

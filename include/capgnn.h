@@ -378,12 +378,14 @@ size_t capgnn_gemm_workspace_bytes(int trans_a, int64_t M, int64_t N, int64_t K)
 int capgnn_mfma_peak(int dtype, int workgroups, int iters, float *out, double *flop, void *stream);
 
 /* Measurement aid for the gather roofline of the aggregation: `workgroups` workgroups of 256 threads whose 8-lane groups
- * each fetch 16 * iters pseudo-random 128-byte lines (16 bytes per lane, 16 loads in flight) of `table` (device,
- * table_lines * 128 bytes, 16-byte aligned), and nothing else.  *bytes (host) = the bytes the launch requests; the
+ * each fetch 16 * iters pseudo-random 128-byte lines (16 bytes per lane, 16 loads in flight) out of table_lines
+ * lines that lie line_stride lines apart in `table` (device, table_lines * line_stride * 128 bytes, 16-byte aligned;
+ * table_lines a power of two, at most 2^24; line_stride 1 = a dense table, 9 = the slices of rows with a pitch of nine
+ * lines), and nothing else.  *bytes (host) = the bytes the launch requests; the
  * caller times it.  With a table that fits an L2 (4 MB per XCD), the Infinity Cache (256 MB) or neither, the rate is
  * what that level delivers for the aggregation's access pattern.  out: device float[workgroups * 256]. */
-int capgnn_gather_peak(const void *table, int64_t table_lines, int workgroups, int iters, float *out, double *bytes,
-                       void *stream);
+int capgnn_gather_peak(const void *table, int64_t table_lines, int line_stride, int workgroups, int iters, float *out,
+                       double *bytes, void *stream);
 int capgnn_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K,
                 const void *A, int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc,
                 int dtype, int out_f32, int accumulate, const float *bias, int relu,

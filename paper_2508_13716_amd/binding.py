@@ -106,7 +106,7 @@ SIGNATURES = {
     "capgnn_halo_gather": (_i32, [_vp, _i32, _vp, _i64, _i32, _vp, _i64, _vp, _vp, _vp, C.POINTER(GatherStats)]),
     "capgnn_gemm_workspace_bytes": (_sz, [_i32, _i64, _i64, _i64]),
     "capgnn_mfma_peak": (_i32, [_i32, _i32, _i32, _vp, C.POINTER(C.c_double), _vp]),
-    "capgnn_gather_peak": (_i32, [_vp, _i64, _i32, _i32, _vp, C.POINTER(C.c_double), _vp]),
+    "capgnn_gather_peak": (_i32, [_vp, _i64, _i32, _i32, _i32, _vp, C.POINTER(C.c_double), _vp]),
     "capgnn_gemm": (_i32, [_i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _i32, _vp, _i32,
                            _vp, _i64, _i32, _vp, _sz, _vp]),
     "capgnn_layer_order": (_i32, [_vp, C.POINTER(Layer), _i32]),
@@ -427,10 +427,10 @@ def mfma_peak(dtype: int, workgroups: int, iters: int, out, stream=None) -> floa
     return float(flop.value)
 
 
-def gather_peak(table, table_lines: int, workgroups: int, iters: int, out, stream=None) -> float:
+def gather_peak(table, table_lines: int, workgroups: int, iters: int, out, stream=None, line_stride: int = 1) -> float:
     """Launches the pure 128-byte-line gather loop over `table`; returns the bytes it requests (the caller times it)."""
     nbytes = C.c_double(0.0)
-    _check(lib().capgnn_gather_peak(_p(table), table_lines, workgroups, iters, _p(out), C.byref(nbytes), _stream(stream)))
+    _check(lib().capgnn_gather_peak(_p(table), table_lines, line_stride, workgroups, iters, _p(out), C.byref(nbytes), _stream(stream)))
     return float(nbytes.value)
 
 

@@ -856,9 +856,11 @@ int launch_spmm(const SpOp &op, bool restrict_sub, const void *X, int64_t ldx, v
 // pseudo-random line numbers inside a table, 16 independent loads in flight per lane, nothing else: no index
 // stream, no lane exchange, no stores but one checksum per thread.  What it reaches on a table that fits an L2, the
 // Infinity Cache, or neither is the rate those levels deliver for this access pattern.
-__global__ __launch_bounds__(256) void gather_peak_kernel(const uint4 *table, uint32_t lines, int iters, float *out) {
+__global__ __launch_bounds__(256) void gather_peak_kernel(const uint4 *table, uint32_t line_mask, uint32_t line_stride, int iters,
+                                                          float *out) {
     const uint32_t group = (blockIdx.x * 256u + threadIdx.x) >> 3;
     const uint32_t l = threadIdx.x & 7u;
+    const uint4 *base = table + l;
     float acc = 0.f;
     uint32_t x = group * 0x9E3779B1u + 12345u;
     for (int it = 0; it < iters; ++it) {
@@ -866,14 +868,12 @@ __global__ __launch_bounds__(256) void gather_peak_kernel(const uint4 *table, ui
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             x = x * 1664525u + 1013904223u;                          // the same sequence in all lanes of a group
-            uint32_t h = x ^ (x >> 15);
-            h *= 0x85EBCA77u;
-            h ^= h >> 13;
-            const uint32_t line = static_cast<uint32_t>((static_cast<uint64_t>(h) * lines) >> 32);
-            v[k] = table[static_cast<uint64_t>(line) * 8u + l];
+            const uint32_t line = (x >> 7) & line_mask;              // the high bits of the generator: the low ones cycle
+            v[k] = base[static_cast<uint64_t>(line * line_stride) << 3];
         }
 #pragma unroll
-        for (int k = 0; k < 16; ++k) acc += __uint_as_float(v[k].x & 0x3f800000u) + __uint_as_float(v[k].w & 0x3f800000u);
+        for (int k = 0; k < 16; ++k)      // all four words are consumed, so the load stays one 16-byte access per lane
+            acc += __uint_as_float((v[k].x ^ v[k].y ^ v[k].z ^ v[k].w) & 0x3f800000u);
     }
     out[blockIdx.x * 256u + threadIdx.x] = acc;
 }
@@ -882,13 +882,14 @@ __global__ __launch_bounds__(256) void gather_peak_kernel(const uint4 *table, ui
 
 using namespace capgnn;
 
-extern "C" int capgnn_gather_peak(const void *table, int64_t table_lines, int workgroups, int iters, float *out,
-                                  double *bytes, void *stream) {
-    if (!table || table_lines <= 0 || table_lines > 0xffffffffLL || workgroups <= 0 || iters <= 0 || !out || !bytes ||
-        !aligned16(table))
-        CG_FAIL(CAPGNN_EINVAL, "gather_peak: bad argument");
+extern "C" int capgnn_gather_peak(const void *table, int64_t table_lines, int line_stride, int workgroups, int iters,
+                                  float *out, double *bytes, void *stream) {
+    if (!table || table_lines <= 0 || table_lines > (1LL << 24) || (table_lines & (table_lines - 1)) != 0 || workgroups <= 0 ||
+        iters <= 0 || !out || !bytes || !aligned16(table) || line_stride < 1 || table_lines * line_stride > (int64_t(1) << 28))
+        CG_FAIL(CAPGNN_EINVAL, "gather_peak: bad argument (table_lines must be a power of two, at most 2^24)");
     hipLaunchKernelGGL(gather_peak_kernel, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint4 *>(table), static_cast<uint32_t>(table_lines), iters, out);
+                       static_cast<const uint4 *>(table), static_cast<uint32_t>(table_lines - 1), static_cast<uint32_t>(line_stride),
+                       iters, out);
     CG_HIP(hipGetLastError());
     *bytes = 128.0 * 16.0 * iters * 32.0 * workgroups;      // 32 lane groups per workgroup
     return CAPGNN_OK;
