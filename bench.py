@@ -375,6 +375,69 @@ def bench_products(args):
                       "products": out}))
 
 
+def bench_spmm_launch(args):
+    """One aggregation launch alone, repeated: the dominant launch of a configuration (or --F / --direction), on the
+    configuration's graph, with scratch, exactly as the layer code calls it.  Before it, two calibration launches of
+    known size for counter runs: capgnn_gather_peak over a 2 GB table (reads its requested bytes from memory: the table
+    is 500 times the L2s) and a 1 GiB fill (writes 1 GiB).  One JSON line."""
+    import numpy as np
+    import torch
+    from paper_2508_13716_amd import binding as B, synth
+    cfg = synth.CONFIGS[args.config]
+    part = synth.partition_for(cfg)
+    bf = cfg.dtype == "bf16"
+    dt, tdt, es = (B.BF16, torch.bfloat16, 2) if bf else (B.F32, torch.float32, 4)
+    F = args.F or {"C1": 128, "C2": 256, "C3": 256, "C4": 256, "C5": 512}[args.config]
+    kind = B.NORM_SYM if cfg.kind == "gcn" else B.NORM_MEAN
+    r, c = B.norm_scales(kind, part.n_loc, part.n_halo, part.rowptr, part.halo_degree if part.n_halo else None)
+    g = B.Graph(part.n_loc, part.n_halo, part.rowptr, part.col, r, c, None, B.GRAPH_SYMMETRIC if part.symmetric else 0)
+    st = torch.cuda.Stream()
+    # calibration launches
+    table = torch.zeros((2 << 30) // 4, dtype=torch.float32, device="cuda")
+    outp = torch.empty(4096 * 256, dtype=torch.float32, device="cuda")
+    cal_read = B.gather_peak(table, (2 << 30) // 128, 4096, 16, outp, st)
+    torch.cuda.synchronize()
+    del table
+    filled = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    filled.fill_(1.0)
+    torch.cuda.synchronize()
+    del filled
+    # the layer code's pitch: whole, odd numbers of 128-byte lines when the graph has a column-blocked copy
+    wsb = B.spmm_workspace_bytes(g, F, dt)
+    pitch = (F * es + 15) // 16 * 16
+    if wsb > part.n_cols * F * es:
+        pitch = (pitch + 127) // 128 * 128
+        pitch += 128 if pitch % 256 == 0 else 0
+    ld = pitch // es
+    fwd = args.direction == "fwd"
+    n_in, n_out = (part.n_cols, part.n_loc) if fwd else (part.n_loc, part.n_cols)
+    X = torch.randn(n_in, ld, device="cuda").to(tdt)
+    Y = torch.empty(n_out, ld, device="cuda", dtype=tdt)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    call = (lambda: B.spmm_fwd(g, X, ld, Y, ld, F, dt, st, ws=ws, ws_bytes=wsb)) if fwd else \
+           (lambda: B.spmm_bwd(g, X, ld, Y, ld, F, dt, st, ws=ws, ws_bytes=wsb))
+    for _ in range(args.warmup):
+        call()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(st)
+    for _ in range(args.steps):
+        call()
+    e1.record(st)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    touched = int(np.unique(part.col).size) if fwd else int((np.diff(part.rowptr) > 0).sum())
+    bmin = spmm_min_bytes(part, F, n_out, touched, es)
+    print(json.dumps({"metric": "one aggregation launch alone", "unit": "ms per launch", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "dtype": cfg.dtype, "data": "synthetic",
+                      "config": {"workload": f"{cfg.name} {args.direction} F={F}: {n_out} output rows, {n_in} source rows, {part.nnz} entries, pitch {pitch} B"},
+                      "ms": ms, "gedges_s": part.nnz / ms / 1e6, "algorithmic_bytes": bmin,
+                      "requested_bytes": part.nnz * F * es, "requested_GBps": part.nnz * F * es / ms / 1e6,
+                      "launches": args.steps + args.warmup,
+                      "calibration": {"gather_peak_2GB_table_read_bytes": cal_read, "fill_written_bytes": (1 << 28) * 4}}))
+    g.close()
+
+
 def bench_reorder(args):
     """Aggregation time of one SpMM launch (forward and transposed, hidden width 256) before and after the
     vertices are stored in a locality order, on the named config's graph (--config; 'clustered' = a graph with
@@ -442,7 +505,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default=None, help="one workload only (C1..C5); default: C2 as the headline line with C1, C3, C4, C5 under 'configs'")
-    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder", "zipf_requests", "mfma_peak", "products", "gather_peak"],
+    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder", "zipf_requests", "mfma_peak", "products", "gather_peak", "spmm"],
                     help="epoch (default): the headline benchmark; cache_update: throughput of the cache write path; "
                          "policy: hit-rate curves of the cache policies; reorder: SpMM before / after vertex reordering "
                          "(--config C2..C5 or clustered); zipf_requests: request-list gather under Zipf(1.1) requests")
@@ -453,6 +516,8 @@ def main():
     ap.add_argument("--f32-product", default="auto", choices=["auto", "native", "split"],
                     help="how products of fp32 operands are formed: the fp32 matrix instruction, three bf16 pieces per operand "
                          "on the bf16 matrix cores, or (default) the library's choice by size")
+    ap.add_argument("--F", type=int, default=0, help="--what spmm: width of the launch (default: the configuration's dominant launch)")
+    ap.add_argument("--direction", default="fwd", choices=["fwd", "bwd"], help="--what spmm: forward or transposed aggregation")
     ap.add_argument("--cpu-scale", type=float, default=None,
                     help="share of the workload the oracle is timed on (0 = skip; default: the whole workload, 0.1-27 s per configuration)")
     args = ap.parse_args()
@@ -476,6 +541,8 @@ def main():
         return bench_reorder(args)
     if args.what == "zipf_requests":
         return bench_zipf_requests(args)
+    if args.what == "spmm":
+        return bench_spmm_launch(args)
     if args.what == "mfma_peak":
         return bench_mfma_peak(args)
     if args.what == "gather_peak":
