@@ -438,6 +438,61 @@ def bench_spmm_launch(args):
     g.close()
 
 
+def bench_spmm_ranges(args):
+    """What tiling the sources of a low-degree aggregation to a cache level could give at best: the configuration's
+    forward launch against the same launch cut into --ranges launches, range k keeping only the entries whose source row
+    lies in the k-th part of the operand (so each launch gathers from 1/ranges of it).  The cut launches write every
+    output row once per range and nothing adds them up: their summed time is a lower bound for a tiled kernel, which
+    would also have to carry or re-read the partial sums.  One JSON line."""
+    import numpy as np
+    import torch
+    from paper_2508_13716_amd import binding as B, synth
+    cfg = synth.CONFIGS[args.config]
+    part = synth.partition_for(cfg)
+    bf = cfg.dtype == "bf16"
+    dt, tdt, es = (B.BF16, torch.bfloat16, 2) if bf else (B.F32, torch.float32, 4)
+    F = args.F or 256
+    kind = B.NORM_SYM if cfg.kind == "gcn" else B.NORM_MEAN
+    r, c = B.norm_scales(kind, part.n_loc, part.n_halo, part.rowptr, part.halo_degree if part.n_halo else None)
+    st = torch.cuda.Stream()
+    ld = (F * es + 15) // 16 * 16 // es
+    X = torch.randn(part.n_cols, ld, device="cuda").to(tdt)
+    Y = torch.empty(part.n_loc, ld, device="cuda", dtype=tdt)
+
+    def time_graph(rowptr, col):
+        g = B.Graph(part.n_loc, part.n_halo, rowptr, col, r, c, None, 0)
+        wsb = B.spmm_workspace_bytes(g, F, dt)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+        for _ in range(args.warmup):
+            B.spmm_fwd(g, X, ld, Y, ld, F, dt, st, ws=ws, ws_bytes=wsb)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(args.steps):
+            B.spmm_fwd(g, X, ld, Y, ld, F, dt, st, ws=ws, ws_bytes=wsb)
+        e1.record(st)
+        torch.cuda.synchronize()
+        g.close()
+        return e0.elapsed_time(e1) / args.steps
+
+    whole = time_graph(part.rowptr, part.col)
+    row_of = np.repeat(np.arange(part.n_loc, dtype=np.int32), np.diff(part.rowptr))
+    cuts = []
+    for k in range(args.ranges):
+        lo, hi = part.n_cols * k // args.ranges, part.n_cols * (k + 1) // args.ranges
+        keep = (part.col >= lo) & (part.col < hi)
+        rp = np.zeros(part.n_loc + 1, np.int64)
+        np.cumsum(np.bincount(row_of[keep], minlength=part.n_loc), out=rp[1:])
+        ms = time_graph(rp, part.col[keep])
+        cuts.append({"source_rows": [int(lo), int(hi)], "operand_MB": (hi - lo) * ld * es / 1e6, "entries": int(keep.sum()), "ms": ms})
+        print(f"range {k}: {cuts[-1]}", file=sys.stderr, flush=True)
+    print(json.dumps({"metric": "aggregation launch whole against cut into source ranges", "unit": "ms", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "dtype": cfg.dtype, "data": "synthetic",
+                      "config": {"workload": f"{cfg.name} fwd F={F}: {part.n_loc} output rows, {part.n_cols} source rows, {part.nnz} entries"},
+                      "whole_ms": whole, "ranges": args.ranges, "cut_ms_sum": sum(c["ms"] for c in cuts), "cuts": cuts,
+                      "note": "the cut launches write each output row once per range and do not add the partial sums"}))
+
+
 def bench_reorder(args):
     """Aggregation time of one SpMM launch (forward and transposed, hidden width 256) before and after the
     vertices are stored in a locality order, on the named config's graph (--config; 'clustered' = a graph with
@@ -505,7 +560,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default=None, help="one workload only (C1..C5); default: C2 as the headline line with C1, C3, C4, C5 under 'configs'")
-    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder", "zipf_requests", "mfma_peak", "products", "gather_peak", "spmm"],
+    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder", "zipf_requests", "mfma_peak", "products", "gather_peak", "spmm", "spmm_ranges"],
                     help="epoch (default): the headline benchmark; cache_update: throughput of the cache write path; "
                          "policy: hit-rate curves of the cache policies; reorder: SpMM before / after vertex reordering "
                          "(--config C2..C5 or clustered); zipf_requests: request-list gather under Zipf(1.1) requests")
@@ -518,6 +573,7 @@ def main():
                          "on the bf16 matrix cores, or (default) the library's choice by size")
     ap.add_argument("--F", type=int, default=0, help="--what spmm: width of the launch (default: the configuration's dominant launch)")
     ap.add_argument("--direction", default="fwd", choices=["fwd", "bwd"], help="--what spmm: forward or transposed aggregation")
+    ap.add_argument("--ranges", type=int, default=5, help="--what spmm_ranges: number of source ranges the launch is cut into")
     ap.add_argument("--cpu-scale", type=float, default=None,
                     help="share of the workload the oracle is timed on (0 = skip; default: the whole workload, 0.1-27 s per configuration)")
     args = ap.parse_args()
@@ -541,6 +597,8 @@ def main():
         return bench_reorder(args)
     if args.what == "zipf_requests":
         return bench_zipf_requests(args)
+    if args.what == "spmm_ranges":
+        return bench_spmm_ranges(args)
     if args.what == "spmm":
         return bench_spmm_launch(args)
     if args.what == "mfma_peak":
@@ -634,7 +692,10 @@ def epoch_record(name, args, peaks, headline):
         # a record may cover more than one launch of the same kind (e.g. the GEMMs of one layer)
         kernels.append({"kind": kind, "layer": layer, "backward": bwd, "ms": float(np.mean(v))})
     spmm_recs = [k for k in kernels if k["kind"] in ("spmm_fwd", "spmm_bwd")]
-    dom = spmm_recs[0] if spmm_recs else kernels[0]
+    # the dominant launch: the slowest forward aggregation (the transposed launch of the same layer takes about as long -
+    # on a symmetric graph it is the same launch - and the choice must not flip between runs)
+    fwd_recs = [k for k in spmm_recs if k["kind"] == "spmm_fwd"]
+    dom = fwd_recs[0] if fwd_recs else (spmm_recs[0] if spmm_recs else kernels[0])
     F, n_out, touched = launches[(dom["layer"], dom["backward"])]
     bmin = spmm_min_bytes(part, F, n_out, touched, es)
     bgather = part.nnz * (4 + F * es) + n_out * F * es
@@ -722,6 +783,36 @@ def epoch_record(name, args, peaks, headline):
     dp.close()
     del dp
     torch.cuda.empty_cache()
+    if headline and part.n_halo and len(cfg.dims) > 2:
+        # JACA refreshes the cached hidden-layer halo rows as training goes on (section "Vertex Importance and Vertex
+        # Update"): the same epoch with every halo row of every hidden-layer table rewritten before each epoch
+        upd = {}
+        for mode, mname in ((B.MISS_PIPELINED, "pipelined"), (B.MISS_STAGED, "staged")):
+            dpu = H.DeviceProblem(prob, orders=orders, miss_mode=mode, f32_product=f32p)
+            ids = torch.arange(part.n_halo, dtype=torch.int64, device="cuda")
+            rows = {l: H.np_to_dev(prob.tables[l]) for l in range(1, dpu.L)}
+            torch.cuda.synchronize()
+
+            def step(it):
+                for l, r in rows.items():
+                    B.cache_update(dpu.cache, l, ids, part.n_halo, r, r.shape[1], it, stream=dpu.stream)
+                dpu.run_epoch()
+
+            for it in range(args.warmup):
+                step(it)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for it in range(args.steps):
+                step(args.warmup + it)
+            torch.cuda.synchronize()
+            upd[mname + "_ms"] = (time.perf_counter() - t0) * 1e3 / args.steps
+            dpu.close()
+            del dpu, rows
+            torch.cuda.empty_cache()
+        upd["rows_rewritten_per_epoch"] = part.n_halo * (len(cfg.dims) - 2)
+        upd["note"] = ("update + epoch, wall; in pipelined mode the prefetched copy of the host tier is patched by the update, "
+                       "not fetched again")
+        out["epoch_with_vertex_update"] = upd
     if args.cpu_scale is None or args.cpu_scale > 0:
         scale = args.cpu_scale
         if scale is None or scale >= 1.0:

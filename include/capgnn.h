@@ -166,7 +166,10 @@ int capgnn_cache_destroy(capgnn_cache *c);
  * capgnn_cache_fill or a mode change make the next call fetch afresh), a side stream must be given, and copies
  * into ws may still be in flight on the side stream after capgnn_epoch returns: synchronise that stream (or the
  * device) before freeing or reusing ws, the tiers or the cache.  The rows an epoch consumes are the host
- * tier's contents at the time of the previous call (or of this call, for the first). */
+ * tier's contents at the time of the previous call (or of this call, for the first), plus every row that
+ * capgnn_cache_update has written since.  The library cannot see other writes: a caller that writes the pinned tier
+ * itself, or lets anything else use ws between two calls, calls capgnn_cache_set_miss_mode again (any mode), which
+ * drops the prefetched copies. */
 int capgnn_cache_set_miss_mode(capgnn_cache *c, int mode);
 
 /* Loads layer `layer`'s logical table (host, [n_halo x ld], halo-local row order) into both tiers.
@@ -215,8 +218,10 @@ int capgnn_halo_gather(capgnn_cache *c, int layer, const int64_t *ids, int64_t n
  * ids: device int64[n] (halo-local indices, or global ids when by_gid); rows: device [n x ld] of the cache's
  * dtype.  Absent ids are skipped.  Asynchronous on `stream` unless stats != NULL (then it synchronises and
  * reports hits = rows written to the GPU tier, misses = rows written to the host tier, absent).
- * In CAPGNN_MISS_PIPELINED mode the rows prefetched for the next epoch are dropped.  Every table starts with
- * stamp 0 (capgnn_cache_fill resets the layer's stamps to 0). */
+ * In CAPGNN_MISS_PIPELINED mode the copy of the host tier that the last capgnn_epoch prefetched stays valid: every
+ * host-tier row written here is written into that copy too (the call first waits for a prefetch still in flight),
+ * so the next epoch consumes the new rows without fetching the table again; `stream` must be ordered before that
+ * epoch's stream.  Every table starts with stamp 0 (capgnn_cache_fill resets the layer's stamps to 0). */
 int capgnn_cache_update(capgnn_cache *c, int layer, const int64_t *ids, int64_t n, int by_gid,
                         const void *rows, int64_t ld, int64_t epoch, void *stream,
                         capgnn_gather_stats *stats);

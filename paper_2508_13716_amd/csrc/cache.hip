@@ -208,9 +208,9 @@ __global__ __launch_bounds__(256) void update_owner_kernel(MapView m, const int6
 
 __global__ __launch_bounds__(256) void update_rows_kernel(MapView m, const int64_t *ids, int64_t n, int by_gid,
                                                           const char *rows, int64_t rows_pitch, char *gpu_table,
-                                                          char *host_table, int64_t pitch, int row_bytes, int lpr,
-                                                          int vec16, int es, const long long *owner, int64_t *stamp,
-                                                          int64_t epoch, unsigned long long *counters) {
+                                                          char *host_table, char *staged_table, int64_t pitch,
+                                                          int row_bytes, int lpr, int vec16, int es, const long long *owner,
+                                                          int64_t *stamp, int64_t epoch, unsigned long long *counters) {
     const int lane = threadIdx.x & 63;
     const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
     const int64_t k = wave * (64 / lpr) + lane / lpr;
@@ -225,6 +225,9 @@ __global__ __launch_bounds__(256) void update_rows_kernel(MapView m, const int64
     const int32_t s = m.slot[h];
     char *d = s >= 0 ? gpu_table + static_cast<int64_t>(s) * pitch : host_table + (-1 - static_cast<int64_t>(s)) * pitch;
     copy_row(rows + k * rows_pitch, d, row_bytes, l, lpr, vec16, es);
+    // a copy of the host tier that was prefetched for the next epoch gets the new row as well
+    if (s < 0 && staged_table)
+        copy_row(rows + k * rows_pitch, staged_table + (-1 - static_cast<int64_t>(s)) * pitch, row_bytes, l, lpr, vec16, es);
     if (counters && l == 0) atomicAdd(&counters[s >= 0 ? 0 : 1], 1ull);
     if (l == 0) stamp[h] = epoch;
 }
@@ -759,15 +762,19 @@ extern "C" int capgnn_cache_update(capgnn_cache *c, int layer, const int64_t *id
     if (!ids || !rows) CG_FAIL(CAPGNN_EINVAL, "cache_update: ids or rows is NULL");
     if (ld < c->dims[layer]) CG_FAIL(CAPGNN_EINVAL, "cache_update: ld=%lld smaller than the row width %d", (long long)ld, c->dims[layer]);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // a prefetch of the previous epoch may still be reading the host tier: let it finish, then drop its copy
+    // a prefetch of the previous epoch may still be reading the host tier: let it finish.  Its copy stays valid: the
+    // kernel writes every host-tier row it updates into that copy too, so the next epoch neither sees an old row nor has
+    // to fetch the table again (GPU-tier rows never were in the copy).
     if (c->last_side) CG_HIP(hipStreamSynchronize(c->last_side));
-    c->staged_valid[layer] = 0;
     const int es = elem_bytes(c->dtype);
     char *gtab = c->gpu_tier + c->gpu_off[layer];
     char *htab = c->host_tier + c->host_off[layer];
+    char *stab = (c->n_host > 0 && c->staged_valid[layer] && c->staged_base)
+                     ? static_cast<char *>(c->staged_base) + c->host_off[layer] : nullptr;
     const int row_bytes = c->dims[layer] * es;
     const int64_t rows_pitch = ld * es;
-    const int vec16 = aligned16(rows) && rows_pitch % 16 == 0 && aligned16(gtab) && aligned16(htab) && c->pitch[layer] % 16 == 0;
+    const int vec16 = aligned16(rows) && rows_pitch % 16 == 0 && aligned16(gtab) && aligned16(htab) && (!stab || aligned16(stab)) &&
+                      c->pitch[layer] % 16 == 0;
     const int lpr = lanes_per_row(row_bytes, vec16, es);
     const MapView m = view_dev(c);
     unsigned long long *ctr = stats ? reinterpret_cast<unsigned long long *>(c->counters_d) : nullptr;
@@ -775,7 +782,7 @@ extern "C" int capgnn_cache_update(capgnn_cache *c, int layer, const int64_t *id
     const unsigned b1 = static_cast<unsigned>((n + 255) / 256);
     hipLaunchKernelGGL(update_owner_kernel, dim3(b1), dim3(256), 0, st, m, ids, n, by_gid, c->owner_d);
     hipLaunchKernelGGL(update_rows_kernel, dim3(blocks_for(n, lpr)), dim3(256), 0, st, m, ids, n, by_gid,
-                       static_cast<const char *>(rows), rows_pitch, gtab, htab, c->pitch[layer], row_bytes, lpr, vec16, es,
+                       static_cast<const char *>(rows), rows_pitch, gtab, htab, stab, c->pitch[layer], row_bytes, lpr, vec16, es,
                        c->owner_d, c->stamp_d + static_cast<size_t>(layer) * c->n_halo, epoch, ctr);
     hipLaunchKernelGGL(update_clear_kernel, dim3(b1), dim3(256), 0, st, m, ids, n, by_gid, c->owner_d);
     CG_HIP(hipGetLastError());

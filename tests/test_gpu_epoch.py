@@ -127,8 +127,15 @@ def test_epoch_after_vertex_update_and_staleness_bound(env, miss_mode):
     B.cache_update(dp.cache, l, torch.from_numpy(ids).cuda(), len(ids), rows_d, cfg.dims[l], 7, stream=dp.stream)
     prob.tables[l][ids] = new_rows
     ref2 = O.oracle_epoch(prob)
-    loss2, _ = dp.run_epoch()
+    loss2, times2 = dp.run_epoch(want_times=True)
     compare_epoch(env, prob, dp, ref2, loss2, TOL["f32"], f"after update (miss_mode {miss_mode})")
+    if miss_mode == B.MISS_PIPELINED:
+        # the copy prefetched before the update was patched, not dropped: per layer the only host-tier transfer of
+        # this epoch is the prefetch for the next one
+        moves = [r["layer"] for r in times2["records"] if r["kind"] == "gather_miss"]
+        assert sorted(moves) == list(range(dp.L)), moves
+        loss3, _ = dp.run_epoch()                    # consumes the copy fetched after the update
+        compare_epoch(env, prob, dp, ref2, loss3, TOL["f32"], "second epoch after update (pipelined)")
     delta = float(np.abs(dp.results()["logits"].astype(np.float64) - logits_before).max())
     W = prob.model[l].W.astype(np.float64)
     eta = max(part.n_cols, W.shape[0], W.shape[1])
