@@ -164,6 +164,12 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
                 const float *bias, int relu, const void *relu_mask, int64_t ldm, void *ws, size_t ws_bytes,
                 hipStream_t stream, const float *row_scale = nullptr,    // row_scale: C[i,:] *= row_scale[i] at the very end (fp32 C)
                 int f32_product = CAPGNN_F32_PRODUCT_AUTO);
+// C = A W + A2 W2 (+ bias, ReLU), one launch where the fp32 three-piece form applies, else the two launches it replaces
+int launch_gemm_dual(int64_t M, int64_t N, int64_t K1, const void *A, int64_t lda, const void *W, int64_t ldw, int64_t K2,
+                     const void *A2, int64_t lda2, const void *W2, int64_t ldw2, void *C, int64_t ldc, int dtype, int out_f32,
+                     const float *bias, int relu, void *ws, size_t ws_bytes, hipStream_t stream, int f32_product);
+// scratch that lets launch_gemm_dual run as one launch
+size_t gemm_dual_ws_bytes(int64_t N, int64_t K1, int64_t K2);
 size_t gemm_ws_bytes(int trans_a, int64_t M, int64_t N, int64_t K);
 
 // dZ = dH * 1[H > 0] in place (when relu) and dbias[f] = sum_i dZ[i,f] (when dbias), fixed summation order.

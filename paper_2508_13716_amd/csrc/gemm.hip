@@ -32,6 +32,10 @@ struct GemmArgs {
     int gx, gy, S;                  // tiles along N, along M, reduction splits
     int c_staged;                   // bf16 kernel: write C through LDS in 16-byte pieces (no mask / accumulate / split)
     const float *rscale;            // C[i,:] *= rscale[i] after everything else (fp32 C), or null
+    // two products into one result, C = A W + A2 W2 (gemm_split_kernel<..., DUAL>): the reduction index runs over A's K1
+    // columns, padded to K1p (whole steps), and then over A2's K - K1p columns; the cut weights lie one after the other
+    const char *A2; int64_t lda2;
+    int64_t K1, K1p;
 };
 
 // Tile of a workgroup in the one-dimensional grid.  Workgroup b runs on L2 domain b % NUM_XCD; the order is
@@ -792,7 +796,7 @@ struct ColUnits8 {
 // C = A B (or A B^T) with A stored along the reduction index; the second operand comes cut into units (Wt: ku_total
 // units along k per piece, n_pad rows).  NW waves: four (2 x 2) or, on a 128 x 128 tile, eight (2 x 4, each a 64 x 32
 // part: half the staging and half the accumulators per thread, four waves per SIMD).
-template <int BM, int BN, int NW = 4>
+template <int BM, int BN, int NW = 4, bool DUAL = false>
 __global__ __launch_bounds__(NW * 64, NW / 2) void gemm_split_kernel(GemmArgs g, const uint16_t *Wt, int64_t ku_total, int64_t n_pad) {
     static_assert(NW == 4 || (NW == 8 && BN == 128), "eight waves: 128 columns");
     constexpr int NT = NW * 64;
@@ -829,7 +833,7 @@ __global__ __launch_bounds__(NW * 64, NW / 2) void gemm_split_kernel(GemmArgs g,
     // uniform over the workgroup: every row of the tile exists and vector loads are allowed
     const bool interior = m0 + BM <= g.M && g.a_vec;
     if (nk > 0) {
-        la_r.fetch(g.A, g.lda, m0, g.M, k_begin, k_end, g.a_vec, tid);
+        la_r.fetch(g.A, g.lda, m0, g.M, k_begin, DUAL ? g.K1 : k_end, g.a_vec, tid);      // DUAL: one split, k_begin = 0
         lb_p.begin(Wt, ku_total, n_pad, n0, k_begin, tid);
         lb_p.fetch(n_pad);
         la_r.cut();
@@ -879,8 +883,21 @@ __global__ __launch_bounds__(NW * 64, NW / 2) void gemm_split_kernel(GemmArgs g,
         }
     };
     for (int64_t kt = 0; kt + 1 < nk; ++kt) {
-        if (interior && kt + 1 < nk_full) la_r.fetch_fast();
-        else la_r.fetch(g.A, g.lda, m0, g.M, k_begin + (kt + 1) * SBK, k_end, g.a_vec, tid);
+        if constexpr (DUAL) {
+            const int64_t k0 = (kt + 1) * SBK;
+            if (k0 < g.K1p) {
+                if (interior && k0 + SBK <= g.K1) la_r.fetch_fast();
+                else la_r.fetch(g.A, g.lda, m0, g.M, k0, g.K1, g.a_vec, tid);
+            } else {
+                const int64_t kk = k0 - g.K1p, K2 = g.K - g.K1p;
+                if (kk == 0 && interior) la_r.fast_begin(g.A2, g.lda2, m0, 0, tid);
+                if (interior && kk + SBK <= K2) la_r.fetch_fast();
+                else la_r.fetch(g.A2, g.lda2, m0, g.M, kk, K2, g.a_vec, tid);
+            }
+        } else {
+            if (interior && kt + 1 < nk_full) la_r.fetch_fast();
+            else la_r.fetch(g.A, g.lda, m0, g.M, k_begin + (kt + 1) * SBK, k_end, g.a_vec, tid);
+        }
         lb_p.fetch(n_pad);
         products(std::true_type{});
         __syncthreads();            // every wave has read this step's operands
@@ -1058,13 +1075,20 @@ __global__ __launch_bounds__(512, BN == 128 ? 4 : 2) void gemm_split_trans_kerne
 // Cuts the (small) second operand of a plain product into bf16 pieces laid out in 16-byte units
 // Wt[piece][k / 8][n][k % 8], n_pad rows, ku_total units along k, zero beyond N and K.  kc: the source is [n][k]
 // (pitch ldw), else [k][n].
+// A second source W2 (K2 rows, or columns when kc) follows from k = K1p on.
 __global__ __launch_bounds__(256) void split_repack_kernel(const float *W, int64_t ldw, int kc, int64_t K, int64_t N,
-                                                           uint16_t *Wt, int64_t n_pad, int64_t ku_total) {
+                                                           uint16_t *Wt, int64_t n_pad, int64_t ku_total,
+                                                           const float *W2 = nullptr, int64_t ldw2 = 0, int64_t K1p = 0,
+                                                           int64_t K2 = 0) {
     const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     const int64_t plane = ku_total * n_pad * 8;
     if (t >= plane) return;
     const int64_t ku = t / (n_pad * 8), n = (t / 8) % n_pad, k = 8 * ku + (t % 8);
-    const float x = (n < N && k < K) ? (kc ? W[n * ldw + k] : W[k * ldw + n]) : 0.f;
+    float x = (n < N && k < K) ? (kc ? W[n * ldw + k] : W[k * ldw + n]) : 0.f;
+    if (W2 && k >= K1p) {
+        const int64_t k2 = k - K1p;
+        x = (n < N && k2 < K2) ? (kc ? W2[n * ldw2 + k2] : W2[k2 * ldw2 + n]) : 0.f;
+    }
     uint32_t p[3];
     split3_pair(x, 0.f, p);
     Wt[t] = static_cast<uint16_t>(p[0]);
@@ -1153,6 +1177,8 @@ size_t gemm_ws_bytes(int trans_a, int64_t M, int64_t N, int64_t K) {
     return b;
 }
 
+size_t gemm_dual_ws_bytes(int64_t N, int64_t K1, int64_t K2) { return split_b_bytes(N, split_ld(K1) + K2); }
+
 // AUTO: smaller products stay on the fp32 instruction, and so do weight gradients at most 64 columns wide (half of
 // the threads that stage their operands would idle; measured slower)
 constexpr int64_t SPLIT_MIN_MACS = int64_t(1) << 28;
@@ -1225,6 +1251,7 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
     g.accumulate = accumulate; g.relu = relu; g.bias = bias;
     g.mask = static_cast<const char *>(relu_mask); g.ldm = ldm; g.mask_bf16 = (dtype == CAPGNN_BF16);
     g.rscale = row_scale;
+    g.A2 = nullptr; g.lda2 = 0; g.K1 = 0; g.K1p = 0;
     if (S > 1) {
         const size_t need = static_cast<size_t>(S) * M * N * sizeof(float);
         if (!ws || ws_bytes < need) CG_FAIL(CAPGNN_ENOMEM, "gemm: workspace of %zu bytes needed, %zu given", need, ws_bytes);
@@ -1277,6 +1304,64 @@ int launch_gemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, const
         hipLaunchKernelGGL(gemm_reduce_kernel, dim3(static_cast<unsigned>((total + 31) / 32)), dim3(256), 0, stream, g, S);
         CG_HIP(hipGetLastError());
     }
+    return CAPGNN_OK;
+}
+
+// C = A W + A2 W2 (+ bias, ReLU): the two products of a GraphSAGE layer (neighbour term and self term) into one result.
+// fp32 operands in the three-piece form run as ONE launch whose reduction walks A's columns and then A2's, so C is
+// written once and never read back; every other case is the two launches it replaces (A2 W2 first, then A W accumulated
+// on top with the epilogue).  Plain operands only: A [M x K1], A2 [M x K2], W [K1 x N], W2 [K2 x N], row-major.
+int launch_gemm_dual(int64_t M, int64_t N, int64_t K1, const void *A, int64_t lda, const void *W, int64_t ldw, int64_t K2,
+                     const void *A2, int64_t lda2, const void *W2, int64_t ldw2, void *C, int64_t ldc, int dtype, int out_f32,
+                     const float *bias, int relu, void *ws, size_t ws_bytes, hipStream_t stream, int f32_product) {
+    if (f32_product != CAPGNN_F32_PRODUCT_AUTO && f32_product != CAPGNN_F32_PRODUCT_NATIVE && f32_product != CAPGNN_F32_PRODUCT_SPLIT)
+        CG_FAIL(CAPGNN_EINVAL, "gemm: unknown form of the fp32 product %d", f32_product);
+    const int64_t K1p = split_ld(K1 > 0 ? K1 : 0), K = K1p + K2;
+    const bool one_launch = dtype == CAPGNN_F32 && f32_product != CAPGNN_F32_PRODUCT_NATIVE && M > 0 && N > 0 && K1 > 0 && K2 > 0 &&
+                            A && A2 && W && W2 && C && lda >= K1 && lda2 >= K2 && ldw >= N && ldw2 >= N && ldc >= N &&
+                            N <= (1 << 22) && M < (int64_t(1) << 31) * 64 &&
+                            (f32_product == CAPGNN_F32_PRODUCT_SPLIT || M * N >= SPLIT_MIN_MACS / (K1 + K2)) &&
+                            ws && ws_bytes >= split_b_bytes(N, K);
+    if (!one_launch) {
+        CG_TRY(launch_gemm(0, 0, M, N, K2, A2, lda2, W2, ldw2, C, ldc, dtype, out_f32, 0, nullptr, 0, nullptr, 0, ws, ws_bytes,
+                           stream, nullptr, f32_product));
+        return launch_gemm(0, 0, M, N, K1, A, lda, W, ldw, C, ldc, dtype, out_f32, 1, bias, relu, nullptr, 0, ws, ws_bytes,
+                           stream, nullptr, f32_product);
+    }
+    int bm, bn;
+    tile_for(N, &bm, &bn);
+    GemmArgs g;
+    g.M = M; g.N = N; g.K = K;
+    g.A = static_cast<const char *>(A); g.lda = lda;
+    g.B = static_cast<const char *>(W); g.ldb = ldw;
+    g.C = static_cast<char *>(C); g.ldc = ldc;
+    g.part = nullptr;
+    g.k_chunk = K;
+    g.a_vec = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && ((lda * 4) % 16 == 0) && (reinterpret_cast<uintptr_t>(A2) % 16 == 0) &&
+              ((lda2 * 4) % 16 == 0);
+    g.b_vec = 0;
+    g.out_bf16 = 0; g.accumulate = 0; g.relu = relu; g.bias = bias;
+    g.mask = nullptr; g.ldm = 0; g.mask_bf16 = 0;
+    g.rscale = nullptr;
+    g.A2 = static_cast<const char *>(A2); g.lda2 = lda2; g.K1 = K1; g.K1p = K1p;
+    const int64_t gy = (M + bm - 1) / bm, gx = (N + bn - 1) / bn;
+    const int64_t n_wg = NUM_XCD * ((gy + NUM_XCD - 1) / NUM_XCD) * gx;
+    if (n_wg >= (int64_t(1) << 31) || gx >= (int64_t(1) << 24) || gy >= (int64_t(1) << 30))
+        CG_FAIL(CAPGNN_EINVAL, "gemm: %lld x %lld tiles exceed the grid", (long long)gy, (long long)gx);
+    g.gx = static_cast<int>(gx); g.gy = static_cast<int>(gy); g.S = 1;
+    g.c_staged = 0;
+    const int64_t n_pad = split_rows(N), ku_total = split_ld(K) / 8;
+    hipLaunchKernelGGL(split_repack_kernel, dim3(static_cast<unsigned>((ku_total * n_pad * 8 + 255) / 256)), dim3(256), 0, stream,
+                       static_cast<const float *>(W), ldw, 0, K1, N, static_cast<uint16_t *>(ws), n_pad, ku_total,
+                       static_cast<const float *>(W2), ldw2, K1p, K2);
+    dim3 grid(static_cast<unsigned>(n_wg), 1, 1);
+    if (bn == 64)
+        hipLaunchKernelGGL((gemm_split_kernel<128, 64, 4, true>), grid, dim3(256), 0, stream, g, static_cast<const uint16_t *>(ws),
+                           ku_total, n_pad);
+    else
+        hipLaunchKernelGGL((gemm_split_kernel<128, 128, 8, true>), grid, dim3(512), 0, stream, g, static_cast<const uint16_t *>(ws),
+                           ku_total, n_pad);
+    CG_HIP(hipGetLastError());
     return CAPGNN_OK;
 }
 

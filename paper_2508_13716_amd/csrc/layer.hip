@@ -107,7 +107,9 @@ static size_t fwd_t_bytes(const capgnn_graph *g, const capgnn_layer *l, int orde
 
 // scratch of the transform GEMMs (the bf16 kernel lays the weight out with the reduction index contiguous)
 static size_t fwd_g_bytes(const capgnn_graph *g, const capgnn_layer *l) {
-    return gemm_ws_bytes(0, g->n_cols, l->f_out, l->f_in);
+    const size_t b = gemm_ws_bytes(0, g->n_cols, l->f_out, l->f_in);
+    // a GraphSAGE layer's two fp32 products run as one launch over both weight matrices
+    return (l->kind == CAPGNN_SAGE_MEAN && l->dtype == CAPGNN_F32) ? std::max(b, gemm_dual_ws_bytes(l->f_out, l->f_in, l->f_in)) : b;
 }
 
 static size_t fwd_ws_bytes(const capgnn_graph *g, const capgnn_layer *l, int order) {
@@ -160,12 +162,11 @@ static int layer_fwd_impl(const capgnn_graph *g, const capgnn_layer *l, int orde
         Scope s(CAPGNN_K_GEMM, li, 0, st);
         void *gws = (ws && ws_bytes >= fwd_g_bytes(g, l)) ? ws : nullptr;
         const size_t gwb = gws ? fwd_g_bytes(g, l) : 0;
-        if (sage) {
-            CG_TRY(launch_gemm(0, 0, g->n_loc, l->f_out, l->f_in, X, ldx, l->W_self, l->f_out, H, ldh, dt, l->out_f32, 0,
-                               nullptr, 0, nullptr, 0, gws, gwb, st, nullptr, l->f32_product));
-        }
-        CG_TRY(launch_gemm(0, 0, g->n_loc, l->f_out, l->f_in, saved, ldm, l->W, l->f_out, H, ldh, dt, l->out_f32,
-                           sage ? 1 : 0, l->bias, relu, nullptr, 0, gws, gwb, st, nullptr, l->f32_product));
+        if (sage)       // H = act(M W + X_loc W_self + b): one launch where the three-piece fp32 form applies
+            return launch_gemm_dual(g->n_loc, l->f_out, l->f_in, saved, ldm, l->W, l->f_out, l->f_in, X, ldx, l->W_self, l->f_out,
+                                    H, ldh, dt, l->out_f32, l->bias, relu, gws, gwb, st, l->f32_product);
+        CG_TRY(launch_gemm(0, 0, g->n_loc, l->f_out, l->f_in, saved, ldm, l->W, l->f_out, H, ldh, dt, l->out_f32, 0, l->bias,
+                           relu, nullptr, 0, gws, gwb, st, nullptr, l->f32_product));
         return CAPGNN_OK;
     }
     // XFORM_FIRST.  When an entry's weight depends on its source alone (no edge values), the product's epilogue

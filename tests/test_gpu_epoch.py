@@ -152,11 +152,14 @@ def test_epoch_after_vertex_update_and_staleness_bound(env, miss_mode):
 @pytest.mark.parametrize("graph", ["small", "blocked"])
 @pytest.mark.parametrize("kind", ["gcn", "sage"])
 @pytest.mark.parametrize("order", ["agg", "xform"])
-def test_layer_fwd_bwd_with_halo_gradient(env, kind, order, graph):
+@pytest.mark.parametrize("product", ["auto", "split"])
+def test_layer_fwd_bwd_with_halo_gradient(env, kind, order, graph, product):
     """One layer, both association orders, with and without the halo part of the input gradient.  "blocked": a
     dense-degree partition whose operator gets the column-blocked copy in both directions, so the aggregations run the
     blocked kernels, on rows that the producing kernels have multiplied by the per-source weights (GCN) or with unit
-    weights (mean aggregator)."""
+    weights (mean aggregator).  "split": every fp32 product in its three-piece form, which these sizes would not pick by
+    themselves; a GraphSAGE layer's two forward products then run as one launch over both weight matrices (the first
+    reduction range, 50, ends inside a step)."""
     torch, B, H, O, orc = env["torch"], env["B"], env["H"], env["O"], env["orc"]
     if graph == "small":
         part = synth.make_partition("layer", 900, 700, 12000, seed=41, max_deg=2500, self_loops=(kind == "gcn"))
@@ -179,7 +182,8 @@ def test_layer_fwd_bwd_with_halo_gradient(env, kind, order, graph):
     g = B.Graph(part.n_loc, part.n_halo, part.rowptr, part.col, r, c)
     Wd, Wsd, bd = H.np_to_dev(W), (None if Ws is None else H.np_to_dev(Ws)), H.np_to_dev(b)
     ly = B.make_layer(B.GCN if kind == "gcn" else B.SAGE_MEAN, fi, fo, B.ACT_RELU, B.F32, Wd, Wsd, bd,
-                      B.AGG_FIRST if order == "agg" else B.XFORM_FIRST)
+                      B.AGG_FIRST if order == "agg" else B.XFORM_FIRST,
+                      f32_product=B.F32_PRODUCT_SPLIT if product == "split" else B.F32_PRODUCT_AUTO)
     ldx, ldh = 52, 36
     Xd = H.padded_matrix(X, ldx)
     Hd = torch.zeros((part.n_loc, ldh), device="cuda")
