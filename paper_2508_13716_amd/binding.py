@@ -98,6 +98,10 @@ SIGNATURES = {
     "capgnn_prune_halo": (_i32, [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp]),
     "capgnn_locality_order": (_i32, [_i32, _i64, _i64, _vp, _vp, _vp]),
     "capgnn_relabel_csr": (_i32, [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "capgnn_epoch_graph_create": (_i32, [C.POINTER(_vp), _vp, _vp, _vp, _i32, _vp, _i64, _vp, _vp, C.c_double, _vp, _vp, _vp, _vp,
+                                         C.c_float, _vp, _vp, _sz, _vp]),
+    "capgnn_epoch_graph_launch": (_i32, [_vp, _vp]),
+    "capgnn_epoch_graph_destroy": (_i32, [_vp]),
     "capgnn_cache_update": (_i32, [_vp, _i32, _vp, _i64, _i32, _vp, _i64, _i64, _vp, _vp]),
     "capgnn_cache_stale": (_i32, [_vp, _i32, _i64, _i64, _vp, _vp, _vp, _vp]),
     "capgnn_cache_fill": (_i32, [_vp, _i32, _vp, _i64, _vp]),
@@ -523,6 +527,41 @@ def epoch_activation(g: Graph, c: Optional[Cache], layers: List[Layer], l: int, 
     _check(lib().capgnn_epoch_activation(g.h, c.h if c is not None else None, arr, len(layers), l, _p(ws),
                                          C.byref(ptr), C.byref(ld)))
     return int(ptr.value), int(ld.value)
+
+
+class EpochGraph:
+    """capgnn_epoch recorded as a HIP graph (capgnn_epoch_graph_create); launch() replays it.  Keeps references to every
+    tensor it was given: the graph holds their addresses."""
+
+    def __init__(self, g: Graph, c: Optional[Cache], layers: List[Layer], X0, ld0: int, labels, mask, loss_norm: float,
+                 logits, dW: Sequence, dW_self: Optional[Sequence], dbias: Sequence, lr: float, loss_dev, ws, ws_bytes: int,
+                 stream):
+        L = len(layers)
+        arr = (Layer * L)(*layers)
+        pw = (C.c_void_p * L)(*[_p(t) for t in dW])
+        ps = (C.c_void_p * L)(*[_p(t) for t in dW_self]) if dW_self is not None else None
+        pb = (C.c_void_p * L)(*[_p(t) for t in dbias])
+        self._keep = (g, c, layers, X0, labels, mask, logits, dW, dW_self, dbias, loss_dev, ws)
+        h = C.c_void_p()
+        _check(lib().capgnn_epoch_graph_create(C.byref(h), g.h, c.h if c is not None else None, arr, L, _p(X0), ld0, _p(labels),
+                                               _p(mask), loss_norm, _p(logits), pw, ps, pb, lr, _p(loss_dev), _p(ws), ws_bytes,
+                                               _stream(stream)))
+        self.h = h
+
+    def launch(self, stream):
+        _check(lib().capgnn_epoch_graph_launch(self.h, _stream(stream)))
+
+    def close(self):
+        if self.h:
+            lib().capgnn_epoch_graph_destroy(self.h)
+            self.h = None
+            self._keep = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def epoch(g: Graph, c: Optional[Cache], layers: List[Layer], X0, ld0: int, labels, mask, loss_norm: float, logits,

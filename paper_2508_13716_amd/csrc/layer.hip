@@ -633,3 +633,68 @@ extern "C" int capgnn_epoch_multilabel(const capgnn_graph *g, capgnn_cache *c, c
     return epoch_impl(g, c, layers, L, X0, ld0, nullptr, targets, ldt, mask, loss_norm, logits, dW, dW_self, dbias, lr,
                       loss_out, times, ws, ws_bytes, stream, side_stream);
 }
+
+// ---- the epoch as a HIP graph: one launch per epoch instead of one per kernel
+
+struct capgnn_epoch_graph {
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+};
+
+__global__ void copy_loss_kernel(const float *src, float *dst) { *dst = *src; }
+
+extern "C" int capgnn_epoch_graph_create(capgnn_epoch_graph **out, const capgnn_graph *g, capgnn_cache *c,
+                                         const capgnn_layer *layers, int L, void *X0, int64_t ld0, const int32_t *labels,
+                                         const uint8_t *mask, double loss_norm, float *logits, float **dW, float **dW_self,
+                                         float **dbias, float lr, float *loss_dev, void *ws, size_t ws_bytes, void *stream) {
+    if (!out) CG_FAIL(CAPGNN_EINVAL, "epoch_graph_create: out is NULL");
+    *out = nullptr;
+    if (!stream) CG_FAIL(CAPGNN_EINVAL, "epoch_graph_create: a stream of the caller's is needed (the default stream cannot be captured)");
+    if (!labels) CG_FAIL(CAPGNN_EINVAL, "epoch_graph_create: labels is NULL");
+    CG_TRY(check_epoch_args(g, c, layers, L));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    CG_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+    // everything on the one stream: host-tier rows, if any, travel inside the epoch that consumes them
+    int rc = epoch_impl(g, c, layers, L, X0, ld0, labels, nullptr, 0, mask, loss_norm, logits, dW, dW_self, dbias, lr, nullptr,
+                        nullptr, ws, ws_bytes, stream, nullptr);
+    if (rc == CAPGNN_OK && loss_dev) {
+        EpochPlan p;
+        plan_epoch(g, c, layers, L, ld0, &p);
+        hipLaunchKernelGGL(copy_loss_kernel, dim3(1), dim3(1), 0, st,
+                           reinterpret_cast<const float *>(static_cast<char *>(ws) + p.loss_val_off), loss_dev);
+    }
+    hipGraph_t graph = nullptr;
+    const hipError_t e_end = hipStreamEndCapture(st, &graph);       // always: the stream must leave capture mode
+    if (rc != CAPGNN_OK) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return rc;
+    }
+    if (e_end != hipSuccess || !graph) {
+        if (graph) (void)hipGraphDestroy(graph);
+        CG_FAIL(CAPGNN_EHIP, "epoch_graph_create: hipStreamEndCapture: %s", hipGetErrorString(e_end));
+    }
+    hipGraphExec_t exec = nullptr;
+    const hipError_t e_inst = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (e_inst != hipSuccess) {
+        (void)hipGraphDestroy(graph);
+        CG_FAIL(CAPGNN_EHIP, "epoch_graph_create: hipGraphInstantiate: %s", hipGetErrorString(e_inst));
+    }
+    capgnn_epoch_graph *eg = new capgnn_epoch_graph;
+    eg->graph = graph; eg->exec = exec;
+    *out = eg;
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_epoch_graph_launch(capgnn_epoch_graph *eg, void *stream) {
+    if (!eg || !eg->exec) CG_FAIL(CAPGNN_EINVAL, "epoch_graph_launch: no graph");
+    CG_HIP(hipGraphLaunch(eg->exec, static_cast<hipStream_t>(stream)));
+    return CAPGNN_OK;
+}
+
+extern "C" int capgnn_epoch_graph_destroy(capgnn_epoch_graph *eg) {
+    if (!eg) return CAPGNN_OK;
+    if (eg->exec) (void)hipGraphExecDestroy(eg->exec);
+    if (eg->graph) (void)hipGraphDestroy(eg->graph);
+    delete eg;
+    return CAPGNN_OK;
+}

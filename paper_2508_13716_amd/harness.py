@@ -173,6 +173,18 @@ class DeviceProblem:
                        self.ws, self.ws_bytes, self.stream, self.side, want_loss=want_loss, want_times=want_times,
                        targets=self.targets, ldt=0 if self.targets is None else self.targets.shape[1])
 
+    def capture_epoch(self, lr: float = 0.0, mask=True):
+        """The epoch as a HIP graph on this problem's buffers; returns (graph, device float the replays write the loss to)."""
+        torch = _torch()
+        if self.targets is not None:
+            raise ValueError("the recorded epoch takes class labels")
+        loss_dev = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        eg = B.EpochGraph(self.graph, self.cache, self.layers, self.X0, self.ld0, self.labels, self.mask if mask else None, 0.0,
+                          self.logits, self.dW, self.dW_self if any(t is not None for t in self.dW_self) else None, self.dbias,
+                          lr, loss_dev, self.ws, self.ws_bytes, self.stream)
+        return eg, loss_dev
+
     def hidden(self, l: int) -> np.ndarray:
         """Output of hidden layer l after the last epoch, [n_loc, f_out(l)] (bf16 as uint16 bits)."""
         torch = _torch()

@@ -245,3 +245,88 @@ def test_epoch_rejects_bad_arguments(env):
                 dp.dbias, 0.0, dp.ws, dp.ws_bytes, dp.stream, dp.side)
     assert e.value.code == B.EINVAL
     dp.close()
+
+
+@pytest.mark.parametrize("case", ["C1", "C2-host-tier", "C1-sgd"])
+def test_epoch_graph_replays_match_eager_epochs(env, case):
+    """capgnn_epoch recorded as a HIP graph: every replay must give exactly what the eager epoch gives on the same buffer
+    contents (same kernels, same order: bit for bit), also after the buffers' contents changed between replays (a cache
+    update), with eager work and synchronisations between the replays, and with host-tier rows travelling inside the
+    graph.  The first eager result is compared with the oracle."""
+    torch, B, H, O = env["torch"], env["B"], env["H"], env["O"]
+    if case == "C2-host-tier":
+        cfg = synth.CONFIGS["C2"].scaled(0.02)
+        prob = H.make_problem(cfg, mask_frac=0.5)
+    else:
+        cfg = synth.CONFIGS["C1"]
+        prob = H.make_problem(cfg, mask_frac=0.5)
+    lr = 0.05 if case == "C1-sgd" else 0.0
+    part = prob.part
+    # the eager side runs on one stream too (no side stream), as the recorded epoch does
+    dp = H.DeviceProblem(prob, miss_mode=B.MISS_STAGED, use_side_stream=False)
+    ref = O.oracle_epoch(prob)
+
+    def snapshot():
+        r = dp.results()
+        return [r["logits"].copy()] + [a.copy() for a in r["dW"]] + [a.copy() for a in r["db"]]
+
+    W0 = [w.clone() for w in dp.W]
+    b0 = [b.clone() for b in dp.bias]
+
+    def reset_weights():
+        for w, w0 in zip(dp.W, W0):
+            w.copy_(w0)
+        for b, bb in zip(dp.bias, b0):
+            b.copy_(bb)
+        torch.cuda.synchronize()
+
+    # eager: three epochs (with the SGD step they differ), a cache update before the third
+    rng = np.random.default_rng(11)
+    l_upd = dp.L - 1
+    ids = rng.permutation(part.n_halo)[: max(part.n_halo // 3, 1)].astype(np.int64)
+    new_rows = rng.standard_normal((len(ids), cfg.dims[l_upd])).astype(np.float32)
+    ids_d, rows_d = torch.from_numpy(ids).cuda(), H.np_to_dev(new_rows)
+    old_rows_d = H.np_to_dev(np.ascontiguousarray(prob.tables[l_upd][ids]))
+    eager = []
+    for it in range(3):
+        if it == 2:
+            B.cache_update(dp.cache, l_upd, ids_d, len(ids), rows_d, cfg.dims[l_upd], 5, stream=dp.stream)
+        loss, _ = dp.run_epoch(lr=lr)
+        eager.append((loss, snapshot()))
+        if it == 0:
+            compare_epoch(env, prob, dp, ref, loss, TOL["f32"], f"graph case {case}: eager epoch")
+    # back to the start: weights, cache rows
+    B.cache_update(dp.cache, l_upd, ids_d, len(ids), old_rows_d, cfg.dims[l_upd], 6, stream=dp.stream)
+    reset_weights()
+    for t in [dp.logits] + dp.dW + dp.dbias:
+        t.zero_()
+    torch.cuda.synchronize()
+
+    eg, loss_dev = dp.capture_epoch(lr=lr)
+    assert np.isnan(loss_dev.cpu().numpy()[0]) and not dp.logits.any()        # recording ran nothing
+    scratch = torch.empty(1 << 20, device="cuda")
+    for it in range(3):
+        if it == 2:
+            B.cache_update(dp.cache, l_upd, ids_d, len(ids), rows_d, cfg.dims[l_upd], 7, stream=dp.stream)
+        eg.launch(dp.stream)
+        torch.cuda.synchronize()
+        got = snapshot()
+        loss_g = float(loss_dev.cpu().numpy()[0])
+        scratch.normal_()                        # the program's own eager work between the replays
+        _ = float(scratch.sum().cpu())
+        say(f"graph case {case}: replay {it}: loss {loss_g:.6f} (eager {eager[it][0]:.6f})")
+        assert loss_g == eager[it][0], (it, loss_g, eager[it][0])
+        for a, b in zip(got, eager[it][1]):
+            assert np.array_equal(a, b), f"replay {it} differs from the eager epoch"
+    if lr == 0.0:
+        assert not np.array_equal(eager[2][1][0], eager[1][1][0])      # the update did change the result
+    else:
+        assert not np.array_equal(eager[1][1][0], eager[0][1][0])      # and so did the SGD step
+    eg.close()
+    with pytest.raises(B.CapgnnError):
+        B.EpochGraph(dp.graph, dp.cache, dp.layers, dp.X0, dp.ld0, dp.labels, dp.mask, 0.0, dp.logits, dp.dW, None, dp.dbias,
+                     0.0, None, dp.ws, dp.ws_bytes, None)             # the default stream cannot be captured
+    # the stream is usable after the failed call, and after a successful capture
+    loss, _ = dp.run_epoch(lr=0.0)
+    assert np.isfinite(loss)
+    dp.close()
