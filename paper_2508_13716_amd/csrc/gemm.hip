@@ -435,6 +435,8 @@ struct HalfTileLoader {
         return make_uint4(w[0], w[1], w[2], w[3]);
     }
 
+    int64_t k_rows = 0;             // rows of the operand when it is stored across the reduction index (set by the kernel)
+
     __device__ __forceinline__ void fetch(const char *base, int64_t ld, int64_t t0, int64_t T, int64_t k0, int64_t k_end,
                                           int tid) {
         if constexpr (KC) {
@@ -452,11 +454,15 @@ struct HalfTileLoader {
             constexpr int CPR = BT / 8;
             const int kb = tt / CPR, tq = tt % CPR;       // four k starting at 4*kb, eight columns starting at 8*tq
             const int64_t t = t0 + 8 * tq;
-            const int ncol = static_cast<int>(T - t < 8 ? T - t : 8);
+            // a ragged last group of columns is still one 16-byte load where the row pitch covers it (every row but the
+            // operand's last, whose padding need not exist): what the padding holds lands in result rows / columns beyond
+            // the matrix, which are never stored
+            const int exact = t >= T ? 0 : static_cast<int>(T - t < 8 ? T - t : 8);
+            const int padded = (exact > 0 && t + 8 <= ld) ? 8 : exact;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int64_t k = k0 + 4 * kb + j;
-                r[j] = load8(base, k * ld + t, k < k_end ? ncol : 0);
+                r[j] = load8(base, k * ld + t, k < k_end ? (k + 1 < k_rows ? padded : exact) : 0);
             }
         }
     }
@@ -542,6 +548,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 
     HalfTileLoader<A_KC, BM, 0> la;
     HalfTileLoader<B_KC, BN, A_KC ? 0 : 128> lb;     // when both operands are transposed they split the threads
+    la.k_rows = g.K; lb.k_rows = g.K;
     const int64_t nk = (k_end > k_begin) ? (k_end - k_begin + HBK - 1) / HBK : 0;
     if (nk > 0) {
         la.fetch(g.A, g.lda, m0, g.M, k_begin, k_end, tid);
@@ -1145,7 +1152,7 @@ static int choose_split(int trans_a, int64_t M, int64_t N, int64_t K, int bm, in
     int64_t s = 1536 / (tiles > 0 ? tiles : 1);
     const int64_t max_by_k = K / (bk * 16) > 0 ? K / (bk * 16) : 1;   // at least 16 k-steps per split
     if (s > max_by_k) s = max_by_k;
-    if (s > 512) s = 512;
+    if (s > 1024) s = 1024;
     if (s < 1) s = 1;
     return static_cast<int>(s);
 }

@@ -378,6 +378,8 @@ def test_gemm_vs_oracle(env, dtype, ta, tb):
         for pad in (0, 3):
             lda, ldb, ldc = A.shape[1] + pad, Bm.shape[1] + pad, N + pad
             Ad, Bd = H.padded_matrix(A, lda), H.padded_matrix(Bm, ldb)
+            Ad[:, A.shape[1]:] = float("nan")            # whatever the padding holds must not reach the result
+            Bd[:, Bm.shape[1]:] = float("nan")
             wsb = B.gemm_workspace_bytes(ta, M, N, K)
             ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
             Cd = torch.full((M, ldc), 2.0, dtype=torch.float32, device="cuda")
@@ -419,6 +421,8 @@ def test_gemm_bf16_matrix_core_path(env, ta, tb):
             ldb = synth.pad_to(Bm.shape[1], 8) if ta else Bm.shape[1] + 1     # a weight's pitch is free
             ldc = N + 3
             Ad, Bd = H.padded_matrix(A, lda), H.padded_matrix(Bm, ldb)
+            Ad[:, A.shape[1]:] = float("nan")            # a ragged last column group is read up to the pitch: the padding
+            Bd[:, Bm.shape[1]:] = float("nan")            # must end up nowhere in the result
             wsb = B.gemm_workspace_bytes(ta, M, N, K)
             ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
             Cd = torch.full((M, ldc), 2.0, dtype=torch.float32, device="cuda")
