@@ -725,6 +725,18 @@ struct SplitRowLoader {
         }
     }
 
+    // check-free loads of one step at a given place (rows t0.., 32 k from k0): no state between steps.  The tile's
+    // corner is uniform over the workgroup, a thread adds a 32-bit offset inside the tile (ld < 2^22 elements).
+    __device__ __forceinline__ void fetch_at(const char *base, int64_t ld, int64_t t0, int64_t k0, int tid) {
+        const char *corner = base + (t0 * ld + k0) * 4;
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const int idx = tid + NT * q;
+            const uint32_t off = (static_cast<uint32_t>(idx >> 3) * static_cast<uint32_t>(ld) + 4u * (idx & 7)) * 4u;
+            r[q] = *reinterpret_cast<const float4 *>(corner + off);
+        }
+    }
+
     uint2 pk[NLD][3];               // the pieces of r, ready for LDS
 
     __device__ __forceinline__ void cut() {
@@ -846,7 +858,7 @@ __global__ __launch_bounds__(NW * 64, NW / 2) void gemm_split_kernel(GemmArgs g,
         la_r.cut();
         la_r.put(As, tid);
         lb_p.stash(Bs, tid);
-        if (interior) la_r.fast_begin(g.A, g.lda, m0, k_begin + SBK, tid);
+        if (!DUAL && interior) la_r.fast_begin(g.A, g.lda, m0, k_begin + SBK, tid);
     }
     __syncthreads();
     // the products of one step (32 k) out of LDS; CUT: the first operand of the next step, which waits in registers, is
@@ -891,16 +903,15 @@ __global__ __launch_bounds__(NW * 64, NW / 2) void gemm_split_kernel(GemmArgs g,
     };
     for (int64_t kt = 0; kt + 1 < nk; ++kt) {
         if constexpr (DUAL) {
+            // which of the two first operands this step reads is uniform over the grid; the check-free loads form their
+            // addresses from it (no per-thread pointers to carry across the change of operand)
             const int64_t k0 = (kt + 1) * SBK;
-            if (k0 < g.K1p) {
-                if (interior && k0 + SBK <= g.K1) la_r.fetch_fast();
-                else la_r.fetch(g.A, g.lda, m0, g.M, k0, g.K1, g.a_vec, tid);
-            } else {
-                const int64_t kk = k0 - g.K1p, K2 = g.K - g.K1p;
-                if (kk == 0 && interior) la_r.fast_begin(g.A2, g.lda2, m0, 0, tid);
-                if (interior && kk + SBK <= K2) la_r.fetch_fast();
-                else la_r.fetch(g.A2, g.lda2, m0, g.M, kk, K2, g.a_vec, tid);
-            }
+            const bool second = k0 >= g.K1p;
+            const char *base = second ? g.A2 : g.A;
+            const int64_t ld = second ? g.lda2 : g.lda;
+            const int64_t kk = second ? k0 - g.K1p : k0, kend = second ? g.K - g.K1p : g.K1;
+            if (interior && kk + SBK <= kend) la_r.fetch_at(base, ld, m0, kk, tid);
+            else la_r.fetch(base, ld, m0, g.M, kk, kend, g.a_vec, tid);
         } else {
             if (interior && kt + 1 < nk_full) la_r.fetch_fast();
             else la_r.fetch(g.A, g.lda, m0, g.M, k_begin + (kt + 1) * SBK, k_end, g.a_vec, tid);
@@ -1326,7 +1337,7 @@ int launch_gemm_dual(int64_t M, int64_t N, int64_t K1, const void *A, int64_t ld
     const int64_t K1p = split_ld(K1 > 0 ? K1 : 0), K = K1p + K2;
     const bool one_launch = dtype == CAPGNN_F32 && f32_product != CAPGNN_F32_PRODUCT_NATIVE && M > 0 && N > 0 && K1 > 0 && K2 > 0 &&
                             A && A2 && W && W2 && C && lda >= K1 && lda2 >= K2 && ldw >= N && ldw2 >= N && ldc >= N &&
-                            N <= (1 << 22) && M < (int64_t(1) << 31) * 64 &&
+                            N <= (1 << 22) && M < (int64_t(1) << 31) * 64 && lda < (1 << 22) && lda2 < (1 << 22) &&
                             (f32_product == CAPGNN_F32_PRODUCT_SPLIT || M * N >= SPLIT_MIN_MACS / (K1 + K2)) &&
                             ws && ws_bytes >= split_b_bytes(N, K);
     if (!one_launch) {
