@@ -571,6 +571,7 @@ def main():
     ap.add_argument("--f32-product", default="auto", choices=["auto", "native", "split"],
                     help="how products of fp32 operands are formed: the fp32 matrix instruction, three bf16 pieces per operand "
                          "on the bf16 matrix cores, or (default) the library's choice by size")
+    ap.add_argument("--plain", action="store_true", help="epoch benchmark: the eager epochs only (no graph replay, no vertex-update leg, no second timing with the GPU tier Alg. 1 grants): what the kernel traces and counter runs under profiles/ use")
     ap.add_argument("--F", type=int, default=0, help="--what spmm: width of the launch (default: the configuration's dominant launch)")
     ap.add_argument("--direction", default="fwd", choices=["fwd", "bwd"], help="--what spmm: forward or transposed aggregation")
     ap.add_argument("--ranges", type=int, default=5, help="--what spmm_ranges: number of source ranges the launch is cut into")
@@ -764,7 +765,7 @@ def epoch_record(name, args, peaks, headline):
         out["f32_product_max_rel_err"] = f32_product_check(cfg)
     # the same epoch replayed as a HIP graph (one launch per epoch): what a launch-bound partition gains.  Only where no
     # host-tier rows exist: the recorded epoch runs on one stream, so a host tier would travel inside the epoch
-    if not dp.cache or dp.cache.cap_gpu >= part.n_halo:
+    if (not dp.cache or dp.cache.cap_gpu >= part.n_halo) and not args.plain:
         eg, loss_dev = dp.capture_epoch()
         for _ in range(args.warmup):
             eg.launch(dp.stream)
@@ -791,7 +792,7 @@ def epoch_record(name, args, peaks, headline):
         cap = B.cal_capacity(total_b / 2 ** 30, 4096.0, cfg.dims[:dp.L], part.n_halo, es)
         out["alg1_capacity"] = {"gpu_memory_GiB": total_b / 2 ** 30, "reserved_MB": 4096, "rows": cap, "halo_rows": part.n_halo,
                                 "note": "Alg. 1 (cal_capacity) with this GPU's memory"}
-        if cap >= part.n_halo and not headline:
+        if cap >= part.n_halo and not headline and not args.plain:
             # the same workload with the GPU tier Alg. 1 grants here: every halo row is a hit, no host-link traffic
             dp.close()
             del dp
@@ -806,7 +807,7 @@ def epoch_record(name, args, peaks, headline):
     dp.close()
     del dp
     torch.cuda.empty_cache()
-    if headline and part.n_halo and len(cfg.dims) > 2:
+    if headline and part.n_halo and len(cfg.dims) > 2 and not args.plain:
         # JACA refreshes the cached hidden-layer halo rows as training goes on (section "Vertex Importance and Vertex
         # Update"): the same epoch with every halo row of every hidden-layer table rewritten before each epoch
         upd = {}
