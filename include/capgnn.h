@@ -221,7 +221,9 @@ int capgnn_halo_gather(capgnn_cache *c, int layer, const int64_t *ids, int64_t n
  * In CAPGNN_MISS_PIPELINED mode the copy of the host tier that the last capgnn_epoch prefetched stays valid: every
  * host-tier row written here is written into that copy too (the call first waits for a prefetch still in flight),
  * so the next epoch consumes the new rows without fetching the table again; `stream` must be ordered before that
- * epoch's stream.  Every table starts with stamp 0 (capgnn_cache_fill resets the layer's stamps to 0). */
+ * epoch's stream.  That copy lives in the ws last passed to capgnn_epoch, which therefore must still be allocated: a
+ * caller that frees or reuses that ws while updates may follow calls capgnn_cache_set_miss_mode first (it forgets the
+ * copy).  Every table starts with stamp 0 (capgnn_cache_fill resets the layer's stamps to 0). */
 int capgnn_cache_update(capgnn_cache *c, int layer, const int64_t *ids, int64_t n, int by_gid,
                         const void *rows, int64_t ld, int64_t epoch, void *stream,
                         capgnn_gather_stats *stats);

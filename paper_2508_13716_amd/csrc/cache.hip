@@ -622,6 +622,7 @@ extern "C" int capgnn_cache_set_miss_mode(capgnn_cache *c, int mode) {
     if (c->last_side) CG_HIP(hipStreamSynchronize(c->last_side));
     c->miss_mode = mode;
     std::fill(c->staged_valid.begin(), c->staged_valid.end(), 0);
+    c->staged_base = nullptr;       // the workspace that held the prefetched copies may go away now
     return CAPGNN_OK;
 }
 
