@@ -180,6 +180,10 @@ int launch_relu_mask_dbias(int64_t n, int F, const void *src, int64_t lds, int s
                            const void *H, int64_t ldh, int dtype, int h_dtype, int relu, float *dbias, void *ws,
                            size_t ws_bytes, hipStream_t stream, const float *row_scale = nullptr);
 int launch_sgd(float *W, const float *dW, int64_t n, float lr, hipStream_t stream);
+// capgnn_softmax_ce that also writes the logits as a dense [n x C] matrix to `copy` (NULL: does not)
+int softmax_ce_with_copy(int64_t n, int C, const float *Z, int64_t ldz, const int32_t *labels, const uint8_t *mask,
+                         double loss_norm, float *loss_dev, void *dZ, int64_t lddz, int dz_dtype, void *ws, size_t ws_bytes,
+                         hipStream_t st, float *copy);
 
 uint64_t hash_gid(uint64_t x);
 

@@ -552,9 +552,9 @@ static int epoch_impl(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer
         if (targets)
             CG_TRY(capgnn_sigmoid_bce(g->n_loc, C, Z, ldz, targets, ldt, mask, loss_norm, loss_dev, dz, lddz, dzt,
                                       w + p.loss_ws_off, capgnn_loss_workspace_bytes(g->n_loc), st));
-        else
-            CG_TRY(capgnn_softmax_ce(g->n_loc, C, Z, ldz, labels, mask, loss_norm, loss_dev, dz, lddz, dzt,
-                                     w + p.loss_ws_off, capgnn_loss_workspace_bytes(g->n_loc), st));
+        else    // the loss kernel reads every logit anyway: it also writes the caller's dense copy
+            CG_TRY(softmax_ce_with_copy(g->n_loc, C, Z, ldz, labels, mask, loss_norm, loss_dev, dz, lddz, dzt,
+                                        w + p.loss_ws_off, capgnn_loss_workspace_bytes(g->n_loc), st, logits));
     }
     // backward
     for (int l = L - 1; l >= 0; --l) {
@@ -580,7 +580,7 @@ static int epoch_impl(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer
             if (layers[l].bias && dbias[l]) CG_TRY(launch_sgd(layers[l].bias, dbias[l], layers[l].f_out, lr, st));
         }
     }
-    if (logits)
+    if (logits && targets)
         CG_HIP(hipMemcpy2DAsync(logits, static_cast<size_t>(C) * sizeof(float), Z, static_cast<size_t>(ldz) * sizeof(float),
                                 static_cast<size_t>(C) * sizeof(float), static_cast<size_t>(g->n_loc),
                                 hipMemcpyDeviceToDevice, st));

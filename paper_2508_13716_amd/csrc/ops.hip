@@ -406,38 +406,62 @@ static int loss_lanes_per_row_host(int C) {
     return lpr;
 }
 
+// One lane group (lpr lanes) per row.  A lane's logits (classes l, l + lpr, ...) are read once and kept: up to four per
+// lane in registers, which covers every C <= 4 * lpr (all C <= 256); beyond that the row is read again from the L1.
+// One exponential per class: the terms of the sum are reused for the gradient, p_k = e_k / s.  copy: when not null, the
+// logits are also written there as a dense [n x C] matrix (what the caller of an epoch asked for as `logits`).
 __global__ __launch_bounds__(256) void softmax_ce_kernel(int64_t n, int C, int lpr, const float *Z, int64_t ldz,
                                                          const int32_t *labels, const uint8_t *mask, float norm_val,
                                                          const float *norm_dev, float *row_loss, char *dZ,
-                                                         int64_t lddz, int dz_bf16) {
+                                                         int64_t lddz, int dz_bf16, float *copy) {
     const int lane = threadIdx.x & 63;
     const int l = lane % lpr;
     const int64_t row = (static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6)) * (64 / lpr) + lane / lpr;
     if (row >= n) return;          // whole lane groups leave; the shuffles below stay inside a group
     const float norm = norm_dev ? norm_dev[0] : norm_val;
     const bool on = !mask || mask[row];
+    const float *z = Z + row * ldz;
+    constexpr int KEEP = 4;
+    float zr[KEEP];
+#pragma unroll
+    for (int j = 0; j < KEEP; ++j) {
+        const int k = l + j * lpr;
+        zr[j] = k < C ? z[k] : -INFINITY;
+        if (copy && k < C) copy[row * C + k] = zr[j];
+    }
+    const bool kept = C <= KEEP * lpr;
+    if (copy && !kept) for (int k = l + KEEP * lpr; k < C; k += lpr) copy[row * C + k] = z[k];
     if (!on) {
         if (l == 0) row_loss[row] = 0.f;
         if (dZ) for (int k = l; k < C; k += lpr) st_elem(dZ, row * lddz + k, 0.f, dz_bf16);
         return;
     }
-    const float *z = Z + row * ldz;
-    float m = -INFINITY;
-    for (int k = l; k < C; k += lpr) m = fmaxf(m, z[k]);
+    float m = fmaxf(fmaxf(zr[0], zr[1]), fmaxf(zr[2], zr[3]));
+    if (!kept) for (int k = l + KEEP * lpr; k < C; k += lpr) m = fmaxf(m, z[k]);
     for (int off = lpr >> 1; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    float er[KEEP];
     float s = 0.f;
-    for (int k = l; k < C; k += lpr) s += expf(z[k] - m);
+#pragma unroll
+    for (int j = 0; j < KEEP; ++j) {
+        er[j] = (l + j * lpr < C) ? expf(zr[j] - m) : 0.f;
+        s += er[j];
+    }
+    if (!kept) for (int k = l + KEEP * lpr; k < C; k += lpr) s += expf(z[k] - m);
     for (int off = lpr >> 1; off > 0; off >>= 1) s += __shfl_xor(s, off);
     const float lse = m + logf(s);
     int y = labels[row];
     y = y < 0 ? 0 : (y >= C ? C - 1 : y);
     if (l == 0) row_loss[row] = lse - z[y];
     if (dZ) {
-        const float inv = 1.f / norm;
-        for (int k = l; k < C; k += lpr) {
-            float p = expf(z[k] - lse);
-            st_elem(dZ, row * lddz + k, (p - (k == y ? 1.f : 0.f)) * inv, dz_bf16);
+        const float inv = 1.f / norm, inv_s = 1.f / s;
+#pragma unroll
+        for (int j = 0; j < KEEP; ++j) {
+            const int k = l + j * lpr;
+            if (k < C) st_elem(dZ, row * lddz + k, (er[j] * inv_s - (k == y ? 1.f : 0.f)) * inv, dz_bf16);
         }
+        if (!kept)
+            for (int k = l + KEEP * lpr; k < C; k += lpr)
+                st_elem(dZ, row * lddz + k, (expf(z[k] - m) * inv_s - (k == y ? 1.f : 0.f)) * inv, dz_bf16);
     }
 }
 
@@ -597,7 +621,7 @@ extern "C" int capgnn_sigmoid_bce(int64_t n, int C, const float *Z, int64_t ldz,
 // everything capgnn_softmax_ce does after its argument checks; `ws` holds capgnn_loss_workspace_bytes(n) bytes
 static int softmax_ce_launch(int64_t n, int C, const float *Z, int64_t ldz, const int32_t *labels, const uint8_t *mask,
                              double loss_norm, float *loss_dev, void *dZ, int64_t lddz, int dz_dtype, void *ws,
-                             hipStream_t st) {
+                             hipStream_t st, float *copy = nullptr) {
     float *norm_dev = nullptr;
     float norm_val = 1.f;
     float *scratch = static_cast<float *>(ws);
@@ -613,7 +637,7 @@ static int softmax_ce_launch(int64_t n, int C, const float *Z, int64_t ldz, cons
     const int lpr = loss_lanes_per_row_host(C);
     const int64_t rows_per_block = 4 * (64 / lpr);
     hipLaunchKernelGGL(softmax_ce_kernel, dim3(static_cast<unsigned>((n + rows_per_block - 1) / rows_per_block)), dim3(256), 0, st, n, C, lpr, Z, ldz,
-                       labels, mask, norm_val, norm_dev, row_loss, static_cast<char *>(dZ), lddz, dz_dtype == CAPGNN_BF16 ? 1 : 0);
+                       labels, mask, norm_val, norm_dev, row_loss, static_cast<char *>(dZ), lddz, dz_dtype == CAPGNN_BF16 ? 1 : 0, copy);
     launch_loss_sum(n, row_loss, part, parts, norm_val, norm_dev, loss_dev, st);
     CG_HIP(hipGetLastError());
     return CAPGNN_OK;
@@ -637,6 +661,16 @@ extern "C" int capgnn_softmax_ce(int64_t n, int C, const float *Z, int64_t ldz, 
     if (!ws || ws_bytes < capgnn_loss_workspace_bytes(n)) CG_FAIL(CAPGNN_ENOMEM, "softmax_ce: workspace too small");
     return softmax_ce_launch(n, C, Z, ldz, labels, mask, loss_norm, loss_dev, dZ, lddz, dz_dtype, ws,
                              static_cast<hipStream_t>(stream));
+}
+
+// capgnn_softmax_ce for the epoch, which also wants the logits as a dense [n x C] copy (or not: copy may be NULL)
+int capgnn::softmax_ce_with_copy(int64_t n, int C, const float *Z, int64_t ldz, const int32_t *labels, const uint8_t *mask,
+                         double loss_norm, float *loss_dev, void *dZ, int64_t lddz, int dz_dtype, void *ws, size_t ws_bytes,
+                         hipStream_t st, float *copy) {
+    CG_TRY(softmax_ce_check(n, C, Z, ldz, labels, loss_dev, dZ, lddz, dz_dtype));
+    if (n == 0) return CAPGNN_OK;
+    if (!ws || ws_bytes < capgnn_loss_workspace_bytes(n)) CG_FAIL(CAPGNN_ENOMEM, "softmax_ce: workspace too small");
+    return softmax_ce_launch(n, C, Z, ldz, labels, mask, loss_norm, loss_dev, dZ, lddz, dz_dtype, ws, st, copy);
 }
 
 // ------------------------------------------------------------------ the same loss without any allocation by anyone

@@ -526,7 +526,7 @@ def test_gemm_relu_mask_epilogue(env):
 
 
 # ----------------------------------------------------------------------------- loss
-@pytest.mark.parametrize("C", [1, 8, 41, 47, 100])
+@pytest.mark.parametrize("C", [1, 8, 41, 47, 100, 300])
 def test_softmax_ce_vs_oracle(env, C):
     torch, B, H, O, orc = env["torch"], env["B"], env["H"], env["O"], env["orc"]
     rng = np.random.default_rng(C)
