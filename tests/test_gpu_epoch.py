@@ -330,3 +330,42 @@ def test_epoch_graph_replays_match_eager_epochs(env, case):
     loss, _ = dp.run_epoch(lr=0.0)
     assert np.isfinite(loss)
     dp.close()
+
+
+@pytest.mark.parametrize("kind", ["gcn", "sage"])
+def test_training_run_tracks_the_oracle(env, kind):
+    """Twelve epochs with the in-place step W <- W - lr * dW (the update of the convergence theorem's proof): the loss of
+    every epoch and the weights at the end must follow the oracle's own fp64 training run, which carries its weights in
+    fp64 from step to step and takes nothing from the GPU.  The loss must also go down in the oracle's run: a sign error
+    in the step would show there first."""
+    torch, B, H, O, orc = env["torch"], env["B"], env["H"], env["O"], env["orc"]
+    cfg = synth.Config(f"train-{kind}", kind, 2500, 1800, 40000, [48, 32, 7], "f32", 0.5, max_deg=600, seed=91)
+    prob = H.make_problem(cfg, mask_frac=0.6)
+    dp = H.DeviceProblem(prob, miss_mode=B.MISS_PIPELINED)
+    lr, steps = 0.2, 12
+    og = O.oracle_graph(prob.part, kind)
+    layers = O.oracle_layers(prob)
+    tables = [O.widen(t) for t in prob.tables]
+    X0 = O.widen(prob.X0)
+    ref_losses, gpu_losses = [], []
+    for it in range(steps):
+        ref = orc.epoch(og, layers, X0, tables, prob.labels, prob.mask, 0.0, lr)
+        ref_losses.append(ref["loss"])
+        for l, ly in enumerate(layers):
+            ly.W = ref["new_W"][l]
+            ly.bias = ref["new_bias"][l]
+            if ly.W_self is not None:
+                ly.W_self = ref["new_W_self"][l]
+        loss, _ = dp.run_epoch(lr=lr)
+        gpu_losses.append(loss)
+    say(f"training {kind}: oracle loss {ref_losses[0]:.5f} -> {ref_losses[-1]:.5f}, GPU {gpu_losses[0]:.5f} -> {gpu_losses[-1]:.5f}")
+    assert all(b < a for a, b in zip(ref_losses, ref_losses[1:])), ref_losses
+    for a, b in zip(gpu_losses, ref_losses):
+        assert abs(a - b) <= 1e-4 * max(1.0, abs(b)), (gpu_losses, ref_losses)
+    torch.cuda.synchronize()
+    for l, ly in enumerate(layers):
+        assert O.normwise(H.dev_to_np(dp.W[l]), ly.W) <= 1e-3, l
+        assert O.normwise(H.dev_to_np(dp.bias[l]), ly.bias) <= 1e-3, l
+        if ly.W_self is not None:
+            assert O.normwise(H.dev_to_np(dp.W_self[l]), ly.W_self) <= 1e-3, l
+    dp.close()
