@@ -527,21 +527,28 @@ int capgnn_epoch_activation(const capgnn_graph *g, const capgnn_cache *c, const 
                             int l, void *ws, void **ptr, int64_t *ld);
 
 /* The same epoch recorded once as a HIP graph and replayed with one launch per epoch: for partitions whose epoch is a
- * few dozen short kernels and therefore bound by their launches (the smallest evaluation graphs).  Arguments as
- * capgnn_epoch, except: everything runs on `stream` (required, not the default stream; no side stream: host-tier rows
- * travel inside the epoch that consumes them, whatever the miss mode), no host loss and no event times; loss_dev: device
- * float that every replay writes the loss to, or NULL.  The graph holds the ADDRESSES of every buffer given here
- * (X0, labels, mask, logits, dW / dW_self / dbias and the arrays of pointers' targets, the layers' weights, ws, the
- * cache's tiers): they must stay allocated and in place until the graph is destroyed; their CONTENTS may change between
- * replays (new features, capgnn_cache_update / capgnn_cache_fill, the SGD step of the epoch itself when lr != 0).
- * create: records without running (the buffers are not touched); launch: asynchronous on `stream` (any stream of the
- * same device; replays on different streams must not overlap: they share ws); destroy: after the last replay has
- * finished.  The graph contains kernels and copies only.  Errors: as capgnn_epoch, EHIP if capture or instantiation fail. */
+ * few dozen short kernels and therefore bound by their launches (the smallest evaluation graphs), and to take the
+ * launch gaps out of any epoch.  Arguments as capgnn_epoch, except: `stream` is required and not the default stream;
+ * no host loss and no event times; loss_dev: device float that every replay writes the loss to, or NULL.
+ * side_stream NULL: everything is recorded on `stream`, host-tier rows travel inside the epoch that consumes them,
+ * whatever the miss mode.  side_stream given: the two-stream epoch is recorded as it runs; in CAPGNN_MISS_PIPELINED
+ * mode every replay consumes the host-tier rows that the run before it prefetched and prefetches for the next one, so
+ * one capgnn_epoch with the same ws and side stream must have run before the recording (EINVAL otherwise), and a
+ * replay ends only when its prefetches have.
+ * The graph holds the ADDRESSES of every buffer given here (X0, labels, mask, logits, dW / dW_self / dbias and the
+ * arrays of pointers' targets, the layers' weights, ws, the cache's tiers): they must stay allocated and in place
+ * until the graph is destroyed; their CONTENTS may change between replays (new features, capgnn_cache_update /
+ * capgnn_cache_fill - after which one eager capgnn_epoch primes the prefetch again -, the SGD step of the epoch itself
+ * when lr != 0).  create: records without running (the buffers are not touched); launch: asynchronous on `stream` (any
+ * stream of the same device; replays must not overlap one another or an eager epoch on the same ws); destroy: after the
+ * last replay has finished.  The graph contains kernels and copies only.  Errors: as capgnn_epoch, EHIP if capture or
+ * instantiation fail. */
 typedef struct capgnn_epoch_graph capgnn_epoch_graph;
 int capgnn_epoch_graph_create(capgnn_epoch_graph **out, const capgnn_graph *g, capgnn_cache *c,
                               const capgnn_layer *layers, int L, void *X0, int64_t ld0, const int32_t *labels,
                               const uint8_t *mask, double loss_norm, float *logits, float **dW, float **dW_self,
-                              float **dbias, float lr, float *loss_dev, void *ws, size_t ws_bytes, void *stream);
+                              float **dbias, float lr, float *loss_dev, void *ws, size_t ws_bytes, void *stream,
+                              void *side_stream);
 int capgnn_epoch_graph_launch(capgnn_epoch_graph *eg, void *stream);
 int capgnn_epoch_graph_destroy(capgnn_epoch_graph *eg);
 

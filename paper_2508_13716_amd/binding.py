@@ -99,7 +99,7 @@ SIGNATURES = {
     "capgnn_locality_order": (_i32, [_i32, _i64, _i64, _vp, _vp, _vp]),
     "capgnn_relabel_csr": (_i32, [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "capgnn_epoch_graph_create": (_i32, [C.POINTER(_vp), _vp, _vp, _vp, _i32, _vp, _i64, _vp, _vp, C.c_double, _vp, _vp, _vp, _vp,
-                                         C.c_float, _vp, _vp, _sz, _vp]),
+                                         C.c_float, _vp, _vp, _sz, _vp, _vp]),
     "capgnn_epoch_graph_launch": (_i32, [_vp, _vp]),
     "capgnn_epoch_graph_destroy": (_i32, [_vp]),
     "capgnn_cache_update": (_i32, [_vp, _i32, _vp, _i64, _i32, _vp, _i64, _i64, _vp, _vp]),
@@ -535,7 +535,7 @@ class EpochGraph:
 
     def __init__(self, g: Graph, c: Optional[Cache], layers: List[Layer], X0, ld0: int, labels, mask, loss_norm: float,
                  logits, dW: Sequence, dW_self: Optional[Sequence], dbias: Sequence, lr: float, loss_dev, ws, ws_bytes: int,
-                 stream):
+                 stream, side_stream=None):
         L = len(layers)
         arr = (Layer * L)(*layers)
         pw = (C.c_void_p * L)(*[_p(t) for t in dW])
@@ -545,7 +545,7 @@ class EpochGraph:
         h = C.c_void_p()
         _check(lib().capgnn_epoch_graph_create(C.byref(h), g.h, c.h if c is not None else None, arr, L, _p(X0), ld0, _p(labels),
                                                _p(mask), loss_norm, _p(logits), pw, ps, pb, lr, _p(loss_dev), _p(ws), ws_bytes,
-                                               _stream(stream)))
+                                               _stream(stream), _stream(side_stream)))
         self.h = h
 
     def launch(self, stream):

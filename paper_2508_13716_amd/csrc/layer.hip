@@ -5,6 +5,7 @@
 // first layer).  XFORM_FIRST runs the GEMM over all n_cols rows and the SpMM at width f_out.  Both
 // give the same result in exact arithmetic; the choice is a cost decision (capgnn_layer_order).
 #include "common.h"
+#include <memory>
 
 #include <algorithm>
 #include <cstring>
@@ -437,10 +438,20 @@ extern "C" int capgnn_epoch_activation(const capgnn_graph *g, const capgnn_cache
 }
 
 // labels (class indices, softmax cross-entropy) or targets (0/1 matrix, binary cross-entropy): exactly one is given
+// The events that order the two streams of an epoch.  An eager epoch uses the cache's own; an epoch that is being
+// recorded into a HIP graph brings a set of its own (an event last recorded during a capture must not be waited for
+// outside it) and sets `capture`.
+struct EpochEvents {
+    hipEvent_t fork = nullptr, join = nullptr;
+    std::vector<hipEvent_t> layer, consumed;
+    bool capture = false;
+};
+
 static int epoch_impl(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer *layers, int L, void *X0,
                       int64_t ld0, const int32_t *labels, const uint8_t *targets, int64_t ldt, const uint8_t *mask,
                       double loss_norm, float *logits, float **dW, float **dW_self, float **dbias, float lr, float *loss_out,
-                      capgnn_epoch_times *times, void *ws, size_t ws_bytes, void *stream, void *side_stream) {
+                      capgnn_epoch_times *times, void *ws, size_t ws_bytes, void *stream, void *side_stream,
+                      const EpochEvents *own_events = nullptr) {
     CG_TRY(check_epoch_args(g, c, layers, L));
     if (!X0 || (!labels && !targets) || !dW || !dbias) CG_FAIL(CAPGNN_EINVAL, "epoch: NULL argument");
     if (targets && ldt < layers[L - 1].f_out) CG_FAIL(CAPGNN_EINVAL, "epoch: ldt smaller than the number of classes");
@@ -474,10 +485,25 @@ static int epoch_impl(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer
     // refilled for the next epoch as soon as this epoch has scattered it
     const bool pipelined = has_miss && c->miss_mode == CAPGNN_MISS_PIPELINED && side != st;
     auto halo_rows = [&](int l) -> char * { return Xl(l) + static_cast<size_t>(g->n_loc) * p.ldx[l] * es; };
+    EpochEvents cache_events;
+    if (!own_events && c) {
+        cache_events.fork = c->ev_fork; cache_events.join = c->ev_join;
+        cache_events.layer = c->ev_layer; cache_events.consumed = c->ev_consumed;
+    }
+    const EpochEvents &ev = own_events ? *own_events : cache_events;
+    const bool capture = ev.capture;
     if (has_miss && side != st) {
-        CG_HIP(hipEventRecord(c->ev_fork, st));
-        CG_HIP(hipStreamWaitEvent(side, c->ev_fork, 0));
-        c->last_side = side;
+        if (pipelined && capture) {
+            // a recorded epoch consumes what the run before it prefetched: that must exist when the first replay starts
+            bool primed = c->staged_base == staging;
+            for (int l = 0; l < L; ++l) primed = primed && c->staged_valid[l];
+            if (!primed)
+                CG_FAIL(CAPGNN_EINVAL, "epoch: a pipelined epoch can only be recorded after one capgnn_epoch with the same ws and "
+                                       "side stream has prefetched the host tier");
+        }
+        CG_HIP(hipEventRecord(ev.fork, st));
+        CG_HIP(hipStreamWaitEvent(side, ev.fork, 0));
+        if (!capture) c->last_side = side;
         if (pipelined) {
             if (c->staged_base != staging) {
                 std::fill(c->staged_valid.begin(), c->staged_valid.end(), 0);
@@ -487,14 +513,14 @@ static int epoch_impl(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer
                 if (c->staged_valid[l]) continue;
                 Scope s(CAPGNN_K_GATHER_MISS, l, 0, side);     // cold start: nothing was prefetched for this layer
                 CG_TRY(stage_misses(c, l, staging, side));
-                CG_HIP(hipEventRecord(c->ev_layer[l], side));
+                CG_HIP(hipEventRecord(ev.layer[l], side));
                 c->staged_valid[l] = 1;
             }
         } else {
             for (int l = 0; l < L; ++l) {
                 Scope s(CAPGNN_K_GATHER_MISS, l, 0, side);
                 CG_TRY(gather_all_misses(c, l, halo_rows(l), p.ldx[l], staging, side));
-                if (!g_rec.on) CG_HIP(hipEventRecord(c->ev_layer[l], side));
+                if (!g_rec.on) CG_HIP(hipEventRecord(ev.layer[l], side));
             }
         }
     }
@@ -504,17 +530,18 @@ static int epoch_impl(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer
         char *halo = halo_rows(l);
         if (c) {
             if (pipelined) {
-                // the staged rows landed while the previous epoch ran: both device-resident sources in one launch
-                CG_HIP(hipStreamWaitEvent(st, c->ev_layer[l], 0));
+                // the staged rows landed while the previous epoch ran: both device-resident sources in one launch.  (In a
+                // recorded epoch the replay before this one ended only after its prefetches had: nothing to wait for.)
+                if (!capture) CG_HIP(hipStreamWaitEvent(st, ev.layer[l], 0));
                 {
                     Scope s(CAPGNN_K_GATHER_HIT, l, 0, st);
                     CG_TRY(gather_hits_and_staged(c, l, halo, p.ldx[l], staging, st));
                 }
-                CG_HIP(hipEventRecord(c->ev_consumed[l], st));
-                CG_HIP(hipStreamWaitEvent(side, c->ev_consumed[l], 0));
+                CG_HIP(hipEventRecord(ev.consumed[l], st));
+                CG_HIP(hipStreamWaitEvent(side, ev.consumed[l], 0));
                 Scope s(CAPGNN_K_GATHER_MISS, l, 0, side);     // the next epoch's rows of this layer
                 CG_TRY(stage_misses(c, l, staging, side));
-                CG_HIP(hipEventRecord(c->ev_layer[l], side));
+                CG_HIP(hipEventRecord(ev.layer[l], side));
             } else {
                 Scope s(CAPGNN_K_GATHER_HIT, l, 0, st);
                 CG_TRY(gather_all_hits(c, l, halo, p.ldx[l], st));
@@ -526,7 +553,7 @@ static int epoch_impl(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer
                         for (auto &r : g_rec.recs)
                             if (r.kind == CAPGNN_K_GATHER_MISS && r.layer == l) CG_HIP(hipStreamWaitEvent(st, r.e1, 0));
                     } else {
-                        CG_HIP(hipStreamWaitEvent(st, c->ev_layer[l], 0));
+                        CG_HIP(hipStreamWaitEvent(st, ev.layer[l], 0));
                     }
                 } else {
                     Scope s(CAPGNN_K_GATHER_MISS, l, 0, st);
@@ -584,6 +611,11 @@ static int epoch_impl(const capgnn_graph *g, capgnn_cache *c, const capgnn_layer
         CG_HIP(hipMemcpy2DAsync(logits, static_cast<size_t>(C) * sizeof(float), Z, static_cast<size_t>(ldz) * sizeof(float),
                                 static_cast<size_t>(C) * sizeof(float), static_cast<size_t>(g->n_loc),
                                 hipMemcpyDeviceToDevice, st));
+    if (capture && has_miss && side != st) {
+        // a recorded epoch ends when its side stream has: the prefetches for the next replay are part of this one
+        CG_HIP(hipEventRecord(ev.join, side));
+        CG_HIP(hipStreamWaitEvent(st, ev.join, 0));
+    }
     if (times) CG_HIP(hipEventRecord(ev_t1, st));
     if (loss_out) {
         CG_HIP(hipMemcpyAsync(loss_out, loss_dev, sizeof(float), hipMemcpyDeviceToHost, st));
@@ -639,6 +671,19 @@ extern "C" int capgnn_epoch_multilabel(const capgnn_graph *g, capgnn_cache *c, c
 struct capgnn_epoch_graph {
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
+    EpochEvents ev;                 // the events the recorded epoch orders its two streams with
+    capgnn_cache *cache = nullptr;  // whose eager epochs may have left work on their side stream
+    hipEvent_t side_done = nullptr;
+
+    ~capgnn_epoch_graph() {
+        if (side_done) (void)hipEventDestroy(side_done);
+        if (exec) (void)hipGraphExecDestroy(exec);
+        if (graph) (void)hipGraphDestroy(graph);
+        if (ev.fork) (void)hipEventDestroy(ev.fork);
+        if (ev.join) (void)hipEventDestroy(ev.join);
+        for (hipEvent_t e : ev.layer) if (e) (void)hipEventDestroy(e);
+        for (hipEvent_t e : ev.consumed) if (e) (void)hipEventDestroy(e);
+    }
 };
 
 __global__ void copy_loss_kernel(const float *src, float *dst) { *dst = *src; }
@@ -646,55 +691,58 @@ __global__ void copy_loss_kernel(const float *src, float *dst) { *dst = *src; }
 extern "C" int capgnn_epoch_graph_create(capgnn_epoch_graph **out, const capgnn_graph *g, capgnn_cache *c,
                                          const capgnn_layer *layers, int L, void *X0, int64_t ld0, const int32_t *labels,
                                          const uint8_t *mask, double loss_norm, float *logits, float **dW, float **dW_self,
-                                         float **dbias, float lr, float *loss_dev, void *ws, size_t ws_bytes, void *stream) {
+                                         float **dbias, float lr, float *loss_dev, void *ws, size_t ws_bytes, void *stream,
+                                         void *side_stream) {
     if (!out) CG_FAIL(CAPGNN_EINVAL, "epoch_graph_create: out is NULL");
     *out = nullptr;
     if (!stream) CG_FAIL(CAPGNN_EINVAL, "epoch_graph_create: a stream of the caller's is needed (the default stream cannot be captured)");
     if (!labels) CG_FAIL(CAPGNN_EINVAL, "epoch_graph_create: labels is NULL");
     CG_TRY(check_epoch_args(g, c, layers, L));
     hipStream_t st = static_cast<hipStream_t>(stream);
+    std::unique_ptr<capgnn_epoch_graph> eg(new capgnn_epoch_graph);
+    eg->ev.capture = true;
+    eg->ev.layer.assign(L, nullptr);
+    eg->ev.consumed.assign(L, nullptr);
+    bool ok = hipEventCreateWithFlags(&eg->ev.fork, hipEventDisableTiming) == hipSuccess &&
+              hipEventCreateWithFlags(&eg->ev.join, hipEventDisableTiming) == hipSuccess;
+    for (int l = 0; l < L && ok; ++l)
+        ok = hipEventCreateWithFlags(&eg->ev.layer[l], hipEventDisableTiming) == hipSuccess &&
+             hipEventCreateWithFlags(&eg->ev.consumed[l], hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&eg->side_done, hipEventDisableTiming) == hipSuccess;
+    if (!ok) CG_FAIL(CAPGNN_EHIP, "epoch_graph_create: hipEventCreate failed");
+    eg->cache = c;
     CG_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
-    // everything on the one stream: host-tier rows, if any, travel inside the epoch that consumes them
+    // the side stream joins the recording when it waits for the epoch's first event and is joined back at the end
     int rc = epoch_impl(g, c, layers, L, X0, ld0, labels, nullptr, 0, mask, loss_norm, logits, dW, dW_self, dbias, lr, nullptr,
-                        nullptr, ws, ws_bytes, stream, nullptr);
+                        nullptr, ws, ws_bytes, stream, side_stream, &eg->ev);
     if (rc == CAPGNN_OK && loss_dev) {
         EpochPlan p;
         plan_epoch(g, c, layers, L, ld0, &p);
         hipLaunchKernelGGL(copy_loss_kernel, dim3(1), dim3(1), 0, st,
                            reinterpret_cast<const float *>(static_cast<char *>(ws) + p.loss_val_off), loss_dev);
     }
-    hipGraph_t graph = nullptr;
-    const hipError_t e_end = hipStreamEndCapture(st, &graph);       // always: the stream must leave capture mode
-    if (rc != CAPGNN_OK) {
-        if (graph) (void)hipGraphDestroy(graph);
-        return rc;
-    }
-    if (e_end != hipSuccess || !graph) {
-        if (graph) (void)hipGraphDestroy(graph);
-        CG_FAIL(CAPGNN_EHIP, "epoch_graph_create: hipStreamEndCapture: %s", hipGetErrorString(e_end));
-    }
-    hipGraphExec_t exec = nullptr;
-    const hipError_t e_inst = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
-    if (e_inst != hipSuccess) {
-        (void)hipGraphDestroy(graph);
-        CG_FAIL(CAPGNN_EHIP, "epoch_graph_create: hipGraphInstantiate: %s", hipGetErrorString(e_inst));
-    }
-    capgnn_epoch_graph *eg = new capgnn_epoch_graph;
-    eg->graph = graph; eg->exec = exec;
-    *out = eg;
+    const hipError_t e_end = hipStreamEndCapture(st, &eg->graph);       // always: the stream must leave capture mode
+    if (rc != CAPGNN_OK) return rc;
+    if (e_end != hipSuccess || !eg->graph) CG_FAIL(CAPGNN_EHIP, "epoch_graph_create: hipStreamEndCapture: %s", hipGetErrorString(e_end));
+    const hipError_t e_inst = hipGraphInstantiate(&eg->exec, eg->graph, nullptr, nullptr, 0);
+    if (e_inst != hipSuccess) CG_FAIL(CAPGNN_EHIP, "epoch_graph_create: hipGraphInstantiate: %s", hipGetErrorString(e_inst));
+    *out = eg.release();
     return CAPGNN_OK;
 }
 
 extern "C" int capgnn_epoch_graph_launch(capgnn_epoch_graph *eg, void *stream) {
     if (!eg || !eg->exec) CG_FAIL(CAPGNN_EINVAL, "epoch_graph_launch: no graph");
-    CG_HIP(hipGraphLaunch(eg->exec, static_cast<hipStream_t>(stream)));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // an eager epoch before this replay may still be prefetching on its side stream into the staging area the replay reads
+    if (eg->cache && eg->cache->last_side && eg->cache->last_side != st) {
+        CG_HIP(hipEventRecord(eg->side_done, eg->cache->last_side));
+        CG_HIP(hipStreamWaitEvent(st, eg->side_done, 0));
+    }
+    CG_HIP(hipGraphLaunch(eg->exec, st));
     return CAPGNN_OK;
 }
 
 extern "C" int capgnn_epoch_graph_destroy(capgnn_epoch_graph *eg) {
-    if (!eg) return CAPGNN_OK;
-    if (eg->exec) (void)hipGraphExecDestroy(eg->exec);
-    if (eg->graph) (void)hipGraphDestroy(eg->graph);
     delete eg;
     return CAPGNN_OK;
 }

@@ -173,8 +173,9 @@ class DeviceProblem:
                        self.ws, self.ws_bytes, self.stream, self.side, want_loss=want_loss, want_times=want_times,
                        targets=self.targets, ldt=0 if self.targets is None else self.targets.shape[1])
 
-    def capture_epoch(self, lr: float = 0.0, mask=True):
-        """The epoch as a HIP graph on this problem's buffers; returns (graph, device float the replays write the loss to)."""
+    def capture_epoch(self, lr: float = 0.0, mask=True, two_streams: bool = False):
+        """The epoch as a HIP graph on this problem's buffers; returns (graph, device float the replays write the loss to).
+        two_streams: record the epoch with its side stream (in pipelined mode one eager epoch must have run before)."""
         torch = _torch()
         if self.targets is not None:
             raise ValueError("the recorded epoch takes class labels")
@@ -182,7 +183,7 @@ class DeviceProblem:
         torch.cuda.synchronize()
         eg = B.EpochGraph(self.graph, self.cache, self.layers, self.X0, self.ld0, self.labels, self.mask if mask else None, 0.0,
                           self.logits, self.dW, self.dW_self if any(t is not None for t in self.dW_self) else None, self.dbias,
-                          lr, loss_dev, self.ws, self.ws_bytes, self.stream)
+                          lr, loss_dev, self.ws, self.ws_bytes, self.stream, self.side if two_streams else None)
         return eg, loss_dev
 
     def hidden(self, l: int) -> np.ndarray:

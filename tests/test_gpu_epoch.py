@@ -369,3 +369,70 @@ def test_training_run_tracks_the_oracle(env, kind):
         if ly.W_self is not None:
             assert O.normwise(H.dev_to_np(dp.W_self[l]), ly.W_self) <= 1e-3, l
     dp.close()
+
+
+@pytest.mark.parametrize("miss_mode", [1, 2])
+def test_epoch_graph_with_side_stream_matches_eager_epochs(env, miss_mode):
+    """The two-stream epoch recorded as a HIP graph (host-tier rows on the side stream; in pipelined mode every replay
+    consumes what the run before it prefetched and prefetches for the next).  Replays must equal eager epochs bit for bit:
+    on the static tables, after a cache update between replays (which patches the prefetched copy), and after a refill
+    followed by one eager epoch that primes the prefetch again; recording a pipelined epoch that nothing has primed is an
+    argument error, and eager epochs after the replays still see the right rows."""
+    torch, B, H, O = env["torch"], env["B"], env["H"], env["O"]
+    cfg = synth.CONFIGS["C2"].scaled(0.02)
+    prob = H.make_problem(cfg, mask_frac=0.5)
+    part = prob.part
+    dp = H.DeviceProblem(prob, miss_mode=miss_mode)
+    ref = O.oracle_epoch(prob)
+
+    def snapshot():
+        r = dp.results()
+        return [r["logits"].copy()] + [a.copy() for a in r["dW"]] + [a.copy() for a in r["db"]]
+
+    if miss_mode == B.MISS_PIPELINED:
+        with pytest.raises(B.CapgnnError):
+            dp.capture_epoch(two_streams=True)                   # nothing has prefetched the host tier yet
+    loss0, _ = dp.run_epoch()
+    compare_epoch(env, prob, dp, ref, loss0, TOL["f32"], f"two-stream graph (miss_mode {miss_mode}): eager epoch")
+    base = snapshot()
+    eg, loss_dev = dp.capture_epoch(two_streams=True)
+    scratch = torch.empty(1 << 20, device="cuda")
+    for it in range(3):
+        eg.launch(dp.stream)
+        torch.cuda.synchronize()
+        scratch.normal_()
+        _ = float(scratch.sum().cpu())
+        assert float(loss_dev.cpu()[0]) == loss0
+        for a, b in zip(snapshot(), base):
+            assert np.array_equal(a, b), f"replay {it} differs from the eager epoch"
+    # rows rewritten between replays, in both tiers
+    rng = np.random.default_rng(17)
+    l_upd = dp.L - 1
+    ids = rng.permutation(part.n_halo)[: part.n_halo // 2].astype(np.int64)
+    new_rows = rng.standard_normal((len(ids), cfg.dims[l_upd])).astype(np.float32)
+    B.cache_update(dp.cache, l_upd, torch.from_numpy(ids).cuda(), len(ids), H.np_to_dev(new_rows), cfg.dims[l_upd], 3,
+                   stream=dp.stream)
+    prob.tables[l_upd][ids] = new_rows
+    ref2 = O.oracle_epoch(prob)
+    for it in range(2):
+        eg.launch(dp.stream)
+        torch.cuda.synchronize()
+        compare_epoch(env, prob, dp, ref2, float(loss_dev.cpu()[0]), TOL["f32"], f"two-stream graph after update, replay {it}")
+    upd = snapshot()
+    loss_e, _ = dp.run_epoch()                                   # an eager epoch after the replays: same rows, same result
+    for a, b in zip(snapshot(), upd):
+        assert np.array_equal(a, b)
+    # a refill drops the prefetched copy: one eager epoch primes it again, then the replays see the new table
+    prob.tables[0] = synth.make_features(part.n_halo, cfg.dims[0], seed=5, stream=3, dtype=cfg.dtype)
+    dp.cache.fill(0, prob.tables[0])
+    ref3 = O.oracle_epoch(prob)
+    loss3, _ = dp.run_epoch()
+    compare_epoch(env, prob, dp, ref3, loss3, TOL["f32"], "two-stream graph: eager epoch after refill")
+    want = snapshot()
+    for it in range(2):
+        eg.launch(dp.stream)
+        torch.cuda.synchronize()
+        for a, b in zip(snapshot(), want):
+            assert np.array_equal(a, b), f"replay {it} after refill differs"
+    eg.close()
+    dp.close()
