@@ -359,6 +359,8 @@ int capgnn_relabel_csr(int64_t n_loc, int64_t n_halo, const int64_t *rowptr, con
  * reduced in a fixed order) and optional otherwise (room to lay the weight matrix out for the bf16
  * matrix cores; without it a slower kernel runs): capgnn_gemm_workspace_bytes().
  * out_f32 != 0 stores C as float even when dtype is BF16 (weight gradients, logits).
+ * The padding of operand rows (columns beyond the operand's width, inside its ld) may be read, whatever it holds, but
+ * never reaches C; nothing is read beyond the last row's width.  Padding columns of C are not written.
  * ---------------------------------------------------------------------------------------- */
 size_t capgnn_gemm_workspace_bytes(int trans_a, int64_t M, int64_t N, int64_t K);
 
