@@ -56,10 +56,16 @@ def test_epoch_pipelined_with_one_tier_empty(env, cache_frac):
     dp.close()
 
 
-@pytest.mark.parametrize("name,scale", [("C2", 0.02), ("C3", 0.01), ("C4", 0.002), ("C5", 0.004)])
+@pytest.mark.parametrize("name,scale", [("C2", 0.02), ("C3", 0.01), ("C4", 0.002), ("C5", 0.004), ("C3-bf16", 0.01),
+                                        ("C4-f32", 0.002)])
 def test_epoch_scaled_configs_match_oracle(env, name, scale):
+    """The named workloads at a fraction of their size (same average degree and widths), plus the two crossings the named
+    ones leave out: the GraphSAGE model with bf16 storage and the three-layer GCN on the symmetric graph in fp32."""
     B, H, O = env["B"], env["H"], env["O"]
-    cfg = synth.CONFIGS[name].scaled(scale)
+    cfg = synth.CONFIGS[name.split("-")[0]].scaled(scale)
+    if "-" in name:
+        cfg.dtype = name.split("-")[1]
+        cfg.name = f"{cfg.name}-{cfg.dtype}"
     prob = H.make_problem(cfg, mask_frac=0.5)
     say(f"{cfg.name}: n_loc={prob.part.n_loc} n_halo={prob.part.n_halo} nnz={prob.part.nnz} dims={cfg.dims} {cfg.dtype}")
     dp = H.DeviceProblem(prob)
