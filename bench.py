@@ -493,6 +493,81 @@ def bench_spmm_ranges(args):
                       "note": "the cut launches write each output row once per range and do not add the partial sums"}))
 
 
+def bench_rapa(args):
+    """RAPA's subgraph adjustment end to end on a synthetic 4-way partition with uneven shares: influence scores on the
+    GPU (Eq. 6), Alg. 2 / Alg. 3 in the library with equal GPUs (every rate 1), pruning, and the measured epoch time of
+    every subgraph on this GPU before and after.  What the method promises is a smaller spread of the per-subgraph cost;
+    the measured spread is printed beside the cost model's.  One JSON line."""
+    import dataclasses
+    import numpy as np
+    import torch
+    from paper_2508_13716_amd import binding as B, harness as H, synth
+    P = 4
+    parts, _ = synth.make_partitioned_graph(600000, 12000000, P, seed=synth.BASE_SEED * 10 + 21, shares=[4, 3, 2, 1])
+    dims = [128, 256, 47]
+
+    def epoch_ms(part):
+        cfg = synth.Config(part.name, "sage", part.n_loc, part.n_halo, part.nnz, dims, "f32", 1.0, seed=synth.BASE_SEED * 10 + 22)
+        dp = H.DeviceProblem(H.make_problem(cfg, part=part))
+        for _ in range(args.warmup):
+            dp.run_epoch()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            dp.run_epoch()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        dp.close()
+        return ms
+
+    n_inner, e_inner, he, scores = [], [], [], []
+    for p in parts:
+        ei, cnt = B.halo_edge_counts(p.n_loc, p.n_halo, p.rowptr, p.col)
+        n_inner.append(p.n_loc); e_inner.append(ei); he.append(cnt)
+        din = np.maximum(np.diff(p.rowptr), 1)
+        dout = np.maximum(np.bincount(p.col, minlength=p.n_cols), 1)
+        count = np.concatenate([np.ones(p.n_loc), p.halo_prio.astype(np.float64)])
+        g = B.Graph(p.n_loc, p.n_halo, p.rowptr, p.col)
+        S = torch.zeros(p.n_cols, device="cuda")
+        B.influence_score(g, torch.from_numpy((1.0 / np.sqrt(din)).astype(np.float32)).cuda(),
+                          torch.from_numpy((1.0 / np.sqrt(dout)).astype(np.float32)).cuda(),
+                          torch.from_numpy(count.astype(np.float32)).cuda(), S)
+        torch.cuda.synchronize()
+        g.close()
+        scores.append(S.cpu().numpy()[p.n_loc:])
+    dev = [B.RapaDevice(1.0, 1.0, 1.0, 1.0, 1.0, 1e18) for _ in range(P)]
+    # the cost model (Eq. 3-4) of the subgraphs as they are, all rate ratios 1: the threshold is 1 % of its mean (the
+    # evaluation's setting)
+    alpha = 0.5
+    lam0 = np.array([alpha * (e_inner[i] + int(he[i].sum())) + (1 - alpha) * n_inner[i] + int(he[i].sum()) * (2.0 * (1 - 1.0 / P) + 1.0 / P)
+                     for i in range(P)])
+    res = B.rapa_adjust(n_inner, e_inner, he, scores, dev,
+                        B.RapaParams(0.5, 0.01 * float(np.mean(lam0)), 8, 12, 4, dims[0], 100.0 * 2 ** 20, 1000))
+    before = [epoch_ms(p) for p in parts]
+    pruned = []
+    for i, p in enumerate(parts):
+        rp, cl, _ = B.prune_halo(p.n_loc, p.n_halo, p.rowptr, p.col, res["keep"][i])
+        k = res["keep"][i].astype(bool)
+        pruned.append(dataclasses.replace(p, name=p.name + "-pruned", n_halo=int(k.sum()), rowptr=rp, col=cl,
+                                          halo_gid=p.halo_gid[k], halo_prio=p.halo_prio[k], halo_degree=p.halo_degree[k]))
+    after = [epoch_ms(p) for p in pruned]
+    print(json.dumps({
+        "metric": "per-subgraph epoch ms before / after RAPA's subgraph adjustment", "unit": "ms", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{P}-way random partition (shares 4:3:2:1) of a power-law graph, 600000 vertices, "
+                               f"{sum(p.nnz for p in parts)} edges in the subgraphs; GraphSAGE {dims}; equal GPUs, alpha 0.5, "
+                               "epsilon 1 % of the mean cost"},
+        "sweeps": res["sweeps"], "r": res["r"],
+        "subgraphs": [{"n_inner": int(n_inner[i]), "halo": [int(parts[i].n_halo), int(pruned[i].n_halo)],
+                       "edges": [int(parts[i].nnz), int(pruned[i].nnz)], "cost_model": [float(lam0[i]), float(res["lam"][i])],
+                       "epoch_ms": [before[i], after[i]]} for i in range(P)],
+        "cost_model_sigma": [float(np.std(lam0)), float(res["sigma"])],
+        "epoch_ms_sigma": [float(np.std(before)), float(np.std(after))],
+        "epoch_ms_max": [max(before), max(after)],
+        "note": "with equal GPUs the adjustment can only shed halo vertices of the costliest subgraphs; the slowest subgraph bounds "
+                "a synchronous epoch, so epoch_ms_max is the figure that matters"}))
+
+
 def bench_reorder(args):
     """Aggregation time of one SpMM launch (forward and transposed, hidden width 256) before and after the
     vertices are stored in a locality order, on the named config's graph (--config; 'clustered' = a graph with
@@ -560,7 +635,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default=None, help="one workload only (C1..C5); default: C2 as the headline line with C1, C3, C4, C5 under 'configs'")
-    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder", "zipf_requests", "mfma_peak", "products", "gather_peak", "spmm", "spmm_ranges"],
+    ap.add_argument("--what", default="epoch", choices=["epoch", "cache_update", "policy", "reorder", "zipf_requests", "mfma_peak", "products", "gather_peak", "spmm", "spmm_ranges", "rapa"],
                     help="epoch (default): the headline benchmark; cache_update: throughput of the cache write path; "
                          "policy: hit-rate curves of the cache policies; reorder: SpMM before / after vertex reordering "
                          "(--config C2..C5 or clustered); zipf_requests: request-list gather under Zipf(1.1) requests")
@@ -600,6 +675,8 @@ def main():
         return bench_zipf_requests(args)
     if args.what == "spmm_ranges":
         return bench_spmm_ranges(args)
+    if args.what == "rapa":
+        return bench_rapa(args)
     if args.what == "spmm":
         return bench_spmm_launch(args)
     if args.what == "mfma_peak":
